@@ -1,0 +1,197 @@
+/*
+ * plogp.h -- C ABI of the MI355X (gfx950) pLogP collective-tuning library.
+ *
+ * The library evaluates the pLogP cost models of the Broadcast and Scatter
+ * implementation strategies (paper: Table 1 and Table 2) over a grid of
+ * message size m, process count P and segment size s, and for every (m, P)
+ * keeps the predicted-fastest strategy and its best segment size (paper:
+ * Section 3.1, the search of the segment size that minimises the predicted
+ * time; Section 1, the choice of the most adapted technique per
+ * (communication pattern, message size, number of processes)).
+ *
+ * Notation follows the paper's Section 2: g(m) is the gap of a message of m
+ * bytes (a measured table), L the latency, P the number of nodes, s the
+ * segment size, k the number of segments (here k = ceil(m / s)).
+ *
+ * Everything is computed by HIP kernels on the current HIP device; there is
+ * no CPU fallback: without a usable GPU every compute entry point returns
+ * PLOGP_EDEVICE.  All functions return a status (0 = PLOGP_OK), never throw,
+ * never abort and never print.  Out-parameters are untouched on error.
+ * Pointers are HOST pointers unless the name starts with d_ (DEVICE).
+ * Calls that enqueue work take the HIP stream as a void* (hipStream_t; NULL
+ * is the default stream) and are asynchronous with respect to the host unless
+ * stated otherwise.  Handles may be used from one host thread at a time.
+ *
+ * Strategy ids (the order of the rows of Table 1, then Table 2):
+ *    0 Broadcast flat tree                 7 Broadcast binomial tree
+ *    1 Broadcast flat tree rendezvous      8 Broadcast binomial tree rendezvous
+ *    2 Broadcast segmented flat tree       9 Broadcast segmented binomial tree
+ *    3 Broadcast chain                    10 Scatter flat tree
+ *    4 Broadcast chain rendezvous         11 Scatter chain
+ *    5 Broadcast segmented chain          12 Scatter binomial tree
+ *    6 Broadcast binary tree
+ * Ids 2, 5 and 9 are the segmented rows (they take s); the others ignore s.
+ */
+#ifndef PLOGP_H
+#define PLOGP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PLOGP_N_STRATEGIES 13
+#define PLOGP_MASK_BCAST 0x03FFu      /* ids 0..9  */
+#define PLOGP_MASK_SCATTER 0x1C00u    /* ids 10..12 */
+#define PLOGP_MASK_ALL 0x1FFFu
+#define PLOGP_NO_STRATEGY 0xFFFFFFFFu
+#define PLOGP_MAX_SAMPLES 4096        /* largest table that fits the LDS staging */
+#define PLOGP_NO_CAP UINT64_MAX
+
+enum {
+    PLOGP_OK = 0,
+    PLOGP_EINVAL = 1,   /* bad argument (see each function)                          */
+    PLOGP_ERANGE = 2,   /* a size that enters a formula would reach 2^53             */
+    PLOGP_ENOSPC = 3,   /* output buffer too small                                   */
+    PLOGP_ENOMEM = 4,   /* host or device allocation failed                          */
+    PLOGP_EDEVICE = 5   /* HIP error; plogp_last_hip_error() returns the HIP code    */
+};
+
+/* One or several pLogP parameter tables {g(.), L}, resident on the device. */
+typedef struct plogp_table plogp_table;
+/* A tuning grid (m list, P list, s candidates), resident on the device. */
+typedef struct plogp_grid plogp_grid;
+
+/* One decision: what Section 1 of the paper selects per (pattern, m, P). */
+typedef struct {
+    double time;        /* predicted completion time of the chosen strategy        */
+    uint32_t s;         /* chosen segment size in bytes, 0 = unsegmented           */
+    uint32_t strategy;  /* chosen strategy id, PLOGP_NO_STRATEGY if none competed  */
+} plogp_cell;           /* 16 bytes */
+
+/* Caller-owned description of a grid; all arrays are host arrays. */
+typedef struct {
+    const uint64_t *m;      /* message sizes in bytes, > 0; duplicates allowed       */
+    size_t n_m;
+    const uint32_t *P;      /* process counts, >= 2, strictly ascending              */
+    size_t n_P;
+    const uint64_t *s;      /* segment-size candidates, > 0, < 2^32, strictly asc.   */
+    size_t n_s;             /* may be 0 (then s may be NULL)                         */
+    uint64_t s_cap;         /* a candidate competes for m iff s <= min(m, s_cap)     */
+    uint32_t dtype_size;    /* m and s must be multiples of it (Section 2: s is a    */
+                            /* multiple of the basic datatype); 0 or 1 = any         */
+    uint32_t strategy_mask; /* bit i set = strategy id i competes                    */
+} plogp_grid_desc;
+
+/*
+ * plogp_load_table / plogp_load_tables -- paper Section 2 (the measured g(m)
+ * and L that feed the models).  Copies n_tables tables of n samples each to
+ * the device and computes there the slope of every interval between samples
+ * (g between samples is read as piecewise linear; below the first sample it is
+ * clamped to the first gap, above the last sample the last line continues).
+ *   sizes [n_tables][n]: sample sizes in bytes, integers in [1, 2^53), strictly
+ *                        increasing within a table;
+ *   gaps  [n_tables][n]: g at those sizes, finite, >= 0 (need not be monotone);
+ *   L     [n_tables]   : latency, finite, >= 0;
+ *   2 <= n <= PLOGP_MAX_SAMPLES, n_tables >= 1.
+ * Synchronous.  Inputs are copied; the handle owns host and device copies and
+ * is released with plogp_free_table.  Errors: EINVAL, ENOMEM, EDEVICE.
+ */
+int plogp_load_table(const double *sizes, const double *gaps, size_t n, double L,
+                     plogp_table **out);
+int plogp_load_tables(const double *sizes, const double *gaps, size_t n, const double *L,
+                      size_t n_tables, plogp_table **out);
+int plogp_free_table(plogp_table *t);
+size_t plogp_table_count(const plogp_table *t);
+size_t plogp_table_samples(const plogp_table *t);
+/* Reads back the device-computed interval slopes of one table (n doubles;
+ * slope[n-1] repeats slope[n-2]).  Synchronous.  For tests. */
+int plogp_table_slopes(const plogp_table *t, size_t table_index, double *slopes_out, size_t n);
+
+/*
+ * plogp_interp_g -- paper Section 2, g(z): the gap of table `table_index`
+ * at n arbitrary sizes.  d_z: n device uint64 (each in [1, 2^53)); d_g_out: n
+ * device doubles.  Enqueued on `stream`.  n = 0 is a no-op.
+ * Errors: EINVAL (null, bad index), EDEVICE.  Values of d_z are not checked.
+ */
+int plogp_interp_g(const plogp_table *t, size_t table_index, const uint64_t *d_z, size_t n,
+                   double *d_g_out, void *stream);
+
+/*
+ * plogp_eval_strategy -- paper Table 1 / Table 2: the predicted time of ONE
+ * strategy at n independent points (m, P, s) on table `table_index`.
+ *   d_m [n] uint64 bytes, > 0; d_P [n] uint32, >= 2; d_s [n] uint64 segment
+ *   sizes (only read for ids 2, 5, 9, where 0 < s <= m; may be NULL for
+ *   the other ids); d_time_out [n] doubles.  All device pointers.
+ * A point outside the domain (m = 0, P < 2, bad s, or a product j*m that
+ * would reach 2^53) yields NaN for that point.  Enqueued on `stream`.
+ * Errors: EINVAL (null pointers, unknown strategy, bad index), EDEVICE.
+ */
+int plogp_eval_strategy(const plogp_table *t, size_t table_index, int strategy,
+                        const uint64_t *d_m, const uint32_t *d_P, const uint64_t *d_s,
+                        size_t n, double *d_time_out, void *stream);
+
+/*
+ * plogp_grid_create -- validates a grid and makes it resident on the device.
+ * Synchronous.  The description and its arrays are copied.
+ * Errors: EINVAL (null array with non-zero count; n_m = 0 or n_P = 0; m = 0;
+ *         P < 2 or not strictly ascending; s = 0, s >= 2^32 or not strictly
+ *         ascending; m or s not a multiple of dtype_size; mask selects no
+ *         known strategy), ERANGE (m >= 2^53, or with Scatter chain / binomial
+ *         enabled (Pmax-1)*m_max or 2^(ceil(log2 Pmax)-1)*m_max >= 2^53),
+ *         ENOMEM, EDEVICE.
+ */
+int plogp_grid_create(const plogp_grid_desc *desc, plogp_grid **out);
+int plogp_grid_free(plogp_grid *g);
+
+/* Number of operation planes of the decision table: Broadcast if any of ids
+ * 0..9 is in the mask, then Scatter if any of ids 10..12 is (1 or 2). */
+size_t plogp_grid_ops(const plogp_grid *g);
+/* Cells / bytes of the decision table for n_tables tables over this grid. */
+size_t plogp_decision_table_cells(size_t n_tables, const plogp_grid *g);
+size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g);
+
+/*
+ * plogp_tune_grid -- the whole sweep (paper Section 3.1 and Section 1): for
+ * every table of `t`, every operation plane and every (m, P) of the grid,
+ * evaluates all enabled strategies (segmented ones for every candidate
+ * s <= min(m, s_cap)) and writes the arg-min: smallest predicted time, ties
+ * to the lowest strategy id, then to the smallest s.  Broadcast and Scatter
+ * never compete with each other.
+ *   d_out: DEVICE buffer, caller-owned, 16-byte aligned, laid out
+ *          [table][operation plane][m index][P index] with P fastest;
+ *          d_out_bytes must be >= plogp_decision_table_bytes().
+ * A cell in which no strategy competed (e.g. only segmented ids enabled and
+ * no candidate <= m) is {+inf, 0, PLOGP_NO_STRATEGY}.
+ * Enqueued on `stream`; the result is complete when the stream reaches this
+ * point.  Scratch memory is owned by the grid handle (allocated on first use,
+ * reused afterwards): two tune calls on the same grid handle must not overlap.
+ * Errors: EINVAL (null, misaligned d_out), ENOSPC, ENOMEM, EDEVICE.
+ */
+int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size_t d_out_bytes,
+                    void *stream);
+
+/*
+ * plogp_tune_grid_profile -- the same work as plogp_tune_grid, with a HIP
+ * event recorded on `stream` between its kernels; waits for completion and
+ * returns the elapsed milliseconds of each stage in stage_ms_out[0..3]:
+ *   [0] per-table and per-m terms (interval slopes, g(1), g(s), g(m), the
+ *       Scatter-binomial prefix sums), [1] Scatter-chain block sums,
+ *   [2] Scatter-chain block prefix, [3] sweep + arg-min + decision-table write.
+ * A stage that did not run reports 0.  Synchronous.  For measurement only.
+ * Errors: as plogp_tune_grid, plus EINVAL for a null stage_ms_out.
+ */
+int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_out,
+                            size_t d_out_bytes, void *stream, float *stage_ms_out);
+
+/* Message for a status code (static string). */
+const char *plogp_strerror(int status);
+/* HIP error code of the calling thread's most recent PLOGP_EDEVICE (0 if none). */
+int plogp_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLOGP_H */

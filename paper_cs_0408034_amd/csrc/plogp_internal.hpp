@@ -1,0 +1,71 @@
+// Internal interface between the C-ABI host layer (plogp_api.hip) and the
+// gfx950 kernels (plogp_kernels.hip).  Not installed; include/plogp.h is the
+// public boundary.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace plogp {
+
+// Number of consecutive terms j summed by one lane in the Scatter-chain sum
+// (Table 2, chain row).  The association order of that sum is: blocks of
+// SUM_BLOCK consecutive j starting at j = 1, a running sum inside a block,
+// block totals added in ascending block order.
+constexpr int SUM_BLOCK = 64;
+
+// Device-resident batch of tables.
+struct DeviceTables {
+    const double *x;      // [n_tables][n] sample sizes
+    const double *y;      // [n_tables][n] gaps
+    double *slope;        // [n_tables][n] interval slopes (written by the kernels)
+    const double *L;      // [n_tables]
+    int n;                // samples per table
+    int n_tables;
+};
+
+// Device-resident grid plus the index metadata of the Scatter-chain blocks.
+struct DeviceGrid {
+    const uint64_t *m;    // [n_m]
+    const uint32_t *P;    // [n_P] strictly ascending
+    const uint64_t *s;    // [n_s] strictly ascending
+    const int *blk_off;   // [n_blk + 1] P-index range whose (P-1)/SUM_BLOCK equals the block
+    int n_m, n_P, n_s;
+    int n_blk;            // (Pmax-1)/SUM_BLOCK + 1 blocks; the last one may be partial
+    int last_terms;       // number of terms of the last block: (Pmax-1) - SUM_BLOCK*(n_blk-1)
+    int cl_max;           // ceil(log2 Pmax)
+    uint64_t s_cap;
+    uint32_t mask;
+    int n_ops;
+};
+
+// Per-(tables, grid) scratch in device memory, all written and read by kernels.
+struct Scratch {
+    double *g1;       // [n_tables]                       g(1)
+    double *gs;       // [n_tables][n_s]                  g(s)
+    double *gm;       // [n_tables][n_m]                  g(m)
+    double *sum2;     // [n_tables][n_m][cl_max+1]        prefix over j of g(2^j m)
+    double *blk;      // [n_tables][n_blk][n_m]           block totals, then their exclusive prefix
+    double *part;     // [n_tables][n_m][n_P]             in-block partial sums at the grid's P
+};
+
+struct plogp_cell_dev {
+    double time;
+    uint32_t s;
+    uint32_t strategy;
+};
+
+// Each returns the hipError_t of the launch (hipGetLastError after it).
+hipError_t launch_slopes(const DeviceTables &T, hipStream_t st);
+hipError_t launch_interp(const DeviceTables &T, int table, const uint64_t *d_z, size_t n,
+                         double *d_out, hipStream_t st);
+hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uint64_t *d_m,
+                       const uint32_t *d_P, const uint64_t *d_s, size_t n, double *d_out,
+                       hipStream_t st);
+// ev: nullptr, or 5 events recorded before the first kernel and after each stage.
+hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
+                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr);
+hipError_t kernels_init();
+
+}  // namespace plogp

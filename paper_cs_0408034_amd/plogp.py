@@ -1,0 +1,208 @@
+"""ctypes binding of libplogp.so -- argument marshalling only.
+
+Function names and argument order are those of include/plogp.h.  Device
+pointers are plain integers (e.g. torch.Tensor.data_ptr()); the stream is a
+hipStream_t as an integer (e.g. torch.cuda.current_stream().cuda_stream).
+The library has no CPU fallback: importing this module without the built
+library raises, and every compute call fails with PlogpError(EDEVICE) when no
+GPU is usable.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import numpy as np
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libplogp.so"
+
+OK, EINVAL, ERANGE, ENOSPC, ENOMEM, EDEVICE = range(6)
+MASK_BCAST, MASK_SCATTER, MASK_ALL = 0x03FF, 0x1C00, 0x1FFF
+NO_STRATEGY = 0xFFFFFFFF
+NO_CAP = (1 << 64) - 1
+MAX_SAMPLES = 4096
+CELL_DTYPE = np.dtype([("time", "<f8"), ("s", "<u4"), ("strategy", "<u4")])
+
+
+class PlogpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.plogp_strerror(status).decode()
+        if status == EDEVICE:
+            msg += " [hip error %d]" % _lib.plogp_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+class GridDesc(ctypes.Structure):
+    _fields_ = [("m", ctypes.POINTER(ctypes.c_uint64)), ("n_m", ctypes.c_size_t),
+                ("P", ctypes.POINTER(ctypes.c_uint32)), ("n_P", ctypes.c_size_t),
+                ("s", ctypes.POINTER(ctypes.c_uint64)), ("n_s", ctypes.c_size_t),
+                ("s_cap", ctypes.c_uint64), ("dtype_size", ctypes.c_uint32),
+                ("strategy_mask", ctypes.c_uint32)]
+
+
+def _load_library():
+    if not LIB_PATH.exists():
+        raise ImportError(
+            "%s is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or paper_cs_0408034_amd/build.py); there is no CPU fallback" % LIB_PATH)
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, sz, dp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double)
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    sigs = {
+        "plogp_load_table": (ctypes.c_int, [dp, dp, sz, ctypes.c_double, pp]),
+        "plogp_load_tables": (ctypes.c_int, [dp, dp, sz, dp, sz, pp]),
+        "plogp_free_table": (ctypes.c_int, [vp]),
+        "plogp_table_count": (sz, [vp]),
+        "plogp_table_samples": (sz, [vp]),
+        "plogp_table_slopes": (ctypes.c_int, [vp, sz, dp, sz]),
+        "plogp_interp_g": (ctypes.c_int, [vp, sz, vp, sz, vp, vp]),
+        "plogp_eval_strategy": (ctypes.c_int, [vp, sz, ctypes.c_int, vp, vp, vp, sz, vp, vp]),
+        "plogp_grid_create": (ctypes.c_int, [ctypes.POINTER(GridDesc), pp]),
+        "plogp_grid_free": (ctypes.c_int, [vp]),
+        "plogp_grid_ops": (sz, [vp]),
+        "plogp_decision_table_cells": (sz, [sz, vp]),
+        "plogp_decision_table_bytes": (sz, [sz, vp]),
+        "plogp_tune_grid": (ctypes.c_int, [vp, vp, vp, sz, vp]),
+        "plogp_tune_grid_profile": (ctypes.c_int, [vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]),
+        "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "plogp_last_hip_error": (ctypes.c_int, []),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = _load_library()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise PlogpError(status, where)
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+class Table:
+    """Handle of plogp_load_table / plogp_load_tables."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    @property
+    def count(self) -> int:
+        return int(_lib.plogp_table_count(self._h))
+
+    @property
+    def samples(self) -> int:
+        return int(_lib.plogp_table_samples(self._h))
+
+    def free(self):
+        if self._h:
+            _lib.plogp_free_table(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Grid:
+    """Handle of plogp_grid_create."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    @property
+    def ops(self) -> int:
+        return int(_lib.plogp_grid_ops(self._h))
+
+    def free(self):
+        if self._h:
+            _lib.plogp_grid_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def plogp_load_table(sizes, gaps, L: float) -> Table:
+    x = np.ascontiguousarray(sizes, dtype=np.float64)
+    y = np.ascontiguousarray(gaps, dtype=np.float64)
+    if x.ndim != 1 or x.shape != y.shape:
+        raise ValueError("sizes and gaps must be 1-D arrays of equal length")
+    h = ctypes.c_void_p()
+    _check(_lib.plogp_load_table(_dp(x), _dp(y), x.size, float(L), ctypes.byref(h)), "plogp_load_table")
+    return Table(h)
+
+
+def plogp_load_tables(sizes, gaps, L) -> Table:
+    x = np.ascontiguousarray(sizes, dtype=np.float64)
+    y = np.ascontiguousarray(gaps, dtype=np.float64)
+    lat = np.ascontiguousarray(L, dtype=np.float64)
+    if x.ndim != 2 or x.shape != y.shape or lat.shape != (x.shape[0],):
+        raise ValueError("sizes, gaps: [n_tables, n]; L: [n_tables]")
+    h = ctypes.c_void_p()
+    _check(_lib.plogp_load_tables(_dp(x), _dp(y), x.shape[1], _dp(lat), x.shape[0], ctypes.byref(h)),
+           "plogp_load_tables")
+    return Table(h)
+
+
+def plogp_table_slopes(table: Table, table_index: int) -> np.ndarray:
+    out = np.empty(table.samples, dtype=np.float64)
+    _check(_lib.plogp_table_slopes(table._h, table_index, _dp(out), out.size), "plogp_table_slopes")
+    return out
+
+
+def plogp_interp_g(table: Table, table_index: int, d_z: int, n: int, d_g_out: int, stream: int = 0):
+    _check(_lib.plogp_interp_g(table._h, table_index, d_z, n, d_g_out, stream), "plogp_interp_g")
+
+
+def plogp_eval_strategy(table: Table, table_index: int, strategy: int, d_m: int, d_P: int, d_s: int,
+                        n: int, d_time_out: int, stream: int = 0):
+    _check(_lib.plogp_eval_strategy(table._h, table_index, strategy, d_m, d_P, d_s or None, n,
+                                    d_time_out, stream), "plogp_eval_strategy")
+
+
+def plogp_grid_create(m, P, s, s_cap: int = NO_CAP, dtype_size: int = 8,
+                      strategy_mask: int = MASK_ALL) -> Grid:
+    m = np.ascontiguousarray(m, dtype=np.uint64)
+    P = np.ascontiguousarray(P, dtype=np.uint32)
+    s = np.ascontiguousarray(s, dtype=np.uint64)
+    d = GridDesc(m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), m.size,
+                 P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), P.size,
+                 s.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), s.size,
+                 int(s_cap), int(dtype_size), int(strategy_mask))
+    h = ctypes.c_void_p()
+    _check(_lib.plogp_grid_create(ctypes.byref(d), ctypes.byref(h)), "plogp_grid_create")
+    return Grid(h)
+
+
+def plogp_decision_table_cells(n_tables: int, grid: Grid) -> int:
+    return int(_lib.plogp_decision_table_cells(n_tables, grid._h))
+
+
+def plogp_decision_table_bytes(n_tables: int, grid: Grid) -> int:
+    return int(_lib.plogp_decision_table_bytes(n_tables, grid._h))
+
+
+def plogp_tune_grid(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0):
+    _check(_lib.plogp_tune_grid(table._h, grid._h, d_out, d_out_bytes, stream), "plogp_tune_grid")
+
+
+def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0):
+    """Runs the sweep with events between its kernels; returns the four stage times in ms."""
+    ms = (ctypes.c_float * 4)()
+    _check(_lib.plogp_tune_grid_profile(table._h, grid._h, d_out, d_out_bytes, stream, ms),
+           "plogp_tune_grid_profile")
+    return [float(v) for v in ms]

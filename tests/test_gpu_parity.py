@@ -1,0 +1,284 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on
+the same seeded inputs.  Strategy ids and segment sizes must be identical,
+predicted times within 1e-12 relative (binary64; the kernels follow the same
+rounding sequence, so they are expected to be bit-identical and the tests say
+when they are not)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from plogp_workloads import ALL_STRATEGIES_MASK, NO_CAP, SEGMENTED_IDS, Workload, make_workload
+from tests.gpu_util import REL_TOL, assert_tables_equal, gpu_tune, stream_handle, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+def _plogp():
+    from paper_cs_0408034_amd import plogp
+    return plogp
+
+
+def _dev(arr, dtype):
+    torch = torch_cuda()
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=dtype).view(
+        {np.uint64: np.int64, np.uint32: np.int32}.get(dtype, dtype))).cuda()
+
+
+# ------------------------------------------------------------------ step a1/a2
+
+@pytest.mark.parametrize("cfg", [1, 2, 4, 5])
+def test_slopes_and_interpolation_bit_exact(cfg):
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(cfg, n_tables=5) if cfg == 4 else make_workload(cfg)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    rng = np.random.default_rng(cfg)
+    for t in range(wl.n_tables):
+        x, y = wl.sizes[t], wl.gaps[t]
+        got = plogp.plogp_table_slopes(tab, t)
+        want = oracle.slopes(x, y)
+        assert (got.view(np.uint64) == want.view(np.uint64)).all()
+        top = math.log2(x[-1]) + 3
+        z = np.floor(2.0 ** (top * rng.random(3000))).astype(np.uint64) + np.uint64(1)
+        z = np.concatenate([z, x.astype(np.uint64), x.astype(np.uint64) + np.uint64(1),
+                            np.maximum(x.astype(np.uint64), 2) - np.uint64(1),
+                            np.array([1, 2, 3, (1 << 53) - 1], dtype=np.uint64)])
+        dz = _dev(z, np.uint64)
+        dg = torch.empty(len(z), dtype=torch.float64, device="cuda")
+        plogp.plogp_interp_g(tab, t, dz.data_ptr(), len(z), dg.data_ptr(), stream_handle())
+        torch.cuda.synchronize()
+        got = dg.cpu().numpy()
+        want = np.array([oracle.g(x, y, int(v)) for v in z])
+        assert (got.view(np.uint64) == want.view(np.uint64)).all()
+    tab.free()
+
+
+# ------------------------------------------------------------------ each row of Tables 1 and 2
+
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_every_strategy_at_random_points(cfg):
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(cfg)
+    x, y, L = wl.sizes[0], wl.gaps[0], float(wl.L[0])
+    tab = plogp.plogp_load_table(x, y, L)
+    rng = np.random.default_rng(50 + cfg)
+    n = 700
+    m = rng.choice(wl.m, size=n)
+    P = rng.choice(wl.P[wl.P <= 3000], size=n).astype(np.uint32)
+    P[:8] = [2, 3, 64, 65, 66, 128, 129, 2049]
+    s = np.array([int(rng.choice(wl.s[wl.s <= mv])) if (wl.s <= mv).any() else int(mv) for mv in m],
+                 dtype=np.uint64)
+    s[::7] = m[::7]                                       # k = 1 cases
+    dm, dP, ds = _dev(m, np.uint64), _dev(P, np.uint32), _dev(s, np.uint64)
+    out = torch.empty(n, dtype=torch.float64, device="cuda")
+    for sid in range(13):
+        plogp.plogp_eval_strategy(tab, 0, sid, dm.data_ptr(), dP.data_ptr(), ds.data_ptr(), n,
+                                  out.data_ptr(), stream_handle())
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want = np.array([oracle.eval_strategy(x, y, L, sid, int(m[i]), int(P[i]), int(s[i]))
+                         for i in range(n)])
+        assert (np.abs(got - want) <= REL_TOL * np.abs(want)).all(), sid
+        assert (got.view(np.uint64) == want.view(np.uint64)).all(), "strategy %d not bit-exact" % sid
+    tab.free()
+
+
+def test_eval_strategy_domain_errors_give_nan():
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(1)
+    tab = plogp.plogp_load_table(wl.sizes[0], wl.gaps[0], 55.0)
+    m = np.array([0, 64, 64, 64, 1 << 52], dtype=np.uint64)
+    P = np.array([4, 1, 4, 4, 4], dtype=np.uint32)
+    s = np.array([8, 8, 0, 128, 8], dtype=np.uint64)
+    dm, dP, ds = _dev(m, np.uint64), _dev(P, np.uint32), _dev(s, np.uint64)
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    plogp.plogp_eval_strategy(tab, 0, 5, dm.data_ptr(), dP.data_ptr(), ds.data_ptr(), 5,
+                              out.data_ptr(), stream_handle())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isnan(got[:4]).all() and np.isfinite(got[4])
+    plogp.plogp_eval_strategy(tab, 0, 11, dm.data_ptr(), dP.data_ptr(), 0, 5, out.data_ptr(),
+                              stream_handle())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isnan(got[0]) and np.isnan(got[1]) and np.isfinite(got[2]) and np.isnan(got[4])
+    tab.free()
+
+
+# ------------------------------------------------------------------ decision tables
+
+def test_config1_full():
+    wl = make_workload(1)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "cfg1"), "times not bit-identical"
+
+
+def test_config2_full():
+    wl = make_workload(2)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "cfg2"), "times not bit-identical"
+
+
+def test_config3_full():
+    wl = make_workload(3)
+    got = gpu_tune(wl)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(got, want, "cfg3"), "times not bit-identical"
+
+
+def test_config4_full_size_sampled_tables():
+    # the launch is the full 10 000-table job; the oracle recomputes every 97th table
+    wl = make_workload(4)
+    got = gpu_tune(wl)
+    pick = np.arange(0, wl.n_tables, 97)
+    want, _ = oracle.tune_grid(wl.sizes[pick], wl.gaps[pick], wl.L[pick], wl.m, wl.P, wl.s,
+                               wl.s_cap, wl.strategy_mask)
+    assert assert_tables_equal(got[pick], want, "cfg4"), "times not bit-identical"
+    # every table: the properties that hold at any size
+    assert (got["strategy"][:, 0] <= 9).all() and (got["strategy"][:, 1] >= 10).all()
+    assert (got["strategy"][:, 1] <= 12).all()
+    seg = np.isin(got["strategy"], SEGMENTED_IDS)
+    assert ((got["s"] > 0) == seg).all()
+    assert (got["s"][seg] <= np.broadcast_to(wl.m[None, None, :, None], got.shape)[seg]).all()
+    assert np.isfinite(got["time"]).all() and (got["time"] > 0).all()
+    # P = 2: the three Scatter rows tie exactly and so do Broadcast flat, chain and
+    # binomial; the tie-break names the lowest id (a segmented row may still beat them)
+    assert (got["strategy"][:, 1, :, 0] == 10).all()
+    assert not np.isin(got["strategy"][:, 0, :, 0], (3, 7)).any()
+
+
+def test_config5_full():
+    wl = make_workload(5)
+    got = gpu_tune(wl)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(got, want, "cfg5"), "times not bit-identical"
+
+
+# ------------------------------------------------------------------ shapes, tiles, ragged tails, edge cases
+
+def _small(cfg=2, **kw):
+    wl = make_workload(cfg, **kw)
+    return wl
+
+
+@pytest.mark.parametrize("sid", range(13))
+def test_each_strategy_alone_over_a_ragged_grid(sid):
+    # one strategy enabled: the table is that row's own minimum over s
+    wl = _small(2, m_slice=slice(3, 1024, 53), P_subset=[2, 3, 5, 64, 65, 66, 127, 129, 700, 1024])
+    wl.strategy_mask = 1 << sid
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "only id %d" % sid)
+
+
+@pytest.mark.parametrize("n_P,n_m", [(1, 1), (7, 3), (255, 2), (256, 5), (257, 4), (1500, 3)])
+def test_tile_shapes(n_P, n_m):
+    rng = np.random.default_rng(n_P * 10 + n_m)
+    base = make_workload(2)
+    P = np.sort(rng.choice(np.arange(2, 3000), size=n_P, replace=False)).astype(np.uint32)
+    m = rng.choice(base.m, size=n_m)
+    wl = Workload("tiles", base.sizes, base.gaps, base.L, m, P, base.s, base.s_cap,
+                  ALL_STRATEGIES_MASK)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "tiles %d x %d" % (n_P, n_m))
+
+
+def test_many_candidates_span_several_lds_passes():
+    wl = make_workload(3, m_slice=slice(0, 1024, 171), P_subset=[2, 3, 9, 64, 4096])
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "cfg3 slice")
+
+
+def test_no_candidates_and_candidates_all_above_m():
+    base = make_workload(2)
+    m = np.array([8, 16, 64], dtype=np.uint64)
+    P = np.array([2, 4, 9], dtype=np.uint32)
+    for s, mask in (([], ALL_STRATEGIES_MASK), ([128, 256], ALL_STRATEGIES_MASK),
+                    ([128, 256], (1 << 2) | (1 << 5) | (1 << 9)), ([8, 64], 1 << 5)):
+        wl = Workload("edge", base.sizes, base.gaps, base.L, m, P, np.array(s, dtype=np.uint64),
+                      NO_CAP, mask)
+        want, _ = oracle.tune_workload(wl)
+        got = gpu_tune(wl)
+        assert_tables_equal(got, want, "edge %s %x" % (s, mask))
+    assert (got["strategy"][0, 0, 0] == 5).all() and (got["s"][0, 0, 0] == 8).all()
+
+
+def test_cap_below_m_and_scatter_only_and_bcast_only():
+    base = make_workload(2, m_slice=slice(0, 1024, 97), P_subset=[2, 6, 33, 512])
+    for mask, cap in ((0x1C00, NO_CAP), (0x3FF, 4096), (ALL_STRATEGIES_MASK, 64)):
+        wl = Workload("masks", base.sizes, base.gaps, base.L, base.m, base.P, base.s, cap, mask)
+        want, _ = oracle.tune_workload(wl)
+        assert_tables_equal(gpu_tune(wl), want, "mask %x cap %d" % (mask, cap))
+
+
+def test_two_sample_table_and_non_monotone_table_and_ties():
+    m = np.array([8, 4096, 4096, 1 << 20], dtype=np.uint64)        # duplicate m on purpose
+    P = np.array([2, 3, 4, 5, 8, 100], dtype=np.uint32)
+    s = np.array([8, 512, 4096, 1 << 16], dtype=np.uint64)
+    for x, y, L in (([1.0, float(1 << 30)], [1.0, float(1 << 30)], 3.0),      # g(2s) = 2 g(s): ties over s
+                    ([1.0, float(1 << 30)], [5.0, 5.0], 0.0),                  # constant gap
+                    ([8.0, 64.0, 100.0, 5000.0, 1e6], [9.0, 3.0, 50.0, 20.0, 400.0], 7.0)):
+        wl = Workload("tiny", np.array([x]), np.array([y]), np.array([L]), m, P, s, NO_CAP,
+                      ALL_STRATEGIES_MASK)
+        want, _ = oracle.tune_workload(wl)
+        got = gpu_tune(wl)
+        assert assert_tables_equal(got, want, "tiny table")
+        assert got[0, 0, 1].tobytes() == got[0, 0, 2].tobytes()
+
+
+def test_largest_sizes_before_the_range_limit():
+    base = make_workload(2)
+    P = np.array([2, 1000, 1 << 16], dtype=np.uint32)
+    m = np.array([8, ((1 << 53) - 1) // ((1 << 16) - 1) // 8 * 8], dtype=np.uint64)
+    s = np.array([8, 1 << 20, (1 << 32) - 8], dtype=np.uint64)
+    wl = Workload("big", base.sizes, base.gaps, base.L, m, P, s, NO_CAP, ALL_STRATEGIES_MASK)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "largest sizes")
+
+
+def test_batch_of_tables_matches_one_by_one():
+    wl = make_workload(4, n_tables=37, table_offset=1000)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "cfg4 x37")
+
+
+def test_output_too_small_and_misaligned_are_refused():
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(1)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, 8, wl.strategy_mask)
+    nbytes = plogp.plogp_decision_table_bytes(1, grid)
+    buf = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(plogp.PlogpError) as e:
+        plogp.plogp_tune_grid(tab, grid, buf.data_ptr(), nbytes - 16, stream_handle())
+    assert e.value.status == plogp.ENOSPC
+    with pytest.raises(plogp.PlogpError) as e:
+        plogp.plogp_tune_grid(tab, grid, buf.data_ptr() + 8, nbytes, stream_handle())
+    assert e.value.status == plogp.EINVAL
+    torch.cuda.synchronize()
+    assert int(buf.sum().item()) == 0                    # nothing was written
+    grid.free(); tab.free()
+
+
+def test_repeated_calls_on_a_side_stream_give_the_same_table():
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(2, m_slice=slice(0, 1024, 8))
+    want, _ = oracle.tune_workload(wl)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, 8, wl.strategy_mask)
+    nbytes = plogp.plogp_decision_table_bytes(1, grid)
+    st = torch.cuda.Stream()
+    outs = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    torch.cuda.synchronize()
+    for o in outs:
+        plogp.plogp_tune_grid(tab, grid, o.data_ptr(), nbytes, st.cuda_stream)
+    st.synchronize()
+    for o in outs:
+        arr = o.cpu().numpy().view(plogp.CELL_DTYPE).reshape(want.shape)
+        assert assert_tables_equal(arr, want, "repeat")
+    grid.free(); tab.free()
