@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the pLogP tuning sweep on one MI355X.
+
+A step is one pass of the whole hot path (table terms, Scatter sums, sweep
+over s, arg-min over strategies, decision-table write: one plogp_tune_grid
+call) over one synthetic workload whose tables and grid are already resident
+in HBM.  The headline workload is config 2; configs 3-5 are timed too and
+reported under "workloads" in the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--extra 3,4,5] [--no-cpu]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+METRIC = "pLogP model evaluations/sec (strategy×m×P×s) + decision-table cells/sec"
+FP64_VECTOR_PEAK = 78.6e12        # flop/s: 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+HBM_PEAK = 8.0e12                 # bytes/s
+STAGES = ("terms", "chain_blocks", "chain_prefix", "sweep")
+
+# flops of one unsegmented row per (m, P), arg-min compare included
+# (convention: fma = 2, add/mul/compare = 1, select/convert/integer = 0)
+UNSEG_FLOPS = {0: 3, 1: 3, 3: 3, 4: 3, 6: 4, 7: 4, 8: 4, 10: 3, 11: 4, 12: 3}
+
+
+def algorithmic_work(wl):
+    """Flops and bytes the method itself needs per stage (after hoisting the
+    terms of the segmented rows that do not depend on P), per tune call."""
+    c = wl.counts()
+    mask, nt, n = wl.strategy_mask, wl.n_tables, wl.sizes.shape[1]
+    n_m, n_P, n_s = len(wl.m), len(wl.P), len(wl.s)
+    Pmax = int(wl.P.max())
+    cl_max = (Pmax - 1).bit_length()
+    search = math.ceil(math.log2(n))
+    interp = search + 3                                   # compares + sub + fma
+    n_seg = sum(1 for i in (2, 5, 9) if (mask >> i) & 1)
+    seg_evals = c["ms_pairs"] * n_P * n_seg
+    unseg = sum(f for i, f in UNSEG_FLOPS.items() if (mask >> i) & 1)
+    work = {
+        "terms": {"flops": nt * ((n - 1) * 3 + interp * (1 + n_s + n_m * (1 + (cl_max if (mask >> 12) & 1 else 0)))),
+                  "bytes": nt * n * 16},
+        "chain_blocks": {"flops": 6 * c["scatter_chain_interps"], "bytes": 0},
+        "chain_prefix": {"flops": nt * n_m * ((Pmax - 1) // 64) if (mask >> 11) & 1 else 0, "bytes": 0},
+        "sweep": {"flops": 3 * seg_evals + 5 * c["ms_pairs"] + unseg * nt * n_m * n_P,
+                  "bytes": c["output_bytes"]},
+    }
+    return work, c
+
+
+def describe(wl):
+    return "%s: %d table(s) x %d samples, %d m x %d P x %d s, mask 0x%x" % (
+        wl.name, wl.n_tables, wl.sizes.shape[1], len(wl.m), len(wl.P), len(wl.s), wl.strategy_mask)
+
+
+def roofline_of(stage, work, ms):
+    w = work[stage]
+    t_alu = w["flops"] / FP64_VECTOR_PEAK
+    t_hbm = w["bytes"] / HBM_PEAK
+    sec = ms * 1e-3
+    if t_hbm > t_alu:
+        ach = w["bytes"] / sec / 1e9
+        return {"kernel": stage, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9,
+                "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9), "traffic": None,
+                "algorithmic_bytes": w["bytes"], "avg_ms": ms}
+    ach = w["flops"] / sec / 1e12
+    return {"kernel": stage, "bound": "alu", "achieved": ach, "peak": FP64_VECTOR_PEAK / 1e12,
+            "unit": "TFLOP/s", "frac": ach / (FP64_VECTOR_PEAK / 1e12), "traffic": None,
+            "algorithmic_flops": w["flops"], "avg_ms": ms}
+
+
+def run_gpu(wl, steps, warmup, profile_reps):
+    import torch
+    from paper_cs_0408034_amd import plogp
+
+    torch.cuda.set_device(0)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, wl.dtype_size, wl.strategy_mask)
+    nbytes = plogp.plogp_decision_table_bytes(tab.count, grid)
+    out = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    for _ in range(warmup):
+        plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, ev_ms) / steps
+    # per-kernel durations: the same launches with a HIP event between the kernels
+    acc = np.zeros(4)
+    for _ in range(profile_reps):
+        acc += np.array(plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh))
+    stage_ms = dict(zip(STAGES, (acc / max(profile_reps, 1)).tolist()))
+    del out
+    grid.free()
+    tab.free()
+    return ms_per_step, stage_ms
+
+
+def cpu_sample(cfg, wl):
+    """A bounded cut of the same workload for the oracle (a few seconds of work)."""
+    from plogp_workloads import make_workload
+    if cfg == 3:
+        return make_workload(3, m_slice=slice(0, 1024, 8)), "every 8th m row of config 3 (128 of 1024), all P, all s"
+    if cfg == 4:
+        return make_workload(4, n_tables=100), "first 100 of the 10 000 tables of config 4, full grid"
+    if cfg == 5:
+        return make_workload(5, m_slice=slice(0, 4096, 8)), "every 8th m row of config 5 (512 of 4096), all P, all s"
+    return wl, "the full %s workload, one run" % wl.name
+
+
+def run_cpu(cfg, wl):
+    import oracle
+    sample, what = cpu_sample(cfg, wl)
+    oracle.tune_grid(sample.sizes[:1], sample.gaps[:1], sample.L[:1], sample.m[:2], sample.P[:2],
+                     sample.s, sample.s_cap, sample.strategy_mask)          # load + warm
+    t0 = time.perf_counter()
+    _, used = oracle.tune_workload(sample)
+    dt = time.perf_counter() - t0
+    c = sample.counts()
+    return {"value": c["nominal_evals"] / dt, "unit": "evaluations/s", "cores": int(used),
+            "kind": "oracle", "sample": what, "seconds": dt,
+            "effective_evals_per_s": c["effective_evals"] / dt, "cells_per_s": c["cells"] / dt}
+
+
+def bench_config(cfg, steps, warmup, with_cpu):
+    from plogp_workloads import make_workload
+    wl = make_workload(cfg)
+    work, c = algorithmic_work(wl)
+    ms, stage_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    dominant = max(STAGES, key=lambda k: stage_ms[k])
+    res = {
+        "workload": describe(wl),
+        "ms_per_step": ms,
+        "value": c["nominal_evals"] / (ms * 1e-3),
+        "effective_evals_per_s": c["effective_evals"] / (ms * 1e-3),
+        "cells_per_s": c["cells"] / (ms * 1e-3),
+        "scatter_chain_interps_per_s": c["scatter_chain_interps"] / (ms * 1e-3),
+        "steps": steps,
+        "stage_ms": stage_ms,
+        "roofline": roofline_of(dominant, work, stage_ms[dominant]),
+        "stage_rooflines": {k: roofline_of(k, work, stage_ms[k]) for k in STAGES if stage_ms[k] > 0},
+    }
+    if with_cpu:
+        res["cpu_baseline"] = run_cpu(cfg, wl)
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="headline workload (1..5)")
+    ap.add_argument("--extra", type=str, default="3,4,5", help="other configs to time, or 'none'")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no inter-GPU path exists); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
+
+    head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu)
+    line = {
+        "metric": METRIC,
+        "value": head["value"],
+        "unit": "evaluations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": head["workload"]},
+        "cells_per_s": head["cells_per_s"],
+        "effective_evals_per_s": head["effective_evals_per_s"],
+        "stage_ms": head["stage_ms"],
+        "roofline": head["roofline"],
+        "stage_rooflines": head["stage_rooflines"],
+    }
+    if "cpu_baseline" in head:
+        line["cpu_baseline"] = head["cpu_baseline"]
+    extras = [] if args.extra in ("", "none") else [int(v) for v in args.extra.split(",")]
+    if extras:
+        line["workloads"] = {}
+        for cfg in extras:
+            if cfg == args.config:
+                continue
+            steps = {3: 20, 4: 5, 5: 20}.get(cfg, 20)
+            line["workloads"]["cfg%d" % cfg] = bench_config(cfg, steps, 2, not args.no_cpu)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
