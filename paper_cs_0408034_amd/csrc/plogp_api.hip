@@ -76,14 +76,15 @@ struct plogp_grid {
     uint64_t *d_m = nullptr, *d_s = nullptr;
     uint32_t *d_P = nullptr;
     int *d_blk_off = nullptr;
+    unsigned long long *d_blk_mask = nullptr;
     // scratch, sized for scratch_tables tables
     size_t scratch_tables = 0;
-    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 
     DeviceGrid view() const
     {
         DeviceGrid g;
-        g.m = d_m; g.P = d_P; g.s = d_s; g.blk_off = d_blk_off;
+        g.m = d_m; g.P = d_P; g.s = d_s; g.blk_off = d_blk_off; g.blk_mask = d_blk_mask;
         g.n_m = (int)n_m; g.n_P = (int)n_P; g.n_s = (int)n_s;
         g.n_blk = n_blk; g.last_terms = last_terms; g.cl_max = cl_max;
         g.s_cap = s_cap; g.mask = mask; g.n_ops = n_ops;
@@ -92,7 +93,7 @@ struct plogp_grid {
     void free_scratch()
     {
         double **all[] = {&scratch.g1, &scratch.gs, &scratch.gm, &scratch.sum2, &scratch.blk,
-                          &scratch.part};
+                          &scratch.part, &scratch.rcp};
         for (double **p : all) {
             if (*p) (void)hipFree(*p);
             *p = nullptr;
@@ -106,6 +107,7 @@ struct plogp_grid {
         if (d_s) (void)hipFree(d_s);
         if (d_P) (void)hipFree(d_P);
         if (d_blk_off) (void)hipFree(d_blk_off);
+        if (d_blk_mask) (void)hipFree(d_blk_mask);
     }
 };
 
@@ -260,14 +262,20 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     g->last_terms = (int)((Pmax - 1) - (uint32_t)SUM_BLOCK * (uint32_t)(g->n_blk - 1));
     // P indices per block of the Scatter-chain sum: block b holds the P with (P-1)/SUM_BLOCK == b
     std::vector<int> off((size_t)g->n_blk + 1, 0);
-    for (size_t i = 0; i < d->n_P; ++i) off[(d->P[i] - 1) / SUM_BLOCK + 1] += 1;
+    std::vector<unsigned long long> bmask((size_t)g->n_blk, 0ull);
+    static_assert(SUM_BLOCK == 64, "one 64-bit mask per block");
+    for (size_t i = 0; i < d->n_P; ++i) {
+        off[(d->P[i] - 1) / SUM_BLOCK + 1] += 1;
+        bmask[(d->P[i] - 1) / SUM_BLOCK] |= 1ull << ((d->P[i] - 1) % SUM_BLOCK);
+    }
     for (int b = 0; b < g->n_blk; ++b) off[b + 1] += off[b];
 
     hipError_t e;
     if ((e = hipMalloc((void **)&g->d_m, d->n_m * sizeof(uint64_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_P, d->n_P * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_s, (d->n_s ? d->n_s : 1) * sizeof(uint64_t))) != hipSuccess ||
-        (e = hipMalloc((void **)&g->d_blk_off, off.size() * sizeof(int))) != hipSuccess) {
+        (e = hipMalloc((void **)&g->d_blk_off, off.size() * sizeof(int))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->d_blk_mask, bmask.size() * sizeof(unsigned long long))) != hipSuccess) {
         delete g;
         if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }
         return device_error(e);
@@ -275,7 +283,8 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     if ((e = hipMemcpy(g->d_m, d->m, d->n_m * sizeof(uint64_t), hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(g->d_P, d->P, d->n_P * sizeof(uint32_t), hipMemcpyHostToDevice)) != hipSuccess ||
         (d->n_s && (e = hipMemcpy(g->d_s, d->s, d->n_s * sizeof(uint64_t), hipMemcpyHostToDevice)) != hipSuccess) ||
-        (e = hipMemcpy(g->d_blk_off, off.data(), off.size() * sizeof(int), hipMemcpyHostToDevice)) != hipSuccess) {
+        (e = hipMemcpy(g->d_blk_off, off.data(), off.size() * sizeof(int), hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(g->d_blk_mask, bmask.data(), bmask.size() * sizeof(unsigned long long), hipMemcpyHostToDevice)) != hipSuccess) {
         delete g;
         return device_error(e);
     }
@@ -315,6 +324,7 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables)
         {&g->scratch.sum2, binom ? n_tables * g->n_m * (size_t)(g->cl_max + 1) : 1},
         {&g->scratch.blk, chain ? n_tables * (size_t)g->n_blk * g->n_m : 1},
         {&g->scratch.part, chain ? n_tables * g->n_m * g->n_P : 1},
+        {&g->scratch.rcp, g->n_s ? g->n_s : 1},
     };
     for (auto &w : want) {
         hipError_t e = hipMalloc((void **)w.p, w.count * sizeof(double));

@@ -31,6 +31,7 @@ struct DeviceGrid {
     const uint32_t *P;    // [n_P] strictly ascending
     const uint64_t *s;    // [n_s] strictly ascending
     const int *blk_off;   // [n_blk + 1] P-index range whose (P-1)/SUM_BLOCK equals the block
+    const unsigned long long *blk_mask;  // [n_blk] bit r set: a grid P has P-1 == SUM_BLOCK*b + r
     int n_m, n_P, n_s;
     int n_blk;            // (Pmax-1)/SUM_BLOCK + 1 blocks; the last one may be partial
     int last_terms;       // number of terms of the last block: (Pmax-1) - SUM_BLOCK*(n_blk-1)
@@ -45,9 +46,10 @@ struct Scratch {
     double *g1;       // [n_tables]                       g(1)
     double *gs;       // [n_tables][n_s]                  g(s)
     double *gm;       // [n_tables][n_m]                  g(m)
-    double *sum2;     // [n_tables][n_m][cl_max+1]        prefix over j of g(2^j m)
+    double *sum2;     // [n_tables][cl_max+1][n_m]        prefix over j of g(2^j m)
     double *blk;      // [n_tables][n_blk][n_m]           block totals, then their exclusive prefix
-    double *part;     // [n_tables][n_m][n_P]             in-block partial sums at the grid's P
+    double *part;     // [n_tables][n_P][n_m]             in-block partial sums at the grid's P
+    double *rcp;      // [n_s]                            1/s, rounded
 };
 
 struct plogp_cell_dev {

@@ -188,8 +188,10 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
 
 // One workgroup per (table, chunk of blockDim m rows).  Computes the interval
 // slopes from the raw samples (chunk 0 publishes them), g(m) and the prefix
-// sums over j of g(2^j m) for its rows; chunk 0 also computes g(1) and g(s).
-__global__ void __launch_bounds__(256) k_prep(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks)
+// sums over j of g(2^j m) for its rows; chunk 0 also computes g(1), g(s) and
+// (first table only) the reciprocals 1/s used to get k = ceil(m/s) without a
+// division per (m, s).
+__global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks)
 {
     extern __shared__ double lds[];
     const int t = blockIdx.x / n_chunks, chunk = blockIdx.x % n_chunks;
@@ -215,90 +217,125 @@ __global__ void __launch_bounds__(256) k_prep(DeviceTables T, DeviceGrid G, Scra
         const u64 m = G.m[mi];
         S.gm[(size_t)t * G.n_m + mi] = gap_at(tab, (double)m);
         if (G.mask & (1u << 12)) {
-            double *o = S.sum2 + ((size_t)t * G.n_m + mi) * (G.cl_max + 1);
+            double *o = S.sum2 + (size_t)t * (G.cl_max + 1) * G.n_m + mi;     // [d][m]
             double acc = 0.0;
             o[0] = 0.0;
             for (int j = 0; j < G.cl_max; ++j) {
                 acc = acc + gap_at(tab, (double)(m << j));
-                o[j + 1] = acc;
+                o[(size_t)(j + 1) * G.n_m] = acc;
             }
         }
     }
     if (chunk == 0) {
         if (threadIdx.x == 0)
             S.g1[t] = gap_at(tab, 1.0);
-        for (int si = threadIdx.x; si < G.n_s; si += blockDim.x)
-            S.gs[(size_t)t * G.n_s + si] = gap_at(tab, (double)G.s[si]);
+        for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
+            const double sd = (double)G.s[si];
+            S.gs[(size_t)t * G.n_s + si] = gap_at(tab, sd);
+            if (t == 0)
+                S.rcp[si] = 1.0 / sd;
+        }
     }
 }
 
 // ---------------------------------------------------------------- tune, step 2: Scatter-chain sum
 
-// One lane per (m, block of SUM_BLOCK consecutive j).  The arguments j*m ascend
-// inside a block, so the interval index only moves forward: one search at the
-// block start, then a pointer walk.  Emits the block total and, for every P of
-// the grid whose P-1 falls inside the block, the running sum at that point.
-__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table)
+// sum_{j=1}^{P-1} g(j m) (Table 2, chain row).  One lane per message size; a
+// workgroup covers blockDim sizes and `nb` consecutive blocks of SUM_BLOCK
+// terms.  Inside a lane the arguments j*m ascend, so the interval of the table
+// only moves forward: one search at the start, then a pointer walk that keeps
+// d = j*m - x_i (exact: integers below 2^53) and the interval width, so a term
+// costs an add, a compare, an fma and the accumulation.  Sizes below the first
+// sample fall into a virtual interval of slope 0 and gap y_0 (the clamp).
+// Emits each block total and, for every P of the grid whose P-1 falls inside a
+// block, the running sum at that point.
+__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bgroups,
+                               int n_mchunks, int nb)
 {
     extern __shared__ double lds[];
-    const int t = blockIdx.x / wg_per_table, w = blockIdx.x % wg_per_table;
+    int bid = blockIdx.x;
+    const int mc = bid % n_mchunks;
+    bid /= n_mchunks;
+    const int bg = bid % n_bgroups;
+    const int t = bid / n_bgroups;
     const LdsTable tab = stage_table(lds, T, t);
-    const long item = (long)w * blockDim.x + threadIdx.x;
-    if (item >= (long)G.n_m * G.n_blk)
+    const int mi = mc * blockDim.x + threadIdx.x;
+    if (mi >= G.n_m)
         return;
-    const int b = (int)(item / G.n_m), mi = (int)(item % G.n_m);
     const int n = tab.n;
     const u64 m = G.m[mi];
-    const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
-    int pi = G.blk_off[b];
-    const int pe = G.blk_off[b + 1];
-    int next = pi < pe ? (int)(G.P[pi] - 1u) - b * SUM_BLOCK : -1;
-    u64 zi = ((u64)b * SUM_BLOCK + 1) * m;
-    double z = (double)zi;
-    int i = last_not_above(tab.x, n, z);
-    double xi = tab.x[i], yi = tab.y[i], si = tab.sl[i];
-    double xn = (i + 1 < n) ? tab.x[i + 1] : INFINITY;
+    const double md = (double)m;
+    const int b0 = bg * nb;
+    const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
     const double x0 = tab.x[0];
-    double run = 0.0;
-    double *part = S.part + ((size_t)t * G.n_m + mi) * G.n_P;
-    for (int jj = 0; jj < nterms; ++jj) {
-        if (jj == next) {
-            part[pi] = run;
-            ++pi;
-            next = pi < pe ? (int)(G.P[pi] - 1u) - b * SUM_BLOCK : -1;
-        }
-        while (z >= xn) {
-            ++i;
-            xi = xn;
-            yi = tab.y[i];
-            si = tab.sl[i];
-            xn = (i + 1 < n) ? tab.x[i + 1] : INFINITY;
-        }
-        const double zc = z > x0 ? z : x0;
-        run = run + __builtin_fma(si, zc - xi, yi);
-        zi += m;
-        z = (double)zi;
+    int i;
+    double d, w, yi, si;                 // d = z - x_i, w = x_{i+1} - x_i
+    if (z0 < x0) {
+        i = -1; d = z0; w = x0; yi = tab.y[0]; si = 0.0;
+    } else {
+        i = last_not_above(tab.x, n, z0);
+        const double xi = tab.x[i];
+        d = z0 - xi;
+        w = (i + 1 < n) ? tab.x[i + 1] - xi : INFINITY;
+        yi = tab.y[i];
+        si = tab.sl[i];
     }
-    if (next == nterms)
-        part[pi] = run;
-    if (nterms == SUM_BLOCK)
-        S.blk[((size_t)t * G.n_blk + b) * G.n_m + mi] = run;
+    const size_t n_m = (size_t)G.n_m;
+    double *part = S.part + (size_t)t * G.n_P * n_m + mi;       // [P index][m]
+    double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
+    for (int bb = 0; bb < nb; ++bb) {
+        const int b = b0 + bb;
+        if (b >= G.n_blk)
+            break;
+        const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
+        const u64 wanted = G.blk_mask[b];   // bit r: some grid P needs the sum after r terms
+        int pi = G.blk_off[b];
+        double run = 0.0;
+        for (int jj = 0; jj < nterms; ++jj) {
+            if ((wanted >> jj) & 1ull) {
+                part[(size_t)pi * n_m] = run;
+                ++pi;
+            }
+            while (d >= w) {
+                d -= w;
+                ++i;
+                yi = tab.y[i];
+                si = tab.sl[i];
+                w = (i + 1 < n) ? tab.x[i + 1] - tab.x[i] : INFINITY;
+            }
+            run = run + __builtin_fma(si, d, yi);
+            d += md;
+        }
+        if (nterms < SUM_BLOCK && ((wanted >> nterms) & 1ull))
+            part[(size_t)pi * n_m] = run;
+        if (nterms == SUM_BLOCK)
+            tot[(size_t)b * n_m] = run;
+    }
 }
 
 // One lane per (table, m): turns the block totals into their exclusive prefix
 // in ascending block order (the sum of all finished blocks before block b).
 __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, int n_tables)
 {
-    const long id = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (id >= (long)n_tables * G.n_m)
+    const int id = blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= n_tables * G.n_m)
         return;
-    const int t = (int)(id / G.n_m), mi = (int)(id % G.n_m);
+    const int t = id / G.n_m, mi = id % G.n_m;
     double *p = S.blk + (size_t)t * G.n_blk * G.n_m + mi;
+    const int full = G.n_blk - 1;          // blocks that have a total
     double done = 0.0;
-    for (int b = 0; b < G.n_blk; ++b) {
-        const double tot = (b < G.n_blk - 1) ? p[(size_t)b * G.n_m] : 0.0;
-        p[(size_t)b * G.n_m] = done;
-        done = done + tot;
+    constexpr int BATCH = 32;              // loads of a batch are independent: issue them together
+    for (int b0 = 0; b0 < G.n_blk; b0 += BATCH) {
+        double tot[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u)
+            tot[u] = (b0 + u < full) ? p[(size_t)(b0 + u) * G.n_m] : 0.0;
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            if (b0 + u < G.n_blk)
+                p[(size_t)(b0 + u) * G.n_m] = done;
+            done = done + tot[u];
+        }
     }
 }
 
@@ -331,40 +368,232 @@ __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
     *reinterpret_cast<uint4 *>(p) = u.v;
 }
 
-// One workgroup per (table, tile of TM message sizes, tile of ptw process
-// counts); one lane per (m, P) cell, P fastest, so a wave writes consecutive
-// 16-byte records.  The terms of the segmented rows that do not depend on P,
-//   A = g(s) k, B = g(s) (k-1), C = g(s) + L,
-// are staged in LDS once per (m, s) in passes of `sch` candidates.
-__global__ void __launch_bounds__(1024)
-k_sweep(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int TM, int ptw,
-        int n_mtiles, int n_ptiles, int sch)
+// The terms of the segmented rows of Table 1 that depend on (m, s) only:
+//   k = ceil(m/s), A = g(s) k, B = g(s) (k-1), C = g(s) + L.
+// k comes from one multiplication by the rounded reciprocal of s, which can be
+// off by one, and one exact remainder m - k s (an fma) that corrects it.
+__device__ __forceinline__ void segment_terms(double md, double sd, double rcp_s, double gs,
+                                              double L, double &A, double &B, double &C)
 {
-    extern __shared__ __align__(16) double sweep_lds[];
-    double2 *AB = reinterpret_cast<double2 *>(sweep_lds);   // [TM][sch]
-    double *C = sweep_lds + 2 * (size_t)TM * sch;           // [sch]
-    __shared__ int wg_valid;
+    double k = ceil(md * rcp_s);
+    const double r = __builtin_fma(-k, sd, md);        // exact: m - k s
+    k = r > 0.0 ? k + 1.0 : (r <= -sd ? k - 1.0 : k);
+    A = gs * k;
+    B = gs * (k - 1.0);
+    C = gs + L;
+}
 
-    int bid = blockIdx.x;
-    const int pt = bid % n_ptiles;
-    bid /= n_ptiles;
-    const int mt = bid % n_mtiles;
-    const int t = bid / n_mtiles;
+// Broadcast: the ten rows of Table 1 in id order, strict '<' (ties: lowest id).
+// t2/t5/t9 are the minima over s of the segmented rows (+inf if none), s2/s5/s9
+// the segment sizes that attain them.
+__device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl, double cl,
+                                             double gm, double L, double g1, double t2,
+                                             uint32_t s2, double t5, uint32_t s5, double t9,
+                                             uint32_t s9)
+{
+    const double R = __builtin_fma(3.0, L, 2.0 * g1);   // rendezvous: 2 g(1) + 3 L
+    const double clL = cl * L;
+    Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+    if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
+    if (mask & (1u << 1)) consider(b, __builtin_fma(q, gm, R), 1, 0);
+    if (mask & (1u << 2)) consider(b, t2, 2, s2);
+    if (mask & (1u << 3)) consider(b, q * (gm + L), 3, 0);
+    if (mask & (1u << 4)) consider(b, q * (gm + R), 4, 0);
+    if (mask & (1u << 5)) consider(b, t5, 5, s5);
+    if (mask & (1u << 6)) consider(b, cl * __builtin_fma(2.0, gm, L), 6, 0);
+    if (mask & (1u << 7)) consider(b, __builtin_fma(fl, gm, clL), 7, 0);
+    if (mask & (1u << 8)) consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
+    if (mask & (1u << 9)) consider(b, t9, 9, s9);
+    return b;
+}
 
-    const int c = threadIdx.x;
-    const int ml = c / ptw, pl = c % ptw;
-    const int mi = mt * TM + ml, pi = pt * ptw + pl;
-    const bool active = ml < TM && mi < G.n_m && pi < G.n_P;
+// Scatter: the three rows of Table 2.  Reads the two sums for (m index mi, P index pi).
+__device__ __forceinline__ Best decide_scatter(const DeviceGrid &G, const Scratch &S, int t, int mi,
+                                               int pi, uint32_t P, double q, int cli, double gm,
+                                               double L)
+{
+    const uint32_t mask = G.mask;
+    const size_t n_m = (size_t)G.n_m;
+    const double cl = (double)cli;
+    Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+    if (mask & (1u << 10)) consider(b, __builtin_fma(q, gm, L), 10, 0);
+    if (mask & (1u << 11)) {
+        const int blk = (int)((P - 1u) / SUM_BLOCK);
+        const double done = S.blk[((size_t)t * G.n_blk + blk) * n_m + mi];
+        const double run = S.part[((size_t)t * G.n_P + pi) * n_m + mi];
+        consider(b, __builtin_fma(q, L, done + run), 11, 0);
+    }
+    if (mask & (1u << 12)) {
+        const double s12 = S.sum2[((size_t)t * (G.cl_max + 1) + cli) * n_m + mi];
+        consider(b, __builtin_fma(cl, L, s12), 12, 0);
+    }
+    return b;
+}
 
+// ---- sweep, few candidates: one lane per message size ------------------------
+//
+// A wave takes 64 consecutive m of one table and PC consecutive process counts.
+// P and s are wave-uniform loop variables (their terms live in scalar
+// registers); A, B are computed in the lane once per (m, s) and shared by the PC
+// process counts.  Per (P, s) and segmented row: one fma, one compare, the
+// running minimum and the index of the candidate that attained it (strict '<'
+// in ascending s: ties go to the smallest s).
+template <int PC>
+__global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, Scratch S,
+                                                 plogp_cell_dev *out, int n_mg, int n_pc,
+                                                 long n_items)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    long wid = (long)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (wid >= n_items)
+        return;
+    const int pc = (int)(wid % n_pc);
+    wid /= n_pc;
+    const int mg = (int)(wid % n_mg);
+    const int t = (int)(wid / n_mg);
+
+    const int mi = mg * 64 + lane;
+    const bool active = mi < G.n_m;
+    const u64 m = active ? G.m[mi] : 1;
+    const double md = (double)m;
+    const u64 lim = active ? (m < G.s_cap ? m : G.s_cap) : 0;
     const double L = T.L[t];
     const uint32_t mask = G.mask;
-    const u64 m = active ? G.m[mi] : 1;
-    const uint32_t P = active ? G.P[pi] : 2;
 
-    // number of candidates s <= min(m, s_cap) (the list ascends)
-    int nv = 0;
-    if (active && (mask & 0x224u)) {
-        const u64 lim = m < G.s_cap ? m : G.s_cap;
+    uint32_t Pv[PC];
+    double q[PC], fl[PC], clL[PC];
+#pragma unroll
+    for (int p = 0; p < PC; ++p) {
+        const int pi = pc * PC + p;
+        Pv[p] = pi < G.n_P ? G.P[pi] : 2u;
+        q[p] = (double)(Pv[p] - 1);
+        fl[p] = (double)floor_log2(Pv[p]);
+        clL[p] = (double)ceil_log2(Pv[p]) * L;
+    }
+    double b2[PC], b5[PC], b9[PC];
+    int i2[PC], i5[PC], i9[PC];
+#pragma unroll
+    for (int p = 0; p < PC; ++p) {
+        b2[p] = b5[p] = b9[p] = INFINITY;
+        i2[p] = i5[p] = i9[p] = 0;
+    }
+    if (mask & 0x224u) {
+        const double *gs = S.gs + (size_t)t * G.n_s;
+        for (int si = 0; si < G.n_s; ++si) {
+            const u64 sv = G.s[si];
+            const bool valid = sv <= lim;
+            if (__ballot(valid) == 0)
+                break;                       // the candidates ascend: nothing further competes
+            if (valid) {
+                double A, B, C;
+                segment_terms(md, (double)sv, S.rcp[si], gs[si], L, A, B, C);
+#pragma unroll
+                for (int p = 0; p < PC; ++p) {
+                    const double T2 = __builtin_fma(q[p], A, L);
+                    const double T5 = __builtin_fma(q[p], C, B);
+                    const double T9 = __builtin_fma(fl[p], A, clL[p]);
+                    i2[p] = T2 < b2[p] ? si : i2[p];
+                    b2[p] = __builtin_fmin(b2[p], T2);
+                    i5[p] = T5 < b5[p] ? si : i5[p];
+                    b5[p] = __builtin_fmin(b5[p], T5);
+                    i9[p] = T9 < b9[p] ? si : i9[p];
+                    b9[p] = __builtin_fmin(b9[p], T9);
+                }
+            }
+        }
+    }
+    if (!active)
+        return;
+    const double gm = S.gm[(size_t)t * G.n_m + mi];
+    const double g1 = S.g1[t];
+    const size_t plane = (size_t)G.n_m * G.n_P;
+#pragma unroll
+    for (int p = 0; p < PC; ++p) {
+        const int pi = pc * PC + p;
+        if (pi >= G.n_P)
+            break;
+        plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + pi;
+        const int cli = ceil_log2(Pv[p]);
+        if (mask & 0x3FFu) {
+            const uint32_t s2 = b2[p] < INFINITY ? (uint32_t)G.s[i2[p]] : 0u;
+            const uint32_t s5 = b5[p] < INFINITY ? (uint32_t)G.s[i5[p]] : 0u;
+            const uint32_t s9 = b9[p] < INFINITY ? (uint32_t)G.s[i9[p]] : 0u;
+            store_cell(o, decide_bcast(mask, q[p], fl[p], (double)cli, gm, L, g1, b2[p], s2, b5[p],
+                                       s5, b9[p], s9));
+            o += plane;
+        }
+        if (mask & 0x1C00u)
+            store_cell(o, decide_scatter(G, S, t, mi, pi, Pv[p], q[p], cli, gm, L));
+    }
+}
+
+// ---- sweep, many candidates: one lane per segment size -----------------------
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Minimum over the 64 lanes of a fully active wave, returned in every lane.
+// DPP butterflies inside each row of 16 lanes (quad permutes, half-row and row
+// mirrors), then the row broadcasts 15 and 31 fold the four rows into lane 63.
+__device__ __forceinline__ double wave_min(double v)
+{
+    v = __builtin_fmin(v, dpp_move<0xB1, 0xf>(v));     // quad_perm [1,0,3,2]
+    v = __builtin_fmin(v, dpp_move<0x4E, 0xf>(v));     // quad_perm [2,3,0,1]
+    v = __builtin_fmin(v, dpp_move<0x141, 0xf>(v));    // row_half_mirror
+    v = __builtin_fmin(v, dpp_move<0x140, 0xf>(v));    // row_mirror
+    v = __builtin_fmin(v, dpp_move<0x142, 0xa>(v));    // row_bcast:15 into rows 1, 3
+    v = __builtin_fmin(v, dpp_move<0x143, 0xc>(v));    // row_bcast:31 into rows 2, 3
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
+constexpr int SWEEP_S_CHUNK = 1024;     // candidates staged in LDS per pass (16 per lane)
+constexpr int SWEEP_S_MAX_WAVES = 10;
+
+// A workgroup takes one (table, m) and up to SWEEP_S_MAX_WAVES groups of GP
+// process counts, one group per wave; lanes run over the candidates s.  A, B, C
+// of a pass of SWEEP_S_CHUNK candidates are computed once by the whole
+// workgroup into LDS (double-buffered) and read by every wave.  In the loop a
+// wave only keeps running minima (one fma and one min per model value); per
+// lane it remembers in which pass each minimum first appeared.  At the end the
+// minima are reduced across lanes, the winner is chosen in id order, and only
+// for a winning segmented row the lanes that hold the minimum re-evaluate the
+// 16 candidates of the pass it came from to find the smallest s that attains it.
+template <int GP>
+__global__ void __launch_bounds__(64 * SWEEP_S_MAX_WAVES)
+k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_ptiles)
+{
+    __shared__ double2 AB[2][SWEEP_S_CHUNK];
+    __shared__ double Cs[2][SWEEP_S_CHUNK];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_waves = blockDim.x >> 6;
+    int bid = blockIdx.x;
+    const int ptile = bid % n_ptiles;
+    bid /= n_ptiles;
+    const int mi = bid % G.n_m;
+    const int t = bid / G.n_m;
+    const int p0 = (ptile * n_waves + wave) * GP;      // first P index of this wave
+    const bool has_work = p0 < G.n_P;
+
+    const u64 m = G.m[mi];
+    const double md = (double)m;
+    const u64 lim = m < G.s_cap ? m : G.s_cap;
+    const double L = T.L[t];
+    const uint32_t mask = G.mask;
+    const double *gs = S.gs + (size_t)t * G.n_s;
+
+    int nv = 0;                                        // candidates s <= min(m, s_cap)
+    {
         int lo = 0, hi = G.n_s;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
@@ -372,92 +601,145 @@ k_sweep(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int TM, in
         }
         nv = lo;
     }
-    if (c == 0)
-        wg_valid = 0;
+    const int n_chunks = (nv + SWEEP_S_CHUNK - 1) / SWEEP_S_CHUNK;
+
+    double q[GP], fl[GP], clL[GP];
+#pragma unroll
+    for (int p = 0; p < GP; ++p) {
+        const uint32_t Pv = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
+        q[p] = (double)(Pv - 1);
+        fl[p] = (double)floor_log2(Pv);
+        clL[p] = (double)ceil_log2(Pv) * L;
+    }
+    double best2[GP], best5[GP], best9[GP];
+    int blk2[GP], blk5[GP], blk9[GP];
+#pragma unroll
+    for (int p = 0; p < GP; ++p) {
+        best2[p] = best5[p] = best9[p] = INFINITY;
+        blk2[p] = blk5[p] = blk9[p] = 0;
+    }
+
+    auto fill = [&](int c) {
+        const int buf = c & 1;
+        for (int e = threadIdx.x; e < SWEEP_S_CHUNK; e += blockDim.x) {
+            const int si = c * SWEEP_S_CHUNK + e;
+            double A = INFINITY, B = INFINITY, C = 0.0;
+            if (si < nv)
+                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
+            AB[buf][e] = make_double2(A, B);
+            Cs[buf][e] = C;
+        }
+    };
+    if (n_chunks > 0)
+        fill(0);
     __syncthreads();
-    if (nv > 0)
-        atomicMax(&wg_valid, nv);
-    __syncthreads();
-    const int wg_nv = wg_valid;
-
-    const double q = (double)(P - 1);
-    const int fli = floor_log2(P), cli = ceil_log2(P);
-    const double fl = (double)fli, cl = (double)cli;
-    const double clL = cl * L;
-
-    double b2 = INFINITY, b5 = INFINITY, b9 = INFINITY;
-    int s2 = 0, s5 = 0, s9 = 0;
-    const double *gs = S.gs + (size_t)t * G.n_s;
-
-    for (int base = 0; base < wg_nv; base += sch) {
-        const int len = min(sch, wg_nv - base);
-        __syncthreads();
-        for (int e = c; e < TM * len; e += blockDim.x) {
-            const int r = e / len, o = e % len;
-            const int rmi = mt * TM + r;
-            if (rmi < G.n_m) {
-                const double g = gs[base + o];
-                const double k = segments(G.m[rmi], G.s[base + o]);
-                AB[(size_t)r * sch + o] = make_double2(g * k, g * (k - 1.0));
+    for (int c = 0; c < n_chunks; ++c) {
+        if (c + 1 < n_chunks)
+            fill(c + 1);
+        if (has_work) {
+            const int buf = c & 1;
+            const int len = min(SWEEP_S_CHUNK, nv - c * SWEEP_S_CHUNK);
+            const int steps = (len + 63) >> 6;
+            double cur2[GP], cur5[GP], cur9[GP];
+#pragma unroll
+            for (int p = 0; p < GP; ++p)
+                cur2[p] = cur5[p] = cur9[p] = INFINITY;
+#pragma unroll 2
+            for (int i = 0; i < steps; ++i) {
+                const double2 ab = AB[buf][64 * i + lane];
+                const double C = Cs[buf][64 * i + lane];
+#pragma unroll
+                for (int p = 0; p < GP; ++p) {
+                    cur2[p] = __builtin_fmin(cur2[p], __builtin_fma(q[p], ab.x, L));
+                    cur5[p] = __builtin_fmin(cur5[p], __builtin_fma(q[p], C, ab.y));
+                    cur9[p] = __builtin_fmin(cur9[p], __builtin_fma(fl[p], ab.x, clL[p]));
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < GP; ++p) {
+                blk2[p] = cur2[p] < best2[p] ? c : blk2[p];
+                best2[p] = __builtin_fmin(best2[p], cur2[p]);
+                blk5[p] = cur5[p] < best5[p] ? c : blk5[p];
+                best5[p] = __builtin_fmin(best5[p], cur5[p]);
+                blk9[p] = cur9[p] < best9[p] ? c : blk9[p];
+                best9[p] = __builtin_fmin(best9[p], cur9[p]);
             }
         }
-        for (int o = c; o < len; o += blockDim.x)
-            C[o] = gs[base + o] + L;
         __syncthreads();
-        const int mine = min(len, nv - base);
-        const double2 *ab = AB + (size_t)ml * sch;
-        for (int o = 0; o < mine; ++o) {
-            const double2 v = ab[o];
-            const double T2 = __builtin_fma(q, v.x, L);
-            const double T5 = __builtin_fma(q, C[o], v.y);
-            const double T9 = __builtin_fma(fl, v.x, clL);
-            if (T2 < b2) { b2 = T2; s2 = base + o; }
-            if (T5 < b5) { b5 = T5; s5 = base + o; }
-            if (T9 < b9) { b9 = T9; s9 = base + o; }
-        }
     }
-    if (!active)
+    if (!has_work)
         return;
 
+    // per process count of the group: the best segmented row, its time and its s
+    double segT = INFINITY;       // kept by lane p for process count p0 + p
+    uint32_t segId = 0xFFFFFFFFu, segS = 0;
+#pragma unroll
+    for (int p = 0; p < GP; ++p) {
+        const double c2 = (mask & (1u << 2)) ? best2[p] : INFINITY;
+        const double c5 = (mask & (1u << 5)) ? best5[p] : INFINITY;
+        const double c9 = (mask & (1u << 9)) ? best9[p] : INFINITY;
+        const double V = wave_min(__builtin_fmin(__builtin_fmin(c2, c5), c9));
+        if (!(V < INFINITY))
+            continue;                                  // wave-uniform
+        int id;
+        double mine;
+        int myblk;
+        if (__ballot(c2 == V) != 0) { id = 2; mine = c2; myblk = blk2[p]; }
+        else if (__ballot(c5 == V) != 0) { id = 5; mine = c5; myblk = blk5[p]; }
+        else { id = 9; mine = c9; myblk = blk9[p]; }
+        // smallest s with T_id(s) == V: every lane that holds V names the pass it
+        // first saw it in; 16 lanes re-evaluate that lane's 16 candidates of the pass
+        unsigned long long holders = __ballot(mine == V);
+        int first = 0x7FFFFFFF;
+        while (holders != 0) {
+            const int l = __builtin_ctzll(holders);
+            holders &= holders - 1;
+            const int c = __builtin_amdgcn_readlane(myblk, l);
+            const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
+            bool hit = false;
+            if (lane < SWEEP_S_CHUNK / 64 && si < nv) {
+                double A, B, C;
+                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
+                const double Tv = id == 2 ? __builtin_fma(q[p], A, L)
+                                : id == 5 ? __builtin_fma(q[p], C, B)
+                                          : __builtin_fma(fl[p], A, clL[p]);
+                hit = Tv == V;
+            }
+            const unsigned long long hits = __ballot(hit);
+            if (hits != 0) {
+                const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
+                first = cand < first ? cand : first;
+            }
+        }
+        if (lane == p) {
+            segT = V;
+            segId = (uint32_t)id;
+            segS = first < nv ? (uint32_t)G.s[first] : 0u;
+        }
+    }
+
+    // lanes 0..GP-1 finish one cell each: unsegmented rows, arg-min, store
+    const int pi = p0 + lane;
+    if (lane >= GP || pi >= G.n_P)
+        return;
+    const uint32_t Pv = G.P[pi];
+    const double qv = (double)(Pv - 1);
+    const int fli = floor_log2(Pv), cli = ceil_log2(Pv);
     const double gm = S.gm[(size_t)t * G.n_m + mi];
     const size_t plane = (size_t)G.n_m * G.n_P;
     plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + pi;
-
     if (mask & 0x3FFu) {
         const double g1 = S.g1[t];
-        const double R = __builtin_fma(3.0, L, 2.0 * g1);
-        Best b = {INFINITY, 0u, 0xFFFFFFFFu};
-        if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
-        if (mask & (1u << 1)) consider(b, __builtin_fma(q, gm, R), 1, 0);
-        if ((mask & (1u << 2)) && nv > 0) consider(b, b2, 2, (uint32_t)G.s[s2]);
-        if (mask & (1u << 3)) consider(b, q * (gm + L), 3, 0);
-        if (mask & (1u << 4)) consider(b, q * (gm + R), 4, 0);
-        if ((mask & (1u << 5)) && nv > 0) consider(b, b5, 5, (uint32_t)G.s[s5]);
-        if (mask & (1u << 6)) consider(b, cl * __builtin_fma(2.0, gm, L), 6, 0);
-        if (mask & (1u << 7)) consider(b, __builtin_fma(fl, gm, clL), 7, 0);
-        if (mask & (1u << 8)) consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
-        if ((mask & (1u << 9)) && nv > 0) consider(b, b9, 9, (uint32_t)G.s[s9]);
-        store_cell(o, b);
+        store_cell(o, decide_bcast(mask, qv, (double)fli, (double)cli, gm, L, g1,
+                                   segId == 2 ? segT : INFINITY, segS,
+                                   segId == 5 ? segT : INFINITY, segS,
+                                   segId == 9 ? segT : INFINITY, segS));
         o += plane;
     }
-    if (mask & 0x1C00u) {
-        Best b = {INFINITY, 0u, 0xFFFFFFFFu};
-        if (mask & (1u << 10)) consider(b, __builtin_fma(q, gm, L), 10, 0);
-        if (mask & (1u << 11)) {
-            const int blk = (int)((P - 1u) / SUM_BLOCK);
-            const double done = S.blk[((size_t)t * G.n_blk + blk) * G.n_m + mi];
-            const double run = S.part[((size_t)t * G.n_m + mi) * G.n_P + pi];
-            consider(b, __builtin_fma(q, L, done + run), 11, 0);
-        }
-        if (mask & (1u << 12)) {
-            const double s12 = S.sum2[((size_t)t * G.n_m + mi) * (G.cl_max + 1) + cli];
-            consider(b, __builtin_fma(cl, L, s12), 12, 0);
-        }
-        store_cell(o, b);
-    }
+    if (mask & 0x1C00u)
+        store_cell(o, decide_scatter(G, S, t, mi, pi, Pv, qv, cli, gm, L));
 }
 
-inline int round_up(int v, int to) { return (v + to - 1) / to * to; }
 
 }  // namespace
 
@@ -474,7 +756,7 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_eval),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_prep),
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_terms),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
@@ -524,20 +806,23 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
 
     PLOGP_MARK(0);
     const int n_chunks = (G.n_m + 255) / 256;
-    hipLaunchKernelGGL(k_prep, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
+    hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
                        S, n_chunks);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(1);
 
     if (G.mask & (1u << 11)) {
-        const int threads = tab_lds > 32768 ? 1024 : 256;
-        const long items = (long)G.n_m * G.n_blk;
-        const int wg_per_table = (int)((items + threads - 1) / threads);
-        hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * wg_per_table), dim3(threads),
-                           tab_lds, st, T, G, S, wg_per_table);
+        // a big table fills most of the LDS of a CU: one large workgroup, several blocks per lane
+        const bool big = tab_lds > 32768;
+        const int threads = big ? 1024 : 256;
+        const int nb = big ? 8 : 1;
+        const int n_mchunks = (G.n_m + threads - 1) / threads;
+        const int n_bgroups = (G.n_blk + nb - 1) / nb;
+        hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * n_bgroups * n_mchunks),
+                           dim3(threads), tab_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
-        const long rows = (long)T.n_tables * G.n_m;
+        const int rows = T.n_tables * G.n_m;
         hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, G,
                            S, T.n_tables);
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -547,20 +832,21 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(3);
     }
 
-    // tile shape: up to 1024 process counts per workgroup; several m rows when P is short
-    const int ptw = G.n_P < 1024 ? G.n_P : 1024;
-    int TM = 256 / ptw;
-    if (TM < 1) TM = 1;
-    if (TM > G.n_m) TM = G.n_m;
-    const int threads = round_up(TM * ptw, 64);
-    const int n_ptiles = (G.n_P + ptw - 1) / ptw;
-    const int n_mtiles = (G.n_m + TM - 1) / TM;
-    int sch = 2048 / TM;
-    if (sch > G.n_s) sch = G.n_s;
-    if (sch < 1) sch = 1;
-    const size_t lds = ((size_t)2 * TM * sch + sch) * sizeof(double);
-    hipLaunchKernelGGL(k_sweep, dim3((unsigned)T.n_tables * n_mtiles * n_ptiles), dim3(threads), lds,
-                       st, T, G, S, d_out, TM, ptw, n_mtiles, n_ptiles, sch);
+    if (G.n_s >= 256) {
+        constexpr int GP = 8;
+        const int n_groups = (G.n_P + GP - 1) / GP;
+        const int waves = n_groups < SWEEP_S_MAX_WAVES ? n_groups : SWEEP_S_MAX_WAVES;
+        const int n_ptiles = (n_groups + waves - 1) / waves;
+        hipLaunchKernelGGL(k_sweep_s<GP>, dim3((unsigned)T.n_tables * G.n_m * n_ptiles),
+                           dim3(64 * waves), 0, st, T, G, S, d_out, n_ptiles);
+    } else {
+        constexpr int PC = 8;
+        const int n_mg = (G.n_m + 63) / 64;
+        const int n_pc = (G.n_P + PC - 1) / PC;
+        const long n_items = (long)T.n_tables * n_mg * n_pc;
+        hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)((n_items + 3) / 4)), dim3(256), 0, st, T, G,
+                           S, d_out, n_mg, n_pc, n_items);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(4);
 #undef PLOGP_MARK
