@@ -252,34 +252,44 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bgroups,
                                int n_mchunks, int nb)
 {
-    extern __shared__ double lds[];
+    extern __shared__ __align__(16) double chain_lds[];
     int bid = blockIdx.x;
     const int mc = bid % n_mchunks;
     bid /= n_mchunks;
     const int bg = bid % n_bgroups;
     const int t = bid / n_bgroups;
-    const LdsTable tab = stage_table(lds, T, t);
+    const int n = T.n;
+    // LDS: YS[0..n] = {gap, slope} per interval, X[0..n+1] = interval starts.
+    // Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0 (the clamp below
+    // the first sample); interval i+1 starts at sample i; X[n+1] = +inf.
+    double2 *YS = reinterpret_cast<double2 *>(chain_lds);
+    double *X = chain_lds + 2 * (n + 1);
+    {
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
+        const double *gsl = T.slope + (size_t)t * n;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            X[i + 1] = gx[i];
+            YS[i + 1] = make_double2(gy[i], gsl[i]);
+        }
+        if (threadIdx.x == 0) {
+            X[0] = 0.0;
+            X[n + 1] = INFINITY;
+            YS[0] = make_double2(gy[0], 0.0);
+        }
+    }
+    __syncthreads();
     const int mi = mc * blockDim.x + threadIdx.x;
     if (mi >= G.n_m)
         return;
-    const int n = tab.n;
     const u64 m = G.m[mi];
     const double md = (double)m;
     const int b0 = bg * nb;
     const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
-    const double x0 = tab.x[0];
-    int i;
-    double d, w, yi, si;                 // d = z - x_i, w = x_{i+1} - x_i
-    if (z0 < x0) {
-        i = -1; d = z0; w = x0; yi = tab.y[0]; si = 0.0;
-    } else {
-        i = last_not_above(tab.x, n, z0);
-        const double xi = tab.x[i];
-        d = z0 - xi;
-        w = (i + 1 < n) ? tab.x[i + 1] - xi : INFINITY;
-        yi = tab.y[i];
-        si = tab.sl[i];
-    }
+    // interval of z0: number of samples not above z0 (0 = the virtual interval)
+    int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
+    double d = z0 - X[i];                 // d = z - start of the interval (exact)
+    double w = X[i + 1] - X[i];           // width of the interval
+    double yi = YS[i].x, si = YS[i].y;
     const size_t n_m = (size_t)G.n_m;
     double *part = S.part + (size_t)t * G.n_P * n_m + mi;       // [P index][m]
     double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
@@ -296,12 +306,14 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
                 part[(size_t)pi * n_m] = run;
                 ++pi;
             }
-            while (d >= w) {
+            while (d >= w) {                // crossed into the next interval
                 d -= w;
                 ++i;
-                yi = tab.y[i];
-                si = tab.sl[i];
-                w = (i + 1 < n) ? tab.x[i + 1] - tab.x[i] : INFINITY;
+                const double xa = X[i], xb = X[i + 1];
+                const double2 ys = YS[i];
+                w = xb - xa;
+                yi = ys.x;
+                si = ys.y;
             }
             run = run + __builtin_fma(si, d, yi);
             d += md;
@@ -430,6 +442,15 @@ __device__ __forceinline__ Best decide_scatter(const DeviceGrid &G, const Scratc
     return b;
 }
 
+// Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
+// adds a canonicalising v_max_f64 per operand in IEEE mode).
+__device__ __forceinline__ double min_f64(double a, double b)
+{
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // ---- sweep, few candidates: one lane per message size ------------------------
 //
 // A wave takes 64 consecutive m of one table and PC consecutive process counts.
@@ -494,11 +515,11 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
                     const double T5 = __builtin_fma(q[p], C, B);
                     const double T9 = __builtin_fma(fl[p], A, clL[p]);
                     i2[p] = T2 < b2[p] ? si : i2[p];
-                    b2[p] = __builtin_fmin(b2[p], T2);
+                    b2[p] = min_f64(b2[p], T2);
                     i5[p] = T5 < b5[p] ? si : i5[p];
-                    b5[p] = __builtin_fmin(b5[p], T5);
+                    b5[p] = min_f64(b5[p], T5);
                     i9[p] = T9 < b9[p] ? si : i9[p];
-                    b9[p] = __builtin_fmin(b9[p], T9);
+                    b9[p] = min_f64(b9[p], T9);
                 }
             }
         }
@@ -555,8 +576,8 @@ __device__ __forceinline__ double wave_min(double v)
     return __hiloint2double(hi, lo);
 }
 
-constexpr int SWEEP_S_CHUNK = 1024;     // candidates staged in LDS per pass (16 per lane)
-constexpr int SWEEP_S_MAX_WAVES = 10;
+constexpr int SWEEP_S_CHUNK = 2048;     // candidates staged in LDS per pass (32 per lane)
+constexpr int SWEEP_S_MAX_WAVES = 12;
 
 // A workgroup takes one (table, m) and up to SWEEP_S_MAX_WAVES groups of GP
 // process counts, one group per wave; lanes run over the candidates s.  A, B, C
@@ -566,7 +587,7 @@ constexpr int SWEEP_S_MAX_WAVES = 10;
 // lane it remembers in which pass each minimum first appeared.  At the end the
 // minima are reduced across lanes, the winner is chosen in id order, and only
 // for a winning segmented row the lanes that hold the minimum re-evaluate the
-// 16 candidates of the pass it came from to find the smallest s that attains it.
+// candidates of the pass it came from to find the smallest s that attains it.
 template <int GP>
 __global__ void __launch_bounds__(64 * SWEEP_S_MAX_WAVES)
 k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_ptiles)
@@ -650,19 +671,19 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 const double C = Cs[buf][64 * i + lane];
 #pragma unroll
                 for (int p = 0; p < GP; ++p) {
-                    cur2[p] = __builtin_fmin(cur2[p], __builtin_fma(q[p], ab.x, L));
-                    cur5[p] = __builtin_fmin(cur5[p], __builtin_fma(q[p], C, ab.y));
-                    cur9[p] = __builtin_fmin(cur9[p], __builtin_fma(fl[p], ab.x, clL[p]));
+                    cur2[p] = min_f64(cur2[p], __builtin_fma(q[p], ab.x, L));
+                    cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], C, ab.y));
+                    cur9[p] = min_f64(cur9[p], __builtin_fma(fl[p], ab.x, clL[p]));
                 }
             }
 #pragma unroll
             for (int p = 0; p < GP; ++p) {
                 blk2[p] = cur2[p] < best2[p] ? c : blk2[p];
-                best2[p] = __builtin_fmin(best2[p], cur2[p]);
+                best2[p] = min_f64(best2[p], cur2[p]);
                 blk5[p] = cur5[p] < best5[p] ? c : blk5[p];
-                best5[p] = __builtin_fmin(best5[p], cur5[p]);
+                best5[p] = min_f64(best5[p], cur5[p]);
                 blk9[p] = cur9[p] < best9[p] ? c : blk9[p];
-                best9[p] = __builtin_fmin(best9[p], cur9[p]);
+                best9[p] = min_f64(best9[p], cur9[p]);
             }
         }
         __syncthreads();
@@ -688,7 +709,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
         else if (__ballot(c5 == V) != 0) { id = 5; mine = c5; myblk = blk5[p]; }
         else { id = 9; mine = c9; myblk = blk9[p]; }
         // smallest s with T_id(s) == V: every lane that holds V names the pass it
-        // first saw it in; 16 lanes re-evaluate that lane's 16 candidates of the pass
+        // first saw it in; 32 lanes re-evaluate that lane's 32 candidates of the pass
         unsigned long long holders = __ballot(mine == V);
         int first = 0x7FFFFFFF;
         while (holders != 0) {
@@ -745,7 +766,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 
 // ---------------------------------------------------------------- launch wrappers
 
-static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double);
+static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 32;
 
 hipError_t kernels_init()
 {
@@ -813,13 +834,14 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
 
     if (G.mask & (1u << 11)) {
         // a big table fills most of the LDS of a CU: one large workgroup, several blocks per lane
-        const bool big = tab_lds > 32768;
+        const size_t chain_lds = tab_lds + 32;      // one virtual interval and a sentinel more
+        const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
         const int nb = big ? 8 : 1;
         const int n_mchunks = (G.n_m + threads - 1) / threads;
         const int n_bgroups = (G.n_blk + nb - 1) / nb;
         hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * n_bgroups * n_mchunks),
-                           dim3(threads), tab_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
+                           dim3(threads), chain_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         const int rows = T.n_tables * G.n_m;
@@ -833,7 +855,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     }
 
     if (G.n_s >= 256) {
-        constexpr int GP = 8;
+        constexpr int GP = 6;
         const int n_groups = (G.n_P + GP - 1) / GP;
         const int waves = n_groups < SWEEP_S_MAX_WAVES ? n_groups : SWEEP_S_MAX_WAVES;
         const int n_ptiles = (n_groups + waves - 1) / waves;
