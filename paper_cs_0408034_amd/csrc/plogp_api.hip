@@ -88,6 +88,7 @@ struct plogp_grid {
         g.n_m = (int)n_m; g.n_P = (int)n_P; g.n_s = (int)n_s;
         g.n_blk = n_blk; g.last_terms = last_terms; g.cl_max = cl_max;
         g.s_cap = s_cap; g.mask = mask; g.n_ops = n_ops;
+        g.blk_is_prefix = n_blk > 32 ? 1 : 0;
         return g;
     }
     void free_scratch()

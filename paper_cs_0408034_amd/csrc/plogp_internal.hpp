@@ -39,6 +39,8 @@ struct DeviceGrid {
     uint64_t s_cap;
     uint32_t mask;
     int n_ops;
+    int blk_is_prefix;    // 1: a kernel turns the block totals into their exclusive prefix;
+                          // 0 (few blocks): the sweep adds the finished blocks itself
 };
 
 // Per-(tables, grid) scratch in device memory, all written and read by kernels.

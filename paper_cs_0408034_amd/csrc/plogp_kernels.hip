@@ -298,28 +298,36 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
         if (b >= G.n_blk)
             break;
         const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
-        const u64 wanted = G.blk_mask[b];   // bit r: some grid P needs the sum after r terms
+        u64 wanted = G.blk_mask[b];         // bit r: some grid P needs the sum after r terms
         int pi = G.blk_off[b];
         double run = 0.0;
-        for (int jj = 0; jj < nterms; ++jj) {
-            if ((wanted >> jj) & 1ull) {
-                part[(size_t)pi * n_m] = run;
-                ++pi;
+        int jj = 0;
+        for (;;) {
+            // run without any bookkeeping up to the next point where a sum is wanted
+            int hit = wanted != 0 ? __builtin_ctzll(wanted) : SUM_BLOCK;
+            if (hit > nterms)
+                hit = SUM_BLOCK;
+            const int stop = hit < nterms ? hit : nterms;
+#pragma unroll 4
+            for (; jj < stop; ++jj) {
+                while (d >= w) {            // crossed into the next interval
+                    d -= w;
+                    ++i;
+                    const double xa = X[i], xb = X[i + 1];
+                    const double2 ys = YS[i];
+                    w = xb - xa;
+                    yi = ys.x;
+                    si = ys.y;
+                }
+                run = run + __builtin_fma(si, d, yi);
+                d += md;
             }
-            while (d >= w) {                // crossed into the next interval
-                d -= w;
-                ++i;
-                const double xa = X[i], xb = X[i + 1];
-                const double2 ys = YS[i];
-                w = xb - xa;
-                yi = ys.x;
-                si = ys.y;
-            }
-            run = run + __builtin_fma(si, d, yi);
-            d += md;
-        }
-        if (nterms < SUM_BLOCK && ((wanted >> nterms) & 1ull))
+            if (hit == SUM_BLOCK)
+                break;
             part[(size_t)pi * n_m] = run;
+            ++pi;
+            wanted &= wanted - 1;
+        }
         if (nterms == SUM_BLOCK)
             tot[(size_t)b * n_m] = run;
     }
@@ -431,7 +439,15 @@ __device__ __forceinline__ Best decide_scatter(const DeviceGrid &G, const Scratc
     if (mask & (1u << 10)) consider(b, __builtin_fma(q, gm, L), 10, 0);
     if (mask & (1u << 11)) {
         const int blk = (int)((P - 1u) / SUM_BLOCK);
-        const double done = S.blk[((size_t)t * G.n_blk + blk) * n_m + mi];
+        const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
+        double done;
+        if (G.blk_is_prefix) {
+            done = tot[(size_t)blk * n_m];
+        } else {                       // few blocks: add the finished ones here, in ascending order
+            done = 0.0;
+            for (int b = 0; b < blk; ++b)
+                done = done + tot[(size_t)b * n_m];
+        }
         const double run = S.part[((size_t)t * G.n_P + pi) * n_m + mi];
         consider(b, __builtin_fma(q, L, done + run), 11, 0);
     }
@@ -837,17 +853,19 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const size_t chain_lds = tab_lds + 32;      // one virtual interval and a sentinel more
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
-        const int nb = big ? 8 : 1;
+        const int nb = big ? 2 : 1;
         const int n_mchunks = (G.n_m + threads - 1) / threads;
         const int n_bgroups = (G.n_blk + nb - 1) / nb;
         hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * n_bgroups * n_mchunks),
                            dim3(threads), chain_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
-        const int rows = T.n_tables * G.n_m;
-        hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, G,
-                           S, T.n_tables);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (G.blk_is_prefix) {
+            const int rows = T.n_tables * G.n_m;
+            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st,
+                               G, S, T.n_tables);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
         PLOGP_MARK(3);
     } else {
         PLOGP_MARK(2);
@@ -862,7 +880,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         hipLaunchKernelGGL(k_sweep_s<GP>, dim3((unsigned)T.n_tables * G.n_m * n_ptiles),
                            dim3(64 * waves), 0, st, T, G, S, d_out, n_ptiles);
     } else {
-        constexpr int PC = 8;
+        constexpr int PC = 4;
         const int n_mg = (G.n_m + 63) / 64;
         const int n_pc = (G.n_P + PC - 1) / PC;
         const long n_items = (long)T.n_tables * n_mg * n_pc;
