@@ -427,35 +427,33 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
     return b;
 }
 
-// Scatter: the three rows of Table 2.  Reads the two sums for (m index mi, P index pi).
-__device__ __forceinline__ Best decide_scatter(const DeviceGrid &G, const Scratch &S, int t, int mi,
-                                               int pi, uint32_t P, double q, int cli, double gm,
-                                               double L)
+// Scatter: the three rows of Table 2, given the two sums for this (m, P).
+__device__ __forceinline__ Best decide_scatter(uint32_t mask, double q, double cl, double gm,
+                                               double L, double s11, double s12)
 {
-    const uint32_t mask = G.mask;
-    const size_t n_m = (size_t)G.n_m;
-    const double cl = (double)cli;
     Best b = {INFINITY, 0u, 0xFFFFFFFFu};
     if (mask & (1u << 10)) consider(b, __builtin_fma(q, gm, L), 10, 0);
-    if (mask & (1u << 11)) {
-        const int blk = (int)((P - 1u) / SUM_BLOCK);
-        const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
-        double done;
-        if (G.blk_is_prefix) {
-            done = tot[(size_t)blk * n_m];
-        } else {                       // few blocks: add the finished ones here, in ascending order
-            done = 0.0;
-            for (int b = 0; b < blk; ++b)
-                done = done + tot[(size_t)b * n_m];
-        }
-        const double run = S.part[((size_t)t * G.n_P + pi) * n_m + mi];
-        consider(b, __builtin_fma(q, L, done + run), 11, 0);
-    }
-    if (mask & (1u << 12)) {
-        const double s12 = S.sum2[((size_t)t * (G.cl_max + 1) + cli) * n_m + mi];
-        consider(b, __builtin_fma(cl, L, s12), 12, 0);
-    }
+    if (mask & (1u << 11)) consider(b, __builtin_fma(q, L, s11), 11, 0);
+    if (mask & (1u << 12)) consider(b, __builtin_fma(cl, L, s12), 12, 0);
     return b;
+}
+
+// sum_{j=1}^{P-1} g(j m) for (m index mi, P index pi) from the block sums
+__device__ __forceinline__ double chain_sum_of(const DeviceGrid &G, const Scratch &S, int t, int mi,
+                                               int pi, uint32_t P)
+{
+    const size_t n_m = (size_t)G.n_m;
+    const int blk = (int)((P - 1u) / SUM_BLOCK);
+    const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
+    double done;
+    if (G.blk_is_prefix) {
+        done = tot[(size_t)blk * n_m];
+    } else {                           // few blocks: add the finished ones here, in ascending order
+        done = 0.0;
+        for (int b = 0; b < blk; ++b)
+            done = done + tot[(size_t)b * n_m];
+    }
+    return done + S.part[((size_t)t * G.n_P + pi) * n_m + mi];
 }
 
 // Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
@@ -515,16 +513,24 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         b2[p] = b5[p] = b9[p] = INFINITY;
         i2[p] = i5[p] = i9[p] = 0;
     }
-    if (mask & 0x224u) {
+    if ((mask & 0x224u) && G.n_s > 0) {
         const double *gs = S.gs + (size_t)t * G.n_s;
+        // the per-candidate scalars of the next iteration are fetched while this one computes
+        u64 sv_n = G.s[0];
+        double rcp_n = S.rcp[0], gs_n = gs[0];
         for (int si = 0; si < G.n_s; ++si) {
-            const u64 sv = G.s[si];
+            const u64 sv = sv_n;
+            const double rcp_s = rcp_n, gsv = gs_n;
+            const int nx = si + 1 < G.n_s ? si + 1 : si;
+            sv_n = G.s[nx];
+            rcp_n = S.rcp[nx];
+            gs_n = gs[nx];
             const bool valid = sv <= lim;
             if (__ballot(valid) == 0)
                 break;                       // the candidates ascend: nothing further competes
             if (valid) {
                 double A, B, C;
-                segment_terms(md, (double)sv, S.rcp[si], gs[si], L, A, B, C);
+                segment_terms(md, (double)sv, rcp_s, gsv, L, A, B, C);
 #pragma unroll
                 for (int p = 0; p < PC; ++p) {
                     const double T2 = __builtin_fma(q[p], A, L);
@@ -542,26 +548,40 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
     }
     if (!active)
         return;
-    const double gm = S.gm[(size_t)t * G.n_m + mi];
+    const size_t n_m = (size_t)G.n_m;
+    const double gm = S.gm[(size_t)t * n_m + mi];
     const double g1 = S.g1[t];
-    const size_t plane = (size_t)G.n_m * G.n_P;
+    const size_t plane = n_m * G.n_P;
+
+    // everything the PC cells read is fetched before the first of them is stored
+    double s11[PC], s12[PC];
+    uint32_t s2[PC], s5[PC], s9[PC];
+#pragma unroll
+    for (int p = 0; p < PC; ++p) {
+        const int pi = pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1;
+        s11[p] = s12[p] = 0.0;
+        if (mask & (1u << 11))
+            s11[p] = chain_sum_of(G, S, t, mi, pi, Pv[p]);
+        if (mask & (1u << 12))
+            s12[p] = S.sum2[((size_t)t * (G.cl_max + 1) + ceil_log2(Pv[p])) * n_m + mi];
+        s2[p] = b2[p] < INFINITY ? (uint32_t)G.s[i2[p]] : 0u;
+        s5[p] = b5[p] < INFINITY ? (uint32_t)G.s[i5[p]] : 0u;
+        s9[p] = b9[p] < INFINITY ? (uint32_t)G.s[i9[p]] : 0u;
+    }
 #pragma unroll
     for (int p = 0; p < PC; ++p) {
         const int pi = pc * PC + p;
         if (pi >= G.n_P)
             break;
         plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + pi;
-        const int cli = ceil_log2(Pv[p]);
+        const double cl = (double)ceil_log2(Pv[p]);
         if (mask & 0x3FFu) {
-            const uint32_t s2 = b2[p] < INFINITY ? (uint32_t)G.s[i2[p]] : 0u;
-            const uint32_t s5 = b5[p] < INFINITY ? (uint32_t)G.s[i5[p]] : 0u;
-            const uint32_t s9 = b9[p] < INFINITY ? (uint32_t)G.s[i9[p]] : 0u;
-            store_cell(o, decide_bcast(mask, q[p], fl[p], (double)cli, gm, L, g1, b2[p], s2, b5[p],
-                                       s5, b9[p], s9));
+            store_cell(o, decide_bcast(mask, q[p], fl[p], cl, gm, L, g1, b2[p], s2[p], b5[p], s5[p],
+                                       b9[p], s9[p]));
             o += plane;
         }
         if (mask & 0x1C00u)
-            store_cell(o, decide_scatter(G, S, t, mi, pi, Pv[p], q[p], cli, gm, L));
+            store_cell(o, decide_scatter(mask, q[p], cl, gm, L, s11[p], s12[p]));
     }
 }
 
@@ -773,8 +793,12 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                                    segId == 9 ? segT : INFINITY, segS));
         o += plane;
     }
-    if (mask & 0x1C00u)
-        store_cell(o, decide_scatter(G, S, t, mi, pi, Pv, qv, cli, gm, L));
+    if (mask & 0x1C00u) {
+        const double s11 = (mask & (1u << 11)) ? chain_sum_of(G, S, t, mi, pi, Pv) : 0.0;
+        const double s12 = (mask & (1u << 12))
+            ? S.sum2[((size_t)t * (G.cl_max + 1) + cli) * (size_t)G.n_m + mi] : 0.0;
+        store_cell(o, decide_scatter(mask, qv, (double)cli, gm, L, s11, s12));
+    }
 }
 
 
