@@ -345,8 +345,10 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
     if (!t || !g || !d_out) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
-    int rc = ensure_scratch(g, t->n_tables);
-    if (rc != PLOGP_OK) return rc;
+    if (!use_fused_path(t->view(), g->view())) {
+        int rc = ensure_scratch(g, t->n_tables);
+        if (rc != PLOGP_OK) return rc;
+    }
     HIP_TRY(launch_tune(t->view(), g->view(), g->scratch,
                         reinterpret_cast<plogp_cell_dev *>(d_out), (hipStream_t)stream));
     return PLOGP_OK;
@@ -358,8 +360,10 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     if (!t || !g || !d_out || !stage_ms_out) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
-    int rc = ensure_scratch(g, t->n_tables);
-    if (rc != PLOGP_OK) return rc;
+    if (!use_fused_path(t->view(), g->view())) {
+        int rc = ensure_scratch(g, t->n_tables);
+        if (rc != PLOGP_OK) return rc;
+    }
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     hipError_t e = hipSuccess;
     for (int i = 0; i < 5 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);

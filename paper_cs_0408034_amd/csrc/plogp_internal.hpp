@@ -71,5 +71,6 @@ hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uin
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
                        plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr);
 hipError_t kernels_init();
+bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
 
 }  // namespace plogp

@@ -414,15 +414,21 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
     const double R = __builtin_fma(3.0, L, 2.0 * g1);   // rendezvous: 2 g(1) + 3 L
     const double clL = cl * L;
     Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+    // When R >= L (always, unless g(1) rounds below zero) a rendezvous row is never
+    // below its plain twin, because rounding is monotone; with the twin enabled
+    // (lower id: it also wins ties) the rendezvous row cannot be chosen and is not
+    // evaluated.
+    const bool twin_wins = R >= L;
     if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
-    if (mask & (1u << 1)) consider(b, __builtin_fma(q, gm, R), 1, 0);
+    if ((mask & 2u) && !((mask & 1u) && twin_wins)) consider(b, __builtin_fma(q, gm, R), 1, 0);
     if (mask & (1u << 2)) consider(b, t2, 2, s2);
     if (mask & (1u << 3)) consider(b, q * (gm + L), 3, 0);
-    if (mask & (1u << 4)) consider(b, q * (gm + R), 4, 0);
+    if ((mask & 0x10u) && !((mask & 8u) && twin_wins)) consider(b, q * (gm + R), 4, 0);
     if (mask & (1u << 5)) consider(b, t5, 5, s5);
     if (mask & (1u << 6)) consider(b, cl * __builtin_fma(2.0, gm, L), 6, 0);
     if (mask & (1u << 7)) consider(b, __builtin_fma(fl, gm, clL), 7, 0);
-    if (mask & (1u << 8)) consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
+    if ((mask & 0x100u) && !((mask & 0x80u) && twin_wins))
+        consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
     if (mask & (1u << 9)) consider(b, t9, 9, s9);
     return b;
 }
@@ -802,6 +808,175 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 }
 
 
+// ---- whole path in one kernel, for batches of many tables -----------------
+//
+// One workgroup per (table, 256 message sizes), one lane per m, everything of
+// that (table, m) row in the lane: g(m), A and B for every candidate (kept in
+// registers), the Scatter-chain sum walked along j while P ascends (the sum for
+// a P is ready exactly when its cells are written), the binomial sum grown term
+// by term with ceil(log2 P).  P and s are wave-uniform loops.  No scratch in
+// global memory is read or written: the only HBM traffic is the tables in and
+// the decision table out.  Used when there are enough (table, m) rows to fill
+// the chip, at most FUSED_NS candidates and few blocks of the chain sum.
+constexpr int FUSED_NS = 24;
+
+__device__ __forceinline__ double lds_gap(const double *X, const double2 *YS, int n, double z)
+{
+    // X[0] = 0 (virtual interval), X[1..n] = samples, X[n+1] = +inf
+    const int i = last_not_above(X + 1, n, z) + (z >= X[1] ? 1 : 0);
+    const double2 ys = YS[i];
+    return __builtin_fma(ys.y, z - X[i], ys.x);
+}
+
+__global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plogp_cell_dev *out,
+                                               int n_mchunks)
+{
+    extern __shared__ __align__(16) double fused_lds[];
+    __shared__ double sS[FUSED_NS], sG[FUSED_NS], sR[FUSED_NS];
+    __shared__ double sG1;
+    const int t = blockIdx.x / n_mchunks, mc = blockIdx.x % n_mchunks;
+    const int n = T.n;
+    double2 *YS = reinterpret_cast<double2 *>(fused_lds);
+    double *X = fused_lds + 2 * (n + 1);
+    const double L = T.L[t];
+    {
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            X[i + 1] = gx[i];
+            YS[i + 1] = make_double2(gy[i], interval_slope(gx, gy, n, i));
+        }
+        if (threadIdx.x == 0) {
+            X[0] = 0.0;
+            X[n + 1] = INFINITY;
+            YS[0] = make_double2(gy[0], 0.0);
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < G.n_s) {
+        const double sd = (double)G.s[threadIdx.x];
+        sS[threadIdx.x] = sd;
+        sG[threadIdx.x] = lds_gap(X, YS, n, sd);
+        sR[threadIdx.x] = 1.0 / sd;
+    }
+    if (threadIdx.x == 0)
+        sG1 = lds_gap(X, YS, n, 1.0);
+    __syncthreads();
+
+    const int mi = mc * blockDim.x + threadIdx.x;
+    const bool active = mi < G.n_m;
+    const u64 m = G.m[active ? mi : 0];
+    const double md = (double)m;
+    const u64 lim = active ? (m < G.s_cap ? m : G.s_cap) : 0;
+    const uint32_t mask = G.mask;
+    const double g1 = sG1;
+    const double gm = lds_gap(X, YS, n, md);
+
+    // segment terms of this m for every candidate; +inf where s > min(m, cap)
+    double A[FUSED_NS], B[FUSED_NS];
+    int wave_nv = 0;                       // candidates that compete for some lane of the wave
+#pragma unroll
+    for (int si = 0; si < FUSED_NS; ++si) {
+        A[si] = B[si] = INFINITY;
+        if (si < G.n_s) {
+            const bool valid = (u64)sS[si] <= lim;
+            if (valid) {
+                double C;
+                segment_terms(md, sS[si], sR[si], sG[si], L, A[si], B[si], C);
+            }
+            if (__ballot(valid) != 0)
+                wave_nv = si + 1;
+        }
+    }
+
+    // Scatter-chain walk: interval of z = m, d = z - start, w = width
+    int iv = last_not_above(X + 1, n, md) + (md >= X[1] ? 1 : 0);
+    double d = md - X[iv], w = X[iv + 1] - X[iv];
+    double yi = YS[iv].x, sl = YS[iv].y;
+    double run = 0.0, done = 0.0;
+    int j_done = 0;
+    // Scatter-binomial sum grown with ceil(log2 P)
+    double s12 = 0.0;
+    int cl_done = 0;
+
+    const size_t plane = (size_t)G.n_m * G.n_P;
+    plogp_cell_dev *o_row = out + (size_t)t * G.n_ops * plane + (size_t)(active ? mi : 0) * G.n_P;
+    const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
+
+    uint32_t P_next = G.P[0];
+    for (int pi = 0; pi < G.n_P; ++pi) {
+        const uint32_t P = P_next;
+        P_next = G.P[pi + 1 < G.n_P ? pi + 1 : pi];
+        const double q = (double)(P - 1);
+        const int fli = floor_log2(P), cli = ceil_log2(P);
+        const double fl = (double)fli, cl = (double)cli;
+        const double clL = cl * L;
+
+        if (want_chain) {
+            const int target = (int)(P - 1);
+            while (j_done < target) {
+                const int block_end = (j_done / SUM_BLOCK + 1) * SUM_BLOCK;
+                const int stop = target < block_end ? target : block_end;
+#pragma unroll 4
+                for (; j_done < stop; ++j_done) {
+                    while (d >= w) {
+                        d -= w;
+                        ++iv;
+                        const double xa = X[iv], xb = X[iv + 1];
+                        const double2 ys = YS[iv];
+                        w = xb - xa;
+                        yi = ys.x;
+                        sl = ys.y;
+                    }
+                    run = run + __builtin_fma(sl, d, yi);
+                    d += md;
+                }
+                if (j_done % SUM_BLOCK == 0) {
+                    done = done + run;
+                    run = 0.0;
+                }
+            }
+        }
+        if (want_binom) {
+            while (cl_done < cli) {
+                s12 = s12 + lds_gap(X, YS, n, (double)(m << cl_done));
+                ++cl_done;
+            }
+        }
+
+        double b2 = INFINITY, b5 = INFINITY, b9 = INFINITY;
+        int i2 = 0, i5 = 0, i9 = 0;
+        if (mask & 0x224u) {
+#pragma unroll
+            for (int si = 0; si < FUSED_NS; ++si) {
+                if (si < wave_nv) {
+                    const double C = sG[si] + L;
+                    const double T2 = __builtin_fma(q, A[si], L);
+                    const double T5 = __builtin_fma(q, C, B[si]);
+                    const double T9 = __builtin_fma(fl, A[si], clL);
+                    i2 = T2 < b2 ? si : i2;
+                    b2 = min_f64(b2, T2);
+                    i5 = T5 < b5 ? si : i5;
+                    b5 = min_f64(b5, T5);
+                    i9 = T9 < b9 ? si : i9;
+                    b9 = min_f64(b9, T9);
+                }
+            }
+        }
+        if (active) {
+            plogp_cell_dev *o = o_row + pi;
+            if (mask & 0x3FFu) {
+                const uint32_t s2 = b2 < INFINITY ? (uint32_t)sS[i2] : 0u;
+                const uint32_t s5 = b5 < INFINITY ? (uint32_t)sS[i5] : 0u;
+                const uint32_t s9 = b9 < INFINITY ? (uint32_t)sS[i9] : 0u;
+                store_cell(o, decide_bcast(mask, q, fl, cl, gm, L, g1, b2, s2, b5, s5, b9, s9));
+                o += plane;
+            }
+            if (mask & 0x1C00u)
+                store_cell(o, decide_scatter(mask, q, cl, gm, L, done + run, s12));
+        }
+    }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launch wrappers
@@ -821,6 +996,9 @@ hipError_t kernels_init()
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     return e;
 }
@@ -855,6 +1033,14 @@ hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uin
     return hipGetLastError();
 }
 
+// Batches with enough (table, m) rows to fill the chip, few candidates and a short
+// chain sum go through the single fused kernel; everything else through the
+// staged kernels.
+bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
+{
+    return (long)T.n_tables * G.n_m >= 8192 && G.n_s <= FUSED_NS && G.n_blk <= 32;
+}
+
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
                        plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev)
 {
@@ -866,6 +1052,17 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     } while (0)
 
     PLOGP_MARK(0);
+    if (use_fused_path(T, G)) {
+        PLOGP_MARK(1);
+        PLOGP_MARK(2);
+        PLOGP_MARK(3);
+        const int n_mchunks = (G.n_m + 255) / 256;
+        hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256), tab_lds + 32,
+                           st, T, G, d_out, n_mchunks);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        PLOGP_MARK(4);
+        return hipSuccess;
+    }
     const int n_chunks = (G.n_m + 255) / 256;
     hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
                        S, n_chunks);

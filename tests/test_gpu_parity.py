@@ -245,6 +245,20 @@ def test_batch_of_tables_matches_one_by_one():
     assert assert_tables_equal(gpu_tune(wl), want, "cfg4 x37")
 
 
+def test_batch_path_ragged_chunk_many_blocks_and_masks():
+    # enough (table, m) rows for the single-kernel batch path: 300 m (one full chunk of
+    # 256 and a tail of 44), 24 candidates, P up to 2048 (32 blocks of the chain sum)
+    base = make_workload(4, n_tables=30, table_offset=500)
+    m = np.sort(np.random.default_rng(3).choice(make_workload(4, n_m=400).m, size=300))
+    P = np.array([2, 3, 63, 64, 65, 66, 128, 129, 130, 1000, 1985, 2047, 2048], dtype=np.uint32)
+    s = np.array([8 << j for j in range(24)], dtype=np.uint64)
+    for mask, cap in ((ALL_STRATEGIES_MASK, NO_CAP), (0x3FF, 1 << 12), (0x1C00, NO_CAP),
+                      ((1 << 1) | (1 << 4) | (1 << 8) | (1 << 11), NO_CAP), (1 << 9, NO_CAP)):
+        wl = Workload("batch", base.sizes, base.gaps, base.L, m, P, s, cap, mask)
+        want, _ = oracle.tune_workload(wl)
+        assert assert_tables_equal(gpu_tune(wl), want, "batch path mask %x" % mask)
+
+
 def test_output_too_small_and_misaligned_are_refused():
     torch = torch_cuda()
     plogp = _plogp()
