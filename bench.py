@@ -138,11 +138,19 @@ def run_cpu(cfg, wl):
             "effective_evals_per_s": c["effective_evals"] / dt, "cells_per_s": c["cells"] / dt}
 
 
-def bench_config(cfg, steps, warmup, with_cpu):
+def bench_config(cfg, steps, warmup, with_cpu, mask=None):
     from plogp_workloads import make_workload
     wl = make_workload(cfg)
+    if mask is not None:
+        wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
     ms, stage_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
+        # the single-kernel batch path did every stage inside one launch
+        work = {"terms": {"flops": 0, "bytes": 0}, "chain_blocks": {"flops": 0, "bytes": 0},
+                "chain_prefix": {"flops": 0, "bytes": 0},
+                "sweep": {"flops": sum(w["flops"] for w in work.values()),
+                          "bytes": sum(w["bytes"] for w in work.values())}}
     dominant = max(STAGES, key=lambda k: stage_ms[k])
     res = {
         "workload": describe(wl),
@@ -169,6 +177,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="headline workload (1..5)")
     ap.add_argument("--extra", type=str, default="3,4,5", help="other configs to time, or 'none'")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--mask", type=lambda v: int(v, 0), default=None,
+                    help="strategy mask override (for profiling parts of the path)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no inter-GPU path exists); use --gpus 1")
@@ -177,7 +187,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
 
-    head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu)
+    head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu, args.mask)
     line = {
         "metric": METRIC,
         "value": head["value"],
