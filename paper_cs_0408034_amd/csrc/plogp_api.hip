@@ -376,7 +376,9 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     for (int i = 0; i < 5; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     if (e != hipSuccess) return device_error(e);
-    const bool chain = (g->mask & (1u << 11)) != 0;
+    const bool fused = use_fused_path(t->view(), g->view());
+    const bool chain = (g->mask & (1u << 11)) != 0 && !fused;
+    if (fused) ms[0] = 0.f;
     stage_ms_out[0] = ms[0];
     stage_ms_out[1] = chain ? ms[1] : 0.f;
     stage_ms_out[2] = chain ? ms[2] : 0.f;

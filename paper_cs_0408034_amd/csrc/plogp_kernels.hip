@@ -811,19 +811,28 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 // ---- whole path in one kernel, for batches of many tables -----------------
 //
 // One workgroup per (table, 256 message sizes), one lane per m, everything of
-// that (table, m) row in the lane: g(m), A and B for every candidate (kept in
-// registers), the Scatter-chain sum walked along j while P ascends (the sum for
-// a P is ready exactly when its cells are written), the binomial sum grown term
-// by term with ceil(log2 P).  P and s are wave-uniform loops.  No scratch in
-// global memory is read or written: the only HBM traffic is the tables in and
-// the decision table out.  Used when there are enough (table, m) rows to fill
-// the chip, at most FUSED_NS candidates and few blocks of the chain sum.
+// that (table, m) row in the lane: g(m), the segment terms, the Scatter-chain sum walked along j while P ascends (the sum
+// for a P is ready exactly when its cells are written), the binomial sum grown
+// term by term with ceil(log2 P).  P and s are wave-uniform loops; P goes in
+// chunks of FUSED_PC so that A and B are formed once per (m, s, chunk).  The
+// cells of a chunk are transposed through LDS so that a store instruction writes
+// 64-byte runs instead of 64 separate records.  No scratch in global memory:
+// the only HBM traffic is the tables in and the decision table out.  Used when
+// there are enough (table, m) rows to fill the chip, at most FUSED_NS candidates
+// and few blocks of the chain sum.
 constexpr int FUSED_NS = 24;
+constexpr int FUSED_PC = 4;
+
+// X[0] = 0 (virtual interval below the first sample, gap y_0, slope 0),
+// X[1..n] = samples, X[n+1] = X[n+2] = +inf; YS[i] = {gap, slope} of interval i.
+__device__ __forceinline__ int lds_interval(const double *X, int n, double z)
+{
+    return last_not_above(X + 1, n, z) + (z >= X[1] ? 1 : 0);
+}
 
 __device__ __forceinline__ double lds_gap(const double *X, const double2 *YS, int n, double z)
 {
-    // X[0] = 0 (virtual interval), X[1..n] = samples, X[n+1] = +inf
-    const int i = last_not_above(X + 1, n, z) + (z >= X[1] ? 1 : 0);
+    const int i = lds_interval(X, n, z);
     const double2 ys = YS[i];
     return __builtin_fma(ys.y, z - X[i], ys.x);
 }
@@ -834,10 +843,15 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     extern __shared__ __align__(16) double fused_lds[];
     __shared__ double sS[FUSED_NS], sG[FUSED_NS], sR[FUSED_NS];
     __shared__ double sG1;
+    // per wave and plane: 64 rows x FUSED_PC cells, rows padded by one cell
+    __shared__ uint4 stage[4][2][64 * (FUSED_PC + 1)];
+
     const int t = blockIdx.x / n_mchunks, mc = blockIdx.x % n_mchunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n = T.n;
-    double2 *YS = reinterpret_cast<double2 *>(fused_lds);
-    double *X = fused_lds + 2 * (n + 1);
+    double2 *YS = reinterpret_cast<double2 *>(fused_lds);      // n + 2 entries
+    double *X = fused_lds + 2 * (n + 2);                       // n + 3 entries
     const double L = T.L[t];
     {
         const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
@@ -848,14 +862,17 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
         if (threadIdx.x == 0) {
             X[0] = 0.0;
             X[n + 1] = INFINITY;
+            X[n + 2] = INFINITY;
             YS[0] = make_double2(gy[0], 0.0);
+            YS[n + 1] = make_double2(0.0, 0.0);
         }
     }
     __syncthreads();
     if ((int)threadIdx.x < G.n_s) {
         const double sd = (double)G.s[threadIdx.x];
+        const double g = lds_gap(X, YS, n, sd);
         sS[threadIdx.x] = sd;
-        sG[threadIdx.x] = lds_gap(X, YS, n, sd);
+        sG[threadIdx.x] = g;
         sR[threadIdx.x] = 1.0 / sd;
     }
     if (threadIdx.x == 0)
@@ -871,109 +888,150 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     const double g1 = sG1;
     const double gm = lds_gap(X, YS, n, md);
 
-    // segment terms of this m for every candidate; +inf where s > min(m, cap)
-    double A[FUSED_NS], B[FUSED_NS];
-    int wave_nv = 0;                       // candidates that compete for some lane of the wave
-#pragma unroll
-    for (int si = 0; si < FUSED_NS; ++si) {
-        A[si] = B[si] = INFINITY;
-        if (si < G.n_s) {
-            const bool valid = (u64)sS[si] <= lim;
-            if (valid) {
-                double C;
-                segment_terms(md, sS[si], sR[si], sG[si], L, A[si], B[si], C);
-            }
-            if (__ballot(valid) != 0)
-                wave_nv = si + 1;
-        }
-    }
+    // candidates that compete for some lane of the wave (they ascend)
+    int wave_nv = 0;
+    for (int si = 0; si < G.n_s; ++si)
+        if (__ballot((u64)sS[si] <= lim) != 0)
+            wave_nv = si + 1;
 
-    // Scatter-chain walk: interval of z = m, d = z - start, w = width
-    int iv = last_not_above(X + 1, n, md) + (md >= X[1] ? 1 : 0);
-    double d = md - X[iv], w = X[iv + 1] - X[iv];
+    // Scatter-chain walk.  Current interval: d = z - start, w = width, {yi, sl};
+    // the next interval's end and {gap, slope} are fetched one crossing ahead.
+    int iv = lds_interval(X, n, md);
+    double xb = X[iv + 1];
+    double d = md - X[iv], w = xb - X[iv];
     double yi = YS[iv].x, sl = YS[iv].y;
+    double nxb = X[iv + 2];
+    double2 nys = YS[iv + 1];
     double run = 0.0, done = 0.0;
     int j_done = 0;
-    // Scatter-binomial sum grown with ceil(log2 P)
-    double s12 = 0.0;
+    double s12 = 0.0;                      // Scatter-binomial sum, grown with ceil(log2 P)
     int cl_done = 0;
 
     const size_t plane = (size_t)G.n_m * G.n_P;
-    plogp_cell_dev *o_row = out + (size_t)t * G.n_ops * plane + (size_t)(active ? mi : 0) * G.n_P;
+    plogp_cell_dev *o_tab = out + (size_t)t * G.n_ops * plane;
     const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
+    const bool has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
+    const int row0 = mc * (int)blockDim.x + wave * 64;         // first m index of this wave
 
-    uint32_t P_next = G.P[0];
-    for (int pi = 0; pi < G.n_P; ++pi) {
-        const uint32_t P = P_next;
-        P_next = G.P[pi + 1 < G.n_P ? pi + 1 : pi];
-        const double q = (double)(P - 1);
-        const int fli = floor_log2(P), cli = ceil_log2(P);
-        const double fl = (double)fli, cl = (double)cli;
-        const double clL = cl * L;
-
-        if (want_chain) {
-            const int target = (int)(P - 1);
-            while (j_done < target) {
-                const int block_end = (j_done / SUM_BLOCK + 1) * SUM_BLOCK;
-                const int stop = target < block_end ? target : block_end;
-#pragma unroll 4
-                for (; j_done < stop; ++j_done) {
-                    while (d >= w) {
-                        d -= w;
-                        ++iv;
-                        const double xa = X[iv], xb = X[iv + 1];
-                        const double2 ys = YS[iv];
-                        w = xb - xa;
-                        yi = ys.x;
-                        sl = ys.y;
-                    }
-                    run = run + __builtin_fma(sl, d, yi);
-                    d += md;
-                }
-                if (j_done % SUM_BLOCK == 0) {
-                    done = done + run;
-                    run = 0.0;
-                }
-            }
-        }
-        if (want_binom) {
-            while (cl_done < cli) {
-                s12 = s12 + lds_gap(X, YS, n, (double)(m << cl_done));
-                ++cl_done;
-            }
-        }
-
-        double b2 = INFINITY, b5 = INFINITY, b9 = INFINITY;
-        int i2 = 0, i5 = 0, i9 = 0;
-        if (mask & 0x224u) {
+    for (int p0 = 0; p0 < G.n_P; p0 += FUSED_PC) {
+        uint32_t Pv[FUSED_PC];
+        double s11v[FUSED_PC], s12v[FUSED_PC];
 #pragma unroll
-            for (int si = 0; si < FUSED_NS; ++si) {
-                if (si < wave_nv) {
-                    const double C = sG[si] + L;
-                    const double T2 = __builtin_fma(q, A[si], L);
-                    const double T5 = __builtin_fma(q, C, B[si]);
-                    const double T9 = __builtin_fma(fl, A[si], clL);
-                    i2 = T2 < b2 ? si : i2;
-                    b2 = min_f64(b2, T2);
-                    i5 = T5 < b5 ? si : i5;
-                    b5 = min_f64(b5, T5);
-                    i9 = T9 < b9 ? si : i9;
-                    b9 = min_f64(b9, T9);
+        for (int p = 0; p < FUSED_PC; ++p) {
+            const int pi = p0 + p < G.n_P ? p0 + p : G.n_P - 1;
+            const uint32_t P = G.P[pi];
+            Pv[p] = P;
+            if (want_chain) {
+                const int target = (int)(P - 1);
+                while (j_done < target) {
+                    const int block_end = (j_done / SUM_BLOCK + 1) * SUM_BLOCK;
+                    const int stop = target < block_end ? target : block_end;
+#pragma unroll 4
+                    for (; j_done < stop; ++j_done) {
+                        while (d >= w) {                       // crossed into the next interval
+                            d -= w;
+                            w = nxb - xb;
+                            yi = nys.x;
+                            sl = nys.y;
+                            xb = nxb;
+                            ++iv;
+                            nxb = X[iv + 2];
+                            nys = YS[iv + 1];
+                        }
+                        run = run + __builtin_fma(sl, d, yi);
+                        d += md;
+                    }
+                    if (j_done % SUM_BLOCK == 0) {
+                        done = done + run;
+                        run = 0.0;
+                    }
+                }
+            }
+            s11v[p] = done + run;
+            if (want_binom) {
+                const int cli = ceil_log2(P);
+                while (cl_done < cli) {
+                    s12 = s12 + lds_gap(X, YS, n, (double)(m << cl_done));
+                    ++cl_done;
+                }
+            }
+            s12v[p] = s12;
+        }
+
+        double q[FUSED_PC], fl[FUSED_PC], clL[FUSED_PC];
+        double b2[FUSED_PC], b5[FUSED_PC], b9[FUSED_PC];
+        int i2[FUSED_PC], i5[FUSED_PC], i9[FUSED_PC];
+#pragma unroll
+        for (int p = 0; p < FUSED_PC; ++p) {
+            q[p] = (double)(Pv[p] - 1);
+            fl[p] = (double)floor_log2(Pv[p]);
+            clL[p] = (double)ceil_log2(Pv[p]) * L;
+            b2[p] = b5[p] = b9[p] = INFINITY;
+            i2[p] = i5[p] = i9[p] = 0;
+        }
+        if (mask & 0x224u) {
+            for (int si = 0; si < wave_nv; ++si) {             // wave-uniform
+                const double sd = sS[si];
+                if ((u64)sd <= lim) {                          // this lane's m admits s
+                    double A, B, C;
+                    segment_terms(md, sd, sR[si], sG[si], L, A, B, C);
+#pragma unroll
+                    for (int p = 0; p < FUSED_PC; ++p) {
+                        const double T2 = __builtin_fma(q[p], A, L);
+                        const double T5 = __builtin_fma(q[p], C, B);
+                        const double T9 = __builtin_fma(fl[p], A, clL[p]);
+                        i2[p] = T2 < b2[p] ? si : i2[p];
+                        b2[p] = min_f64(b2[p], T2);
+                        i5[p] = T5 < b5[p] ? si : i5[p];
+                        b5[p] = min_f64(b5[p], T5);
+                        i9[p] = T9 < b9[p] ? si : i9[p];
+                        b9[p] = min_f64(b9[p], T9);
+                    }
                 }
             }
         }
-        if (active) {
-            plogp_cell_dev *o = o_row + pi;
-            if (mask & 0x3FFu) {
-                const uint32_t s2 = b2 < INFINITY ? (uint32_t)sS[i2] : 0u;
-                const uint32_t s5 = b5 < INFINITY ? (uint32_t)sS[i5] : 0u;
-                const uint32_t s9 = b9 < INFINITY ? (uint32_t)sS[i9] : 0u;
-                store_cell(o, decide_bcast(mask, q, fl, cl, gm, L, g1, b2, s2, b5, s5, b9, s9));
-                o += plane;
+        // the chunk's cells go to LDS as [row][cell], then out as 64-byte runs
+#pragma unroll
+        for (int p = 0; p < FUSED_PC; ++p) {
+            const double cl = (double)ceil_log2(Pv[p]);
+            union { plogp_cell_dev c; uint4 v; } u;
+            if (has_b) {
+                const uint32_t s2 = b2[p] < INFINITY ? (uint32_t)sS[i2[p]] : 0u;
+                const uint32_t s5 = b5[p] < INFINITY ? (uint32_t)sS[i5[p]] : 0u;
+                const uint32_t s9 = b9[p] < INFINITY ? (uint32_t)sS[i9[p]] : 0u;
+                const Best r = decide_bcast(mask, q[p], fl[p], cl, gm, L, g1, b2[p], s2, b5[p], s5,
+                                            b9[p], s9);
+                u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
+                stage[wave][0][lane * (FUSED_PC + 1) + p] = u.v;
             }
-            if (mask & 0x1C00u)
-                store_cell(o, decide_scatter(mask, q, cl, gm, L, done + run, s12));
+            if (has_s) {
+                const Best r = decide_scatter(mask, q[p], cl, gm, L, s11v[p], s12v[p]);
+                u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
+                stage[wave][1][lane * (FUSED_PC + 1) + p] = u.v;
+            }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        {
+            const int pl = lane % FUSED_PC;                    // cell within the run
+            const int pi = p0 + pl;
+#pragma unroll
+            for (int it = 0; it < FUSED_PC; ++it) {
+                const int row = it * (64 / FUSED_PC) + lane / FUSED_PC;
+                const int rmi = row0 + row;
+                if (rmi < G.n_m && pi < G.n_P) {
+                    plogp_cell_dev *o = o_tab + (size_t)rmi * G.n_P + pi;
+                    if (has_b) {
+                        *reinterpret_cast<uint4 *>(o) = stage[wave][0][row * (FUSED_PC + 1) + pl];
+                        o += plane;
+                    }
+                    if (has_s)
+                        *reinterpret_cast<uint4 *>(o) = stage[wave][1][row * (FUSED_PC + 1) + pl];
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -981,7 +1039,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
 
 // ---------------------------------------------------------------- launch wrappers
 
-static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 32;
+static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 64;
 
 hipError_t kernels_init()
 {
@@ -1057,7 +1115,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(2);
         PLOGP_MARK(3);
         const int n_mchunks = (G.n_m + 255) / 256;
-        hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256), tab_lds + 32,
+        hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256), tab_lds + 64,
                            st, T, G, d_out, n_mchunks);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(4);
