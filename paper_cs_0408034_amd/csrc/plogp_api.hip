@@ -78,8 +78,8 @@ struct plogp_grid {
     int *d_blk_off = nullptr;
     unsigned long long *d_blk_mask = nullptr;
     // scratch, sized for scratch_tables tables
-    size_t scratch_tables = 0;
-    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    size_t scratch_tables = 0, scratch_samples = 0;
+    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 
     DeviceGrid view() const
     {
@@ -94,12 +94,13 @@ struct plogp_grid {
     void free_scratch()
     {
         double **all[] = {&scratch.g1, &scratch.gs, &scratch.gm, &scratch.sum2, &scratch.blk,
-                          &scratch.part, &scratch.rcp};
+                          &scratch.part, &scratch.rcp, &scratch.cx, &scratch.cys};
         for (double **p : all) {
             if (*p) (void)hipFree(*p);
             *p = nullptr;
         }
         scratch_tables = 0;
+        scratch_samples = 0;
     }
     ~plogp_grid()
     {
@@ -311,9 +312,9 @@ size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g)
     return plogp_decision_table_cells(n_tables, g) * sizeof(plogp_cell);
 }
 
-static int ensure_scratch(plogp_grid *g, size_t n_tables)
+static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
 {
-    if (g->scratch_tables >= n_tables) return PLOGP_OK;
+    if (g->scratch_tables >= n_tables && g->scratch_samples >= n_samples) return PLOGP_OK;
     // a previous tune on this handle may still be running on some stream
     HIP_TRY(hipDeviceSynchronize());
     g->free_scratch();
@@ -326,6 +327,8 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables)
         {&g->scratch.blk, chain ? n_tables * (size_t)g->n_blk * g->n_m : 1},
         {&g->scratch.part, chain ? n_tables * g->n_m * g->n_P : 1},
         {&g->scratch.rcp, g->n_s ? g->n_s : 1},
+        {&g->scratch.cx, chain ? n_tables * (n_samples + 3) : 1},
+        {&g->scratch.cys, chain ? n_tables * (n_samples + 2) * 2 : 1},
     };
     for (auto &w : want) {
         hipError_t e = hipMalloc((void **)w.p, w.count * sizeof(double));
@@ -336,6 +339,7 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables)
         }
     }
     g->scratch_tables = n_tables;
+    g->scratch_samples = n_samples;
     return PLOGP_OK;
 }
 
@@ -346,7 +350,7 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
     if (!use_fused_path(t->view(), g->view())) {
-        int rc = ensure_scratch(g, t->n_tables);
+        int rc = ensure_scratch(g, t->n_tables, t->n);
         if (rc != PLOGP_OK) return rc;
     }
     HIP_TRY(launch_tune(t->view(), g->view(), g->scratch,
@@ -361,7 +365,7 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
     if (!use_fused_path(t->view(), g->view())) {
-        int rc = ensure_scratch(g, t->n_tables);
+        int rc = ensure_scratch(g, t->n_tables, t->n);
         if (rc != PLOGP_OK) return rc;
     }
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};

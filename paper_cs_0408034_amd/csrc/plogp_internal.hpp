@@ -52,6 +52,8 @@ struct Scratch {
     double *blk;      // [n_tables][n_blk][n_m]           block totals, then their exclusive prefix
     double *part;     // [n_tables][n_P][n_m]             in-block partial sums at the grid's P
     double *rcp;      // [n_s]                            1/s, rounded
+    double *cx;       // [n_tables][n+3]                  table as intervals: starts (0, samples, inf, inf)
+    double *cys;      // [n_tables][n+2][2]               {gap, slope} per interval
 };
 
 struct plogp_cell_dev {

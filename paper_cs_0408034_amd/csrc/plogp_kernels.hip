@@ -206,8 +206,26 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const double v = interval_slope(x, y, n, i);
         sl[i] = v;
-        if (chunk == 0)
+        if (chunk == 0) {
             T.slope[(size_t)t * n + i] = v;
+            if (G.mask & (1u << 11)) {      // the table as intervals, for the chain-sum walk
+                S.cx[(size_t)t * (n + 3) + i + 1] = x[i];
+                double *ys = S.cys + ((size_t)t * (n + 2) + i + 1) * 2;
+                ys[0] = y[i];
+                ys[1] = v;
+            }
+        }
+    }
+    if (chunk == 0 && threadIdx.x == 0 && (G.mask & (1u << 11))) {
+        double *cx = S.cx + (size_t)t * (n + 3);
+        double *ys = S.cys + (size_t)t * (n + 2) * 2;
+        cx[0] = 0.0;
+        cx[n + 1] = INFINITY;
+        cx[n + 2] = INFINITY;
+        ys[0] = y[0];
+        ys[1] = 0.0;
+        ys[2 * (n + 1)] = 0.0;
+        ys[2 * (n + 1) + 1] = 0.0;
     }
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
@@ -259,22 +277,20 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     const int bg = bid % n_bgroups;
     const int t = bid / n_bgroups;
     const int n = T.n;
-    // LDS: YS[0..n] = {gap, slope} per interval, X[0..n+1] = interval starts.
-    // Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0 (the clamp below
-    // the first sample); interval i+1 starts at sample i; X[n+1] = +inf.
+    // Table as intervals (written by k_terms): YS[0..n+1] = {gap, slope}, X[0..n+2] =
+    // interval starts.  Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0
+    // (the clamp below the first sample); interval i+1 starts at sample i;
+    // X[n+1] = X[n+2] = +inf.  Copied to LDS; each interval is fetched from there one
+    // crossing before it is needed.
     double2 *YS = reinterpret_cast<double2 *>(chain_lds);
-    double *X = chain_lds + 2 * (n + 1);
+    double *X = chain_lds + 2 * (n + 2);
     {
-        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
-        const double *gsl = T.slope + (size_t)t * n;
-        for (int i = threadIdx.x; i < n; i += blockDim.x) {
-            X[i + 1] = gx[i];
-            YS[i + 1] = make_double2(gy[i], gsl[i]);
-        }
-        if (threadIdx.x == 0) {
-            X[0] = 0.0;
-            X[n + 1] = INFINITY;
-            YS[0] = make_double2(gy[0], 0.0);
+        const double2 *gys = reinterpret_cast<const double2 *>(S.cys) + (size_t)t * (n + 2);
+        const double *gx = S.cx + (size_t)t * (n + 3);
+        for (int i = threadIdx.x; i < n + 3; i += blockDim.x) {
+            X[i] = gx[i];
+            if (i < n + 2)
+                YS[i] = gys[i];
         }
     }
     __syncthreads();
@@ -287,9 +303,12 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
     // interval of z0: number of samples not above z0 (0 = the virtual interval)
     int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
+    double xb = X[i + 1];
     double d = z0 - X[i];                 // d = z - start of the interval (exact)
-    double w = X[i + 1] - X[i];           // width of the interval
+    double w = xb - X[i];                 // width of the interval
     double yi = YS[i].x, si = YS[i].y;
+    double nxb = X[i + 2];                // the next interval, fetched ahead
+    double2 nys = YS[i + 1];
     const size_t n_m = (size_t)G.n_m;
     double *part = S.part + (size_t)t * G.n_P * n_m + mi;       // [P index][m]
     double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
@@ -312,12 +331,13 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
             for (; jj < stop; ++jj) {
                 while (d >= w) {            // crossed into the next interval
                     d -= w;
+                    w = nxb - xb;
+                    yi = nys.x;
+                    si = nys.y;
+                    xb = nxb;
                     ++i;
-                    const double xa = X[i], xb = X[i + 1];
-                    const double2 ys = YS[i];
-                    w = xb - xa;
-                    yi = ys.x;
-                    si = ys.y;
+                    nxb = X[i + 2];
+                    nys = YS[i + 1];
                 }
                 run = run + __builtin_fma(si, d, yi);
                 d += md;
@@ -1128,8 +1148,8 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     PLOGP_MARK(1);
 
     if (G.mask & (1u << 11)) {
-        // a big table fills most of the LDS of a CU: one large workgroup, several blocks per lane
-        const size_t chain_lds = tab_lds + 32;      // one virtual interval and a sentinel more
+        // a big table fills most of the LDS of a CU: one large workgroup per CU then
+        const size_t chain_lds = tab_lds + 64;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
         const int nb = big ? 2 : 1;
