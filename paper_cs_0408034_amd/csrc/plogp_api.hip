@@ -79,7 +79,7 @@ struct plogp_grid {
     unsigned long long *d_blk_mask = nullptr;
     // scratch, sized for scratch_tables tables
     size_t scratch_tables = 0, scratch_samples = 0;
-    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 
     DeviceGrid view() const
     {
@@ -99,6 +99,8 @@ struct plogp_grid {
             if (*p) (void)hipFree(*p);
             *p = nullptr;
         }
+        if (scratch.nv) (void)hipFree(scratch.nv);
+        scratch.nv = nullptr;
         scratch_tables = 0;
         scratch_samples = 0;
     }
@@ -332,6 +334,14 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
     };
     for (auto &w : want) {
         hipError_t e = hipMalloc((void **)w.p, w.count * sizeof(double));
+        if (e != hipSuccess) {
+            g->free_scratch();
+            if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }
+            return device_error(e);
+        }
+    }
+    {
+        hipError_t e = hipMalloc((void **)&g->scratch.nv, g->n_m * sizeof(int));
         if (e != hipSuccess) {
             g->free_scratch();
             if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }

@@ -54,6 +54,7 @@ struct Scratch {
     double *rcp;      // [n_s]                            1/s, rounded
     double *cx;       // [n_tables][n+3]                  table as intervals: starts (0, samples, inf, inf)
     double *cys;      // [n_tables][n+2][2]               {gap, slope} per interval
+    int *nv;          // [n_m]                            candidates s <= min(m, s_cap)
 };
 
 struct plogp_cell_dev {

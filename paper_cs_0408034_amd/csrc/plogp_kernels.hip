@@ -234,6 +234,15 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     if (mi < G.n_m) {
         const u64 m = G.m[mi];
         S.gm[(size_t)t * G.n_m + mi] = gap_at(tab, (double)m);
+        if (t == 0) {                  // candidates s <= min(m, s_cap): the list ascends
+            const u64 lim = m < G.s_cap ? m : G.s_cap;
+            int lo = 0, hi = G.n_s;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
+            }
+            S.nv[mi] = lo;
+        }
         if (G.mask & (1u << 12)) {
             double *o = S.sum2 + (size_t)t * (G.cl_max + 1) * G.n_m + mi;     // [d][m]
             double acc = 0.0;
@@ -491,6 +500,47 @@ __device__ __forceinline__ double min_f64(double a, double b)
     return r;
 }
 
+// Rows 2 and 9 of Table 1 are monotone in A = g(s) k for a fixed P (q >= 1,
+// floor(log2 P) >= 1, rounding is monotone), so their minima over s are
+//   min_s T2 = fma(q, min_s A, L),   min_s T9 = fma(fl, min_s A, cl L)
+// exactly, and only min_s A (one v_min per (m, s)) is tracked in the sweeps.
+// The segment size is then needed only in the cells that row 2 or 9 wins: there
+// the candidates are walked once more, in ascending order, for the first s whose
+// value equals the minimum (several A can round to the same time, so this is
+// not simply the s of the smallest A).
+//
+// One lane per m, PC process counts per lane.  want[p]: 0 = nothing to find,
+// else the row (2 or 9) that won cell p; V[p] its time.  cand(si, sd, rcp, gs)
+// supplies the wave-uniform scalars of candidate si.  found[p] receives s.
+template <int PC, class Cand>
+__device__ __forceinline__ void first_s_of_flat_or_binomial(
+    int n_cand, u64 lim, double md, double L, const double (&q)[PC], const double (&fl)[PC],
+    const double (&clL)[PC], const int (&want)[PC], const double (&V)[PC], uint32_t (&found)[PC],
+    Cand cand)
+{
+    bool open[PC];
+#pragma unroll
+    for (int p = 0; p < PC; ++p)
+        open[p] = want[p] != 0;
+    for (int si = 0; si < n_cand; ++si) {
+        double sd, rcp_s, gs;
+        cand(si, sd, rcp_s, gs);
+        if ((u64)sd <= lim) {
+            double A, B, C;
+            segment_terms(md, sd, rcp_s, gs, L, A, B, C);
+#pragma unroll
+            for (int p = 0; p < PC; ++p) {
+                const double Tv = want[p] == 2 ? __builtin_fma(q[p], A, L)
+                                               : __builtin_fma(fl[p], A, clL[p]);
+                if (open[p] && Tv == V[p]) {
+                    found[p] = (uint32_t)sd;
+                    open[p] = false;
+                }
+            }
+        }
+    }
+}
+
 // ---- sweep, few candidates: one lane per message size ------------------------
 //
 // A wave takes 64 consecutive m of one table and PC consecutive process counts.
@@ -532,15 +582,17 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         fl[p] = (double)floor_log2(Pv[p]);
         clL[p] = (double)ceil_log2(Pv[p]) * L;
     }
-    double b2[PC], b5[PC], b9[PC];
-    int i2[PC], i5[PC], i9[PC];
+    double b5[PC];
+    int i5[PC];
 #pragma unroll
     for (int p = 0; p < PC; ++p) {
-        b2[p] = b5[p] = b9[p] = INFINITY;
-        i2[p] = i5[p] = i9[p] = 0;
+        b5[p] = INFINITY;
+        i5[p] = 0;
     }
+    double amin = INFINITY;                  // min over s of A = g(s) k (rows 2 and 9)
+    int n_seen = 0;                          // candidates walked (wave-uniform)
+    const double *gs = S.gs + (size_t)t * G.n_s;
     if ((mask & 0x224u) && G.n_s > 0) {
-        const double *gs = S.gs + (size_t)t * G.n_s;
         // the per-candidate scalars of the next iteration are fetched while this one computes
         u64 sv_n = G.s[0];
         double rcp_n = S.rcp[0], gs_n = gs[0];
@@ -554,20 +606,16 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
             const bool valid = sv <= lim;
             if (__ballot(valid) == 0)
                 break;                       // the candidates ascend: nothing further competes
+            n_seen = si + 1;
             if (valid) {
                 double A, B, C;
                 segment_terms(md, (double)sv, rcp_s, gsv, L, A, B, C);
+                amin = min_f64(amin, A);
 #pragma unroll
                 for (int p = 0; p < PC; ++p) {
-                    const double T2 = __builtin_fma(q[p], A, L);
                     const double T5 = __builtin_fma(q[p], C, B);
-                    const double T9 = __builtin_fma(fl[p], A, clL[p]);
-                    i2[p] = T2 < b2[p] ? si : i2[p];
-                    b2[p] = min_f64(b2[p], T2);
                     i5[p] = T5 < b5[p] ? si : i5[p];
                     b5[p] = min_f64(b5[p], T5);
-                    i9[p] = T9 < b9[p] ? si : i9[p];
-                    b9[p] = min_f64(b9[p], T9);
                 }
             }
         }
@@ -581,7 +629,7 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
 
     // everything the PC cells read is fetched before the first of them is stored
     double s11[PC], s12[PC];
-    uint32_t s2[PC], s5[PC], s9[PC];
+    uint32_t s5[PC];
 #pragma unroll
     for (int p = 0; p < PC; ++p) {
         const int pi = pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1;
@@ -590,9 +638,38 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
             s11[p] = chain_sum_of(G, S, t, mi, pi, Pv[p]);
         if (mask & (1u << 12))
             s12[p] = S.sum2[((size_t)t * (G.cl_max + 1) + ceil_log2(Pv[p])) * n_m + mi];
-        s2[p] = b2[p] < INFINITY ? (uint32_t)G.s[i2[p]] : 0u;
         s5[p] = b5[p] < INFINITY ? (uint32_t)G.s[i5[p]] : 0u;
-        s9[p] = b9[p] < INFINITY ? (uint32_t)G.s[i9[p]] : 0u;
+    }
+    Best bc[PC];
+    if (mask & 0x3FFu) {
+        int want[PC];
+        double V[PC];
+        uint32_t found[PC];
+        bool any = false;
+#pragma unroll
+        for (int p = 0; p < PC; ++p) {
+            const double t2 = amin < INFINITY ? __builtin_fma(q[p], amin, L) : INFINITY;
+            const double t9 = amin < INFINITY ? __builtin_fma(fl[p], amin, clL[p]) : INFINITY;
+            bc[p] = decide_bcast(mask, q[p], fl[p], (double)ceil_log2(Pv[p]), gm, L, g1, t2, 0u,
+                                 b5[p], s5[p], t9, 0u);
+            want[p] = (bc[p].id == 2u || bc[p].id == 9u) ? (int)bc[p].id : 0;
+            V[p] = bc[p].t;
+            found[p] = 0u;
+            any = any || want[p] != 0;
+        }
+        if (__ballot(any) != 0) {
+            first_s_of_flat_or_binomial<PC>(
+                n_seen, lim, md, L, q, fl, clL, want, V, found,
+                [&](int si, double &sd, double &rcp_s, double &g) {
+                    sd = (double)G.s[si];
+                    rcp_s = S.rcp[si];
+                    g = gs[si];
+                });
+#pragma unroll
+            for (int p = 0; p < PC; ++p)
+                if (want[p] != 0)
+                    bc[p].s = found[p];
+        }
     }
 #pragma unroll
     for (int p = 0; p < PC; ++p) {
@@ -602,8 +679,7 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + pi;
         const double cl = (double)ceil_log2(Pv[p]);
         if (mask & 0x3FFu) {
-            store_cell(o, decide_bcast(mask, q[p], fl[p], cl, gm, L, g1, b2[p], s2[p], b5[p], s5[p],
-                                       b9[p], s9[p]));
+            store_cell(o, bc[p]);
             o += plane;
         }
         if (mask & 0x1C00u)
@@ -627,35 +703,40 @@ __device__ __forceinline__ double dpp_move(double v)
 // mirrors), then the row broadcasts 15 and 31 fold the four rows into lane 63.
 __device__ __forceinline__ double wave_min(double v)
 {
-    v = __builtin_fmin(v, dpp_move<0xB1, 0xf>(v));     // quad_perm [1,0,3,2]
-    v = __builtin_fmin(v, dpp_move<0x4E, 0xf>(v));     // quad_perm [2,3,0,1]
-    v = __builtin_fmin(v, dpp_move<0x141, 0xf>(v));    // row_half_mirror
-    v = __builtin_fmin(v, dpp_move<0x140, 0xf>(v));    // row_mirror
-    v = __builtin_fmin(v, dpp_move<0x142, 0xa>(v));    // row_bcast:15 into rows 1, 3
-    v = __builtin_fmin(v, dpp_move<0x143, 0xc>(v));    // row_bcast:31 into rows 2, 3
+    v = min_f64(v, dpp_move<0xB1, 0xf>(v));            // quad_perm [1,0,3,2]
+    v = min_f64(v, dpp_move<0x4E, 0xf>(v));            // quad_perm [2,3,0,1]
+    v = min_f64(v, dpp_move<0x141, 0xf>(v));           // row_half_mirror
+    v = min_f64(v, dpp_move<0x140, 0xf>(v));           // row_mirror
+    v = min_f64(v, dpp_move<0x142, 0xa>(v));           // row_bcast:15 into rows 1, 3
+    v = min_f64(v, dpp_move<0x143, 0xc>(v));           // row_bcast:31 into rows 2, 3
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
     return __hiloint2double(hi, lo);
 }
 
-constexpr int SWEEP_S_CHUNK = 2048;     // candidates staged in LDS per pass (32 per lane)
+constexpr int SWEEP_S_CHUNK = 1024;     // candidates staged in LDS per pass (16 per lane)
 constexpr int SWEEP_S_MAX_WAVES = 12;
+constexpr int SWEEP_S_PASSES = 64;      // passes whose minimum of A is remembered
 
 // A workgroup takes one (table, m) and up to SWEEP_S_MAX_WAVES groups of GP
 // process counts, one group per wave; lanes run over the candidates s.  A, B, C
 // of a pass of SWEEP_S_CHUNK candidates are computed once by the whole
 // workgroup into LDS (double-buffered) and read by every wave.  In the loop a
-// wave only keeps running minima (one fma and one min per model value); per
-// lane it remembers in which pass each minimum first appeared.  At the end the
-// minima are reduced across lanes, the winner is chosen in id order, and only
-// for a winning segmented row the lanes that hold the minimum re-evaluate the
-// candidates of the pass it came from to find the smallest s that attains it.
+// wave keeps, per process count, the running minimum of the segmented chain
+// (row 5: one fma and one min per value) and, once per candidate, the running
+// minimum of A (rows 2 and 9 are monotone in A); per lane it remembers in which
+// pass each row-5 minimum first appeared.  At the end the minima are reduced
+// across lanes with DPP, the winner is chosen in id order, and only for a
+// winning segmented row the smallest s that attains the minimum is looked for:
+// for row 5 among the candidates of the pass the holding lanes remember, for
+// rows 2 and 9 by one ascending walk over the candidates.
 template <int GP>
 __global__ void __launch_bounds__(64 * SWEEP_S_MAX_WAVES)
 k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_ptiles)
 {
     __shared__ double2 AB[2][SWEEP_S_CHUNK];
     __shared__ double Cs[2][SWEEP_S_CHUNK];
+    __shared__ double passMinA[SWEEP_S_PASSES];        // min of A over each of the first passes
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -675,123 +756,157 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     const uint32_t mask = G.mask;
     const double *gs = S.gs + (size_t)t * G.n_s;
 
-    int nv = 0;                                        // candidates s <= min(m, s_cap)
-    {
-        int lo = 0, hi = G.n_s;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
-        }
-        nv = lo;
-    }
+    const int nv = S.nv[mi];                           // candidates s <= min(m, s_cap)
     const int n_chunks = (nv + SWEEP_S_CHUNK - 1) / SWEEP_S_CHUNK;
 
-    double q[GP], fl[GP], clL[GP];
+    double q[GP];
 #pragma unroll
     for (int p = 0; p < GP; ++p) {
         const uint32_t Pv = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
         q[p] = (double)(Pv - 1);
-        fl[p] = (double)floor_log2(Pv);
-        clL[p] = (double)ceil_log2(Pv) * L;
     }
-    double best2[GP], best5[GP], best9[GP];
-    int blk2[GP], blk5[GP], blk9[GP];
+    double best5[GP];
+    int blk5[GP];
 #pragma unroll
     for (int p = 0; p < GP; ++p) {
-        best2[p] = best5[p] = best9[p] = INFINITY;
-        blk2[p] = blk5[p] = blk9[p] = 0;
+        best5[p] = INFINITY;
+        blk5[p] = 0;
     }
+    double amin = INFINITY;
 
-    auto fill = [&](int c) {
-        const int buf = c & 1;
-        for (int e = threadIdx.x; e < SWEEP_S_CHUNK; e += blockDim.x) {
-            const int si = c * SWEEP_S_CHUNK + e;
-            double A = INFINITY, B = INFINITY, C = 0.0;
-            if (si < nv)
-                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
-            AB[buf][e] = make_double2(A, B);
-            Cs[buf][e] = C;
+    // Filling a pass: the loads of the per-candidate scalars are issued before the
+    // previous pass is consumed, the arithmetic and the LDS stores come after it.
+    // A workgroup has at least SWEEP_S_CHUNK / FILL_SLOTS threads.
+    constexpr int FILL_SLOTS = 4;
+    double f_s[FILL_SLOTS], f_rcp[FILL_SLOTS], f_gs[FILL_SLOTS];
+    auto fill_load = [&](int c) {
+#pragma unroll
+        for (int k = 0; k < FILL_SLOTS; ++k) {
+            const int si = c * SWEEP_S_CHUNK + (int)threadIdx.x + k * (int)blockDim.x;
+            const int idx = si < nv ? si : nv - 1;
+            f_s[k] = (double)G.s[idx];
+            f_rcp[k] = S.rcp[idx];
+            f_gs[k] = gs[idx];
         }
     };
-    if (n_chunks > 0)
-        fill(0);
+    auto fill_store = [&](int c) {
+        const int buf = c & 1;
+#pragma unroll
+        for (int k = 0; k < FILL_SLOTS; ++k) {
+            const int e = (int)threadIdx.x + k * (int)blockDim.x;
+            if (e < SWEEP_S_CHUNK) {
+                double A = INFINITY, B = INFINITY, C = 0.0;
+                if (c * SWEEP_S_CHUNK + e < nv)
+                    segment_terms(md, f_s[k], f_rcp[k], f_gs[k], L, A, B, C);
+                AB[buf][e] = make_double2(A, B);
+                Cs[buf][e] = C;
+            }
+        }
+    };
+    if (n_chunks > 0) {
+        fill_load(0);
+        fill_store(0);
+    }
     __syncthreads();
     for (int c = 0; c < n_chunks; ++c) {
         if (c + 1 < n_chunks)
-            fill(c + 1);
+            fill_load(c + 1);
         if (has_work) {
             const int buf = c & 1;
             const int len = min(SWEEP_S_CHUNK, nv - c * SWEEP_S_CHUNK);
             const int steps = (len + 63) >> 6;
-            double cur2[GP], cur5[GP], cur9[GP];
+            double cur5[GP];
 #pragma unroll
             for (int p = 0; p < GP; ++p)
-                cur2[p] = cur5[p] = cur9[p] = INFINITY;
+                cur5[p] = INFINITY;
+            double curA = INFINITY;
 #pragma unroll 2
             for (int i = 0; i < steps; ++i) {
                 const double2 ab = AB[buf][64 * i + lane];
                 const double C = Cs[buf][64 * i + lane];
+                curA = min_f64(curA, ab.x);
 #pragma unroll
-                for (int p = 0; p < GP; ++p) {
-                    cur2[p] = min_f64(cur2[p], __builtin_fma(q[p], ab.x, L));
+                for (int p = 0; p < GP; ++p)
                     cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], C, ab.y));
-                    cur9[p] = min_f64(cur9[p], __builtin_fma(fl[p], ab.x, clL[p]));
-                }
             }
 #pragma unroll
             for (int p = 0; p < GP; ++p) {
-                blk2[p] = cur2[p] < best2[p] ? c : blk2[p];
-                best2[p] = min_f64(best2[p], cur2[p]);
                 blk5[p] = cur5[p] < best5[p] ? c : blk5[p];
                 best5[p] = min_f64(best5[p], cur5[p]);
-                blk9[p] = cur9[p] < best9[p] ? c : blk9[p];
-                best9[p] = min_f64(best9[p], cur9[p]);
+            }
+            amin = min_f64(amin, curA);
+            if (wave == 0 && c < SWEEP_S_PASSES) {     // wave 0 always has work
+                const double pm = wave_min(curA);
+                if (lane == 0)
+                    passMinA[c] = pm;
             }
         }
+        if (c + 1 < n_chunks)
+            fill_store(c + 1);
         __syncthreads();
     }
     if (!has_work)
         return;
 
     // per process count of the group: the best segmented row, its time and its s
+    const double Aw = (mask & 0x204u) ? wave_min(amin) : INFINITY;
+    const bool haveA = Aw < INFINITY;
+    // candidate si of this lane re-evaluated: value of the row given by (mul, add, use_chain)
+    auto value_at = [&](int si, double mul, double add, bool chain_row) {
+        double A, B, C;
+        segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
+        return chain_row ? __builtin_fma(mul, C, B) : __builtin_fma(mul, A, add);
+    };
     double segT = INFINITY;       // kept by lane p for process count p0 + p
     uint32_t segId = 0xFFFFFFFFu, segS = 0;
 #pragma unroll
     for (int p = 0; p < GP; ++p) {
-        const double c2 = (mask & (1u << 2)) ? best2[p] : INFINITY;
+        const uint32_t Pv = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
+        const double flp = (double)floor_log2(Pv);
+        const double clLp = (double)ceil_log2(Pv) * L;
+        const double V2 = ((mask & (1u << 2)) && haveA) ? __builtin_fma(q[p], Aw, L) : INFINITY;
+        const double V9 = ((mask & (1u << 9)) && haveA) ? __builtin_fma(flp, Aw, clLp) : INFINITY;
         const double c5 = (mask & (1u << 5)) ? best5[p] : INFINITY;
-        const double c9 = (mask & (1u << 9)) ? best9[p] : INFINITY;
-        const double V = wave_min(__builtin_fmin(__builtin_fmin(c2, c5), c9));
+        const double V5 = wave_min(c5);
+        const double V = __builtin_fmin(__builtin_fmin(V2, V5), V9);
         if (!(V < INFINITY))
             continue;                                  // wave-uniform
-        int id;
-        double mine;
-        int myblk;
-        if (__ballot(c2 == V) != 0) { id = 2; mine = c2; myblk = blk2[p]; }
-        else if (__ballot(c5 == V) != 0) { id = 5; mine = c5; myblk = blk5[p]; }
-        else { id = 9; mine = c9; myblk = blk9[p]; }
-        // smallest s with T_id(s) == V: every lane that holds V names the pass it
-        // first saw it in; 32 lanes re-evaluate that lane's 32 candidates of the pass
-        unsigned long long holders = __ballot(mine == V);
+        const int id = V2 == V ? 2 : (V5 == V ? 5 : 9);
         int first = 0x7FFFFFFF;
-        while (holders != 0) {
-            const int l = __builtin_ctzll(holders);
-            holders &= holders - 1;
-            const int c = __builtin_amdgcn_readlane(myblk, l);
-            const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
-            bool hit = false;
-            if (lane < SWEEP_S_CHUNK / 64 && si < nv) {
-                double A, B, C;
-                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
-                const double Tv = id == 2 ? __builtin_fma(q[p], A, L)
-                                : id == 5 ? __builtin_fma(q[p], C, B)
-                                          : __builtin_fma(fl[p], A, clL[p]);
-                hit = Tv == V;
+        if (id == 5) {
+            // every lane that holds V names the pass it first saw it in; lanes 0..15
+            // re-evaluate that lane's 16 candidates of the pass
+            unsigned long long holders = __ballot(c5 == V);
+            while (holders != 0) {
+                const int l = __builtin_ctzll(holders);
+                holders &= holders - 1;
+                const int c = __builtin_amdgcn_readlane(blk5[p], l);
+                const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
+                const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
+                                 value_at(si, q[p], 0.0, true) == V;
+                const unsigned long long hits = __ballot(hit);
+                if (hits != 0) {
+                    const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
+                    first = cand < first ? cand : first;
+                }
             }
-            const unsigned long long hits = __ballot(hit);
-            if (hits != 0) {
-                const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
-                first = cand < first ? cand : first;
+        } else {
+            // rows 2 and 9: the first pass whose minimum of A already gives V holds the
+            // smallest such s; walk that pass in ascending order, 64 candidates at a time
+            const double mul = id == 2 ? q[p] : flp;
+            const double add = id == 2 ? L : clLp;
+            int c0 = 0;
+            const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
+            while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
+                ++c0;
+            for (int base = c0 * SWEEP_S_CHUNK; base < nv; base += 64) {
+                const int si = base + lane;
+                const bool hit = si < nv && value_at(si, mul, add, false) == V;
+                const unsigned long long hits = __ballot(hit);
+                if (hits != 0) {
+                    first = base + __builtin_ctzll(hits);
+                    break;
+                }
             }
         }
         if (lane == p) {
@@ -826,7 +941,6 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
         store_cell(o, decide_scatter(mask, qv, (double)cli, gm, L, s11, s12));
     }
 }
-
 
 // ---- whole path in one kernel, for batches of many tables -----------------
 //
@@ -1174,8 +1288,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (G.n_s >= 256) {
         constexpr int GP = 6;
         const int n_groups = (G.n_P + GP - 1) / GP;
-        const int waves = n_groups < SWEEP_S_MAX_WAVES ? n_groups : SWEEP_S_MAX_WAVES;
+        int waves = n_groups < SWEEP_S_MAX_WAVES ? n_groups : SWEEP_S_MAX_WAVES;
         const int n_ptiles = (n_groups + waves - 1) / waves;
+        if (waves < 4) waves = 4;           // the fill of a pass needs 256 threads
         hipLaunchKernelGGL(k_sweep_s<GP>, dim3((unsigned)T.n_tables * G.n_m * n_ptiles),
                            dim3(64 * waves), 0, st, T, G, S, d_out, n_ptiles);
     } else {

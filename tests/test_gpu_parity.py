@@ -192,6 +192,26 @@ def test_many_candidates_span_several_lds_passes():
     assert assert_tables_equal(gpu_tune(wl), want, "cfg3 slice")
 
 
+@pytest.mark.parametrize("mask", [1 << 2, 1 << 9, (1 << 2) | (1 << 9), 1 << 5, 0x224, ALL_STRATEGIES_MASK])
+def test_many_candidates_with_exact_ties_over_s(mask):
+    # g(z) = z / 4 exactly: g(s) ceil(m/s) = m / 4 for every s that divides m, so rows
+    # 2 and 9 tie over many candidates and the smallest such s must be reported;
+    # 600 candidates go through the lane-per-candidate sweep, 40 through the lane-per-m one
+    x = np.array([[1.0, float(1 << 40)]])
+    y = x / 4.0
+    m = np.array([1 << 12, 3 << 11, (1 << 13) + 8, 1 << 16, 40], dtype=np.uint64)
+    P = np.array([2, 3, 4, 7, 8, 9, 100, 1024], dtype=np.uint32)
+    for n_s in (600, 40):
+        s = np.arange(8, 8 * n_s + 1, 8, dtype=np.uint64)
+        for L in (0.0, 3.0):
+            wl = Workload("ties", x, y, np.array([L]), m, P, s, NO_CAP, mask)
+            want, _ = oracle.tune_workload(wl)
+            got = gpu_tune(wl)
+            assert assert_tables_equal(got, want, "ties n_s=%d L=%g mask=%x" % (n_s, L, mask))
+    if mask == 1 << 2:
+        assert (got["s"][0, 0, 0] == 8).all()           # m = 4096: every power of two ties
+
+
 def test_no_candidates_and_candidates_all_above_m():
     base = make_workload(2)
     m = np.array([8, 16, 64], dtype=np.uint64)
