@@ -715,7 +715,7 @@ __device__ __forceinline__ double wave_min(double v)
 }
 
 constexpr int SWEEP_S_CHUNK = 1024;     // candidates staged in LDS per pass (16 per lane)
-constexpr int SWEEP_S_MAX_WAVES = 12;
+constexpr int SWEEP_S_MAX_WAVES = 8;
 constexpr int SWEEP_S_PASSES = 64;      // passes whose minimum of A is remembered
 
 // A workgroup takes one (table, m) and up to SWEEP_S_MAX_WAVES groups of GP
@@ -759,11 +759,13 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     const int nv = S.nv[mi];                           // candidates s <= min(m, s_cap)
     const int n_chunks = (nv + SWEEP_S_CHUNK - 1) / SWEEP_S_CHUNK;
 
-    double q[GP];
+    double q[GP];                                      // wave-uniform: kept in scalar registers
 #pragma unroll
     for (int p = 0; p < GP; ++p) {
         const uint32_t Pv = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
-        q[p] = (double)(Pv - 1);
+        const double qv = (double)(Pv - 1);
+        q[p] = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(qv)),
+                                __builtin_amdgcn_readfirstlane(__double2loint(qv)));
     }
     double best5[GP];
     int blk5[GP];
@@ -777,7 +779,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     // Filling a pass: the loads of the per-candidate scalars are issued before the
     // previous pass is consumed, the arithmetic and the LDS stores come after it.
     // A workgroup has at least SWEEP_S_CHUNK / FILL_SLOTS threads.
-    constexpr int FILL_SLOTS = 4;
+    constexpr int FILL_SLOTS = 2;
     double f_s[FILL_SLOTS], f_rcp[FILL_SLOTS], f_gs[FILL_SLOTS];
     auto fill_load = [&](int c) {
 #pragma unroll
@@ -899,13 +901,25 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
             const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
             while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
                 ++c0;
-            for (int base = c0 * SWEEP_S_CHUNK; base < nv; base += 64) {
-                const int si = base + lane;
-                const bool hit = si < nv && value_at(si, mul, add, false) == V;
-                const unsigned long long hits = __ballot(hit);
-                if (hits != 0) {
-                    first = base + __builtin_ctzll(hits);
-                    break;
+            for (int base = c0 * SWEEP_S_CHUNK; base < nv && first == 0x7FFFFFFF; base += 256) {
+                // four groups of 64 candidates per round trip to memory
+                double sdv[4], rcv[4], gsv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int si = base + 64 * u + lane;
+                    const int idx = si < nv ? si : nv - 1;
+                    sdv[u] = (double)G.s[idx];
+                    rcv[u] = S.rcp[idx];
+                    gsv[u] = gs[idx];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    double A, B, C;
+                    segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
+                    const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
+                    const unsigned long long hits = __ballot(hit);
+                    if (hits != 0 && first == 0x7FFFFFFF)
+                        first = base + 64 * u + __builtin_ctzll(hits);
                 }
             }
         }
@@ -1286,13 +1300,20 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     }
 
     if (G.n_s >= 256) {
-        constexpr int GP = 6;
-        const int n_groups = (G.n_P + GP - 1) / GP;
-        int waves = n_groups < SWEEP_S_MAX_WAVES ? n_groups : SWEEP_S_MAX_WAVES;
-        const int n_ptiles = (n_groups + waves - 1) / waves;
-        if (waves < 4) waves = 4;           // the fill of a pass needs 256 threads
-        hipLaunchKernelGGL(k_sweep_s<GP>, dim3((unsigned)T.n_tables * G.n_m * n_ptiles),
-                           dim3(64 * waves), 0, st, T, G, S, d_out, n_ptiles);
+        // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
+        // process counts per wave are chosen so that one workgroup covers all of them if
+        // it can
+        const int waves = 8;
+        const unsigned rows = (unsigned)T.n_tables * G.n_m;
+        if (G.n_P <= 6 * waves) {
+            hipLaunchKernelGGL(k_sweep_s<6>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
+        } else if (G.n_P <= 9 * waves) {
+            hipLaunchKernelGGL(k_sweep_s<9>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
+        } else {
+            const int n_ptiles = (G.n_P + 12 * waves - 1) / (12 * waves);
+            hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * n_ptiles), dim3(64 * waves), 0, st, T, G, S,
+                               d_out, n_ptiles);
+        }
     } else {
         constexpr int PC = 4;
         const int n_mg = (G.n_m + 63) / 64;
