@@ -186,11 +186,12 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
 
 // ---------------------------------------------------------------- tune, step 1: per-table and per-m terms
 
-// One workgroup per (table, chunk of blockDim m rows).  Computes the interval
-// slopes from the raw samples (chunk 0 publishes them), g(m) and the prefix
-// sums over j of g(2^j m) for its rows; chunk 0 also computes g(1), g(s) and
-// (first table only) the reciprocals 1/s used to get k = ceil(m/s) without a
-// division per (m, s).
+// One workgroup per (table, chunk of blockDim items); a lane takes one m and
+// one s.  Computes the interval slopes from the raw samples (chunk 0 publishes
+// them, and the table as intervals for the chain-sum walk), g(m), the number of
+// candidates that compete for m and the prefix sums over j of g(2^j m) for its
+// rows, g(s) for its candidates and (first table only) the reciprocals 1/s used
+// to get k = ceil(m/s) without a division per (m, s); chunk 0 also g(1).
 __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks)
 {
     extern __shared__ double lds[];
@@ -253,15 +254,14 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
             }
         }
     }
-    if (chunk == 0) {
-        if (threadIdx.x == 0)
-            S.g1[t] = gap_at(tab, 1.0);
-        for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
-            const double sd = (double)G.s[si];
-            S.gs[(size_t)t * G.n_s + si] = gap_at(tab, sd);
-            if (t == 0)
-                S.rcp[si] = 1.0 / sd;
-        }
+    if (chunk == 0 && threadIdx.x == 0)
+        S.g1[t] = gap_at(tab, 1.0);
+    // the candidates are shared out over the chunks of this table
+    for (int si = chunk * blockDim.x + threadIdx.x; si < G.n_s; si += n_chunks * blockDim.x) {
+        const double sd = (double)G.s[si];
+        S.gs[(size_t)t * G.n_s + si] = gap_at(tab, sd);
+        if (t == 0)
+            S.rcp[si] = 1.0 / sd;
     }
 }
 
@@ -1269,7 +1269,8 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(4);
         return hipSuccess;
     }
-    const int n_chunks = (G.n_m + 255) / 256;
+    const int n_items = G.n_m > G.n_s ? G.n_m : G.n_s;     // a lane takes one m and one s
+    const int n_chunks = (n_items + 255) / 256;
     hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
                        S, n_chunks);
     if ((e = hipGetLastError()) != hipSuccess) return e;
