@@ -1036,11 +1036,22 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     const double g1 = sG1;
     const double gm = lds_gap(X, YS, n, md);
 
-    // candidates that compete for some lane of the wave (they ascend)
+    // candidates that compete for some lane of the wave (they ascend), and the
+    // minimum over s of A = g(s) k for this m (rows 2 and 9 are monotone in A)
     int wave_nv = 0;
-    for (int si = 0; si < G.n_s; ++si)
-        if (__ballot((u64)sS[si] <= lim) != 0)
-            wave_nv = si + 1;
+    double amin = INFINITY;
+    for (int si = 0; si < G.n_s; ++si) {
+        const double sd = sS[si];
+        const bool valid = (u64)sd <= lim;
+        if (__ballot(valid) == 0)
+            break;
+        wave_nv = si + 1;
+        if (valid && (mask & 0x204u)) {
+            double A, B, C;
+            segment_terms(md, sd, sR[si], sG[si], L, A, B, C);
+            amin = min_f64(amin, A);
+        }
+    }
 
     // Scatter-chain walk.  Current interval: d = z - start, w = width, {yi, sl};
     // the next interval's end and {gap, slope} are fetched one crossing ahead.
@@ -1107,17 +1118,17 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
         }
 
         double q[FUSED_PC], fl[FUSED_PC], clL[FUSED_PC];
-        double b2[FUSED_PC], b5[FUSED_PC], b9[FUSED_PC];
-        int i2[FUSED_PC], i5[FUSED_PC], i9[FUSED_PC];
+        double b5[FUSED_PC];
+        int i5[FUSED_PC];
 #pragma unroll
         for (int p = 0; p < FUSED_PC; ++p) {
             q[p] = (double)(Pv[p] - 1);
             fl[p] = (double)floor_log2(Pv[p]);
             clL[p] = (double)ceil_log2(Pv[p]) * L;
-            b2[p] = b5[p] = b9[p] = INFINITY;
-            i2[p] = i5[p] = i9[p] = 0;
+            b5[p] = INFINITY;
+            i5[p] = 0;
         }
-        if (mask & 0x224u) {
+        if (mask & (1u << 5)) {
             for (int si = 0; si < wave_nv; ++si) {             // wave-uniform
                 const double sd = sS[si];
                 if ((u64)sd <= lim) {                          // this lane's m admits s
@@ -1125,35 +1136,58 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
                     segment_terms(md, sd, sR[si], sG[si], L, A, B, C);
 #pragma unroll
                     for (int p = 0; p < FUSED_PC; ++p) {
-                        const double T2 = __builtin_fma(q[p], A, L);
                         const double T5 = __builtin_fma(q[p], C, B);
-                        const double T9 = __builtin_fma(fl[p], A, clL[p]);
-                        i2[p] = T2 < b2[p] ? si : i2[p];
-                        b2[p] = min_f64(b2[p], T2);
                         i5[p] = T5 < b5[p] ? si : i5[p];
                         b5[p] = min_f64(b5[p], T5);
-                        i9[p] = T9 < b9[p] ? si : i9[p];
-                        b9[p] = min_f64(b9[p], T9);
                     }
                 }
             }
         }
         // the chunk's cells go to LDS as [row][cell], then out as 64-byte runs
+        if (has_b) {
+            Best bc[FUSED_PC];
+            int want[FUSED_PC];
+            double V[FUSED_PC];
+            uint32_t found[FUSED_PC];
+            bool any = false;
 #pragma unroll
-        for (int p = 0; p < FUSED_PC; ++p) {
-            const double cl = (double)ceil_log2(Pv[p]);
-            union { plogp_cell_dev c; uint4 v; } u;
-            if (has_b) {
-                const uint32_t s2 = b2[p] < INFINITY ? (uint32_t)sS[i2[p]] : 0u;
+            for (int p = 0; p < FUSED_PC; ++p) {
+                const double t2 = amin < INFINITY ? __builtin_fma(q[p], amin, L) : INFINITY;
+                const double t9 = amin < INFINITY ? __builtin_fma(fl[p], amin, clL[p]) : INFINITY;
                 const uint32_t s5 = b5[p] < INFINITY ? (uint32_t)sS[i5[p]] : 0u;
-                const uint32_t s9 = b9[p] < INFINITY ? (uint32_t)sS[i9[p]] : 0u;
-                const Best r = decide_bcast(mask, q[p], fl[p], cl, gm, L, g1, b2[p], s2, b5[p], s5,
-                                            b9[p], s9);
-                u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
+                bc[p] = decide_bcast(mask, q[p], fl[p], (double)ceil_log2(Pv[p]), gm, L, g1, t2, 0u,
+                                     b5[p], s5, t9, 0u);
+                want[p] = (bc[p].id == 2u || bc[p].id == 9u) ? (int)bc[p].id : 0;
+                V[p] = bc[p].t;
+                found[p] = 0u;
+                any = any || want[p] != 0;
+            }
+            if (__ballot(any) != 0) {
+                first_s_of_flat_or_binomial<FUSED_PC>(
+                    wave_nv, lim, md, L, q, fl, clL, want, V, found,
+                    [&](int si, double &sd, double &rcp_s, double &g) {
+                        sd = sS[si];
+                        rcp_s = sR[si];
+                        g = sG[si];
+                    });
+#pragma unroll
+                for (int p = 0; p < FUSED_PC; ++p)
+                    if (want[p] != 0)
+                        bc[p].s = found[p];
+            }
+#pragma unroll
+            for (int p = 0; p < FUSED_PC; ++p) {
+                union { plogp_cell_dev c; uint4 v; } u;
+                u.c.time = bc[p].t; u.c.s = bc[p].s; u.c.strategy = bc[p].id;
                 stage[wave][0][lane * (FUSED_PC + 1) + p] = u.v;
             }
-            if (has_s) {
-                const Best r = decide_scatter(mask, q[p], cl, gm, L, s11v[p], s12v[p]);
+        }
+        if (has_s) {
+#pragma unroll
+            for (int p = 0; p < FUSED_PC; ++p) {
+                const Best r = decide_scatter(mask, q[p], (double)ceil_log2(Pv[p]), gm, L, s11v[p],
+                                              s12v[p]);
+                union { plogp_cell_dev c; uint4 v; } u;
                 u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
                 stage[wave][1][lane * (FUSED_PC + 1) + p] = u.v;
             }
