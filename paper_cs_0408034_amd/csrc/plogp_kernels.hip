@@ -276,6 +276,8 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
 // sample fall into a virtual interval of slope 0 and gap y_0 (the clamp).
 // Emits each block total and, for every P of the grid whose P-1 falls inside a
 // block, the running sum at that point.
+constexpr int CHAIN_SINGLE = 8;      // leading blocks of the chain sum that get a lane each
+
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bgroups,
                                int n_mchunks, int nb)
 {
@@ -291,13 +293,13 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     // (the clamp below the first sample); interval i+1 starts at sample i;
     // X[n+1] = X[n+2] = +inf.  Copied to LDS; each interval is fetched from there one
     // crossing before it is needed.
-    double2 *YS = reinterpret_cast<double2 *>(chain_lds);
-    double *X = chain_lds + 2 * (n + 2);
+    double2 *YS = reinterpret_cast<double2 *>(chain_lds);          // n + 2 entries
+    double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries, +inf from n + 1 on
     {
         const double2 *gys = reinterpret_cast<const double2 *>(S.cys) + (size_t)t * (n + 2);
         const double *gx = S.cx + (size_t)t * (n + 3);
-        for (int i = threadIdx.x; i < n + 3; i += blockDim.x) {
-            X[i] = gx[i];
+        for (int i = threadIdx.x; i < n + 6; i += blockDim.x) {
+            X[i] = i < n + 1 ? gx[i] : INFINITY;
             if (i < n + 2)
                 YS[i] = gys[i];
         }
@@ -308,7 +310,11 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
         return;
     const u64 m = G.m[mi];
     const double md = (double)m;
-    const int b0 = bg * nb;
+    // the first blocks (small j, where the walk crosses many intervals per term)
+    // go one per lane, the others nb per lane
+    const int b0 = bg < CHAIN_SINGLE ? bg : CHAIN_SINGLE + (bg - CHAIN_SINGLE) * nb;
+    if (bg < CHAIN_SINGLE)
+        nb = 1;
     const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
     // interval of z0: number of samples not above z0 (0 = the virtual interval)
     int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
@@ -338,13 +344,39 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
             const int stop = hit < nterms ? hit : nterms;
 #pragma unroll 4
             for (; jj < stop; ++jj) {
-                while (d >= w) {            // crossed into the next interval
+                if (d >= w) {               // crossed into the next interval (fetched ahead)
                     d -= w;
                     w = nxb - xb;
                     yi = nys.x;
                     si = nys.y;
                     xb = nxb;
                     ++i;
+                    if (d >= w) {
+                        // dense part of the table (small j): z is several intervals on; skip
+                        // whole intervals, four per LDS round trip.  e = z - end of interval i
+                        double e = d - w;
+                        for (;;) {
+                            const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
+                            const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
+                            if (e >= r4) {
+                                i += 4;
+                                e -= r4;
+                                xb += r4;
+                                continue;
+                            }
+                            const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
+                            const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
+                            const double hi = c == 0 ? r1 : (c == 1 ? r2 : (c == 2 ? r3 : r4));
+                            d = e - lo;
+                            w = hi - lo;
+                            xb += hi;
+                            i += 1 + c;
+                            break;
+                        }
+                        const double2 ys = YS[i];
+                        yi = ys.x;
+                        si = ys.y;
+                    }
                     nxb = X[i + 2];
                     nys = YS[i + 1];
                 }
@@ -1221,7 +1253,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
 
 // ---------------------------------------------------------------- launch wrappers
 
-static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 64;
+static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 96;
 
 hipError_t kernels_init()
 {
@@ -1311,13 +1343,15 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     PLOGP_MARK(1);
 
     if (G.mask & (1u << 11)) {
-        // a big table fills most of the LDS of a CU: one large workgroup per CU then
-        const size_t chain_lds = tab_lds + 64;
+        // a big table fills most of the LDS of a CU: one large workgroup per CU then, and
+        // several blocks per lane so that staging the table is amortised
+        const size_t chain_lds = tab_lds + 96;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
-        const int nb = big ? 2 : 1;
+        const int nb = big ? 4 : 1;
         const int n_mchunks = (G.n_m + threads - 1) / threads;
-        const int n_bgroups = (G.n_blk + nb - 1) / nb;
+        const int single = G.n_blk < CHAIN_SINGLE ? G.n_blk : CHAIN_SINGLE;
+        const int n_bgroups = single + (G.n_blk - single + nb - 1) / nb;
         hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * n_bgroups * n_mchunks),
                            dim3(threads), chain_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
