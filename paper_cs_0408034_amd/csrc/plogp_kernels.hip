@@ -394,29 +394,53 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     }
 }
 
-// One lane per (table, m): turns the block totals into their exclusive prefix
-// in ascending block order (the sum of all finished blocks before block b).
-__global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, int n_tables)
+// Turns the block totals of 64 message sizes into their exclusive prefix in
+// ascending block order (the sum of all finished blocks before block b).  The
+// sum itself is sequential per m; what a lane can do on its own is bounded by
+// the memory latency of its few loads in flight, so the whole workgroup moves
+// tiles of PFX_TILE blocks x 64 m through LDS (every thread 64 loads in flight)
+// and wave 0 scans a tile from there.
+constexpr int PFX_TILE = 256;
+
+__global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, int n_mgroups)
 {
-    const int id = blockIdx.x * blockDim.x + threadIdx.x;
-    if (id >= n_tables * G.n_m)
-        return;
-    const int t = id / G.n_m, mi = id % G.n_m;
-    double *p = S.blk + (size_t)t * G.n_blk * G.n_m + mi;
-    const int full = G.n_blk - 1;          // blocks that have a total
+    extern __shared__ double pfx_tile[];                 // [PFX_TILE][64]
+    const int t = blockIdx.x / n_mgroups, mg = blockIdx.x % n_mgroups;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int mi = mg * 64 + lane;
+    const bool active = mi < G.n_m;
+    const size_t n_m = (size_t)G.n_m;
+    double *p = S.blk + (size_t)t * G.n_blk * n_m + (active ? mi : 0);
+    const int full = G.n_blk - 1;                        // blocks that have a total
     double done = 0.0;
-    constexpr int BATCH = 32;              // loads of a batch are independent: issue them together
-    for (int b0 = 0; b0 < G.n_blk; b0 += BATCH) {
-        double tot[BATCH];
+    for (int b0 = 0; b0 < G.n_blk; b0 += PFX_TILE) {
+        double v[PFX_TILE / 4];
 #pragma unroll
-        for (int u = 0; u < BATCH; ++u)
-            tot[u] = (b0 + u < full) ? p[(size_t)(b0 + u) * G.n_m] : 0.0;
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            if (b0 + u < G.n_blk)
-                p[(size_t)(b0 + u) * G.n_m] = done;
-            done = done + tot[u];
+        for (int k = 0; k < PFX_TILE / 4; ++k) {
+            const int b = b0 + w + 4 * k;
+            v[k] = (active && b < full) ? p[(size_t)b * n_m] : 0.0;
         }
+#pragma unroll
+        for (int k = 0; k < PFX_TILE / 4; ++k)
+            pfx_tile[(w + 4 * k) * 64 + lane] = v[k];
+        __syncthreads();
+        if (w == 0) {
+            const int nb = G.n_blk - b0 < PFX_TILE ? G.n_blk - b0 : PFX_TILE;
+#pragma unroll 8
+            for (int bb = 0; bb < nb; ++bb) {
+                const double tot = pfx_tile[bb * 64 + lane];
+                pfx_tile[bb * 64 + lane] = done;
+                done = done + tot;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < PFX_TILE / 4; ++k) {
+            const int b = b0 + w + 4 * k;
+            if (active && b < G.n_blk)
+                p[(size_t)b * n_m] = pfx_tile[(w + 4 * k) * 64 + lane];
+        }
+        __syncthreads();
     }
 }
 
@@ -1270,6 +1294,10 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_prefix),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(PFX_TILE * 64 * sizeof(double)));
+    if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     return e;
@@ -1357,9 +1385,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
-            const int rows = T.n_tables * G.n_m;
-            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st,
-                               G, S, T.n_tables);
+            const int n_mgroups = (G.n_m + 63) / 64;
+            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256),
+                               (size_t)PFX_TILE * 64 * sizeof(double), st, G, S, n_mgroups);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         PLOGP_MARK(3);
