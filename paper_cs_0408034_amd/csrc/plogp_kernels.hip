@@ -570,7 +570,7 @@ __device__ __forceinline__ double min_f64(double a, double b)
 // supplies the wave-uniform scalars of candidate si.  found[p] receives s.
 template <int PC, class Cand>
 __device__ __forceinline__ void first_s_of_flat_or_binomial(
-    int n_cand, u64 lim, double md, double L, const double (&q)[PC], const double (&fl)[PC],
+    int n_cand, double limd, double md, double L, const double (&q)[PC], const double (&fl)[PC],
     const double (&clL)[PC], const int (&want)[PC], const double (&V)[PC], uint32_t (&found)[PC],
     Cand cand)
 {
@@ -581,7 +581,7 @@ __device__ __forceinline__ void first_s_of_flat_or_binomial(
     for (int si = 0; si < n_cand; ++si) {
         double sd, rcp_s, gs;
         cand(si, sd, rcp_s, gs);
-        if ((u64)sd <= lim) {
+        if (sd <= limd) {
             double A, B, C;
             segment_terms(md, sd, rcp_s, gs, L, A, B, C);
 #pragma unroll
@@ -605,26 +605,39 @@ __device__ __forceinline__ void first_s_of_flat_or_binomial(
 // process counts.  Per (P, s) and segmented row: one fma, one compare, the
 // running minimum and the index of the candidate that attained it (strict '<'
 // in ascending s: ties go to the smallest s).
+constexpr int SWEEP_M_MAX_S = 256;      // candidates the lane-per-m sweep stages in LDS
+
 template <int PC>
 __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, Scratch S,
-                                                 plogp_cell_dev *out, int n_mg, int n_pc,
-                                                 long n_items)
+                                                 plogp_cell_dev *out, int n_mg, int n_pcg)
 {
+    // the four waves of a workgroup share the table and the m group and take four
+    // consecutive chunks of PC process counts; the per-candidate scalars (s, 1/s,
+    // g(s)) are staged in LDS once for all of them
+    __shared__ double sS[SWEEP_M_MAX_S], sR[SWEEP_M_MAX_S], sG[SWEEP_M_MAX_S];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    long wid = (long)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (wid >= n_items)
+    int bid = blockIdx.x;
+    const int pcg = bid % n_pcg;
+    bid /= n_pcg;
+    const int mg = bid % n_mg;
+    const int t = bid / n_mg;
+    const int pc = pcg * 4 + wave;
+    for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
+        sS[si] = (double)G.s[si];
+        sR[si] = S.rcp[si];
+        sG[si] = S.gs[(size_t)t * G.n_s + si];
+    }
+    __syncthreads();
+    if (pc * PC >= G.n_P)
         return;
-    const int pc = (int)(wid % n_pc);
-    wid /= n_pc;
-    const int mg = (int)(wid % n_mg);
-    const int t = (int)(wid / n_mg);
 
     const int mi = mg * 64 + lane;
     const bool active = mi < G.n_m;
     const u64 m = active ? G.m[mi] : 1;
     const double md = (double)m;
     const u64 lim = active ? (m < G.s_cap ? m : G.s_cap) : 0;
+    const double limd = (double)lim;         // exact: at most m < 2^53 (0 for an idle lane)
     const double L = T.L[t];
     const uint32_t mask = G.mask;
 
@@ -647,25 +660,22 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
     }
     double amin = INFINITY;                  // min over s of A = g(s) k (rows 2 and 9)
     int n_seen = 0;                          // candidates walked (wave-uniform)
-    const double *gs = S.gs + (size_t)t * G.n_s;
     if ((mask & 0x224u) && G.n_s > 0) {
-        // the per-candidate scalars of the next iteration are fetched while this one computes
-        u64 sv_n = G.s[0];
-        double rcp_n = S.rcp[0], gs_n = gs[0];
+        // the scalars of the next candidate are read from LDS while this one computes
+        double sd_n = sS[0], rcp_n = sR[0], gs_n = sG[0];
         for (int si = 0; si < G.n_s; ++si) {
-            const u64 sv = sv_n;
-            const double rcp_s = rcp_n, gsv = gs_n;
+            const double sd = sd_n, rcp_s = rcp_n, gsv = gs_n;
             const int nx = si + 1 < G.n_s ? si + 1 : si;
-            sv_n = G.s[nx];
-            rcp_n = S.rcp[nx];
-            gs_n = gs[nx];
-            const bool valid = sv <= lim;
+            sd_n = sS[nx];
+            rcp_n = sR[nx];
+            gs_n = sG[nx];
+            const bool valid = sd <= limd;
             if (__ballot(valid) == 0)
                 break;                       // the candidates ascend: nothing further competes
             n_seen = si + 1;
             if (valid) {
                 double A, B, C;
-                segment_terms(md, (double)sv, rcp_s, gsv, L, A, B, C);
+                segment_terms(md, sd, rcp_s, gsv, L, A, B, C);
                 amin = min_f64(amin, A);
 #pragma unroll
                 for (int p = 0; p < PC; ++p) {
@@ -686,15 +696,54 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
     // everything the PC cells read is fetched before the first of them is stored
     double s11[PC], s12[PC];
     uint32_t s5[PC];
+    double done[PC];                         // finished blocks of the chain sum before each P
+#pragma unroll
+    for (int p = 0; p < PC; ++p)
+        done[p] = 0.0;
+    if (mask & (1u << 11)) {
+        const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
+        if (G.blk_is_prefix) {
+#pragma unroll
+            for (int p = 0; p < PC; ++p)
+                done[p] = tot[(size_t)((Pv[p] - 1u) / SUM_BLOCK) * n_m];
+        } else {
+            // few blocks (at most 32): the totals are added here, in ascending order; the
+            // P of the chunk ascend, so one pass over the blocks serves all of them, and
+            // the loads of eight blocks are in flight together
+            int last = 0;
+#pragma unroll
+            for (int p = 0; p < PC; ++p) {
+                const int blk = (int)((Pv[p] - 1u) / SUM_BLOCK);
+                last = blk > last ? blk : last;
+            }
+            double acc = 0.0;
+            for (int b0 = 0; b0 < last; b0 += 8) {
+                double tv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    tv[u] = b0 + u < last ? tot[(size_t)(b0 + u) * n_m] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (b0 + u < last) {
+                        acc = acc + tv[u];
+#pragma unroll
+                        for (int p = 0; p < PC; ++p)
+                            if ((int)((Pv[p] - 1u) / SUM_BLOCK) == b0 + u + 1)
+                                done[p] = acc;
+                    }
+                }
+            }
+        }
+    }
 #pragma unroll
     for (int p = 0; p < PC; ++p) {
         const int pi = pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1;
         s11[p] = s12[p] = 0.0;
         if (mask & (1u << 11))
-            s11[p] = chain_sum_of(G, S, t, mi, pi, Pv[p]);
+            s11[p] = done[p] + S.part[((size_t)t * G.n_P + pi) * n_m + mi];
         if (mask & (1u << 12))
             s12[p] = S.sum2[((size_t)t * (G.cl_max + 1) + ceil_log2(Pv[p])) * n_m + mi];
-        s5[p] = b5[p] < INFINITY ? (uint32_t)G.s[i5[p]] : 0u;
+        s5[p] = b5[p] < INFINITY ? (uint32_t)sS[i5[p]] : 0u;
     }
     Best bc[PC];
     if (mask & 0x3FFu) {
@@ -715,11 +764,11 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         }
         if (__ballot(any) != 0) {
             first_s_of_flat_or_binomial<PC>(
-                n_seen, lim, md, L, q, fl, clL, want, V, found,
+                n_seen, limd, md, L, q, fl, clL, want, V, found,
                 [&](int si, double &sd, double &rcp_s, double &g) {
-                    sd = (double)G.s[si];
-                    rcp_s = S.rcp[si];
-                    g = gs[si];
+                    sd = sS[si];
+                    rcp_s = sR[si];
+                    g = sG[si];
                 });
 #pragma unroll
             for (int p = 0; p < PC; ++p)
@@ -807,7 +856,6 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 
     const u64 m = G.m[mi];
     const double md = (double)m;
-    const u64 lim = m < G.s_cap ? m : G.s_cap;
     const double L = T.L[t];
     const uint32_t mask = G.mask;
     const double *gs = S.gs + (size_t)t * G.n_s;
@@ -1088,6 +1136,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     const u64 m = G.m[active ? mi : 0];
     const double md = (double)m;
     const u64 lim = active ? (m < G.s_cap ? m : G.s_cap) : 0;
+    const double limd = (double)lim;       // exact: at most m < 2^53 (0 for an idle lane)
     const uint32_t mask = G.mask;
     const double g1 = sG1;
     const double gm = lds_gap(X, YS, n, md);
@@ -1098,7 +1147,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     double amin = INFINITY;
     for (int si = 0; si < G.n_s; ++si) {
         const double sd = sS[si];
-        const bool valid = (u64)sd <= lim;
+        const bool valid = sd <= limd;
         if (__ballot(valid) == 0)
             break;
         wave_nv = si + 1;
@@ -1187,7 +1236,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
         if (mask & (1u << 5)) {
             for (int si = 0; si < wave_nv; ++si) {             // wave-uniform
                 const double sd = sS[si];
-                if ((u64)sd <= lim) {                          // this lane's m admits s
+                if (sd <= limd) {                              // this lane's m admits s
                     double A, B, C;
                     segment_terms(md, sd, sR[si], sG[si], L, A, B, C);
 #pragma unroll
@@ -1220,7 +1269,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
             }
             if (__ballot(any) != 0) {
                 first_s_of_flat_or_binomial<FUSED_PC>(
-                    wave_nv, lim, md, L, q, fl, clL, want, V, found,
+                    wave_nv, limd, md, L, q, fl, clL, want, V, found,
                     [&](int si, double &sd, double &rcp_s, double &g) {
                         sd = sS[si];
                         rcp_s = sR[si];
@@ -1396,7 +1445,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(3);
     }
 
-    if (G.n_s >= 256) {
+    if (G.n_s > SWEEP_M_MAX_S) {
         // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
         // process counts per wave are chosen so that one workgroup covers all of them if
         // it can
@@ -1414,10 +1463,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     } else {
         constexpr int PC = 4;
         const int n_mg = (G.n_m + 63) / 64;
-        const int n_pc = (G.n_P + PC - 1) / PC;
-        const long n_items = (long)T.n_tables * n_mg * n_pc;
-        hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)((n_items + 3) / 4)), dim3(256), 0, st, T, G,
-                           S, d_out, n_mg, n_pc, n_items);
+        const int n_pcg = (G.n_P + 4 * PC - 1) / (4 * PC);
+        hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)T.n_tables * n_mg * n_pcg), dim3(256), 0, st,
+                           T, G, S, d_out, n_mg, n_pcg);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(4);
