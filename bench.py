@@ -121,7 +121,7 @@ def cpu_sample(cfg, wl):
         return make_workload(4, n_tables=100), "first 100 of the 10 000 tables of config 4, full grid"
     if cfg == 5:
         return make_workload(5, m_slice=slice(0, 4096, 8)), "every 8th m row of config 5 (512 of 4096), all P, all s"
-    return wl, "the full %s workload, one run" % wl.name
+    return wl, "the full %s workload" % wl.name
 
 
 def run_cpu(cfg, wl):
@@ -129,13 +129,17 @@ def run_cpu(cfg, wl):
     sample, what = cpu_sample(cfg, wl)
     oracle.tune_grid(sample.sizes[:1], sample.gaps[:1], sample.L[:1], sample.m[:2], sample.P[:2],
                      sample.s, sample.s_cap, sample.strategy_mask)          # load + warm
-    t0 = time.perf_counter()
-    _, used = oracle.tune_workload(sample)
-    dt = time.perf_counter() - t0
+    runs, dt = 0, 0.0
+    while dt < 1.5 and runs < 50:               # about 1.5 s of wall time on all cores
+        t0 = time.perf_counter()
+        _, used = oracle.tune_workload(sample)
+        dt += time.perf_counter() - t0
+        runs += 1
     c = sample.counts()
-    return {"value": c["nominal_evals"] / dt, "unit": "evaluations/s", "cores": int(used),
-            "kind": "oracle", "sample": what, "seconds": dt,
-            "effective_evals_per_s": c["effective_evals"] / dt, "cells_per_s": c["cells"] / dt}
+    return {"value": runs * c["nominal_evals"] / dt, "unit": "evaluations/s", "cores": int(used),
+            "kind": "oracle", "sample": "%s, %d run(s)" % (what, runs), "seconds": dt,
+            "effective_evals_per_s": runs * c["effective_evals"] / dt,
+            "cells_per_s": runs * c["cells"] / dt}
 
 
 def bench_config(cfg, steps, warmup, with_cpu, mask=None):
@@ -179,6 +183,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--mask", type=lambda v: int(v, 0), default=None,
                     help="strategy mask override (for profiling parts of the path)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, "
+                         "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no inter-GPU path exists); use --gpus 1")
@@ -187,6 +194,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
 
+    if args.calibrate_copy:
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu, args.mask)
     line = {
         "metric": METRIC,
