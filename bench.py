@@ -184,7 +184,7 @@ def main():
     ap.add_argument("--mask", type=lambda v: int(v, 0), default=None,
                     help="strategy mask override (for profiling parts of the path)")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, "
+                    help="also run one elementwise kernel that copies 256 MiB (known traffic, "
                          "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -195,9 +195,12 @@ def main():
         sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
 
     if args.calibrate_copy:
-        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        # One elementwise kernel that reads 256 MiB and writes 256 MiB (float64 add of 0):
+        # the plain copy of known size that the HBM counters are scaled by.
+        a = torch.ones(32 << 20, dtype=torch.float64, device="cuda")
         b = torch.empty_like(a)
-        b.copy_(a)
+        torch.cuda.synchronize()
+        torch.add(a, 0.0, out=b)
         torch.cuda.synchronize()
         del a, b
     head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu, args.mask)

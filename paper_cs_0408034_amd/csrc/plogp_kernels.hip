@@ -278,6 +278,37 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
 // block, the running sum at that point.
 constexpr int CHAIN_SINGLE = 8;      // leading blocks of the chain sum that get a lane each
 
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+// The interval after the current one is fetched from LDS when the walk enters
+// the current one and is first looked at one crossing later, so its latency
+// must not be waited for at the point of issue.  The compiler's own wait
+// insertion would do exactly that (the loaded values feed loop-carried
+// registers), so the two reads are issued here, into the registers that carry
+// the values round the loop, and waited for in chain_await(), through which
+// every use of the fetched values passes.
+// w_addr, ys_addr: LDS byte addresses of W[i] and YS[i]; fetched: W[i + 1], YS[i + 1].
+__device__ __forceinline__ void chain_fetch_ahead(unsigned w_addr, unsigned ys_addr, double &nw,
+                                                  f64x2 &nys)
+{
+    asm volatile("ds_read_b64 %0, %2 offset:8\n\tds_read_b128 %1, %3 offset:16"
+                 : "+v"(nw), "+v"(nys)
+                 : "v"(w_addr), "v"(ys_addr)
+                 : "memory");
+}
+
+__device__ __forceinline__ void chain_await(double &nw, f64x2 &nys)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(nw), "+v"(nys) : : "memory");
+}
+
+// Makes the wait for an ordinary LDS read happen here rather than at a later
+// join of the control flow (where it would also wait for reads fetched ahead).
+__device__ __forceinline__ void settle(double &a, double &b, double &c, double &e)
+{
+    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(e));
+}
+
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bgroups,
                                int n_mchunks, int nb)
 {
@@ -291,21 +322,29 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     // Table as intervals (written by k_terms): YS[0..n+1] = {gap, slope}, X[0..n+2] =
     // interval starts.  Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0
     // (the clamp below the first sample); interval i+1 starts at sample i;
-    // X[n+1] = X[n+2] = +inf.  Copied to LDS; each interval is fetched from there one
+    // X[n+1] = X[n+2] = +inf.  Copied to LDS together with the widths W[i] =
+    // X[i+1] - X[i] (W[n] = W[n+1] = +inf); each interval is fetched from there one
     // crossing before it is needed.
-    double2 *YS = reinterpret_cast<double2 *>(chain_lds);          // n + 2 entries
+    f64x2 *YS = reinterpret_cast<f64x2 *>(chain_lds);              // n + 2 entries
     double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries, +inf from n + 1 on
+    double *W = X + (n + 6);                                       // n + 2 entries
     {
-        const double2 *gys = reinterpret_cast<const double2 *>(S.cys) + (size_t)t * (n + 2);
+        const f64x2 *gys = reinterpret_cast<const f64x2 *>(S.cys) + (size_t)t * (n + 2);
         const double *gx = S.cx + (size_t)t * (n + 3);
         for (int i = threadIdx.x; i < n + 6; i += blockDim.x) {
-            X[i] = i < n + 1 ? gx[i] : INFINITY;
-            if (i < n + 2)
+            const double x0 = i < n + 1 ? gx[i] : INFINITY;
+            X[i] = x0;
+            if (i < n + 2) {
                 YS[i] = gys[i];
+                W[i] = i < n ? gx[i + 1] - x0 : INFINITY;
+            }
         }
     }
     __syncthreads();
-    const int mi = mc * blockDim.x + threadIdx.x;
+    // The waves of a workgroup take groups of 64 sizes that lie n_mchunks groups apart:
+    // how often the walk crosses an interval depends on the magnitude of m, and this
+    // way every workgroup (and every SIMD in it) gets the same mix.
+    const int mi = ((int)(threadIdx.x >> 6) * n_mchunks + mc) * 64 + (int)(threadIdx.x & 63);
     if (mi >= G.n_m)
         return;
     const u64 m = G.m[mi];
@@ -318,12 +357,14 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
     // interval of z0: number of samples not above z0 (0 = the virtual interval)
     int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
-    double xb = X[i + 1];
     double d = z0 - X[i];                 // d = z - start of the interval (exact)
-    double w = xb - X[i];                 // width of the interval
+    double w = W[i];                      // width of the interval
     double yi = YS[i].x, si = YS[i].y;
-    double nxb = X[i + 2];                // the next interval, fetched ahead
-    double2 nys = YS[i + 1];
+    settle(d, w, yi, si);
+    const unsigned w_lds = (unsigned)(uintptr_t)W, ys_lds = (unsigned)(uintptr_t)YS;
+    double nw = 0.0;                      // the next interval, fetched ahead
+    f64x2 nys = {0.0, 0.0};
+    chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
     const size_t n_m = (size_t)G.n_m;
     double *part = S.part + (size_t)t * G.n_P * n_m + mi;       // [P index][m]
     double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
@@ -342,23 +383,33 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
             if (hit > nterms)
                 hit = SUM_BLOCK;
             const int stop = hit < nterms ? hit : nterms;
-#pragma unroll 4
             for (; jj < stop; ++jj) {
                 if (d >= w) {               // crossed into the next interval (fetched ahead)
+                    chain_await(nw, nys);
                     d -= w;
-                    w = nxb - xb;
+                    w = nw;
                     yi = nys.x;
                     si = nys.y;
-                    xb = nxb;
                     ++i;
                     if (d >= w) {
-                        // dense part of the table (small j): z is several intervals on; skip
-                        // whole intervals, four per LDS round trip.  e = z - end of interval i
+                        // dense part of the table (small j): z is several intervals on.
+                        // e = z - end of interval i.  Look four intervals ahead a few
+                        // times, then search the rest of the table for z = xb + e
+                        // (exact: integers below 2^53).
+                        double xb = X[i + 1];
                         double e = d - w;
+                        int hops = 0;
                         for (;;) {
                             const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
                             const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
                             if (e >= r4) {
+                                if (++hops == 3) {
+                                    const double z = xb + e;
+                                    // samples not above z = index of its interval
+                                    i = last_not_above(X + 1, n, z) + 1;
+                                    d = z - X[i];
+                                    break;
+                                }
                                 i += 4;
                                 e -= r4;
                                 xb += r4;
@@ -366,19 +417,17 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
                             }
                             const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
                             const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
-                            const double hi = c == 0 ? r1 : (c == 1 ? r2 : (c == 2 ? r3 : r4));
                             d = e - lo;
-                            w = hi - lo;
-                            xb += hi;
                             i += 1 + c;
                             break;
                         }
-                        const double2 ys = YS[i];
+                        const f64x2 ys = YS[i];
+                        w = W[i];
                         yi = ys.x;
                         si = ys.y;
+                        settle(d, w, yi, si);
                     }
-                    nxb = X[i + 2];
-                    nys = YS[i + 1];
+                    chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
                 }
                 run = run + __builtin_fma(si, d, yi);
                 d += md;
@@ -392,6 +441,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
         if (nterms == SUM_BLOCK)
             tot[(size_t)b * n_m] = run;
     }
+    chain_await(nw, nys);                 // nothing in flight when the wave ends
 }
 
 // Turns the block totals of 64 message sizes into their exclusive prefix in
@@ -1327,6 +1377,7 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
 // ---------------------------------------------------------------- launch wrappers
 
 static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 96;
+static const size_t kMaxChainLds = (size_t)4 * 4096 * sizeof(double) + 112;   // + interval widths
 
 hipError_t kernels_init()
 {
@@ -1341,7 +1392,7 @@ hipError_t kernels_init()
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChainLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_prefix),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1422,7 +1473,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (G.mask & (1u << 11)) {
         // a big table fills most of the LDS of a CU: one large workgroup per CU then, and
         // several blocks per lane so that staging the table is amortised
-        const size_t chain_lds = tab_lds + 96;
+        const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
         const int nb = big ? 4 : 1;
