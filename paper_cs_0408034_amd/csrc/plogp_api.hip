@@ -79,7 +79,7 @@ struct plogp_grid {
     unsigned long long *d_blk_mask = nullptr;
     // scratch, sized for scratch_tables tables
     size_t scratch_tables = 0, scratch_samples = 0;
-    Scratch scratch = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    Scratch scratch = {};
 
     DeviceGrid view() const
     {
@@ -94,7 +94,8 @@ struct plogp_grid {
     void free_scratch()
     {
         double **all[] = {&scratch.g1, &scratch.gs, &scratch.gm, &scratch.sum2, &scratch.blk,
-                          &scratch.part, &scratch.rcp, &scratch.cx, &scratch.cys};
+                          &scratch.pre, &scratch.part, &scratch.rcp, &scratch.cx, &scratch.cys,
+                          &scratch.segC, &scratch.segA, &scratch.segB};
         for (double **p : all) {
             if (*p) (void)hipFree(*p);
             *p = nullptr;
@@ -321,6 +322,7 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
     HIP_TRY(hipDeviceSynchronize());
     g->free_scratch();
     const bool chain = (g->mask & (1u << 11)) != 0, binom = (g->mask & (1u << 12)) != 0;
+    const bool pairs = g->n_s > 0 && g->n_s <= (size_t)SWEEP_M_MAX_S && g->n_P >= 32;
     struct { double **p; size_t count; } want[] = {
         {&g->scratch.g1, n_tables},
         {&g->scratch.gs, n_tables * (g->n_s ? g->n_s : 1)},
@@ -331,6 +333,10 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
         {&g->scratch.rcp, g->n_s ? g->n_s : 1},
         {&g->scratch.cx, chain ? n_tables * (n_samples + 3) : 1},
         {&g->scratch.cys, chain ? n_tables * (n_samples + 2) * 2 : 1},
+        {&g->scratch.pre, chain && g->n_blk > 32 ? n_tables * g->n_m * (size_t)g->n_blk : 1},
+        {&g->scratch.segC, n_tables * (g->n_s ? g->n_s : 1)},
+        {&g->scratch.segA, pairs ? n_tables * g->n_m * g->n_s : 1},
+        {&g->scratch.segB, pairs ? n_tables * g->n_m * g->n_s : 1},
     };
     for (auto &w : want) {
         hipError_t e = hipMalloc((void **)w.p, w.count * sizeof(double));

@@ -15,6 +15,10 @@ namespace plogp {
 // block totals added in ascending block order.
 constexpr int SUM_BLOCK = 64;
 
+// Most candidates s for which the sweeps that keep s in a lane's loop are used
+// (more: the sweep that runs its lanes over s).
+constexpr int SWEEP_M_MAX_S = 256;
+
 // Device-resident batch of tables.
 struct DeviceTables {
     const double *x;      // [n_tables][n] sample sizes
@@ -48,12 +52,16 @@ struct Scratch {
     double *g1;       // [n_tables]                       g(1)
     double *gs;       // [n_tables][n_s]                  g(s)
     double *gm;       // [n_tables][n_m]                  g(m)
-    double *sum2;     // [n_tables][cl_max+1][n_m]        prefix over j of g(2^j m)
-    double *blk;      // [n_tables][n_blk][n_m]           block totals, then their exclusive prefix
-    double *part;     // [n_tables][n_P][n_m]             in-block partial sums at the grid's P
+    double *sum2;     // [n_tables][n_m][cl_max+1]        prefix over j of g(2^j m)
+    double *blk;      // [n_tables][n_blk][n_m]           totals of the blocks of the chain sum
+    double *pre;      // [n_tables][n_m][n_blk]           their exclusive prefix (more than 32 blocks only)
+    double *part;     // [n_tables][n_m][n_P]             in-block partial sums at the grid's P
     double *rcp;      // [n_s]                            1/s, rounded
     double *cx;       // [n_tables][n+3]                  table as intervals: starts (0, samples, inf, inf)
     double *cys;      // [n_tables][n+2][2]               {gap, slope} per interval
+    double *segC;     // [n_tables][n_s]                  C = g(s) + L
+    double *segA;     // [n_tables][n_m][n_s]             A = g(s) ceil(m/s), +inf where s does not compete
+    double *segB;     // [n_tables][n_m][n_s]             B = g(s) (ceil(m/s) - 1)   (both: n_s <= SWEEP_M_MAX_S only)
     int *nv;          // [n_m]                            candidates s <= min(m, s_cap)
 };
 

@@ -49,6 +49,31 @@ __device__ __forceinline__ double gap_at(const LdsTable &t, double z)
     return __builtin_fma(t.sl[i], zc - t.x[i], t.y[i]);
 }
 
+// g() at four points at once: the four searches run side by side, so that the
+// LDS latencies of one halving step overlap (the step sequence depends on n only).
+__device__ __forceinline__ void gap_at4(const LdsTable &t, const double (&z)[4], double (&g)[4])
+{
+    int lo[4] = {0, 0, 0, 0};
+    int len = t.n;
+    while (len > 1) {
+        const int half = len >> 1;
+        double xv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            xv[u] = t.x[lo[u] + half];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            lo[u] = xv[u] <= z[u] ? lo[u] + half : lo[u];
+        len -= half;
+    }
+    const double x0 = t.x[0];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const double zc = z[u] > x0 ? z[u] : x0;
+        g[u] = __builtin_fma(t.sl[lo[u]], zc - t.x[lo[u]], t.y[lo[u]]);
+    }
+}
+
 __device__ __forceinline__ double interval_slope(const double *x, const double *y, int n, int i)
 {
     const int a = i < n - 1 ? i : n - 2;
@@ -86,6 +111,21 @@ __device__ __forceinline__ int ceil_log2(uint32_t P)
 // integers cannot reach or cross an integer it is not equal to (its error is
 // below 1/s, the smallest possible distance), so ceil() of it is exact.
 __device__ __forceinline__ double segments(u64 m, u64 s) { return ceil((double)m / (double)s); }
+
+// The terms of the segmented rows of Table 1 that depend on (m, s) only:
+//   k = ceil(m/s), A = g(s) k, B = g(s) (k-1), C = g(s) + L.
+// k comes from one multiplication by the rounded reciprocal of s, which can be
+// off by one, and one exact remainder m - k s (an fma) that corrects it.
+__device__ __forceinline__ void segment_terms(double md, double sd, double rcp_s, double gs,
+                                              double L, double &A, double &B, double &C)
+{
+    double k = ceil(md * rcp_s);
+    const double r = __builtin_fma(-k, sd, md);        // exact: m - k s
+    k = r > 0.0 ? k + 1.0 : (r <= -sd ? k - 1.0 : k);
+    A = gs * k;
+    B = gs * (k - 1.0);
+    C = gs + L;
+}
 
 // ---------------------------------------------------------------- slopes (table load)
 
@@ -192,7 +232,8 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
 // candidates that compete for m and the prefix sums over j of g(2^j m) for its
 // rows, g(s) for its candidates and (first table only) the reciprocals 1/s used
 // to get k = ceil(m/s) without a division per (m, s); chunk 0 also g(1).
-__global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks)
+__global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks,
+                                               int with_pairs)
 {
     extern __shared__ double lds[];
     const int t = blockIdx.x / n_chunks, chunk = blockIdx.x % n_chunks;
@@ -231,8 +272,13 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
 
-    const int mi = chunk * blockDim.x + threadIdx.x;
-    if (mi < G.n_m) {
+    // per message size: g(m), the number of candidates, the prefix of g(2^j m).  Groups
+    // of 64 sizes are dealt to the waves of this table's workgroups.
+    const int n_mw = (G.n_m + 63) / 64;
+    for (int mw = chunk * 4 + (int)(threadIdx.x >> 6); mw < n_mw; mw += n_chunks * 4) {
+        const int mi = mw * 64 + (int)(threadIdx.x & 63);
+        if (mi >= G.n_m)
+            continue;
         const u64 m = G.m[mi];
         S.gm[(size_t)t * G.n_m + mi] = gap_at(tab, (double)m);
         if (t == 0) {                  // candidates s <= min(m, s_cap): the list ascends
@@ -245,23 +291,57 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
             S.nv[mi] = lo;
         }
         if (G.mask & (1u << 12)) {
-            double *o = S.sum2 + (size_t)t * (G.cl_max + 1) * G.n_m + mi;     // [d][m]
+            double *o = S.sum2 + ((size_t)t * G.n_m + mi) * (G.cl_max + 1);   // [m][d]
             double acc = 0.0;
             o[0] = 0.0;
-            for (int j = 0; j < G.cl_max; ++j) {
-                acc = acc + gap_at(tab, (double)(m << j));
-                o[(size_t)(j + 1) * G.n_m] = acc;
+            for (int j0 = 0; j0 < G.cl_max; j0 += 4) {
+                double z[4], g[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u < G.cl_max ? j0 + u : G.cl_max - 1;
+                    z[u] = (double)(m << j);
+                }
+                gap_at4(tab, z, g);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (j0 + u < G.cl_max) {
+                        acc = acc + g[u];
+                        o[j0 + u + 1] = acc;
+                    }
+                }
             }
         }
     }
     if (chunk == 0 && threadIdx.x == 0)
         S.g1[t] = gap_at(tab, 1.0);
-    // the candidates are shared out over the chunks of this table
+    // per candidate: g(s), 1/s, C = g(s) + L; shared out over the chunks of this table
+    const double L = T.L[t];
     for (int si = chunk * blockDim.x + threadIdx.x; si < G.n_s; si += n_chunks * blockDim.x) {
         const double sd = (double)G.s[si];
-        S.gs[(size_t)t * G.n_s + si] = gap_at(tab, sd);
+        const double gs = gap_at(tab, sd);
+        S.gs[(size_t)t * G.n_s + si] = gs;
+        S.segC[(size_t)t * G.n_s + si] = gs + L;
         if (t == 0)
             S.rcp[si] = 1.0 / sd;
+    }
+    // per (m, s): A = g(s) k and B = g(s)(k-1) for the sweep that runs its lanes over P
+    // (there they are wave-uniform); +inf where s does not compete
+    if (with_pairs) {
+        const long n_pairs = (long)G.n_m * G.n_s;
+        for (long id = (long)chunk * blockDim.x + threadIdx.x; id < n_pairs;
+             id += (long)n_chunks * blockDim.x) {
+            const int mi = (int)(id / G.n_s), si = (int)(id % G.n_s);
+            const u64 m = G.m[mi], sv = G.s[si];
+            const u64 lim = m < G.s_cap ? m : G.s_cap;
+            double A = INFINITY, B = INFINITY, C;
+            if (sv <= lim) {
+                const double sd = (double)sv;
+                segment_terms((double)m, sd, 1.0 / sd, gap_at(tab, sd), L, A, B, C);
+            }
+            const size_t o = ((size_t)t * G.n_m + mi) * G.n_s + si;
+            S.segA[o] = A;
+            S.segB[o] = B;
+        }
     }
 }
 
@@ -366,7 +446,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     f64x2 nys = {0.0, 0.0};
     chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
     const size_t n_m = (size_t)G.n_m;
-    double *part = S.part + (size_t)t * G.n_P * n_m + mi;       // [P index][m]
+    double *part = S.part + ((size_t)t * n_m + mi) * G.n_P;     // [m][P index]
     double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
     for (int bb = 0; bb < nb; ++bb) {
         const int b = b0 + bb;
@@ -434,7 +514,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
             }
             if (hit == SUM_BLOCK)
                 break;
-            part[(size_t)pi * n_m] = run;
+            part[pi] = run;
             ++pi;
             wanted &= wanted - 1;
         }
@@ -444,51 +524,56 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
     chain_await(nw, nys);                 // nothing in flight when the wave ends
 }
 
-// Turns the block totals of 64 message sizes into their exclusive prefix in
-// ascending block order (the sum of all finished blocks before block b).  The
-// sum itself is sequential per m; what a lane can do on its own is bounded by
-// the memory latency of its few loads in flight, so the whole workgroup moves
-// tiles of PFX_TILE blocks x 64 m through LDS (every thread 64 loads in flight)
-// and wave 0 scans a tile from there.
+// Turns the block totals of PFX_M message sizes into their exclusive prefix in
+// ascending block order (the sum of all finished blocks before block b) and
+// writes it transposed, pre[m][b], which is how the sweeps read it.  The sum is
+// sequential per m; the workgroup moves tiles of PFX_TILE blocks through LDS
+// (every thread 16 loads in flight) and the first PFX_M lanes scan a tile there.
 constexpr int PFX_TILE = 256;
+constexpr int PFX_M = 16;
 
 __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, int n_mgroups)
 {
-    extern __shared__ double pfx_tile[];                 // [PFX_TILE][64]
+    __shared__ double tile[PFX_TILE * (PFX_M + 1)];      // [block][m], rows padded by one
     const int t = blockIdx.x / n_mgroups, mg = blockIdx.x % n_mgroups;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int mi = mg * 64 + lane;
+    const int tid = threadIdx.x;
+    const int ml = tid % PFX_M, br = tid / PFX_M;        // br: 0 .. 256 / PFX_M - 1
+    constexpr int ROWS = 256 / PFX_M;                    // rows of the tile loaded per pass
+    const int mi = mg * PFX_M + ml;
     const bool active = mi < G.n_m;
     const size_t n_m = (size_t)G.n_m;
-    double *p = S.blk + (size_t)t * G.n_blk * n_m + (active ? mi : 0);
+    const double *src = S.blk + (size_t)t * G.n_blk * n_m + (active ? mi : 0);
     const int full = G.n_blk - 1;                        // blocks that have a total
     double done = 0.0;
     for (int b0 = 0; b0 < G.n_blk; b0 += PFX_TILE) {
-        double v[PFX_TILE / 4];
+        double v[PFX_TILE / ROWS];
 #pragma unroll
-        for (int k = 0; k < PFX_TILE / 4; ++k) {
-            const int b = b0 + w + 4 * k;
-            v[k] = (active && b < full) ? p[(size_t)b * n_m] : 0.0;
+        for (int k = 0; k < PFX_TILE / ROWS; ++k) {
+            const int b = b0 + br + ROWS * k;
+            v[k] = (active && b < full) ? src[(size_t)b * n_m] : 0.0;
         }
 #pragma unroll
-        for (int k = 0; k < PFX_TILE / 4; ++k)
-            pfx_tile[(w + 4 * k) * 64 + lane] = v[k];
+        for (int k = 0; k < PFX_TILE / ROWS; ++k)
+            tile[(br + ROWS * k) * (PFX_M + 1) + ml] = v[k];
         __syncthreads();
-        if (w == 0) {
+        if (tid < PFX_M) {
             const int nb = G.n_blk - b0 < PFX_TILE ? G.n_blk - b0 : PFX_TILE;
 #pragma unroll 8
             for (int bb = 0; bb < nb; ++bb) {
-                const double tot = pfx_tile[bb * 64 + lane];
-                pfx_tile[bb * 64 + lane] = done;
+                const double tot = tile[bb * (PFX_M + 1) + tid];
+                tile[bb * (PFX_M + 1) + tid] = done;
                 done = done + tot;
             }
         }
         __syncthreads();
-#pragma unroll
-        for (int k = 0; k < PFX_TILE / 4; ++k) {
-            const int b = b0 + w + 4 * k;
-            if (active && b < G.n_blk)
-                p[(size_t)b * n_m] = pfx_tile[(w + 4 * k) * 64 + lane];
+        // thread tid writes block b0 + tid of every m: runs of up to 2 KB per m
+        if (b0 + tid < G.n_blk) {
+#pragma unroll 4
+            for (int mm = 0; mm < PFX_M; ++mm) {
+                const int m2 = mg * PFX_M + mm;
+                if (m2 < G.n_m)
+                    S.pre[((size_t)t * n_m + m2) * G.n_blk + b0 + tid] = tile[tid * (PFX_M + 1) + mm];
+            }
         }
         __syncthreads();
     }
@@ -521,21 +606,6 @@ __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
     u.c.s = b.s;
     u.c.strategy = b.id;
     *reinterpret_cast<uint4 *>(p) = u.v;
-}
-
-// The terms of the segmented rows of Table 1 that depend on (m, s) only:
-//   k = ceil(m/s), A = g(s) k, B = g(s) (k-1), C = g(s) + L.
-// k comes from one multiplication by the rounded reciprocal of s, which can be
-// off by one, and one exact remainder m - k s (an fma) that corrects it.
-__device__ __forceinline__ void segment_terms(double md, double sd, double rcp_s, double gs,
-                                              double L, double &A, double &B, double &C)
-{
-    double k = ceil(md * rcp_s);
-    const double r = __builtin_fma(-k, sd, md);        // exact: m - k s
-    k = r > 0.0 ? k + 1.0 : (r <= -sd ? k - 1.0 : k);
-    A = gs * k;
-    B = gs * (k - 1.0);
-    C = gs + L;
 }
 
 // Broadcast: the ten rows of Table 1 in id order, strict '<' (ties: lowest id).
@@ -585,16 +655,16 @@ __device__ __forceinline__ double chain_sum_of(const DeviceGrid &G, const Scratc
 {
     const size_t n_m = (size_t)G.n_m;
     const int blk = (int)((P - 1u) / SUM_BLOCK);
-    const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
     double done;
     if (G.blk_is_prefix) {
-        done = tot[(size_t)blk * n_m];
+        done = S.pre[((size_t)t * n_m + mi) * G.n_blk + blk];
     } else {                           // few blocks: add the finished ones here, in ascending order
+        const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
         done = 0.0;
         for (int b = 0; b < blk; ++b)
             done = done + tot[(size_t)b * n_m];
     }
-    return done + S.part[((size_t)t * G.n_P + pi) * n_m + mi];
+    return done + S.part[((size_t)t * n_m + mi) * G.n_P + pi];
 }
 
 // Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
@@ -655,7 +725,6 @@ __device__ __forceinline__ void first_s_of_flat_or_binomial(
 // process counts.  Per (P, s) and segmented row: one fma, one compare, the
 // running minimum and the index of the candidate that attained it (strict '<'
 // in ascending s: ties go to the smallest s).
-constexpr int SWEEP_M_MAX_S = 256;      // candidates the lane-per-m sweep stages in LDS
 
 template <int PC>
 __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, Scratch S,
@@ -753,9 +822,10 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
     if (mask & (1u << 11)) {
         const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
         if (G.blk_is_prefix) {
+            const double *pre = S.pre + ((size_t)t * n_m + mi) * G.n_blk;
 #pragma unroll
             for (int p = 0; p < PC; ++p)
-                done[p] = tot[(size_t)((Pv[p] - 1u) / SUM_BLOCK) * n_m];
+                done[p] = pre[(Pv[p] - 1u) / SUM_BLOCK];
         } else {
             // few blocks (at most 32): the totals are added here, in ascending order; the
             // P of the chunk ascend, so one pass over the blocks serves all of them, and
@@ -790,9 +860,9 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         const int pi = pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1;
         s11[p] = s12[p] = 0.0;
         if (mask & (1u << 11))
-            s11[p] = done[p] + S.part[((size_t)t * G.n_P + pi) * n_m + mi];
+            s11[p] = done[p] + S.part[((size_t)t * n_m + mi) * G.n_P + pi];
         if (mask & (1u << 12))
-            s12[p] = S.sum2[((size_t)t * (G.cl_max + 1) + ceil_log2(Pv[p])) * n_m + mi];
+            s12[p] = S.sum2[((size_t)t * n_m + mi) * (G.cl_max + 1) + ceil_log2(Pv[p])];
         s5[p] = b5[p] < INFINITY ? (uint32_t)sS[i5[p]] : 0u;
     }
     Best bc[PC];
@@ -867,6 +937,169 @@ __device__ __forceinline__ double wave_min(double v)
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
     return __hiloint2double(hi, lo);
+}
+
+// ---- sweep, few candidates, many process counts: one lane per P -----------------
+//
+// A wave takes 64 consecutive process counts of the grid (its lanes) and walks
+// over message sizes.  Everything that depends on (m, s) only -- A, B (from
+// k_terms), C, the candidate count, g(m) -- is the same in all lanes then: per
+// candidate the lanes do one fma, one compare, the index select and the running
+// minimum for row 5 of Table 1; min_s A for rows 2 and 9 is one reduction over the
+// wave per m.  A cell costs two coalesced 16-byte stores.  The sizes of a wave lie
+// n_w apart, so every wave meets the same mix of short and long candidate lists;
+// the loads for the next size are issued before the current one is worked on.
+// NSV: candidates per lane when a row of (m, s) terms is moved (n_s <= 64 NSV).
+template <int NSV>
+__global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, Scratch S,
+                                                 plogp_cell_dev *out, int n_pg, int n_w)
+{
+    __shared__ double sC[64 * NSV];                  // g(s) + L
+    __shared__ uint32_t sSv[64 * NSV];               // s
+    __shared__ double rowA[4][64 * NSV], rowB[4][64 * NSV];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int bid = blockIdx.x;
+    const int n_wq = (n_w + 3) / 4;
+    const int wq = bid % n_wq;
+    bid /= n_wq;
+    const int pg = bid % n_pg;
+    const int t = bid / n_pg;
+    for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
+        sC[si] = S.segC[(size_t)t * G.n_s + si];
+        sSv[si] = (uint32_t)G.s[si];
+    }
+    __syncthreads();
+    const int w = wq * 4 + wave;
+    if (w >= n_w || w >= G.n_m)
+        return;
+
+    const uint32_t mask = G.mask;
+    const int n_P = G.n_P, n_s = G.n_s, n_blk = G.n_blk;
+    const size_t n_m = (size_t)G.n_m;
+    const int pi = pg * 64 + lane;
+    const bool active = pi < n_P;
+    const uint32_t Pv = G.P[active ? pi : n_P - 1];
+    const double q = (double)(Pv - 1u);
+    const int cli = ceil_log2(Pv);
+    const double fl = (double)floor_log2(Pv), cl = (double)cli;
+    const int blk = (int)((Pv - 1u) / SUM_BLOCK);
+    const double L = T.L[t];
+    const double clL = cl * L;
+    const double g1 = S.g1[t];
+    const bool chain = (mask & (1u << 11)) != 0, binom = (mask & (1u << 12)) != 0;
+    const bool seg = (mask & 0x224u) != 0 && n_s > 0;
+    // the largest block index among the lanes (the P of the grid ascend)
+    const int last_lane = (n_P - pg * 64 < 64 ? n_P - pg * 64 : 64) - 1;
+    const int bmax = __builtin_amdgcn_readlane(blk, last_lane);
+    const size_t plane = n_m * n_P;
+    plogp_cell_dev *const obase = out + (size_t)t * G.n_ops * plane + pi;
+
+    // what is fetched one size ahead
+    double fA[NSV], fB[NSV], f_part = 0.0, f_s12 = 0.0, f_done = 0.0, f_gm;
+    int f_nv;
+    auto fetch = [&](int mi) {
+        const size_t row = (size_t)t * n_m + mi;
+        f_gm = S.gm[row];
+        f_nv = S.nv[mi];
+        if (seg) {
+#pragma unroll
+            for (int k = 0; k < NSV; ++k) {
+                const int si = lane + 64 * k;
+                fA[k] = si < n_s ? S.segA[row * n_s + si] : INFINITY;
+                fB[k] = si < n_s ? S.segB[row * n_s + si] : INFINITY;
+            }
+        }
+        if (chain) {
+            f_part = S.part[row * n_P + (active ? pi : n_P - 1)];
+            if (G.blk_is_prefix)
+                f_done = S.pre[row * n_blk + blk];
+            else                       // few blocks: lane b holds the total of block b
+                f_done = lane < n_blk - 1 ? S.blk[((size_t)t * n_blk + lane) * n_m + mi] : 0.0;
+        }
+        if (binom)
+            f_s12 = S.sum2[row * (G.cl_max + 1) + cli];
+    };
+    fetch(w);
+    for (int mi = w; mi < (int)n_m; mi += n_w) {
+        const double gm = f_gm, part = f_part, s12 = f_s12, dn = f_done;
+        const int nv = f_nv;
+        double a_lane = INFINITY;
+        if (seg) {
+#pragma unroll
+            for (int k = 0; k < NSV; ++k) {
+                rowA[wave][lane + 64 * k] = fA[k];
+                rowB[wave][lane + 64 * k] = fB[k];
+                a_lane = min_f64(a_lane, fA[k]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (mi + n_w < (int)n_m)
+            fetch(mi + n_w);
+
+        // row 5: min over s of fma(q, C, B), first candidate that attains it
+        double b5 = INFINITY;
+        int i5 = 0;
+        if (mask & 0x20u) {
+#pragma unroll 4
+            for (int si = 0; si < nv; ++si) {
+                const double T5 = __builtin_fma(q, sC[si], rowB[wave][si]);
+                i5 = T5 < b5 ? si : i5;
+                b5 = min_f64(b5, T5);
+            }
+        }
+        const double amin = seg ? wave_min(a_lane) : INFINITY;
+        const uint32_t s5 = b5 < INFINITY ? sSv[i5] : 0u;
+
+        plogp_cell_dev *o = obase + (size_t)mi * n_P;
+        if (mask & 0x3FFu) {
+            const double t2 = amin < INFINITY ? __builtin_fma(q, amin, L) : INFINITY;
+            const double t9 = amin < INFINITY ? __builtin_fma(fl, amin, clL) : INFINITY;
+            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
+            // a winning row 2 or 9: the first candidate whose value equals the minimum
+            bool open = active && (bc.id == 2u || bc.id == 9u);
+            if (__ballot(open) != 0) {
+                const double mul = bc.id == 2u ? q : fl, add = bc.id == 2u ? L : clL;
+                uint32_t found = 0u;
+                for (int si = 0; si < nv; ++si) {
+                    const bool hit = open && __builtin_fma(mul, rowA[wave][si], add) == bc.t;
+                    found = hit ? sSv[si] : found;
+                    open = open && !hit;
+                    if (__ballot(open) == 0)
+                        break;
+                }
+                if (bc.id == 2u || bc.id == 9u)
+                    bc.s = found;
+            }
+            if (active)
+                store_cell(o, bc);
+            o += plane;
+        }
+        if (mask & 0x1C00u) {
+            double s11 = 0.0;
+            if (chain) {
+                double done = dn;
+                if (!G.blk_is_prefix) {
+                    // the finished blocks are added in ascending order, the same sum in
+                    // every lane; a lane keeps the value that belongs to its own block
+                    double acc = 0.0;
+                    done = 0.0;
+                    for (int b = 0; b < bmax; ++b) {
+                        const double v = __hiloint2double(
+                            __builtin_amdgcn_readlane(__double2hiint(dn), b),
+                            __builtin_amdgcn_readlane(__double2loint(dn), b));
+                        acc = acc + v;
+                        done = blk == b + 1 ? acc : done;
+                    }
+                }
+                s11 = done + part;
+            }
+            if (active)
+                store_cell(o, decide_scatter(mask, q, cl, gm, L, s11, s12));
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 constexpr int SWEEP_S_CHUNK = 1024;     // candidates staged in LDS per pass (16 per lane)
@@ -1105,7 +1338,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     if (mask & 0x1C00u) {
         const double s11 = (mask & (1u << 11)) ? chain_sum_of(G, S, t, mi, pi, Pv) : 0.0;
         const double s12 = (mask & (1u << 12))
-            ? S.sum2[((size_t)t * (G.cl_max + 1) + cli) * (size_t)G.n_m + mi] : 0.0;
+            ? S.sum2[((size_t)t * G.n_m + mi) * (size_t)(G.cl_max + 1) + cli] : 0.0;
         store_cell(o, decide_scatter(mask, qv, (double)cli, gm, L, s11, s12));
     }
 }
@@ -1394,10 +1627,6 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChainLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_prefix),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)(PFX_TILE * 64 * sizeof(double)));
-    if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     return e;
@@ -1463,10 +1692,19 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(4);
         return hipSuccess;
     }
-    const int n_items = G.n_m > G.n_s ? G.n_m : G.n_s;     // a lane takes one m and one s
-    const int n_chunks = (n_items + 255) / 256;
+    // which sweep runs: lanes over s for many candidates, else lanes over P if the grid
+    // has enough process counts to fill a wave, else lanes over m
+    const bool lanes_s = G.n_s > SWEEP_M_MAX_S;
+    const bool lanes_p = !lanes_s && G.n_P >= 32;
+    long n_items = G.n_m > G.n_s ? G.n_m : G.n_s;          // a lane takes one m and one s ...
+    if (lanes_p && (long)G.n_m * G.n_s > n_items)
+        n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
+    long n_chunks_l = (n_items + 255) / 256;
+    const long chunk_cap = 512 / T.n_tables > 1 ? 512 / T.n_tables : 1;
+    if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
+    const int n_chunks = (int)n_chunks_l;
     hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
-                       S, n_chunks);
+                       S, n_chunks, lanes_p ? 1 : 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(1);
 
@@ -1485,9 +1723,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
-            const int n_mgroups = (G.n_m + 63) / 64;
-            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256),
-                               (size_t)PFX_TILE * 64 * sizeof(double), st, G, S, n_mgroups);
+            const int n_mgroups = (G.n_m + PFX_M - 1) / PFX_M;
+            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256), 0,
+                               st, G, S, n_mgroups);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         PLOGP_MARK(3);
@@ -1496,7 +1734,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(3);
     }
 
-    if (G.n_s > SWEEP_M_MAX_S) {
+    if (lanes_s) {
         // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
         // process counts per wave are chosen so that one workgroup covers all of them if
         // it can
@@ -1511,6 +1749,21 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * n_ptiles), dim3(64 * waves), 0, st, T, G, S,
                                d_out, n_ptiles);
         }
+    } else if (lanes_p) {
+        // as many waves as the chip holds at four per SIMD, shared out over the tables and
+        // the groups of 64 process counts; each walks over every n_w-th message size
+        const int n_pg = (G.n_P + 63) / 64;
+        long n_w = 4096 / ((long)T.n_tables * n_pg);
+        if (n_w > G.n_m) n_w = G.n_m;
+        if (n_w < 1) n_w = 1;
+        n_w = (n_w + 3) / 4 * 4;
+        const unsigned blocks = (unsigned)(T.n_tables * (long)n_pg * (n_w / 4));
+        if (G.n_s <= 64)
+            hipLaunchKernelGGL(k_sweep_p<1>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
+                               (int)n_w);
+        else
+            hipLaunchKernelGGL(k_sweep_p<4>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
+                               (int)n_w);
     } else {
         constexpr int PC = 4;
         const int n_mg = (G.n_m + 63) / 64;
