@@ -954,9 +954,11 @@ template <int NSV>
 __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, Scratch S,
                                                  plogp_cell_dev *out, int n_pg, int n_w)
 {
-    __shared__ double sC[64 * NSV];                  // g(s) + L
-    __shared__ uint32_t sSv[64 * NSV];               // s
-    __shared__ double rowA[4][64 * NSV], rowB[4][64 * NSV];
+    // the loops below read up to 7 entries past the last candidate: rows are 8 longer
+    constexpr int ROW = 64 * NSV + 8;
+    __shared__ double sC[ROW];                       // g(s) + L (0 past the end)
+    __shared__ uint32_t sSv[ROW];                    // s
+    __shared__ double rowA[4][ROW], rowB[4][ROW];    // A, B of the current size (+inf past the end)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int bid = blockIdx.x;
@@ -965,9 +967,14 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     bid /= n_wq;
     const int pg = bid % n_pg;
     const int t = bid / n_pg;
-    for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
-        sC[si] = S.segC[(size_t)t * G.n_s + si];
-        sSv[si] = (uint32_t)G.s[si];
+    for (int si = threadIdx.x; si < ROW; si += blockDim.x) {
+        sC[si] = si < G.n_s ? S.segC[(size_t)t * G.n_s + si] : 0.0;
+        sSv[si] = si < G.n_s ? (uint32_t)G.s[si] : 0u;
+        if (si >= 64 * NSV) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                rowA[k][si] = rowB[k][si] = INFINITY;
+        }
     }
     __syncthreads();
     const int w = wq * 4 + wave;
@@ -989,9 +996,13 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     const double g1 = S.g1[t];
     const bool chain = (mask & (1u << 11)) != 0, binom = (mask & (1u << 12)) != 0;
     const bool seg = (mask & 0x224u) != 0 && n_s > 0;
+    // every Broadcast row enabled and rendezvous no cheaper than a plain send: rows 1,
+    // 4, 8 are never below rows 0, 3, 7 (rounding is monotone) and lose ties to them
+    const bool plain_rows = (mask & 0x3FFu) == 0x3FFu && __builtin_fma(3.0, L, 2.0 * g1) >= L;
     // the largest block index among the lanes (the P of the grid ascend)
     const int last_lane = (n_P - pg * 64 < 64 ? n_P - pg * 64 : 64) - 1;
     const int bmax = __builtin_amdgcn_readlane(blk, last_lane);
+    const int bmin = __builtin_amdgcn_readfirstlane(blk);
     const size_t plane = n_m * n_P;
     plogp_cell_dev *const obase = out + (size_t)t * G.n_ops * plane + pi;
 
@@ -1042,11 +1053,21 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         double b5 = INFINITY;
         int i5 = 0;
         if (mask & 0x20u) {
-#pragma unroll 4
-            for (int si = 0; si < nv; ++si) {
-                const double T5 = __builtin_fma(q, sC[si], rowB[wave][si]);
-                i5 = T5 < b5 ? si : i5;
-                b5 = min_f64(b5, T5);
+            // eight candidates per round trip to LDS; past the last competing one B is
+            // +inf (and C is finite), so the value is +inf and never taken
+            for (int s0 = 0; s0 < nv; s0 += 8) {
+                double Bv[8], Cv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    Bv[u] = rowB[wave][s0 + u];
+                    Cv[u] = sC[s0 + u];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const double T5 = __builtin_fma(q, Cv[u], Bv[u]);
+                    i5 = T5 < b5 ? s0 + u : i5;
+                    b5 = min_f64(b5, T5);
+                }
             }
         }
         const double amin = seg ? wave_min(a_lane) : INFINITY;
@@ -1054,18 +1075,54 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
 
         plogp_cell_dev *o = obase + (size_t)mi * n_P;
         if (mask & 0x3FFu) {
+            const double gmL = gm + L, gm2L = __builtin_fma(2.0, gm, L);
             const double t2 = amin < INFINITY ? __builtin_fma(q, amin, L) : INFINITY;
             const double t9 = amin < INFINITY ? __builtin_fma(fl, amin, clL) : INFINITY;
-            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
+            Best bc;
+            if (plain_rows) {
+                // rows 0, 2, 3, 5, 6, 7, 9 compete (the rendezvous rows cannot win): the
+                // running minimum and the id of the first row that attains it
+                const double v0 = __builtin_fma(q, gm, L), v3 = q * gmL, v6 = cl * gm2L;
+                const double v7 = __builtin_fma(fl, gm, clL);
+                double best = v0;
+                uint32_t id = 0u;
+                id = t2 < best ? 2u : id;
+                best = min_f64(best, t2);
+                id = v3 < best ? 3u : id;
+                best = min_f64(best, v3);
+                id = b5 < best ? 5u : id;
+                best = min_f64(best, b5);
+                id = v6 < best ? 6u : id;
+                best = min_f64(best, v6);
+                id = v7 < best ? 7u : id;
+                best = min_f64(best, v7);
+                id = t9 < best ? 9u : id;
+                best = min_f64(best, t9);
+                bc.t = best;
+                bc.id = id;
+                bc.s = id == 5u ? s5 : 0u;
+            } else {
+                bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
+            }
             // a winning row 2 or 9: the first candidate whose value equals the minimum
             bool open = active && (bc.id == 2u || bc.id == 9u);
             if (__ballot(open) != 0) {
                 const double mul = bc.id == 2u ? q : fl, add = bc.id == 2u ? L : clL;
                 uint32_t found = 0u;
-                for (int si = 0; si < nv; ++si) {
-                    const bool hit = open && __builtin_fma(mul, rowA[wave][si], add) == bc.t;
-                    found = hit ? sSv[si] : found;
-                    open = open && !hit;
+                for (int s0 = 0; s0 < nv; s0 += 4) {     // past the last candidate A is +inf
+                    double Av[4];
+                    uint32_t Sv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        Av[u] = rowA[wave][s0 + u];
+                        Sv[u] = sSv[s0 + u];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const bool hit = open && __builtin_fma(mul, Av[u], add) == bc.t;
+                        found = hit ? Sv[u] : found;
+                        open = open && !hit;
+                    }
                     if (__ballot(open) == 0)
                         break;
                 }
@@ -1084,12 +1141,15 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                     // the finished blocks are added in ascending order, the same sum in
                     // every lane; a lane keeps the value that belongs to its own block
                     double acc = 0.0;
-                    done = 0.0;
-                    for (int b = 0; b < bmax; ++b) {
-                        const double v = __hiloint2double(
-                            __builtin_amdgcn_readlane(__double2hiint(dn), b),
-                            __builtin_amdgcn_readlane(__double2loint(dn), b));
-                        acc = acc + v;
+                    for (int b = 0; b < bmin; ++b)
+                        acc = acc + __hiloint2double(
+                                        __builtin_amdgcn_readlane(__double2hiint(dn), b),
+                                        __builtin_amdgcn_readlane(__double2loint(dn), b));
+                    done = acc;                  // lanes of block bmin
+                    for (int b = bmin; b < bmax; ++b) {
+                        acc = acc + __hiloint2double(
+                                        __builtin_amdgcn_readlane(__double2hiint(dn), b),
+                                        __builtin_amdgcn_readlane(__double2loint(dn), b));
                         done = blk == b + 1 ? acc : done;
                     }
                 }
