@@ -389,15 +389,19 @@ __device__ __forceinline__ void settle(double &a, double &b, double &c, double &
     asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(e));
 }
 
-__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bgroups,
-                               int n_mchunks, int nb)
+// Work items: (unit u, group of 64 sizes mg).  Unit u is block u alone for the
+// first CHAIN_SINGLE blocks (small j: the walk crosses many intervals per term, so
+// those are the heavy ones), then nb consecutive blocks.  Item i = u * n_mg + mg
+// belongs to workgroup i mod wg_per_table of its table, so every workgroup gets
+// its share of the heavy items and meets them first; inside a workgroup the waves
+// take the next item of that list from a counter in LDS, because how long an item
+// takes depends on how often its sizes cross an interval.
+__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
+                               int n_units, int nb)
 {
     extern __shared__ __align__(16) double chain_lds[];
-    int bid = blockIdx.x;
-    const int mc = bid % n_mchunks;
-    bid /= n_mchunks;
-    const int bg = bid % n_bgroups;
-    const int t = bid / n_bgroups;
+    __shared__ unsigned next_item;
+    const int t = blockIdx.x / wg_per_table, wg = blockIdx.x % wg_per_table;
     const int n = T.n;
     // Table as intervals (written by k_terms): YS[0..n+1] = {gap, slope}, X[0..n+2] =
     // interval starts.  Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0
@@ -419,109 +423,120 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int n_bg
                 W[i] = i < n ? gx[i + 1] - x0 : INFINITY;
             }
         }
+        if (threadIdx.x == 0)
+            next_item = 0u;
     }
     __syncthreads();
-    // The waves of a workgroup take groups of 64 sizes that lie n_mchunks groups apart:
-    // how often the walk crosses an interval depends on the magnitude of m, and this
-    // way every workgroup (and every SIMD in it) gets the same mix.
-    const int mi = ((int)(threadIdx.x >> 6) * n_mchunks + mc) * 64 + (int)(threadIdx.x & 63);
-    if (mi >= G.n_m)
-        return;
-    const u64 m = G.m[mi];
-    const double md = (double)m;
-    // the first blocks (small j, where the walk crosses many intervals per term)
-    // go one per lane, the others nb per lane
-    const int b0 = bg < CHAIN_SINGLE ? bg : CHAIN_SINGLE + (bg - CHAIN_SINGLE) * nb;
-    if (bg < CHAIN_SINGLE)
-        nb = 1;
-    const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
-    // interval of z0: number of samples not above z0 (0 = the virtual interval)
-    int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
-    double d = z0 - X[i];                 // d = z - start of the interval (exact)
-    double w = W[i];                      // width of the interval
-    double yi = YS[i].x, si = YS[i].y;
-    settle(d, w, yi, si);
+    const int lane = threadIdx.x & 63;
+    const int n_mg = (G.n_m + 63) / 64;
+    const unsigned n_items = (unsigned)n_units * (unsigned)n_mg;
+    // items of this workgroup: wg, wg + wg_per_table, ...
+    const unsigned my_items = n_items > (unsigned)wg ? (n_items - wg + wg_per_table - 1) / wg_per_table : 0u;
     const unsigned w_lds = (unsigned)(uintptr_t)W, ys_lds = (unsigned)(uintptr_t)YS;
+    const size_t n_m = (size_t)G.n_m;
     double nw = 0.0;                      // the next interval, fetched ahead
     f64x2 nys = {0.0, 0.0};
-    chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
-    const size_t n_m = (size_t)G.n_m;
-    double *part = S.part + ((size_t)t * n_m + mi) * G.n_P;     // [m][P index]
-    double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
-    for (int bb = 0; bb < nb; ++bb) {
-        const int b = b0 + bb;
-        if (b >= G.n_blk)
+    for (;;) {
+        unsigned k = 0;
+        if (lane == 0)
+            k = atomicAdd(&next_item, 1u);
+        k = __builtin_amdgcn_readfirstlane(k);
+        if (k >= my_items)
             break;
-        const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
-        u64 wanted = G.blk_mask[b];         // bit r: some grid P needs the sum after r terms
-        int pi = G.blk_off[b];
-        double run = 0.0;
-        int jj = 0;
-        for (;;) {
-            // run without any bookkeeping up to the next point where a sum is wanted
-            int hit = wanted != 0 ? __builtin_ctzll(wanted) : SUM_BLOCK;
-            if (hit > nterms)
-                hit = SUM_BLOCK;
-            const int stop = hit < nterms ? hit : nterms;
-            for (; jj < stop; ++jj) {
-                if (d >= w) {               // crossed into the next interval (fetched ahead)
-                    chain_await(nw, nys);
-                    d -= w;
-                    w = nw;
-                    yi = nys.x;
-                    si = nys.y;
-                    ++i;
-                    if (d >= w) {
-                        // dense part of the table (small j): z is several intervals on.
-                        // e = z - end of interval i.  Look four intervals ahead a few
-                        // times, then search the rest of the table for z = xb + e
-                        // (exact: integers below 2^53).
-                        double xb = X[i + 1];
-                        double e = d - w;
-                        int hops = 0;
-                        for (;;) {
-                            const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
-                            const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
-                            if (e >= r4) {
-                                if (++hops == 3) {
-                                    const double z = xb + e;
-                                    // samples not above z = index of its interval
-                                    i = last_not_above(X + 1, n, z) + 1;
-                                    d = z - X[i];
-                                    break;
-                                }
-                                i += 4;
-                                e -= r4;
-                                xb += r4;
-                                continue;
-                            }
-                            const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
-                            const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
-                            d = e - lo;
-                            i += 1 + c;
-                            break;
-                        }
-                        const f64x2 ys = YS[i];
-                        w = W[i];
-                        yi = ys.x;
-                        si = ys.y;
-                        settle(d, w, yi, si);
-                    }
-                    chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
-                }
-                run = run + __builtin_fma(si, d, yi);
-                d += md;
-            }
-            if (hit == SUM_BLOCK)
+        const unsigned item = (unsigned)wg + k * (unsigned)wg_per_table;
+        const int u = (int)(item / (unsigned)n_mg), mg = (int)(item % (unsigned)n_mg);
+        const int mi = mg * 64 + lane;
+        if (mi >= G.n_m)
+            continue;
+        const int b0 = u < CHAIN_SINGLE ? u : CHAIN_SINGLE + (u - CHAIN_SINGLE) * nb;
+        const int nbl = u < CHAIN_SINGLE ? 1 : nb;
+        const u64 m = G.m[mi];
+        const double md = (double)m;
+        const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
+        // interval of z0: number of samples not above z0 (0 = the virtual interval)
+        int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
+        double d = z0 - X[i];                 // d = z - start of the interval (exact)
+        double w = W[i];                      // width of the interval
+        double yi = YS[i].x, si = YS[i].y;
+        settle(d, w, yi, si);
+        chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
+        double *part = S.part + ((size_t)t * n_m + mi) * G.n_P;     // [m][P index]
+        double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
+        for (int bb = 0; bb < nbl; ++bb) {
+            const int b = b0 + bb;
+            if (b >= G.n_blk)
                 break;
-            part[pi] = run;
-            ++pi;
-            wanted &= wanted - 1;
+            const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
+            u64 wanted = G.blk_mask[b];         // bit r: some grid P needs the sum after r terms
+            int pi = G.blk_off[b];
+            double run = 0.0;
+            int jj = 0;
+            for (;;) {
+                // run without any bookkeeping up to the next point where a sum is wanted
+                int hit = wanted != 0 ? __builtin_ctzll(wanted) : SUM_BLOCK;
+                if (hit > nterms)
+                    hit = SUM_BLOCK;
+                const int stop = hit < nterms ? hit : nterms;
+                for (; jj < stop; ++jj) {
+                    if (d >= w) {               // crossed into the next interval (fetched ahead)
+                        chain_await(nw, nys);
+                        d -= w;
+                        w = nw;
+                        yi = nys.x;
+                        si = nys.y;
+                        ++i;
+                        if (d >= w) {
+                            // dense part of the table (small j): z is several intervals on.
+                            // e = z - end of interval i.  Look four intervals ahead a few
+                            // times, then search the rest of the table for z = xb + e
+                            // (exact: integers below 2^53).
+                            double xb = X[i + 1];
+                            double e = d - w;
+                            int hops = 0;
+                            for (;;) {
+                                const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
+                                const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
+                                if (e >= r4) {
+                                    if (++hops == 3) {
+                                        const double z = xb + e;
+                                        // samples not above z = index of its interval
+                                        i = last_not_above(X + 1, n, z) + 1;
+                                        d = z - X[i];
+                                        break;
+                                    }
+                                    i += 4;
+                                    e -= r4;
+                                    xb += r4;
+                                    continue;
+                                }
+                                const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
+                                const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
+                                d = e - lo;
+                                i += 1 + c;
+                                break;
+                            }
+                            const f64x2 ys = YS[i];
+                            w = W[i];
+                            yi = ys.x;
+                            si = ys.y;
+                            settle(d, w, yi, si);
+                        }
+                        chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
+                    }
+                    run = run + __builtin_fma(si, d, yi);
+                    d += md;
+                }
+                if (hit == SUM_BLOCK)
+                    break;
+                part[pi] = run;
+                ++pi;
+                wanted &= wanted - 1;
+            }
+            if (nterms == SUM_BLOCK)
+                tot[(size_t)b * n_m] = run;
         }
-        if (nterms == SUM_BLOCK)
-            tot[(size_t)b * n_m] = run;
+        chain_await(nw, nys);             // nothing in flight when the item ends
     }
-    chain_await(nw, nys);                 // nothing in flight when the wave ends
 }
 
 // Turns the block totals of PFX_M message sizes into their exclusive prefix in
@@ -1769,17 +1784,22 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     PLOGP_MARK(1);
 
     if (G.mask & (1u << 11)) {
-        // a big table fills most of the LDS of a CU: one large workgroup per CU then, and
-        // several blocks per lane so that staging the table is amortised
+        // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
+        // stays for its whole share of the work (the table is staged once), and several
+        // blocks per item so that the search at the start of an item is amortised
         const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
         const int nb = big ? 4 : 1;
-        const int n_mchunks = (G.n_m + threads - 1) / threads;
         const int single = G.n_blk < CHAIN_SINGLE ? G.n_blk : CHAIN_SINGLE;
-        const int n_bgroups = single + (G.n_blk - single + nb - 1) / nb;
-        hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)T.n_tables * n_bgroups * n_mchunks),
-                           dim3(threads), chain_lds, st, T, G, S, n_bgroups, n_mchunks, nb);
+        const int n_units = single + (G.n_blk - single + nb - 1) / nb;
+        const long n_items = (long)n_units * ((G.n_m + 63) / 64);
+        long wg = (big ? 256 : 1024) / T.n_tables;
+        const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
+        if (wg > wg_need) wg = wg_need;
+        if (wg < 1) wg = 1;
+        hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)(T.n_tables * wg)), dim3(threads),
+                           chain_lds, st, T, G, S, (int)wg, n_units, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
