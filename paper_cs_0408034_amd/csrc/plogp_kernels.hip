@@ -623,6 +623,15 @@ __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
     *reinterpret_cast<uint4 *>(p) = u.v;
 }
 
+// Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
+// adds a canonicalising v_max_f64 per operand in IEEE mode).
+__device__ __forceinline__ double min_f64(double a, double b)
+{
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Broadcast: the ten rows of Table 1 in id order, strict '<' (ties: lowest id).
 // t2/t5/t9 are the minima over s of the segmented rows (+inf if none), s2/s5/s9
 // the segment sizes that attain them.
@@ -639,6 +648,30 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
     // (lower id: it also wins ties) the rendezvous row cannot be chosen and is not
     // evaluated.
     const bool twin_wins = R >= L;
+    if ((mask & 0x3FFu) == 0x3FFu && twin_wins) {
+        // the usual case, every row enabled: rows 0, 2, 3, 5, 6, 7, 9 compete; the running
+        // minimum and the id of the first row that attains it
+        const double v0 = __builtin_fma(q, gm, L), v3 = q * (gm + L);
+        const double v6 = cl * __builtin_fma(2.0, gm, L), v7 = __builtin_fma(fl, gm, clL);
+        double best = v0;
+        uint32_t id = 0u;
+        id = t2 < best ? 2u : id;
+        best = min_f64(best, t2);
+        id = v3 < best ? 3u : id;
+        best = min_f64(best, v3);
+        id = t5 < best ? 5u : id;
+        best = min_f64(best, t5);
+        id = v6 < best ? 6u : id;
+        best = min_f64(best, v6);
+        id = v7 < best ? 7u : id;
+        best = min_f64(best, v7);
+        id = t9 < best ? 9u : id;
+        best = min_f64(best, t9);
+        b.t = best;
+        b.id = id;
+        b.s = id == 2u ? s2 : (id == 5u ? s5 : (id == 9u ? s9 : 0u));
+        return b;
+    }
     if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
     if ((mask & 2u) && !((mask & 1u) && twin_wins)) consider(b, __builtin_fma(q, gm, R), 1, 0);
     if (mask & (1u << 2)) consider(b, t2, 2, s2);
@@ -680,15 +713,6 @@ __device__ __forceinline__ double chain_sum_of(const DeviceGrid &G, const Scratc
             done = done + tot[(size_t)b * n_m];
     }
     return done + S.part[((size_t)t * n_m + mi) * G.n_P + pi];
-}
-
-// Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
-// adds a canonicalising v_max_f64 per operand in IEEE mode).
-__device__ __forceinline__ double min_f64(double a, double b)
-{
-    double r;
-    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
 }
 
 // Rows 2 and 9 of Table 1 are monotone in A = g(s) k for a fixed P (q >= 1,
@@ -1011,9 +1035,6 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     const double g1 = S.g1[t];
     const bool chain = (mask & (1u << 11)) != 0, binom = (mask & (1u << 12)) != 0;
     const bool seg = (mask & 0x224u) != 0 && n_s > 0;
-    // every Broadcast row enabled and rendezvous no cheaper than a plain send: rows 1,
-    // 4, 8 are never below rows 0, 3, 7 (rounding is monotone) and lose ties to them
-    const bool plain_rows = (mask & 0x3FFu) == 0x3FFu && __builtin_fma(3.0, L, 2.0 * g1) >= L;
     // the largest block index among the lanes (the P of the grid ascend)
     const int last_lane = (n_P - pg * 64 < 64 ? n_P - pg * 64 : 64) - 1;
     const int bmax = __builtin_amdgcn_readlane(blk, last_lane);
@@ -1090,35 +1111,9 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
 
         plogp_cell_dev *o = obase + (size_t)mi * n_P;
         if (mask & 0x3FFu) {
-            const double gmL = gm + L, gm2L = __builtin_fma(2.0, gm, L);
             const double t2 = amin < INFINITY ? __builtin_fma(q, amin, L) : INFINITY;
             const double t9 = amin < INFINITY ? __builtin_fma(fl, amin, clL) : INFINITY;
-            Best bc;
-            if (plain_rows) {
-                // rows 0, 2, 3, 5, 6, 7, 9 compete (the rendezvous rows cannot win): the
-                // running minimum and the id of the first row that attains it
-                const double v0 = __builtin_fma(q, gm, L), v3 = q * gmL, v6 = cl * gm2L;
-                const double v7 = __builtin_fma(fl, gm, clL);
-                double best = v0;
-                uint32_t id = 0u;
-                id = t2 < best ? 2u : id;
-                best = min_f64(best, t2);
-                id = v3 < best ? 3u : id;
-                best = min_f64(best, v3);
-                id = b5 < best ? 5u : id;
-                best = min_f64(best, b5);
-                id = v6 < best ? 6u : id;
-                best = min_f64(best, v6);
-                id = v7 < best ? 7u : id;
-                best = min_f64(best, v7);
-                id = t9 < best ? 9u : id;
-                best = min_f64(best, t9);
-                bc.t = best;
-                bc.id = id;
-                bc.s = id == 5u ? s5 : 0u;
-            } else {
-                bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
-            }
+            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
             // a winning row 2 or 9: the first candidate whose value equals the minimum
             bool open = active && (bc.id == 2u || bc.id == 9u);
             if (__ballot(open) != 0) {
