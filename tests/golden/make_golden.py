@@ -17,6 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
 
 import oracle  # noqa: E402
+from oracle import plogp_cutover  # noqa: E402
 from plogp_workloads import make_workload  # noqa: E402
 
 
@@ -35,6 +36,14 @@ def main():
                 c = out[0, 0, mi, pi]
                 f.write("%d %d %d %d %d %s\n" % (mi, int(wl.m[mi]), int(wl.P[pi]), int(c["strategy"]),
                                                  int(c["s"]), float(c["time"]).hex()))
+    off, runs = plogp_cutover.cutovers(out, wl.m, 0)
+    with open(os.path.join(HERE, "cfg1_cutovers.txt"), "w") as f:
+        f.write("# config 1, Broadcast plane: the runs of equal strategy along m for some P\n")
+        f.write("# P m_from strategy s   (s of the first cell of the run)\n")
+        for pi in (0, 1, 2, 6, 14, 30, 48):
+            for k in range(int(off[pi]), int(off[pi + 1])):      # plane 0, table 0: row index = pi
+                f.write("%d %d %d %d\n" % (int(wl.P[pi]), int(runs["m_from"][k]), int(runs["strategy"][k]),
+                                          int(runs["s"][k])))
 
 
 if __name__ == "__main__":
