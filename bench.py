@@ -61,7 +61,26 @@ def describe(wl):
         wl.name, wl.n_tables, wl.sizes.shape[1], len(wl.m), len(wl.P), len(wl.s), wl.strategy_mask)
 
 
-def roofline_of(stage, work, ms):
+# HBM bytes per launch (fetched + written) of each stage's kernel, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
+# kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
+MEASURED_TRAFFIC = {
+    2: {"terms": 0.139e6 + 0.662e6, "chain_blocks": 0.075e6 + 8.503e6, "sweep": 9.790e6 + 33.546e6},
+    3: {"terms": 0.169e6 + 0.318e6, "chain_blocks": 0.079e6 + 1.081e6,
+        "chain_prefix": 0.577e6 + 0.524e6, "sweep": 3.653e6 + 2.294e6},
+    4: {"sweep": 12.066e6 + 2378.371e6},
+    5: {"terms": 0.761e6 + 3.491e6, "chain_blocks": 0.971e6 + 62.343e6,
+        "chain_prefix": 33.583e6 + 33.554e6, "sweep": 80.749e6 + 93.323e6},
+}
+
+
+def roofline_of(stage, work, ms, traffic=None):
+    r = _roofline_of(stage, work, ms)
+    r["traffic"] = traffic
+    return r
+
+
+def _roofline_of(stage, work, ms):
     w = work[stage]
     t_alu = w["flops"] / FP64_VECTOR_PEAK
     t_hbm = w["bytes"] / HBM_PEAK
@@ -101,11 +120,11 @@ def run_gpu(wl, steps, warmup, profile_reps):
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = max(wall_ms, ev_ms) / steps
-    # per-kernel durations: the same launches with a HIP event between the kernels
-    acc = np.zeros(4)
-    for _ in range(profile_reps):
-        acc += np.array(plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh))
-    stage_ms = dict(zip(STAGES, (acc / max(profile_reps, 1)).tolist()))
+    # per-kernel durations: every kernel launched profile_reps times back to back between two
+    # HIP events on the launch stream; the median of five such rounds
+    rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, profile_reps)
+              for _ in range(5)]
+    stage_ms = dict(zip(STAGES, np.median(np.array(rounds), axis=0).tolist()))
     del out
     grid.free()
     tab.free()
@@ -149,6 +168,7 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
         wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
     ms, stage_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    traffic = MEASURED_TRAFFIC.get(cfg, {}) if mask is None else {}
     if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
         # the single-kernel batch path did every stage inside one launch
         work = {"terms": {"flops": 0, "bytes": 0}, "chain_blocks": {"flops": 0, "bytes": 0},
@@ -165,8 +185,9 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
         "scatter_chain_interps_per_s": c["scatter_chain_interps"] / (ms * 1e-3),
         "steps": steps,
         "stage_ms": stage_ms,
-        "roofline": roofline_of(dominant, work, stage_ms[dominant]),
-        "stage_rooflines": {k: roofline_of(k, work, stage_ms[k]) for k in STAGES if stage_ms[k] > 0},
+        "roofline": roofline_of(dominant, work, stage_ms[dominant], traffic.get(dominant)),
+        "stage_rooflines": {k: roofline_of(k, work, stage_ms[k], traffic.get(k))
+                            for k in STAGES if stage_ms[k] > 0},
     }
     if with_cpu:
         res["cpu_baseline"] = run_cpu(cfg, wl)

@@ -174,17 +174,20 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
                     void *stream);
 
 /*
- * plogp_tune_grid_profile -- the same work as plogp_tune_grid, with a HIP
- * event recorded on `stream` between its kernels; waits for completion and
- * returns the elapsed milliseconds of each stage in stage_ms_out[0..3]:
+ * plogp_tune_grid_profile -- the same work as plogp_tune_grid, measured: every
+ * kernel of the sweep is launched `reps` times back to back (each launch
+ * overwrites its outputs with the same values) between two HIP events on
+ * `stream`; waits for completion and returns the mean milliseconds per launch
+ * of each stage in stage_ms_out[0..3]:
  *   [0] per-table and per-m terms (interval slopes, g(1), g(s), g(m), the
  *       Scatter-binomial prefix sums), [1] Scatter-chain block sums,
  *   [2] Scatter-chain block prefix, [3] sweep + arg-min + decision-table write.
  * A stage that did not run reports 0.  Synchronous.  For measurement only.
- * Errors: as plogp_tune_grid, plus EINVAL for a null stage_ms_out.
+ * Errors: as plogp_tune_grid, plus EINVAL for a null stage_ms_out or reps
+ * outside [1, 10000].
  */
 int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_out,
-                            size_t d_out_bytes, void *stream, float *stage_ms_out);
+                            size_t d_out_bytes, void *stream, int reps, float *stage_ms_out);
 
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);

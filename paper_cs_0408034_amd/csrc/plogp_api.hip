@@ -375,9 +375,9 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
 }
 
 int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_out,
-                            size_t d_out_bytes, void *stream, float *stage_ms_out)
+                            size_t d_out_bytes, void *stream, int reps, float *stage_ms_out)
 {
-    if (!t || !g || !d_out || !stage_ms_out) return PLOGP_EINVAL;
+    if (!t || !g || !d_out || !stage_ms_out || reps < 1 || reps > 10000) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
     if (!use_fused_path(t->view(), g->view())) {
@@ -389,10 +389,13 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     for (int i = 0; i < 5 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
     if (e == hipSuccess)
         e = launch_tune(t->view(), g->view(), g->scratch, reinterpret_cast<plogp_cell_dev *>(d_out),
-                        (hipStream_t)stream, ev);
+                        (hipStream_t)stream, ev, reps);
     if (e == hipSuccess) e = hipEventSynchronize(ev[4]);
     float ms[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
+    for (int i = 0; i < 4 && e == hipSuccess; ++i) {
+        e = hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
+        ms[i] /= (float)reps;
+    }
     for (int i = 0; i < 5; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     if (e != hipSuccess) return device_error(e);

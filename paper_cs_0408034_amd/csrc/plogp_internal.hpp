@@ -78,9 +78,11 @@ hipError_t launch_interp(const DeviceTables &T, int table, const uint64_t *d_z, 
 hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uint64_t *d_m,
                        const uint32_t *d_P, const uint64_t *d_s, size_t n, double *d_out,
                        hipStream_t st);
-// ev: nullptr, or 5 events recorded before the first kernel and after each stage.
+// ev: nullptr, or 5 events recorded before the first kernel and after each stage;
+// reps: launches of every stage between its two events (1 outside measurement).
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
-                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr);
+                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr,
+                       int reps = 1);
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
 

@@ -1741,9 +1741,12 @@ bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
 }
 
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
-                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev)
+                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev, int reps)
 {
+    // reps > 1 (measurement only): every stage is launched reps times back to back
+    // between its two events; each stage overwrites its own outputs with the same values
     hipError_t e;
+    if (reps < 1) reps = 1;
     const size_t tab_lds = (size_t)3 * T.n * sizeof(double);
 #define PLOGP_MARK(i)                                                            \
     do {                                                                         \
@@ -1756,8 +1759,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(2);
         PLOGP_MARK(3);
         const int n_mchunks = (G.n_m + 255) / 256;
-        hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256), tab_lds + 64,
-                           st, T, G, d_out, n_mchunks);
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256),
+                               tab_lds + 64, st, T, G, d_out, n_mchunks);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(4);
         return hipSuccess;
@@ -1773,8 +1777,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const long chunk_cap = 512 / T.n_tables > 1 ? 512 / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
-    hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T, G,
-                       S, n_chunks, lanes_p ? 1 : 0);
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T,
+                           G, S, n_chunks, lanes_p ? 1 : 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(1);
 
@@ -1793,14 +1798,16 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
-        hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)(T.n_tables * wg)), dim3(threads),
-                           chain_lds, st, T, G, S, (int)wg, n_units, nb);
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)(T.n_tables * wg)), dim3(threads),
+                               chain_lds, st, T, G, S, (int)wg, n_units, nb);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
             const int n_mgroups = (G.n_m + PFX_M - 1) / PFX_M;
-            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256), 0,
-                               st, G, S, n_mgroups);
+            for (int r = 0; r < reps; ++r)
+                hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256),
+                                   0, st, G, S, n_mgroups);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         PLOGP_MARK(3);
@@ -1809,42 +1816,44 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(3);
     }
 
-    if (lanes_s) {
-        // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
-        // process counts per wave are chosen so that one workgroup covers all of them if
-        // it can
-        const int waves = 8;
-        const unsigned rows = (unsigned)T.n_tables * G.n_m;
-        if (G.n_P <= 6 * waves) {
-            hipLaunchKernelGGL(k_sweep_s<6>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
-        } else if (G.n_P <= 9 * waves) {
-            hipLaunchKernelGGL(k_sweep_s<9>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
+    for (int r = 0; r < reps; ++r) {
+        if (lanes_s) {
+            // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
+            // process counts per wave are chosen so that one workgroup covers all of them if
+            // it can
+            const int waves = 8;
+            const unsigned rows = (unsigned)T.n_tables * G.n_m;
+            if (G.n_P <= 6 * waves) {
+                hipLaunchKernelGGL(k_sweep_s<6>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
+            } else if (G.n_P <= 9 * waves) {
+                hipLaunchKernelGGL(k_sweep_s<9>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
+            } else {
+                const int n_ptiles = (G.n_P + 12 * waves - 1) / (12 * waves);
+                hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * n_ptiles), dim3(64 * waves), 0, st, T, G, S,
+                                   d_out, n_ptiles);
+            }
+        } else if (lanes_p) {
+            // as many waves as the chip holds at four per SIMD, shared out over the tables and
+            // the groups of 64 process counts; each walks over every n_w-th message size
+            const int n_pg = (G.n_P + 63) / 64;
+            long n_w = 4096 / ((long)T.n_tables * n_pg);
+            if (n_w > G.n_m) n_w = G.n_m;
+            if (n_w < 1) n_w = 1;
+            n_w = (n_w + 3) / 4 * 4;
+            const unsigned blocks = (unsigned)(T.n_tables * (long)n_pg * (n_w / 4));
+            if (G.n_s <= 64)
+                hipLaunchKernelGGL(k_sweep_p<1>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
+                                   (int)n_w);
+            else
+                hipLaunchKernelGGL(k_sweep_p<4>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
+                                   (int)n_w);
         } else {
-            const int n_ptiles = (G.n_P + 12 * waves - 1) / (12 * waves);
-            hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * n_ptiles), dim3(64 * waves), 0, st, T, G, S,
-                               d_out, n_ptiles);
+            constexpr int PC = 4;
+            const int n_mg = (G.n_m + 63) / 64;
+            const int n_pcg = (G.n_P + 4 * PC - 1) / (4 * PC);
+            hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)T.n_tables * n_mg * n_pcg), dim3(256), 0, st,
+                               T, G, S, d_out, n_mg, n_pcg);
         }
-    } else if (lanes_p) {
-        // as many waves as the chip holds at four per SIMD, shared out over the tables and
-        // the groups of 64 process counts; each walks over every n_w-th message size
-        const int n_pg = (G.n_P + 63) / 64;
-        long n_w = 4096 / ((long)T.n_tables * n_pg);
-        if (n_w > G.n_m) n_w = G.n_m;
-        if (n_w < 1) n_w = 1;
-        n_w = (n_w + 3) / 4 * 4;
-        const unsigned blocks = (unsigned)(T.n_tables * (long)n_pg * (n_w / 4));
-        if (G.n_s <= 64)
-            hipLaunchKernelGGL(k_sweep_p<1>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
-                               (int)n_w);
-        else
-            hipLaunchKernelGGL(k_sweep_p<4>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
-                               (int)n_w);
-    } else {
-        constexpr int PC = 4;
-        const int n_mg = (G.n_m + 63) / 64;
-        const int n_pcg = (G.n_P + 4 * PC - 1) / (4 * PC);
-        hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)T.n_tables * n_mg * n_pcg), dim3(256), 0, st,
-                           T, G, S, d_out, n_mg, n_pcg);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(4);

@@ -65,7 +65,8 @@ def _load_library():
         "plogp_decision_table_cells": (sz, [sz, vp]),
         "plogp_decision_table_bytes": (sz, [sz, vp]),
         "plogp_tune_grid": (ctypes.c_int, [vp, vp, vp, sz, vp]),
-        "plogp_tune_grid_profile": (ctypes.c_int, [vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]),
+        "plogp_tune_grid_profile": (ctypes.c_int, [vp, vp, vp, sz, vp, ctypes.c_int,
+                                                   ctypes.POINTER(ctypes.c_float)]),
         "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "plogp_last_hip_error": (ctypes.c_int, []),
     }
@@ -200,9 +201,11 @@ def plogp_tune_grid(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stre
     _check(_lib.plogp_tune_grid(table._h, grid._h, d_out, d_out_bytes, stream), "plogp_tune_grid")
 
 
-def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0):
-    """Runs the sweep with events between its kernels; returns the four stage times in ms."""
+def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0,
+                            reps: int = 1):
+    """Runs the sweep with each kernel launched reps times between two events; returns the
+    mean time per launch of the four stages in ms."""
     ms = (ctypes.c_float * 4)()
-    _check(_lib.plogp_tune_grid_profile(table._h, grid._h, d_out, d_out_bytes, stream, ms),
+    _check(_lib.plogp_tune_grid_profile(table._h, grid._h, d_out, d_out_bytes, stream, reps, ms),
            "plogp_tune_grid_profile")
     return [float(v) for v in ms]
