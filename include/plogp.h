@@ -189,6 +189,63 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
 int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_out,
                             size_t d_out_bytes, void *stream, int reps, float *stage_ms_out);
 
+/*
+ * Cut-over extraction -- paper Section 3.1 (how the tuned segment size is
+ * applied: messages above some size are segmented, smaller ones are not) and
+ * Section 1 (one technique per pattern, message size and node count): every
+ * row of a decision table -- the cells of one (table, operation, P) read along
+ * the grid's message sizes in their given order -- is compressed into its runs
+ * of equal decision.  A run starts at the first cell of a row and at every
+ * cell whose key differs from the key of the cell before it; the key is the
+ * strategy id (PLOGP_KEY_STRATEGY) or the pair (strategy id, s)
+ * (PLOGP_KEY_STRATEGY_AND_SEGMENT).  A run is reported by its first cell.
+ */
+#define PLOGP_KEY_STRATEGY 0
+#define PLOGP_KEY_STRATEGY_AND_SEGMENT 1
+
+typedef struct {
+    uint64_t m_from;    /* message size of the first cell of the run               */
+    uint32_t s;         /* that cell's segment size, 0 = unsegmented               */
+    uint32_t strategy;  /* that cell's strategy id                                  */
+} plogp_run;            /* 16 bytes */
+
+/* Rows of the decision table of n_tables tables over this grid:
+ * n_tables * operation planes * process counts, ordered (table, operation, P). */
+size_t plogp_cutover_rows(size_t n_tables, const plogp_grid *g);
+
+/*
+ * plogp_cutovers -- extracts the runs of a decision table that is laid out as
+ * plogp_tune_grid writes it for n_tables tables over grid g.
+ *   d_cells:       DEVICE, the decision table, 16-byte aligned (read only);
+ *   d_row_offsets: DEVICE, plogp_cutover_rows() + 1 uint64: the runs of row r
+ *                  are d_runs[d_row_offsets[r] .. d_row_offsets[r+1]); the last
+ *                  entry is the total number of runs;
+ *   d_runs:        DEVICE, room for runs_capacity records, 16-byte aligned,
+ *                  ordered by row, then by message-size index.  Runs whose
+ *                  index is >= runs_capacity are not written (the offsets and
+ *                  the total still are): the caller compares the total with
+ *                  its capacity.  plogp_decision_table_cells() records always
+ *                  suffice.  May be NULL when runs_capacity is 0 (count only).
+ * Enqueued on `stream`.  Scratch is owned by the grid handle (allocated on
+ * first use): two extractions on one grid handle must not overlap.
+ * Errors: EINVAL (null, misaligned, bad key_mode, n_tables = 0), ERANGE (more
+ * than 2^36 (row, 16 sizes) pieces), ENOMEM, EDEVICE.
+ */
+int plogp_cutovers(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                   uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity, void *stream);
+
+/*
+ * plogp_cutovers_profile -- the same work, measured: each of the three steps
+ * (mark run starts, prefix of their counts, write the runs) is launched `reps`
+ * times back to back between two HIP events on `stream`; waits and returns
+ * the mean milliseconds per launch in stage_ms_out[0..2].  Synchronous.
+ * Errors: as plogp_cutovers, plus EINVAL for a null stage_ms_out or reps
+ * outside [1, 10000].
+ */
+int plogp_cutovers_profile(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                           uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity,
+                           void *stream, int reps, float *stage_ms_out);
+
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);
 /* HIP error code of the calling thread's most recent PLOGP_EDEVICE (0 if none). */

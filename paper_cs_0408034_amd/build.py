@@ -8,7 +8,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libplogp.so"
-SOURCES = [CSRC / "plogp_api.hip", CSRC / "plogp_kernels.hip"]
+SOURCES = [CSRC / "plogp_api.hip", CSRC / "plogp_kernels.hip", CSRC / "plogp_cutover.hip"]
 HEADERS = [CSRC / "plogp_internal.hpp", PKG.parent / "include" / "plogp.h"]
 
 HIPCC_FLAGS = [

@@ -80,6 +80,9 @@ struct plogp_grid {
     // scratch, sized for scratch_tables tables
     size_t scratch_tables = 0, scratch_samples = 0;
     Scratch scratch = {};
+    // scratch of the cut-over extraction, sized for cut_tables tables
+    size_t cut_tables = 0;
+    CutScratch cut = {};
 
     DeviceGrid view() const
     {
@@ -105,9 +108,19 @@ struct plogp_grid {
         scratch_tables = 0;
         scratch_samples = 0;
     }
+    void free_cut_scratch()
+    {
+        if (cut.counts) (void)hipFree(cut.counts);
+        if (cut.local) (void)hipFree(cut.local);
+        if (cut.flags) (void)hipFree(cut.flags);
+        if (cut.group_total) (void)hipFree(cut.group_total);
+        cut = CutScratch{};
+        cut_tables = 0;
+    }
     ~plogp_grid()
     {
         free_scratch();
+        free_cut_scratch();
         if (d_m) (void)hipFree(d_m);
         if (d_s) (void)hipFree(d_s);
         if (d_P) (void)hipFree(d_P);
@@ -406,6 +419,88 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     stage_ms_out[1] = chain ? ms[1] : 0.f;
     stage_ms_out[2] = chain ? ms[2] : 0.f;
     stage_ms_out[3] = ms[3];
+    return PLOGP_OK;
+}
+
+static int ensure_cut_scratch(plogp_grid *g, size_t n_tables)
+{
+    if (g->cut_tables >= n_tables) return PLOGP_OK;
+    HIP_TRY(hipDeviceSynchronize());     // an earlier extraction on this handle may still run
+    g->free_cut_scratch();
+    const size_t items = cutover_items(g->view(), (int)n_tables);
+    const size_t groups = (items + CUT_SCAN_WG - 1) / CUT_SCAN_WG;
+    hipError_t e;
+    if ((e = hipMalloc((void **)&g->cut.counts, items * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->cut.local, items * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->cut.flags, items * sizeof(uint32_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->cut.group_total, (groups ? groups : 1) * sizeof(uint64_t))) != hipSuccess) {
+        g->free_cut_scratch();
+        if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }
+        return device_error(e);
+    }
+    g->cut_tables = n_tables;
+    return PLOGP_OK;
+}
+
+static int check_cutover_args(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells,
+                              int key_mode, const uint64_t *d_row_offsets, const plogp_run *d_runs,
+                              size_t runs_capacity)
+{
+    if (!g || !d_cells || !d_row_offsets || n_tables < 1 || n_tables > (1u << 24)) return PLOGP_EINVAL;
+    if (key_mode != PLOGP_KEY_STRATEGY && key_mode != PLOGP_KEY_STRATEGY_AND_SEGMENT) return PLOGP_EINVAL;
+    if (runs_capacity > 0 && !d_runs) return PLOGP_EINVAL;
+    if (((uintptr_t)d_cells & 15u) != 0 || ((uintptr_t)d_runs & 15u) != 0 ||
+        ((uintptr_t)d_row_offsets & 7u) != 0)
+        return PLOGP_EINVAL;
+    // one thread per (row, tile of sizes), padded to whole waves: must fit a launch
+    if (cutover_items(g->view(), (int)n_tables) > ((size_t)1 << 36)) return PLOGP_ERANGE;
+    return PLOGP_OK;
+}
+
+size_t plogp_cutover_rows(size_t n_tables, const plogp_grid *g)
+{
+    return g ? n_tables * (size_t)g->n_ops * g->n_P : 0;
+}
+
+int plogp_cutovers(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                   uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity, void *stream)
+{
+    int rc = check_cutover_args(g, n_tables, d_cells, key_mode, d_row_offsets, d_runs, runs_capacity);
+    if (rc != PLOGP_OK) return rc;
+    if ((rc = ensure_init()) != PLOGP_OK) return rc;
+    if ((rc = ensure_cut_scratch(g, n_tables)) != PLOGP_OK) return rc;
+    HIP_TRY(launch_cutovers(g->view(), (int)n_tables, reinterpret_cast<const plogp_cell_dev *>(d_cells),
+                            key_mode, g->cut, d_row_offsets, d_runs, runs_capacity,
+                            (hipStream_t)stream));
+    return PLOGP_OK;
+}
+
+int plogp_cutovers_profile(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                           uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity,
+                           void *stream, int reps, float *stage_ms_out)
+{
+    if (!stage_ms_out || reps < 1 || reps > 10000) return PLOGP_EINVAL;
+    int rc = check_cutover_args(g, n_tables, d_cells, key_mode, d_row_offsets, d_runs, runs_capacity);
+    if (rc != PLOGP_OK) return rc;
+    if ((rc = ensure_init()) != PLOGP_OK) return rc;
+    if ((rc = ensure_cut_scratch(g, n_tables)) != PLOGP_OK) return rc;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+    if (e == hipSuccess)
+        e = launch_cutovers(g->view(), (int)n_tables, reinterpret_cast<const plogp_cell_dev *>(d_cells),
+                            key_mode, g->cut, d_row_offsets, d_runs, runs_capacity,
+                            (hipStream_t)stream, ev, reps);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[3]);
+    float ms[3] = {0.f, 0.f, 0.f};
+    for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+        e = hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
+        ms[i] /= (float)reps;
+    }
+    for (int i = 0; i < 4; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    if (e != hipSuccess) return device_error(e);
+    for (int i = 0; i < 3; ++i) stage_ms_out[i] = ms[i];
     return PLOGP_OK;
 }
 

@@ -1,0 +1,277 @@
+// gfx950 kernels of the cut-over extraction: each row (table, operation, P)
+// of a decision table, read along the message sizes, is compressed into its
+// runs of equal decision.  This is the form in which the tuned decisions are
+// applied (paper, Section 3.1: above some message size a collective is
+// segmented, below it is not; Section 1: one technique per pattern, message
+// size and node count).
+//
+// Integer and index work only; the result is unique, so it must equal the
+// plain definition bit for bit.
+//
+// Three steps, all bound by HBM traffic:
+//   k_cut_mark  one thread per (row, tile of CUT_TM sizes): compares the key of
+//               every cell with the key of the cell before it, keeps the start
+//               flags of the tile as a bit mask and their count;
+//   k_cut_scan1 / k_cut_scan2  exclusive prefix of the counts in (row, tile)
+//               order: per workgroup of CUT_SCAN_WG counts, then over the
+//               workgroup totals;
+//   k_cut_emit  one thread per (row, tile) again: writes a run record for every
+//               flagged cell at its place, and the row offsets.
+// The decision table is stored [table][operation][m][P] with P fastest, so the
+// lanes of a wave run over consecutive P (coalesced) and, when the grid has
+// fewer than 64 process counts, over consecutive tiles as well.
+#include "plogp_internal.hpp"
+
+namespace plogp {
+namespace {
+
+typedef unsigned long long u64;
+
+struct CutShape {
+    int n_tables, n_ops, n_m, n_P;
+    int n_tiles;      // tiles of CUT_TM sizes per row
+    int lp;           // lanes of a wave along P: a power of two, at most 64
+    int n_pg;         // groups of lp process counts
+    long n_items;     // n_tables * n_ops * n_pg * n_tiles * lp threads
+};
+
+// Thread -> (row, tile).  Returns false for the padding lanes past n_P.
+__device__ __forceinline__ bool cut_item(const CutShape &sh, long item, int &t, int &op, int &pi,
+                                         int &tile)
+{
+    const int pl = (int)(item % sh.lp);
+    item /= sh.lp;
+    tile = (int)(item % sh.n_tiles);
+    item /= sh.n_tiles;
+    const int pg = (int)(item % sh.n_pg);
+    item /= sh.n_pg;
+    op = (int)(item % sh.n_ops);
+    t = (int)(item / sh.n_ops);
+    pi = pg * sh.lp + pl;
+    return pi < sh.n_P;
+}
+
+// (s, strategy) of a cell: the second half of its 16-byte record.
+__device__ __forceinline__ uint2 cell_key(const plogp_cell_dev *cells, size_t idx)
+{
+    return reinterpret_cast<const uint2 *>(cells)[idx * 2 + 1];
+}
+
+__global__ void __launch_bounds__(256) k_cut_mark(CutShape sh, const plogp_cell_dev *cells, int key_mode,
+                                                  uint32_t *counts, uint32_t *flags)
+{
+    const long item = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= sh.n_items)
+        return;
+    int t, op, pi, tile;
+    if (!cut_item(sh, item, t, op, pi, tile))
+        return;
+    const int m0 = tile * CUT_TM;
+    const int len = sh.n_m - m0 < CUT_TM ? sh.n_m - m0 : CUT_TM;
+    const size_t base = ((size_t)(t * sh.n_ops + op) * sh.n_m + m0) * sh.n_P + pi;
+    // all keys of the tile and the one before it are fetched before any is compared
+    uint2 key[CUT_TM + 1];
+    key[0] = m0 > 0 ? cell_key(cells, base - sh.n_P) : make_uint2(0u, 0u);
+#pragma unroll
+    for (int k = 0; k < CUT_TM; ++k)
+        key[k + 1] = k < len ? cell_key(cells, base + (size_t)k * sh.n_P) : make_uint2(0u, 0u);
+    uint32_t bits = 0u;
+#pragma unroll
+    for (int k = 0; k < CUT_TM; ++k) {
+        bool differs = key[k + 1].y != key[k].y;              // strategy
+        if (key_mode == 1)
+            differs = differs || key[k + 1].x != key[k].x;    // and segment size
+        if (k < len && (differs || (m0 == 0 && k == 0)))      // the first cell of a row starts a run
+            bits |= 1u << k;
+    }
+    const size_t row = (size_t)(t * sh.n_ops + op) * sh.n_P + pi;
+    counts[row * sh.n_tiles + tile] = (uint32_t)__builtin_popcount(bits);
+    flags[row * sh.n_tiles + tile] = bits;
+}
+
+// Exclusive prefix inside each group of CUT_SCAN_WG counts and the group
+// totals.  A thread takes CUT_SCAN_PER consecutive counts.
+__global__ void __launch_bounds__(CUT_SCAN_THREADS) k_cut_scan1(const uint32_t *counts, uint32_t *local,
+                                                                 size_t n, u64 *group_total)
+{
+    __shared__ uint32_t wave_sum[CUT_SCAN_THREADS / 64];
+    const size_t first = ((size_t)blockIdx.x * CUT_SCAN_THREADS + threadIdx.x) * CUT_SCAN_PER;
+    uint32_t v[CUT_SCAN_PER];
+    uint32_t sum = 0u;
+#pragma unroll
+    for (int k = 0; k < CUT_SCAN_PER; ++k) {
+        v[k] = first + k < n ? counts[first + k] : 0u;
+        sum += v[k];
+    }
+    // inclusive scan of the thread sums over the wave (log steps through the lanes)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)inc, d, 64);
+        if (lane >= d)
+            inc += up;
+    }
+    if (lane == 63)
+        wave_sum[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0u, total = 0u;
+#pragma unroll
+    for (int w = 0; w < CUT_SCAN_THREADS / 64; ++w) {
+        before += w < wave ? wave_sum[w] : 0u;
+        total += wave_sum[w];
+    }
+    uint32_t run = before + inc - sum;
+#pragma unroll
+    for (int k = 0; k < CUT_SCAN_PER; ++k) {
+        if (first + k < n)
+            local[first + k] = run;
+        run += v[k];
+    }
+    if (threadIdx.x == 0)
+        group_total[blockIdx.x] = total;
+}
+
+// Exclusive prefix of the group totals (in place), one workgroup; the grand
+// total goes to *total_out (the entry after the last row offset).
+__global__ void __launch_bounds__(1024) k_cut_scan2(u64 *group_total, size_t n_groups, u64 *total_out)
+{
+    __shared__ u64 wave_sum[16];
+    __shared__ u64 carry_s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0)
+        carry_s = 0ull;
+    __syncthreads();
+    for (size_t g0 = 0; g0 < n_groups; g0 += 1024) {
+        const size_t i = g0 + threadIdx.x;
+        const u64 v = i < n_groups ? group_total[i] : 0ull;
+        u64 inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const u64 up = (u64)__shfl_up((long long)inc, d, 64);
+            if (lane >= d)
+                inc += up;
+        }
+        if (lane == 63)
+            wave_sum[wave] = inc;
+        __syncthreads();
+        u64 before = carry_s, all = 0ull;
+        for (int w = 0; w < 16; ++w) {
+            before += w < wave ? wave_sum[w] : 0ull;
+            all += wave_sum[w];
+        }
+        if (i < n_groups)
+            group_total[i] = before + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            carry_s += all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        *total_out = carry_s;
+}
+
+struct plogp_run_dev {
+    u64 m_from;
+    uint32_t s;
+    uint32_t strategy;
+};
+
+__global__ void __launch_bounds__(256) k_cut_emit(CutShape sh, const plogp_cell_dev *cells, const u64 *m,
+                                                  const uint32_t *local, const uint32_t *flags,
+                                                  const u64 *group_before, u64 *row_offsets,
+                                                  plogp_run_dev *runs, u64 capacity)
+{
+    const long item = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= sh.n_items)
+        return;
+    int t, op, pi, tile;
+    if (!cut_item(sh, item, t, op, pi, tile))
+        return;
+    const size_t row = (size_t)(t * sh.n_ops + op) * sh.n_P + pi;
+    const size_t idx = row * sh.n_tiles + tile;
+    u64 at = group_before[idx / CUT_SCAN_WG] + local[idx];
+    if (tile == 0)
+        row_offsets[row] = at;
+    uint32_t bits = flags[idx];
+    const int m0 = tile * CUT_TM;
+    const size_t base = ((size_t)(t * sh.n_ops + op) * sh.n_m + m0) * sh.n_P + pi;
+    while (bits != 0u) {
+        const int k = __builtin_ctz(bits);
+        bits &= bits - 1u;
+        if (at < capacity) {
+            const uint2 key = cell_key(cells, base + (size_t)k * sh.n_P);
+            union {
+                plogp_run_dev r;
+                uint4 v;
+            } u;
+            u.r.m_from = m[m0 + k];
+            u.r.s = key.x;
+            u.r.strategy = key.y;
+            reinterpret_cast<uint4 *>(runs)[at] = u.v;
+        }
+        ++at;
+    }
+}
+
+}  // namespace
+
+size_t cutover_items(const DeviceGrid &G, int n_tables)
+{
+    const size_t n_tiles = ((size_t)G.n_m + CUT_TM - 1) / CUT_TM;
+    return (size_t)n_tables * G.n_ops * G.n_P * n_tiles;
+}
+
+hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
+                           const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
+                           uint64_t capacity, hipStream_t st, hipEvent_t *ev, int reps)
+{
+    hipError_t e;
+    if (reps < 1) reps = 1;
+    CutShape sh;
+    sh.n_tables = n_tables;
+    sh.n_ops = G.n_ops;
+    sh.n_m = G.n_m;
+    sh.n_P = G.n_P;
+    sh.n_tiles = (G.n_m + CUT_TM - 1) / CUT_TM;
+    int lp = 1;
+    while (lp < 64 && lp < G.n_P) lp <<= 1;
+    sh.lp = lp;
+    sh.n_pg = (G.n_P + lp - 1) / lp;
+    sh.n_items = (long)n_tables * G.n_ops * sh.n_pg * sh.n_tiles * lp;
+    const size_t n_counts = cutover_items(G, n_tables);
+    const size_t n_groups = (n_counts + CUT_SCAN_WG - 1) / CUT_SCAN_WG;
+    const size_t n_rows = (size_t)n_tables * G.n_ops * G.n_P;
+    const unsigned blocks = (unsigned)((sh.n_items + 255) / 256);
+#define PLOGP_MARK(i)                                                            \
+    do {                                                                         \
+        if (ev && (e = hipEventRecord(ev[i], st)) != hipSuccess) return e;       \
+    } while (0)
+    PLOGP_MARK(0);
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_cut_mark, dim3(blocks), dim3(256), 0, st, sh, d_cells, key_mode, C.counts,
+                           C.flags);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    PLOGP_MARK(1);
+    for (int r = 0; r < reps; ++r) {
+        hipLaunchKernelGGL(k_cut_scan1, dim3((unsigned)n_groups), dim3(CUT_SCAN_THREADS), 0, st,
+                           C.counts, C.local, n_counts, reinterpret_cast<u64 *>(C.group_total));
+        hipLaunchKernelGGL(k_cut_scan2, dim3(1), dim3(1024), 0, st,
+                           reinterpret_cast<u64 *>(C.group_total), n_groups,
+                           reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    PLOGP_MARK(2);
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_cut_emit, dim3(blocks), dim3(256), 0, st, sh, d_cells,
+                           reinterpret_cast<const u64 *>(G.m), C.local, C.flags,
+                           reinterpret_cast<const u64 *>(C.group_total),
+                           reinterpret_cast<u64 *>(d_row_offsets),
+                           reinterpret_cast<plogp_run_dev *>(d_runs), (u64)capacity);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    PLOGP_MARK(3);
+#undef PLOGP_MARK
+    return hipSuccess;
+}
+
+}  // namespace plogp

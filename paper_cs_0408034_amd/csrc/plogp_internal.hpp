@@ -83,6 +83,28 @@ hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uin
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
                        plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr,
                        int reps = 1);
+
+// ---- cut-over extraction (plogp_cutover.hip)
+constexpr int CUT_TM = 16;                 // message sizes per thread (a tile of one row)
+constexpr int CUT_SCAN_THREADS = 256;
+constexpr int CUT_SCAN_PER = 8;            // counts per thread of the group scan
+constexpr int CUT_SCAN_WG = CUT_SCAN_THREADS * CUT_SCAN_PER;
+
+// Scratch of the cut-over extraction, one entry per (row, tile) unless noted.
+struct CutScratch {
+    uint32_t *counts;        // run starts in the tile
+    uint32_t *local;         // their exclusive prefix inside a group of CUT_SCAN_WG entries
+    uint32_t *flags;         // bit k: cell k of the tile starts a run
+    uint64_t *group_total;   // [groups] totals, then their exclusive prefix
+};
+
+// Number of (row, tile) entries for n_tables tables over grid G.
+size_t cutover_items(const DeviceGrid &G, int n_tables);
+// ev: nullptr, or 4 events recorded before the first kernel and after mark, scan, emit.
+hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
+                           const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
+                           uint64_t capacity, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
 

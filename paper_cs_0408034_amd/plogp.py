@@ -23,6 +23,8 @@ NO_STRATEGY = 0xFFFFFFFF
 NO_CAP = (1 << 64) - 1
 MAX_SAMPLES = 4096
 CELL_DTYPE = np.dtype([("time", "<f8"), ("s", "<u4"), ("strategy", "<u4")])
+RUN_DTYPE = np.dtype([("m_from", "<u8"), ("s", "<u4"), ("strategy", "<u4")])
+KEY_STRATEGY, KEY_STRATEGY_AND_SEGMENT = 0, 1
 
 
 class PlogpError(RuntimeError):
@@ -67,6 +69,10 @@ def _load_library():
         "plogp_tune_grid": (ctypes.c_int, [vp, vp, vp, sz, vp]),
         "plogp_tune_grid_profile": (ctypes.c_int, [vp, vp, vp, sz, vp, ctypes.c_int,
                                                    ctypes.POINTER(ctypes.c_float)]),
+        "plogp_cutover_rows": (sz, [sz, vp]),
+        "plogp_cutovers": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, sz, vp]),
+        "plogp_cutovers_profile": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, sz, vp, ctypes.c_int,
+                                                  ctypes.POINTER(ctypes.c_float)]),
         "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "plogp_last_hip_error": (ctypes.c_int, []),
     }
@@ -208,4 +214,24 @@ def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: i
     ms = (ctypes.c_float * 4)()
     _check(_lib.plogp_tune_grid_profile(table._h, grid._h, d_out, d_out_bytes, stream, reps, ms),
            "plogp_tune_grid_profile")
+    return [float(v) for v in ms]
+
+
+def plogp_cutover_rows(n_tables: int, grid: Grid) -> int:
+    return int(_lib.plogp_cutover_rows(n_tables, grid._h))
+
+
+def plogp_cutovers(grid: Grid, n_tables: int, d_cells: int, key_mode: int, d_row_offsets: int,
+                   d_runs: int, runs_capacity: int, stream: int = 0):
+    _check(_lib.plogp_cutovers(grid._h, n_tables, d_cells, key_mode, d_row_offsets, d_runs or None,
+                               runs_capacity, stream), "plogp_cutovers")
+
+
+def plogp_cutovers_profile(grid: Grid, n_tables: int, d_cells: int, key_mode: int, d_row_offsets: int,
+                           d_runs: int, runs_capacity: int, stream: int = 0, reps: int = 1):
+    """Each step launched reps times between two events; mean ms per launch of mark, scan, emit."""
+    ms = (ctypes.c_float * 3)()
+    _check(_lib.plogp_cutovers_profile(grid._h, n_tables, d_cells, key_mode, d_row_offsets,
+                                       d_runs or None, runs_capacity, stream, reps, ms),
+           "plogp_cutovers_profile")
     return [float(v) for v in ms]

@@ -122,6 +122,14 @@ def test_null_handles_are_refused(plogp):
     assert lib.plogp_grid_create(None, None) == plogp.EINVAL
     assert lib.plogp_table_count(None) == 0 and lib.plogp_decision_table_bytes(3, None) == 0
     assert lib.plogp_free_table(None) == plogp.OK and lib.plogp_grid_free(None) == plogp.OK
+    assert lib.plogp_cutovers(None, 1, None, 0, None, None, 0, None) == plogp.EINVAL
+    assert lib.plogp_cutovers_profile(None, 1, None, 0, None, None, 0, None, 1, None) == plogp.EINVAL
+    assert lib.plogp_cutover_rows(3, None) == 0
+
+
+def test_run_is_sixteen_bytes(plogp):
+    assert plogp.RUN_DTYPE.itemsize == 16
+    assert plogp.RUN_DTYPE.fields["s"][1] == 8 and plogp.RUN_DTYPE.fields["strategy"][1] == 12
 
 
 def test_without_a_gpu_valid_calls_fail_loudly(plogp):
