@@ -96,7 +96,7 @@ def _roofline_of(stage, work, ms):
             "algorithmic_flops": w["flops"], "avg_ms": ms}
 
 
-def run_gpu(wl, steps, warmup, profile_reps):
+def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     import torch
     from paper_cs_0408034_amd import plogp
 
@@ -125,10 +125,67 @@ def run_gpu(wl, steps, warmup, profile_reps):
     rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, profile_reps)
               for _ in range(5)]
     stage_ms = dict(zip(STAGES, np.median(np.array(rounds), axis=0).tolist()))
+    cut = run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps) if with_cut else None
     del out
     grid.free()
     tab.free()
-    return ms_per_step, stage_ms
+    return ms_per_step, stage_ms, cut
+
+
+CUT_STAGES = ("mark", "scan", "emit")
+
+
+def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps):
+    """The cut-over extraction (runs of equal (strategy, s) along m) of the table just tuned."""
+    sh = stream.cuda_stream
+    n_cells = nbytes // 16
+    rows = plogp.plogp_cutover_rows(tab.count, grid)
+    d_off = torch.empty(rows + 1, dtype=torch.int64, device="cuda")
+    cap = n_cells                      # one record per cell always suffices
+    d_runs = torch.empty(cap * 16, dtype=torch.uint8, device="cuda")
+    args = (grid, tab.count, out.data_ptr(), plogp.KEY_STRATEGY_AND_SEGMENT, d_off.data_ptr(),
+            d_runs.data_ptr(), cap, sh)
+    for _ in range(3):
+        plogp.plogp_cutovers(*args)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        plogp.plogp_cutovers(*args)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
+    n_runs = int(d_off[-1].item())
+    assert n_runs <= cap, "bench: run buffer too small (%d runs)" % n_runs
+    rounds = [plogp.plogp_cutovers_profile(*args, profile_reps) for _ in range(5)]
+    stage_ms = dict(zip(CUT_STAGES, np.median(np.array(rounds), axis=0).tolist()))
+    # what the extraction itself has to move: the 8-byte key of every cell once, a 16-byte
+    # record per run, an 8-byte offset per row
+    alg_bytes = 8 * n_cells + 16 * n_runs + 8 * (rows + 1)
+    kernels_ms = sum(stage_ms.values())
+    ach = alg_bytes / (kernels_ms * 1e-3) / 1e9
+    return {"ms_per_call": ms, "cells_per_s": n_cells / (ms * 1e-3), "runs": n_runs, "rows": rows,
+            "key": "strategy and segment size", "stage_ms": stage_ms,
+            "roofline": {"kernel": "mark+scan+emit", "bound": "hbm", "achieved": ach,
+                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9),
+                         "traffic": None, "algorithmic_bytes": alg_bytes, "avg_ms": kernels_ms}}
+
+
+def cut_cpu(sample):
+    """The oracle's extraction (array operations, one thread) on the oracle's table of the sample."""
+    import oracle
+    from oracle import plogp_cutover as oc
+    cells, _ = oracle.tune_workload(sample)
+    oc.cutovers(cells[:1, :, :, :2], sample.m, 1)
+    runs, dt = 0, 0.0
+    while dt < 1.0 and runs < 20:
+        t0 = time.perf_counter()
+        oc.cutovers(cells, sample.m, 1)
+        dt += time.perf_counter() - t0
+        runs += 1
+    return {"value": runs * cells.size / dt, "unit": "cells/s", "cores": 1, "kind": "oracle",
+            "seconds": dt}
 
 
 def cpu_sample(cfg, wl):
@@ -167,7 +224,7 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
     if mask is not None:
         wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
-    ms, stage_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    ms, stage_ms, cut = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
     traffic = MEASURED_TRAFFIC.get(cfg, {}) if mask is None else {}
     if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
         # the single-kernel batch path did every stage inside one launch
@@ -189,8 +246,13 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
         "stage_rooflines": {k: roofline_of(k, work, stage_ms[k], traffic.get(k))
                             for k in STAGES if stage_ms[k] > 0},
     }
+    if cut is not None:
+        res["cutover_extraction"] = cut
     if with_cpu:
         res["cpu_baseline"] = run_cpu(cfg, wl)
+        if cut is not None:
+            sample, what = cpu_sample(cfg, wl)
+            cut["cpu_baseline"] = dict(cut_cpu(sample), sample=what)
     return res
 
 
@@ -247,6 +309,8 @@ def main():
     }
     if "cpu_baseline" in head:
         line["cpu_baseline"] = head["cpu_baseline"]
+    if "cutover_extraction" in head:
+        line["cutover_extraction"] = head["cutover_extraction"]
     extras = [] if args.extra in ("", "none") else [int(v) for v in args.extra.split(",")]
     if extras:
         line["workloads"] = {}

@@ -348,15 +348,15 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
 // ---------------------------------------------------------------- tune, step 2: Scatter-chain sum
 
 // sum_{j=1}^{P-1} g(j m) (Table 2, chain row).  One lane per message size; a
-// workgroup covers blockDim sizes and `nb` consecutive blocks of SUM_BLOCK
-// terms.  Inside a lane the arguments j*m ascend, so the interval of the table
-// only moves forward: one search at the start, then a pointer walk that keeps
-// d = j*m - x_i (exact: integers below 2^53) and the interval width, so a term
-// costs an add, a compare, an fma and the accumulation.  Sizes below the first
-// sample fall into a virtual interval of slope 0 and gap y_0 (the clamp).
-// Emits each block total and, for every P of the grid whose P-1 falls inside a
-// block, the running sum at that point.
-constexpr int CHAIN_SINGLE = 8;      // leading blocks of the chain sum that get a lane each
+// lane walks U consecutive blocks of SUM_BLOCK terms side by side (they
+// are independent chains of additions, so their instructions interleave and
+// hide each other's latency).  Inside a chain the arguments j*m ascend, so the
+// interval of the table only moves forward: one search at the start, then a
+// pointer walk that keeps d = j*m - x_i (exact: integers below 2^53) and the
+// interval width, so a term costs an add, a compare, an fma and the
+// accumulation.  Sizes below the first sample fall into a virtual interval of
+// slope 0 and gap y_0 (the clamp).  Emits each block total and, for every P of
+// the grid whose P-1 falls inside a block, the running sum at that point.
 
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 
@@ -377,9 +377,25 @@ __device__ __forceinline__ void chain_fetch_ahead(unsigned w_addr, unsigned ys_a
                  : "memory");
 }
 
-__device__ __forceinline__ void chain_await(double &nw, f64x2 &nys)
+// Waits for every fetch issued so far; all registers that a fetch may still be
+// writing pass through here.
+template <int U>
+__device__ __forceinline__ void chain_await(double (&nw)[U], f64x2 (&nys)[U])
 {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(nw), "+v"(nys) : : "memory");
+    static_assert(U == 1 || U == 2 || U == 4, "one operand pair per chain");
+    if constexpr (U == 1)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(nw[0]), "+v"(nys[0]) : : "memory");
+    else if constexpr (U == 2)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(nw[0]), "+v"(nys[0]), "+v"(nw[1]), "+v"(nys[1])
+                     :
+                     : "memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(nw[0]), "+v"(nys[0]), "+v"(nw[1]), "+v"(nys[1]), "+v"(nw[2]),
+                       "+v"(nys[2]), "+v"(nw[3]), "+v"(nys[3])
+                     :
+                     : "memory");
 }
 
 // Makes the wait for an ordinary LDS read happen here rather than at a later
@@ -389,15 +405,254 @@ __device__ __forceinline__ void settle(double &a, double &b, double &c, double &
     asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(e));
 }
 
-// Work items: (unit u, group of 64 sizes mg).  Unit u is block u alone for the
-// first CHAIN_SINGLE blocks (small j: the walk crosses many intervals per term, so
-// those are the heavy ones), then nb consecutive blocks.  Item i = u * n_mg + mg
-// belongs to workgroup i mod wg_per_table of its table, so every workgroup gets
-// its share of the heavy items and meets them first; inside a workgroup the waves
-// take the next item of that list from a counter in LDS, because how long an item
-// takes depends on how often its sizes cross an interval.
+// Dense part of the table (small j): after moving into interval i the size is
+// still at or past its end (d >= w), i.e. several intervals on.  e = z - end of
+// interval i.  Looks four intervals ahead a few times, then searches the rest
+// of the table for z = xb + e (exact: integers below 2^53).  Leaves i, d, w and
+// the interval's {gap, slope}.
+__device__ __forceinline__ void chain_skip_ahead(const double *X, const f64x2 *YS, const double *W,
+                                                 int n, int &i, double &d, double &w, double &yi,
+                                                 double &si)
+{
+    double xb = X[i + 1];
+    double e = d - w;
+    int hops = 0;
+    for (;;) {
+        const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
+        const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
+        if (e >= r4) {
+            if (++hops == 3) {
+                const double z = xb + e;
+                i = last_not_above(X + 1, n, z) + 1;       // samples not above z
+                d = z - X[i];
+                break;
+            }
+            i += 4;
+            e -= r4;
+            xb += r4;
+            continue;
+        }
+        const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
+        const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
+        d = e - lo;
+        i += 1 + c;
+        break;
+    }
+    const f64x2 ys = YS[i];
+    w = W[i];
+    yi = ys.x;
+    si = ys.y;
+    settle(d, w, yi, si);
+}
+
+// What a lane needs to know about the blocks of one work item.
+struct ChainCtx {
+    const f64x2 *YS;      // LDS: {gap, slope} per interval
+    const double *X;      // LDS: interval starts
+    const double *W;      // LDS: interval widths
+    unsigned w_lds, ys_lds;
+    int n;                // samples of the table
+    int n_blk;
+    size_t n_m;
+    const u64 *blk_mask;
+    const int *blk_off;
+};
+
+// U consecutive blocks from block b0 on, walked side by side for the size m of
+// this lane.  part: this size's row of in-block partial sums; tot: its column of
+// block totals.  nw, nys: the registers of the fetches ahead (nothing in flight
+// on entry and on return).
+template <int U>
+__device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, double *part,
+                                           double *tot, double (&nw)[U], f64x2 (&nys)[U])
+{
+    const int n = C.n;
+    const double *X = C.X, *W = C.W;
+    const f64x2 *YS = C.YS;
+    const int n_act = C.n_blk - b0 < U ? C.n_blk - b0 : U;      // chains that have a block
+    const double md = (double)m;
+    // per chain (wave-uniform): the points of its block at which some grid P needs the
+    // running sum (bit r: after r terms), and where the next such sum goes
+    u64 wanted[U], any_wanted = 0;
+    int pi[U];
+#pragma unroll
+    for (int c = 0; c < U; ++c) {
+        wanted[c] = c < n_act ? C.blk_mask[b0 + c] : 0ull;
+        pi[c] = c < n_act ? C.blk_off[b0 + c] : 0;
+        any_wanted |= wanted[c];
+    }
+    // interval of each chain's first size: number of samples not above it (0 = the
+    // virtual interval); the searches run side by side.  A chain without a block
+    // repeats the first one and is not stored.
+    double z0[U];
+    int i[U];
+#pragma unroll
+    for (int c = 0; c < U; ++c) {
+        const int b = c < n_act ? b0 + c : b0;
+        z0[c] = (double)(((u64)b * SUM_BLOCK + 1) * m);
+        i[c] = 0;
+    }
+    for (int len = n; len > 1;) {
+        const int half = len >> 1;
+        double xv[U];
+#pragma unroll
+        for (int c = 0; c < U; ++c)
+            xv[c] = X[1 + i[c] + half];
+#pragma unroll
+        for (int c = 0; c < U; ++c)
+            i[c] = xv[c] <= z0[c] ? i[c] + half : i[c];
+        len -= half;
+    }
+    const double x_first = X[1];
+    double d[U], w[U], yi[U], si[U], run[U];
+#pragma unroll
+    for (int c = 0; c < U; ++c) {
+        i[c] += z0[c] >= x_first ? 1 : 0;
+        d[c] = z0[c] - X[i[c]];           // d = z - start of the interval (exact)
+        w[c] = W[i[c]];                   // width of the interval
+        const f64x2 ys = YS[i[c]];
+        yi[c] = ys.x;
+        si[c] = ys.y;
+        run[c] = 0.0;
+    }
+#pragma unroll
+    for (int c = 0; c < U; ++c) {
+        settle(d[c], w[c], yi[c], si[c]);
+        chain_fetch_ahead(C.w_lds + 8u * i[c], C.ys_lds + 16u * i[c], nw[c], nys[c]);
+    }
+    // Above the last sample nothing is crossed any more: when every size of the wave is
+    // there already, the walk needs no comparison at all.
+    bool beyond = true;
+#pragma unroll
+    for (int c = 0; c < U; ++c)
+        beyond = beyond && i[c] == n;
+    const bool no_crossing = __ballot(!beyond) == 0;
+    int jj = 0;
+    for (;;) {
+        // run without any bookkeeping up to the next point where a sum is wanted
+        const int hit = any_wanted != 0 ? __builtin_ctzll(any_wanted) : SUM_BLOCK;
+        if (no_crossing) {
+            for (; jj < hit; ++jj) {
+#pragma unroll
+                for (int c = 0; c < U; ++c) {
+                    run[c] = run[c] + __builtin_fma(si[c], d[c], yi[c]);
+                    d[c] += md;
+                }
+            }
+        }
+        for (; jj < hit; ++jj) {
+            bool cross[U], any_cross = false;
+#pragma unroll
+            for (int c = 0; c < U; ++c) {
+                cross[c] = d[c] >= w[c];
+                any_cross = any_cross || cross[c];
+            }
+            if (any_cross) {            // some chain enters its next interval (fetched ahead)
+                chain_await<U>(nw, nys);
+#pragma unroll
+                for (int c = 0; c < U; ++c) {
+                    if (cross[c]) {
+                        d[c] -= w[c];
+                        w[c] = nw[c];
+                        yi[c] = nys[c].x;
+                        si[c] = nys[c].y;
+                        ++i[c];
+                        if (d[c] >= w[c])
+                            chain_skip_ahead(X, YS, W, n, i[c], d[c], w[c], yi[c], si[c]);
+                        chain_fetch_ahead(C.w_lds + 8u * i[c], C.ys_lds + 16u * i[c], nw[c], nys[c]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < U; ++c) {
+                run[c] = run[c] + __builtin_fma(si[c], d[c], yi[c]);
+                d[c] += md;
+            }
+        }
+        if (hit == SUM_BLOCK)
+            break;
+#pragma unroll
+        for (int c = 0; c < U; ++c) {
+            if ((wanted[c] >> hit) & 1ull) {
+                part[pi[c]] = run[c];
+                ++pi[c];
+            }
+        }
+        any_wanted &= any_wanted - 1;
+    }
+#pragma unroll
+    for (int c = 0; c < U; ++c)
+        if (c < n_act && b0 + c < C.n_blk - 1)     // the last block is never complete
+            tot[(size_t)(b0 + c) * C.n_m] = run[c];
+    chain_await<U>(nw, nys);              // nothing in flight when the item ends
+}
+
+// One block whose consecutive sizes j m lie many intervals apart (small j on a
+// table with many samples): every term gets its own search of the table, four
+// terms side by side; the terms are added in ascending j as everywhere.
+__device__ __forceinline__ void chain_search_block(const ChainCtx &C, int b, u64 m, double *part,
+                                                   double *tot)
+{
+    constexpr int V = 4;
+    const int n = C.n;
+    const double *X = C.X;
+    const f64x2 *YS = C.YS;
+    const u64 wanted = C.blk_mask[b];
+    int pi = C.blk_off[b];
+    const double x_first = X[1];
+    const u64 j0 = (u64)b * SUM_BLOCK + 1;
+    double run = 0.0;
+    for (int r0 = 0; r0 < SUM_BLOCK; r0 += V) {
+        double z[V], g[V];
+        int i[V];
+#pragma unroll
+        for (int c = 0; c < V; ++c) {
+            z[c] = (double)((j0 + r0 + c) * m);
+            i[c] = 0;
+        }
+        for (int len = n; len > 1;) {
+            const int half = len >> 1;
+            double xv[V];
+#pragma unroll
+            for (int c = 0; c < V; ++c)
+                xv[c] = X[1 + i[c] + half];
+#pragma unroll
+            for (int c = 0; c < V; ++c)
+                i[c] = xv[c] <= z[c] ? i[c] + half : i[c];
+            len -= half;
+        }
+#pragma unroll
+        for (int c = 0; c < V; ++c) {
+            i[c] += z[c] >= x_first ? 1 : 0;
+            const f64x2 ys = YS[i[c]];
+            g[c] = __builtin_fma(ys.y, z[c] - X[i[c]], ys.x);
+        }
+#pragma unroll
+        for (int c = 0; c < V; ++c) {
+            if ((wanted >> (r0 + c)) & 1ull) {      // bit r: the sum after r terms is wanted
+                part[pi] = run;
+                ++pi;
+            }
+            run = run + g[c];
+        }
+    }
+    if (b < C.n_blk - 1)
+        tot[(size_t)b * C.n_m] = run;
+}
+
+// Work items of one table, in this order: (block b, group of 64 sizes mg) for the
+// n_single leading blocks, one block each -- small j, where the walk crosses
+// many intervals per term and an item takes longest; the first n_search of them
+// search per term -- then (unit u, mg) with CHAIN_U blocks each.  The items are
+// dealt to the workgroups of the table in rounds, every other round in reverse
+// order, so that every workgroup gets its share of the heavy items and meets
+// them first; inside a workgroup the waves take the next item of its list from
+// a counter in LDS, because how long an item takes depends on how often its
+// sizes cross an interval.
+constexpr int CHAIN_U = 4;           // blocks walked side by side by a lane in the sparse part
+
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
-                               int n_units, int nb)
+                               int n_single, int n_search)
 {
     extern __shared__ __align__(16) double chain_lds[];
     __shared__ unsigned next_item;
@@ -429,113 +684,57 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int n_mg = (G.n_m + 63) / 64;
-    const unsigned n_items = (unsigned)n_units * (unsigned)n_mg;
-    // items of this workgroup: wg, wg + wg_per_table, ...
-    const unsigned my_items = n_items > (unsigned)wg ? (n_items - wg + wg_per_table - 1) / wg_per_table : 0u;
-    const unsigned w_lds = (unsigned)(uintptr_t)W, ys_lds = (unsigned)(uintptr_t)YS;
-    const size_t n_m = (size_t)G.n_m;
-    double nw = 0.0;                      // the next interval, fetched ahead
-    f64x2 nys = {0.0, 0.0};
+    const unsigned n_single_items = (unsigned)n_single * (unsigned)n_mg;
+    const unsigned n_units = (unsigned)((G.n_blk - n_single + CHAIN_U - 1) / CHAIN_U);
+    const unsigned n_items = n_single_items + n_units * (unsigned)n_mg;
+    const unsigned W_ = (unsigned)wg_per_table;
+    ChainCtx C;
+    C.YS = YS;
+    C.X = X;
+    C.W = W;
+    C.w_lds = (unsigned)(uintptr_t)W;
+    C.ys_lds = (unsigned)(uintptr_t)YS;
+    C.n = n;
+    C.n_blk = G.n_blk;
+    C.n_m = (size_t)G.n_m;
+    C.blk_mask = G.blk_mask;
+    C.blk_off = G.blk_off;
+    double nw[CHAIN_U];                   // the next interval of each chain, fetched ahead
+    f64x2 nys[CHAIN_U];
+#pragma unroll
+    for (int c = 0; c < CHAIN_U; ++c) {
+        nw[c] = 0.0;
+        nys[c] = f64x2{0.0, 0.0};
+    }
     for (;;) {
         unsigned k = 0;
         if (lane == 0)
             k = atomicAdd(&next_item, 1u);
         k = __builtin_amdgcn_readfirstlane(k);
-        if (k >= my_items)
-            break;
-        const unsigned item = (unsigned)wg + k * (unsigned)wg_per_table;
-        const int u = (int)(item / (unsigned)n_mg), mg = (int)(item % (unsigned)n_mg);
+        // round k of the deal: this workgroup's place is wg, or W_ - 1 - wg in odd rounds
+        const unsigned item = k * W_ + ((k & 1u) ? W_ - 1u - (unsigned)wg : (unsigned)wg);
+        if (item >= n_items)
+            break;                        // later rounds lie further on still
+        const bool single = item < n_single_items;
+        const unsigned rest = single ? item : item - n_single_items;
+        const int u = (int)(rest / (unsigned)n_mg), mg = (int)(rest % (unsigned)n_mg);
         const int mi = mg * 64 + lane;
         if (mi >= G.n_m)
             continue;
-        const int b0 = u < CHAIN_SINGLE ? u : CHAIN_SINGLE + (u - CHAIN_SINGLE) * nb;
-        const int nbl = u < CHAIN_SINGLE ? 1 : nb;
         const u64 m = G.m[mi];
-        const double md = (double)m;
-        const double z0 = (double)(((u64)b0 * SUM_BLOCK + 1) * m);
-        // interval of z0: number of samples not above z0 (0 = the virtual interval)
-        int i = last_not_above(X + 1, n, z0) + (z0 >= X[1] ? 1 : 0);
-        double d = z0 - X[i];                 // d = z - start of the interval (exact)
-        double w = W[i];                      // width of the interval
-        double yi = YS[i].x, si = YS[i].y;
-        settle(d, w, yi, si);
-        chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
-        double *part = S.part + ((size_t)t * n_m + mi) * G.n_P;     // [m][P index]
-        double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;       // [block][m]
-        for (int bb = 0; bb < nbl; ++bb) {
-            const int b = b0 + bb;
-            if (b >= G.n_blk)
-                break;
-            const int nterms = (b == G.n_blk - 1) ? G.last_terms : SUM_BLOCK;
-            u64 wanted = G.blk_mask[b];         // bit r: some grid P needs the sum after r terms
-            int pi = G.blk_off[b];
-            double run = 0.0;
-            int jj = 0;
-            for (;;) {
-                // run without any bookkeeping up to the next point where a sum is wanted
-                int hit = wanted != 0 ? __builtin_ctzll(wanted) : SUM_BLOCK;
-                if (hit > nterms)
-                    hit = SUM_BLOCK;
-                const int stop = hit < nterms ? hit : nterms;
-                for (; jj < stop; ++jj) {
-                    if (d >= w) {               // crossed into the next interval (fetched ahead)
-                        chain_await(nw, nys);
-                        d -= w;
-                        w = nw;
-                        yi = nys.x;
-                        si = nys.y;
-                        ++i;
-                        if (d >= w) {
-                            // dense part of the table (small j): z is several intervals on.
-                            // e = z - end of interval i.  Look four intervals ahead a few
-                            // times, then search the rest of the table for z = xb + e
-                            // (exact: integers below 2^53).
-                            double xb = X[i + 1];
-                            double e = d - w;
-                            int hops = 0;
-                            for (;;) {
-                                const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
-                                const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
-                                if (e >= r4) {
-                                    if (++hops == 3) {
-                                        const double z = xb + e;
-                                        // samples not above z = index of its interval
-                                        i = last_not_above(X + 1, n, z) + 1;
-                                        d = z - X[i];
-                                        break;
-                                    }
-                                    i += 4;
-                                    e -= r4;
-                                    xb += r4;
-                                    continue;
-                                }
-                                const int c = (e >= r1 ? 1 : 0) + (e >= r2 ? 1 : 0) + (e >= r3 ? 1 : 0);
-                                const double lo = c == 0 ? 0.0 : (c == 1 ? r1 : (c == 2 ? r2 : r3));
-                                d = e - lo;
-                                i += 1 + c;
-                                break;
-                            }
-                            const f64x2 ys = YS[i];
-                            w = W[i];
-                            yi = ys.x;
-                            si = ys.y;
-                            settle(d, w, yi, si);
-                        }
-                        chain_fetch_ahead(w_lds + 8u * i, ys_lds + 16u * i, nw, nys);
-                    }
-                    run = run + __builtin_fma(si, d, yi);
-                    d += md;
-                }
-                if (hit == SUM_BLOCK)
-                    break;
-                part[pi] = run;
-                ++pi;
-                wanted &= wanted - 1;
-            }
-            if (nterms == SUM_BLOCK)
-                tot[(size_t)b * n_m] = run;
+        double *part = S.part + ((size_t)t * C.n_m + mi) * G.n_P;     // [m][P index]
+        double *tot = S.blk + (size_t)t * G.n_blk * C.n_m + mi;       // [block][m]
+        if (!single) {
+            chain_walk<CHAIN_U>(C, n_single + u * CHAIN_U, m, part, tot, nw, nys);
+        } else if (u < n_search) {
+            chain_search_block(C, u, m, part, tot);
+        } else {
+            double nw1[1] = {nw[0]};
+            f64x2 nys1[1] = {nys[0]};
+            chain_walk<1>(C, u, m, part, tot, nw1, nys1);
+            nw[0] = nw1[0];
+            nys[0] = nys1[0];
         }
-        chain_await(nw, nys);             // nothing in flight when the item ends
     }
 }
 
@@ -1785,22 +1984,26 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
 
     if (G.mask & (1u << 11)) {
         // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
-        // stays for its whole share of the work (the table is staged once), and several
-        // blocks per item so that the search at the start of an item is amortised
+        // stays for its whole share of the work (the table is staged once)
         const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
-        const int nb = big ? 4 : 1;
-        const int single = G.n_blk < CHAIN_SINGLE ? G.n_blk : CHAIN_SINGLE;
-        const int n_units = single + (G.n_blk - single + nb - 1) / nb;
-        const long n_items = (long)n_units * ((G.n_m + 63) / 64);
+        const int n_mg = (G.n_m + 63) / 64;
+        // leading blocks that are items of their own: the dense part of a table with many
+        // samples (its first blocks search per term), or every block when the whole sum is
+        // too small to fill the chip with units of CHAIN_U blocks
+        int n_single = T.n > 256 ? 32 : 0, n_search = T.n > 256 ? 4 : 0;
+        if ((long)T.n_tables * n_mg * ((G.n_blk + CHAIN_U - 1) / CHAIN_U) < 2048) n_single = G.n_blk;
+        if (n_single > G.n_blk) n_single = G.n_blk;
+        if (n_search > n_single) n_search = n_single;
+        const long n_items = (long)n_mg * (n_single + (G.n_blk - n_single + CHAIN_U - 1) / CHAIN_U);
         long wg = (big ? 256 : 1024) / T.n_tables;
         const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
         for (int r = 0; r < reps; ++r)
             hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)(T.n_tables * wg)), dim3(threads),
-                               chain_lds, st, T, G, S, (int)wg, n_units, nb);
+                               chain_lds, st, T, G, S, (int)wg, n_single, n_search);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
