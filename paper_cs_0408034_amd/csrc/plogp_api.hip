@@ -51,12 +51,14 @@ int ceil_log2_u32(uint32_t v) { int f = floor_log2_u32(v); return ((1u << f) == 
 
 struct plogp_table {
     size_t n_tables = 0, n = 0;
+    bool shared_x = false;      // every table has the sample sizes of the first one
     double *d_x = nullptr, *d_y = nullptr, *d_slope = nullptr, *d_L = nullptr;
     DeviceTables view() const
     {
         DeviceTables v;
         v.x = d_x; v.y = d_y; v.slope = d_slope; v.L = d_L;
         v.n = (int)n; v.n_tables = (int)n_tables;
+        v.shared_x = shared_x ? 1 : 0;
         return v;
     }
     ~plogp_table()
@@ -80,6 +82,8 @@ struct plogp_grid {
     // scratch, sized for scratch_tables tables
     size_t scratch_tables = 0, scratch_samples = 0;
     Scratch scratch = {};
+    // scratch of the path for batches with shared sample sizes
+    size_t batch_tables = 0, batch_samples = 0;
     // scratch of the cut-over extraction, sized for cut_tables tables
     size_t cut_tables = 0;
     CutScratch cut = {};
@@ -108,6 +112,16 @@ struct plogp_grid {
         scratch_tables = 0;
         scratch_samples = 0;
     }
+    void free_batch_scratch()
+    {
+        BatchPrep &b = scratch.batch;
+        void *all[] = {b.rec, b.tab, scratch.batch_ys};
+        for (void *p : all)
+            if (p) (void)hipFree(p);
+        b = BatchPrep{};
+        scratch.batch_ys = nullptr;
+        batch_tables = batch_samples = 0;
+    }
     void free_cut_scratch()
     {
         if (cut.counts) (void)hipFree(cut.counts);
@@ -120,6 +134,7 @@ struct plogp_grid {
     ~plogp_grid()
     {
         free_scratch();
+        free_batch_scratch();
         free_cut_scratch();
         if (d_m) (void)hipFree(d_m);
         if (d_s) (void)hipFree(d_s);
@@ -166,6 +181,10 @@ int plogp_load_tables(const double *sizes, const double *gaps, size_t n, const d
     if (!h) return PLOGP_ENOMEM;
     h->n = n;
     h->n_tables = n_tables;
+    h->shared_x = true;
+    for (size_t t = 1; t < n_tables && h->shared_x; ++t)
+        for (size_t i = 0; i < n; ++i)
+            if (sizes[t * n + i] != sizes[i]) { h->shared_x = false; break; }
     const size_t bytes = n_tables * n * sizeof(double);
     hipError_t e;
     if ((e = hipMalloc((void **)&h->d_x, bytes)) != hipSuccess ||
@@ -372,14 +391,47 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
     return PLOGP_OK;
 }
 
+static int ensure_batch_scratch(plogp_grid *g, size_t n_tables, size_t n)
+{
+    if (g->batch_tables >= n_tables && g->batch_samples == n) return PLOGP_OK;
+    HIP_TRY(hipDeviceSynchronize());     // an earlier tune on this handle may still run
+    g->free_batch_scratch();
+    BatchPrep &b = g->scratch.batch;
+    const BatchRec R((int)n, (int)g->n_s, g->cl_max);
+    struct { void **p; size_t bytes; } want[] = {
+        {(void **)&b.rec, g->n_m * (size_t)R.slots * sizeof(double)},
+        {(void **)&b.tab, (2 + (n + 1) + 2 * (g->n_s ? g->n_s : 1)) * sizeof(double)},
+        {(void **)&g->scratch.batch_ys, (n + 2) * n_tables * 2 * sizeof(double)},
+    };
+    for (auto &w : want) {
+        hipError_t e = hipMalloc(w.p, w.bytes);
+        if (e != hipSuccess) {
+            g->free_batch_scratch();
+            if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }
+            return device_error(e);
+        }
+    }
+    g->batch_tables = n_tables;
+    g->batch_samples = n;
+    return PLOGP_OK;
+}
+
+// Scratch for whichever path launch_tune will take.
+static int ensure_tune_scratch(const plogp_table *t, plogp_grid *g)
+{
+    if (use_table_lane_path(t->view(), g->view())) return ensure_batch_scratch(g, t->n_tables, t->n);
+    if (use_fused_path(t->view(), g->view())) return PLOGP_OK;
+    return ensure_scratch(g, t->n_tables, t->n);
+}
+
 int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size_t d_out_bytes,
                     void *stream)
 {
     if (!t || !g || !d_out) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
-    if (!use_fused_path(t->view(), g->view())) {
-        int rc = ensure_scratch(g, t->n_tables, t->n);
+    {
+        int rc = ensure_tune_scratch(t, g);
         if (rc != PLOGP_OK) return rc;
     }
     HIP_TRY(launch_tune(t->view(), g->view(), g->scratch,
@@ -393,8 +445,8 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     if (!t || !g || !d_out || !stage_ms_out || reps < 1 || reps > 10000) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
     if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
-    if (!use_fused_path(t->view(), g->view())) {
-        int rc = ensure_scratch(g, t->n_tables, t->n);
+    {
+        int rc = ensure_tune_scratch(t, g);
         if (rc != PLOGP_OK) return rc;
     }
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -412,9 +464,10 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
     for (int i = 0; i < 5; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     if (e != hipSuccess) return device_error(e);
-    const bool fused = use_fused_path(t->view(), g->view());
+    const bool table_lanes = use_table_lane_path(t->view(), g->view());
+    const bool fused = table_lanes || use_fused_path(t->view(), g->view());
     const bool chain = (g->mask & (1u << 11)) != 0 && !fused;
-    if (fused) ms[0] = 0.f;
+    if (fused && !table_lanes) ms[0] = 0.f;
     stage_ms_out[0] = ms[0];
     stage_ms_out[1] = chain ? ms[1] : 0.f;
     stage_ms_out[2] = chain ? ms[2] : 0.f;

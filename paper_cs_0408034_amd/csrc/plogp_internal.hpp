@@ -27,6 +27,7 @@ struct DeviceTables {
     const double *L;      // [n_tables]
     int n;                // samples per table
     int n_tables;
+    int shared_x;         // 1: every table has the sample sizes of table 0
 };
 
 // Device-resident grid plus the index metadata of the Scatter-chain blocks.
@@ -47,6 +48,36 @@ struct DeviceGrid {
                           // 0 (few blocks): the sweep adds the finished blocks itself
 };
 
+// Facts about where the grid's sizes fall among the samples, for batches whose
+// tables share their sample sizes (the same for every table; written by
+// k_batch_prep).  Intervals: 0 = below the first sample, i + 1 = from sample i on.
+struct BatchPrep {
+    double *rec;      // [n_m][BatchRec::slots]  everything about one message size (see BatchRec)
+    double *tab;      // [2 + (n+1) + 2 n_s]     interval of size 1 and 1 minus its start; widths of
+                      //                         the intervals (the last: +inf); per candidate: s minus
+                      //                         the start of its interval, then that interval
+};
+
+// Layout of one record of BatchPrep::rec, in 8-byte slots.
+struct BatchRec {
+    int DM;       // m minus the start of its interval
+    int MD;       // m as a double
+    int IM_NV;    // two int32: interval of m; candidates s <= min(m, s_cap)
+    int D2;       // [cl_max] 2^j m minus the start of its interval
+    int K;        // [n_s] k = ceil(m / s)
+    int I2;       // [cl_max] int32: interval of 2^j m
+    int JEND;     // [n+1] uint32: last j whose size j m lies in interval i
+    int slots;
+    __host__ __device__ BatchRec(int n, int n_s, int cl_max)
+    {
+        DM = 0; MD = 1; IM_NV = 2; D2 = 3;
+        K = D2 + cl_max;
+        I2 = K + n_s;
+        JEND = I2 + (cl_max + 1) / 2;
+        slots = JEND + (n + 2) / 2;
+    }
+};
+
 // Per-(tables, grid) scratch in device memory, all written and read by kernels.
 struct Scratch {
     double *g1;       // [n_tables]                       g(1)
@@ -63,6 +94,8 @@ struct Scratch {
     double *segA;     // [n_tables][n_m][n_s]             A = g(s) ceil(m/s), +inf where s does not compete
     double *segB;     // [n_tables][n_m][n_s]             B = g(s) (ceil(m/s) - 1)   (both: n_s <= SWEEP_M_MAX_S only)
     int *nv;          // [n_m]                            candidates s <= min(m, s_cap)
+    BatchPrep batch;  // shared sample sizes only
+    double *batch_ys; // [n+2][n_tables][2]               {gap, slope} by interval (shared sample sizes only)
 };
 
 struct plogp_cell_dev {
@@ -107,5 +140,6 @@ hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_d
 
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
+bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G);
 
 }  // namespace plogp

@@ -1874,6 +1874,365 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     }
 }
 
+// ---- whole path for batches of tables that share their sample sizes ----------
+//
+// Measured tables of many clusters are normally taken at the same list of
+// message sizes.  Then, for a fixed m, everything that depends on where a size
+// falls among the samples -- the interval of m, of 2^j m, of every j m of the
+// Scatter-chain sum, the candidates that compete, k = ceil(m / s) -- is the same
+// for all tables, and only the gaps, slopes and L differ.  So here the lanes of a
+// wave run over 64 tables and the wave walks over message sizes: all control
+// flow is wave-uniform (no lane ever waits for another lane's interval
+// crossing), the table entries are read as coalesced rows of a copy laid out
+// [interval][table], and the per-m facts come from small tables prepared once
+// per call by k_batch_prep.
+
+// One thread per entry of the prepared facts.  Uses table 0's sample sizes.
+// Intervals are numbered as in the chain walk: 0 = [0, x_0) (the clamp: gap y_0,
+// slope 0), i + 1 = [x_i, x_{i+1}), n = [x_{n-1}, inf).  Everything about one
+// message size sits in one record of B.rec (layout: BatchRec).
+__global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G, BatchPrep B)
+{
+    extern __shared__ double lds[];
+    const int n = T.n;
+    double *x = lds;                              // samples of table 0
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+        x[i] = T.x[i];
+    __syncthreads();
+    // interval of size z and z minus the start of that interval (exact)
+    auto locate = [&](double z, int &iv, double &dz) {
+        const int cnt = last_not_above(x, n, z) + (z >= x[0] ? 1 : 0);     // samples not above z
+        iv = cnt;
+        dz = cnt == 0 ? z : z - x[cnt - 1];
+    };
+    const BatchRec R(n, G.n_s, G.cl_max);
+    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long stride = (long)gridDim.x * blockDim.x;
+    for (long e = tid; e < G.n_m; e += stride) {
+        double *rec = B.rec + (size_t)e * R.slots;
+        const u64 m = G.m[e];
+        int iv;
+        double dz;
+        locate((double)m, iv, dz);
+        const u64 lim = m < G.s_cap ? m : G.s_cap;          // candidates s <= min(m, s_cap) ascend
+        int lo = 0, hi = G.n_s;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
+        }
+        rec[R.DM] = dz;
+        rec[R.MD] = (double)m;
+        reinterpret_cast<int *>(rec + R.IM_NV)[0] = iv;
+        reinterpret_cast<int *>(rec + R.IM_NV)[1] = lo;
+    }
+    for (long e = tid; e < (long)G.n_m * G.cl_max; e += stride) {
+        const long mi = e / G.cl_max;
+        const int j = (int)(e % G.cl_max);
+        double *rec = B.rec + (size_t)mi * R.slots;
+        int iv;
+        double dz;
+        locate((double)(G.m[mi] << j), iv, dz);
+        rec[R.D2 + j] = dz;
+        reinterpret_cast<int *>(rec + R.I2)[j] = iv;
+    }
+    for (long e = tid; e < (long)G.n_m * (n + 1); e += stride) {
+        // last j whose size j m still lies in interval i of this m: below the next sample
+        const long mi = e / (n + 1);
+        const int i = (int)(e % (n + 1));
+        const u64 m = G.m[mi];
+        u64 last = 0xFFFFFFFFull;
+        if (i < n) {
+            last = ((u64)x[i] - 1ull) / m;
+            last = last < 0xFFFFFFFFull ? last : 0xFFFFFFFFull;
+        }
+        reinterpret_cast<unsigned *>(B.rec + (size_t)mi * R.slots + R.JEND)[i] = (unsigned)last;
+    }
+    for (long e = tid; e < (long)G.n_m * G.n_s; e += stride) {
+        const long mi = e / G.n_s;
+        const int si = (int)(e % G.n_s);
+        const u64 m = G.m[mi], sv = G.s[si];
+        B.rec[(size_t)mi * R.slots + R.K + si] = (double)((m + sv - 1ull) / sv);   // k = ceil(m / s), exact
+    }
+    // B.tab: interval of size 1 and 1 minus its start; widths of the intervals; per candidate
+    // s minus the start of its interval, then its interval
+    for (long e = tid; e < G.n_s; e += stride) {
+        int iv;
+        double dz;
+        locate((double)G.s[e], iv, dz);
+        B.tab[2 + (n + 1) + e] = dz;
+        B.tab[2 + (n + 1) + G.n_s + e] = (double)iv;
+    }
+    for (long e = tid; e <= n; e += stride)
+        B.tab[2 + e] = e == 0 ? x[0] : (e < n ? x[e] - x[e - 1] : INFINITY);
+    if (tid == 0) {
+        int i1;
+        double d1;
+        locate(1.0, i1, d1);
+        B.tab[0] = (double)i1;
+        B.tab[1] = d1;
+    }
+}
+
+// The tables laid out by interval: ysT[i][t] = {gap, slope} of interval i of table t
+// (i = 0: the clamp {y_0, 0}; i = n + 1: zeros, only ever fetched ahead).  The slopes
+// are formed here from the raw samples.
+__global__ void __launch_bounds__(256) k_batch_stage(DeviceTables T, f64x2 *ysT)
+{
+    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = T.n;
+    const long total = (long)(n + 2) * T.n_tables;
+    if (e >= total)
+        return;
+    const int i = (int)(e / T.n_tables), t = (int)(e % T.n_tables);
+    const double *x = T.x + (size_t)t * n, *y = T.y + (size_t)t * n;
+    f64x2 v = {0.0, 0.0};
+    if (i == 0)
+        v = f64x2{y[0], 0.0};
+    else if (i <= n)
+        v = f64x2{y[i - 1], interval_slope(x, y, n, i - 1)};
+    ysT[e] = v;
+}
+
+constexpr size_t BATCH_T_LDS_MAX = 160 * 1024;     // LDS of a compute unit
+
+// A wave-uniform read of data that no kernel writes while this one runs, through the
+// scalar cache (constant address space).  Unlike a vector load it does not queue behind
+// the wave's outstanding stores.
+template <class V>
+__device__ __forceinline__ V uniform_load(const V *p)
+{
+    typedef const V __attribute__((address_space(4))) *const_ptr;
+    return *(const_ptr)(p);
+}
+constexpr int BATCH_T_WAVES = 16;      // waves of a workgroup; they share the 64 tables
+constexpr int BATCH_T_PC = 4;          // process counts per pass over the candidates
+
+struct BatchDims {
+    int n, n_tables, n_m, n_P, n_s, cl_max, n_ops, n_mchunks, m_per_wave;
+    uint32_t mask;
+};
+
+// A workgroup stages its 64 tables by interval in LDS (YS[i][lane] = {gap, slope}
+// of interval i of the lane's table) together with their g(s); every later
+// access to a table is one conflict-free LDS read of a whole row.  All other
+// inputs are wave-uniform and come through the scalar cache.  The cells of PC
+// process counts are turned round in LDS so that a store writes 64-byte runs.
+template <int PC>
+__global__ void __launch_bounds__(64 * BATCH_T_WAVES)
+k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
+          const double *__restrict__ recs, const double *__restrict__ tab,
+          const uint32_t *__restrict__ p_P, const u64 *__restrict__ p_s,
+          plogp_cell_dev *__restrict__ out)
+{
+    extern __shared__ __align__(16) double batch_lds[];
+    const int n = D.n, n_s = D.n_s, n_P = D.n_P;
+    const BatchRec R(n, n_s, D.cl_max);
+    f64x2 *YS = reinterpret_cast<f64x2 *>(batch_lds);          // [n + 2][64]
+    double *GS = batch_lds + (size_t)2 * (n + 2) * 64;         // [n_s][64]
+    // per wave: the PC cells of 64 tables on their way out, rows padded by one cell
+    uint4 *stage_all = reinterpret_cast<uint4 *>(GS + (size_t)(n_s ? n_s : 1) * 64);
+    uint32_t *sS = reinterpret_cast<uint32_t *>(stage_all + (size_t)BATCH_T_WAVES * 64 * (PC + 1));   // [n_s]
+    const int tg = blockIdx.x / D.n_mchunks, mc = blockIdx.x % D.n_mchunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int t = tg * 64 + lane;
+    const int tc = t < D.n_tables ? t : D.n_tables - 1;
+    const double L = Lt[tc];
+    const uint32_t mask = D.mask;
+    for (int si = threadIdx.x; si < n_s; si += blockDim.x)
+        sS[si] = (uint32_t)p_s[si];
+    for (int i = wave; i < n + 2; i += BATCH_T_WAVES)
+        YS[i * 64 + lane] = ysT[(size_t)i * D.n_tables + tc];
+    __syncthreads();
+    const f64x2 *ys = YS + lane;                               // this lane's table: ys[64 i]
+    const double *tab_ds = tab + 2 + (n + 1), *tab_is = tab_ds + n_s, *Wd = tab + 2;
+    for (int si = wave; si < n_s; si += BATCH_T_WAVES) {
+        const f64x2 v = ys[64 * (int)uniform_load(tab_is + si)];
+        GS[si * 64 + lane] = __builtin_fma(v.y, uniform_load(tab_ds + si), v.x);
+    }
+    double g1;
+    {
+        const f64x2 v = ys[64 * (int)uniform_load(tab)];
+        g1 = __builtin_fma(v.y, uniform_load(tab + 1), v.x);
+    }
+    __syncthreads();
+    const double *gsl = GS + lane;                             // g(s) of this lane's table: gsl[64 si]
+    uint4 *stage = stage_all + (size_t)wave * 64 * (PC + 1);
+    // A store instruction writes the PC cells (PC x 16 contiguous bytes) of 64 / PC tables:
+    // lane l takes cell l % PC of table row l / PC + (64 / PC) it, it = 0 .. PC - 1.
+    static_assert(PC == 4, "64-byte runs");
+    const int out_p = lane % PC, out_row = lane / PC;
+    const size_t plane = (size_t)D.n_m * n_P;
+    const size_t table_cells = (size_t)D.n_ops * plane;
+    // first cell this lane writes in a flush, less the (plane, m, p0) part
+    plogp_cell_dev *const o_lane = out + ((size_t)tg * 64 + out_row) * table_cells + out_p;
+    const int rows_left = D.n_tables - tg * 64 - out_row;      // rows 'it' with (64 / PC) it < rows_left exist
+    auto flush = [&](size_t cell0, int p0) {
+        // cell0: index of cell (plane, mi, p0) inside a table
+        __builtin_amdgcn_wave_barrier();
+        if (p0 + out_p < n_P) {
+#pragma unroll
+            for (int it = 0; it < PC; ++it)
+                if ((64 / PC) * it < rows_left)
+                    *reinterpret_cast<uint4 *>(o_lane + (size_t)(64 / PC) * it * table_cells + cell0) =
+                        stage[(out_row + (64 / PC) * it) * (PC + 1) + out_p];
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
+    const bool has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
+
+    for (int mw = 0; mw < D.m_per_wave; ++mw) {
+        const int mi = (mc * BATCH_T_WAVES + wave) * D.m_per_wave + mw;      // wave-uniform
+        if (mi >= D.n_m)
+            break;
+        const double *rec = recs + (size_t)mi * R.slots;
+        const double md = uniform_load(rec + R.MD);
+        const int nvm = uniform_load(reinterpret_cast<const int *>(rec + R.IM_NV) + 1);
+        const double *Krow = rec + R.K;
+        const unsigned *jend = reinterpret_cast<const unsigned *>(rec + R.JEND);
+        // g(m); the chain sum starts at j = 1 in the same interval
+        int ci = uniform_load(reinterpret_cast<const int *>(rec + R.IM_NV));
+        f64x2 cur = ys[64 * ci];
+        double d = uniform_load(rec + R.DM);                    // size - start of its interval
+        const double gm = __builtin_fma(cur.y, d, cur.x);
+        unsigned je = uniform_load(jend + ci);                  // last j inside interval ci
+        f64x2 nxt = ys[64 * (ci + 1)];                          // fetched one crossing ahead
+        double run = 0.0, done = 0.0;
+        unsigned j_done = 0;
+        double s12 = 0.0;
+        int cl_done = 0;
+        // minimum over s of A = g(s) k (rows 2 and 9 of Table 1 are monotone in A)
+        double amin = INFINITY;
+        if (mask & 0x204u)
+            for (int si = 0; si < nvm; ++si)
+                amin = min_f64(amin, gsl[64 * si] * uniform_load(Krow + si));
+
+        for (int p0 = 0; p0 < n_P; p0 += PC) {
+            const size_t cell0 = (size_t)mi * n_P + p0;
+            if (has_s) {
+                // Scatter plane, one process count after the other: the chain sum is walked
+                // along j while P ascends, the binomial sum grows with ceil(log2 P)
+#pragma nounroll
+                for (int p = 0; p < PC; ++p) {
+                    const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
+                    if (want_chain) {
+                        const unsigned target = P - 1u;
+                        while (j_done < target) {
+                            // up to the next process count, block end or interval end
+                            const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
+                            unsigned stop = target < block_end ? target : block_end;
+                            stop = stop < je ? stop : je;
+                            unsigned j = j_done;
+                            for (; j + 4u <= stop; j += 4u) {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) {
+                                    run = run + __builtin_fma(cur.y, d, cur.x);
+                                    d += md;
+                                }
+                            }
+                            for (; j < stop; ++j) {
+                                run = run + __builtin_fma(cur.y, d, cur.x);
+                                d += md;
+                            }
+                            j_done = stop;
+                            if (j_done % SUM_BLOCK == 0u) {
+                                done = done + run;
+                                run = 0.0;
+                            }
+                            while (je <= j_done) {              // the next size lies further on
+                                d -= uniform_load(Wd + ci);
+                                ++ci;
+                                cur = nxt;
+                                je = uniform_load(jend + ci);
+                                nxt = ys[64 * (ci + 1)];
+                            }
+                        }
+                    }
+                    if (want_binom) {
+                        const int cli = ceil_log2(P);
+                        while (cl_done < cli) {
+                            const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
+                            s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
+                            ++cl_done;
+                        }
+                    }
+                    const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
+                                                  done + run, s12);
+                    union { plogp_cell_dev c; uint4 v; } u;
+                    u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
+                    stage[lane * (PC + 1) + p] = u.v;
+                }
+                flush((has_b ? plane : 0) + cell0, p0);
+            }
+            if (!has_b)
+                continue;
+
+            double q[PC], fl[PC], clL[PC], cl[PC], b5[PC];
+            int i5[PC];
+#pragma unroll
+            for (int p = 0; p < PC; ++p) {
+                const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
+                q[p] = (double)(P - 1u);
+                fl[p] = (double)floor_log2(P);
+                cl[p] = (double)ceil_log2(P);
+                clL[p] = cl[p] * L;
+                b5[p] = INFINITY;
+                i5[p] = 0;
+            }
+            if (mask & (1u << 5)) {
+                for (int si = 0; si < nvm; ++si) {
+                    const double gs = gsl[64 * si], k = uniform_load(Krow + si);
+                    const double Bv = gs * (k - 1.0), Cv = gs + L;
+#pragma unroll
+                    for (int p = 0; p < PC; ++p) {
+                        const double T5 = __builtin_fma(q[p], Cv, Bv);
+                        i5[p] = T5 < b5[p] ? si : i5[p];
+                        b5[p] = min_f64(b5[p], T5);
+                    }
+                }
+            }
+            Best bc[PC];
+            bool any = false;
+#pragma unroll
+            for (int p = 0; p < PC; ++p) {
+                const double t2 = amin < INFINITY ? __builtin_fma(q[p], amin, L) : INFINITY;
+                const double t9 = amin < INFINITY ? __builtin_fma(fl[p], amin, clL[p]) : INFINITY;
+                const uint32_t s5 = b5[p] < INFINITY ? sS[i5[p]] : 0u;
+                bc[p] = decide_bcast(mask, q[p], fl[p], cl[p], gm, L, g1, t2, 0u, b5[p], s5, t9, 0u);
+                any = any || bc[p].id == 2u || bc[p].id == 9u;
+            }
+            if (__ballot(any) != 0) {
+                // a winning row 2 or 9: the first candidate whose value equals the minimum
+                bool open[PC];
+#pragma unroll
+                for (int p = 0; p < PC; ++p)
+                    open[p] = bc[p].id == 2u || bc[p].id == 9u;
+                for (int si = 0; si < nvm; ++si) {
+                    const double A = gsl[64 * si] * uniform_load(Krow + si);
+                    const uint32_t sv = sS[si];
+#pragma unroll
+                    for (int p = 0; p < PC; ++p) {
+                        const double Tv = bc[p].id == 2u ? __builtin_fma(q[p], A, L)
+                                                         : __builtin_fma(fl[p], A, clL[p]);
+                        if (open[p] && Tv == bc[p].t) {
+                            bc[p].s = sv;
+                            open[p] = false;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PC; ++p) {
+                union { plogp_cell_dev c; uint4 v; } u;
+                u.c.time = bc[p].t; u.c.s = bc[p].s; u.c.strategy = bc[p].id;
+                stage[lane * (PC + 1) + p] = u.v;
+            }
+            flush(cell0, p0);
+        }
+    }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launch wrappers
@@ -1898,6 +2257,9 @@ hipError_t kernels_init()
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
     return e;
 }
 
@@ -1939,6 +2301,21 @@ bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
     return (long)T.n_tables * G.n_m >= 8192 && G.n_s <= FUSED_NS && G.n_blk <= 32;
 }
 
+// LDS of a k_batch_t workgroup: 64 tables by interval, their g(s), the output staging.
+static size_t batch_t_lds(int n, int n_s)
+{
+    return ((size_t)2 * (n + 2) + (n_s ? n_s : 1)) * 64 * sizeof(double) +
+           (size_t)BATCH_T_WAVES * 64 * (BATCH_T_PC + 1) * 16 + (size_t)(n_s ? n_s : 1) * 4;
+}
+
+// Batches whose tables share their sample sizes, with enough tables to fill waves and
+// few enough samples and candidates for the LDS staging: lanes over tables.
+bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G)
+{
+    return T.shared_x && T.n_tables >= 64 && (long)T.n_tables * G.n_m >= 8192 &&
+           batch_t_lds(T.n, G.n_s) <= BATCH_T_LDS_MAX;
+}
+
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
                        plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev, int reps)
 {
@@ -1953,6 +2330,44 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     } while (0)
 
     PLOGP_MARK(0);
+    if (use_table_lane_path(T, G)) {
+        // tables by interval and the per-m facts, then everything else in one kernel
+        const long stage_items = (long)(T.n + 2) * T.n_tables;
+        for (int r = 0; r < reps; ++r) {
+            hipLaunchKernelGGL(k_batch_stage, dim3((unsigned)((stage_items + 255) / 256)), dim3(256), 0,
+                               st, T, reinterpret_cast<f64x2 *>(S.batch_ys));
+            long prep_items = (long)G.n_m * (T.n + 1);
+            if ((long)G.n_m * G.n_s > prep_items) prep_items = (long)G.n_m * G.n_s;
+            long prep_wg = (prep_items + 255) / 256;
+            if (prep_wg > 1024) prep_wg = 1024;
+            hipLaunchKernelGGL(k_batch_prep, dim3((unsigned)prep_wg), dim3(256),
+                               (size_t)T.n * sizeof(double), st, T, G, S.batch);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        PLOGP_MARK(1);
+        PLOGP_MARK(2);
+        PLOGP_MARK(3);
+        // a workgroup: 64 tables x (BATCH_T_WAVES waves x m_per_wave sizes)
+        const int n_tg = (T.n_tables + 63) / 64;
+        const int per = BATCH_T_WAVES;
+        int m_per_wave = 8;
+        while (m_per_wave > 1 && (long)n_tg * ((G.n_m + per * m_per_wave - 1) / (per * m_per_wave)) < 1024)
+            m_per_wave >>= 1;
+        const int n_mchunks = (G.n_m + per * m_per_wave - 1) / (per * m_per_wave);
+        const size_t lds = batch_t_lds(T.n, G.n_s);
+        BatchDims D;
+        D.n = T.n; D.n_tables = T.n_tables; D.n_m = G.n_m; D.n_P = G.n_P; D.n_s = G.n_s;
+        D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = n_mchunks; D.m_per_wave = m_per_wave;
+        D.mask = G.mask;
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_batch_t<BATCH_T_PC>, dim3((unsigned)n_tg * n_mchunks),
+                               dim3(64 * BATCH_T_WAVES), lds, st, D,
+                               reinterpret_cast<const f64x2 *>(S.batch_ys), T.L, S.batch.rec, S.batch.tab,
+                               G.P, reinterpret_cast<const u64 *>(G.s), d_out);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        PLOGP_MARK(4);
+        return hipSuccess;
+    }
     if (use_fused_path(T, G)) {
         PLOGP_MARK(1);
         PLOGP_MARK(2);

@@ -279,6 +279,41 @@ def test_batch_path_ragged_chunk_many_blocks_and_masks():
         assert assert_tables_equal(gpu_tune(wl), want, "batch path mask %x" % mask)
 
 
+def test_table_lane_path_on_config_4_tables():
+    # 100 tables with the same sample sizes (one full group of 64 and a ragged one of 36)
+    # over the whole grid of config 4: the path whose lanes run over tables
+    wl = make_workload(4, n_tables=100, table_offset=2000)
+    assert (wl.sizes == wl.sizes[0]).all()
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "cfg4 x100, lanes over tables")
+
+
+def test_table_lane_path_ragged_many_blocks_and_masks():
+    # 70 tables x 300 sizes; P up to 2048 (32 blocks of the chain sum, process counts at
+    # and next to block ends), 13 process counts (a ragged chunk), 24 candidates, a cap
+    base = make_workload(4, n_tables=70, table_offset=700)
+    m = np.sort(np.random.default_rng(5).choice(make_workload(4, n_m=400).m, size=300))
+    P = np.array([2, 3, 63, 64, 65, 66, 128, 129, 130, 1000, 1985, 2047, 2048], dtype=np.uint32)
+    s = np.array([8 << j for j in range(24)], dtype=np.uint64)
+    for mask, cap in ((ALL_STRATEGIES_MASK, NO_CAP), (0x3FF, 1 << 12), (0x1C00, NO_CAP),
+                      ((1 << 1) | (1 << 4) | (1 << 8) | (1 << 11), NO_CAP), (1 << 9, NO_CAP),
+                      ((1 << 2) | (1 << 12), NO_CAP)):
+        wl = Workload("batch", base.sizes, base.gaps, base.L, m, P, s, cap, mask)
+        want, _ = oracle.tune_workload(wl)
+        assert assert_tables_equal(gpu_tune(wl), want, "lanes over tables, mask %x" % mask)
+
+
+def test_batch_whose_tables_do_not_share_sample_sizes():
+    # one table of 128 sampled elsewhere: the batch must not take the path that assumes
+    # shared sample sizes
+    wl = make_workload(4, n_tables=128, table_offset=300, n_m=64)
+    sizes = wl.sizes.copy()
+    sizes[77, 5:9] += 1.0
+    wl2 = Workload("mixed", sizes, wl.gaps, wl.L, wl.m, wl.P, wl.s, wl.s_cap, wl.strategy_mask)
+    want, _ = oracle.tune_workload(wl2)
+    assert assert_tables_equal(gpu_tune(wl2), want, "batch with one table sampled elsewhere")
+
+
 def test_output_too_small_and_misaligned_are_refused():
     torch = torch_cuda()
     plogp = _plogp()
