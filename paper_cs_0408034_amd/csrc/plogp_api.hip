@@ -400,7 +400,7 @@ static int ensure_batch_scratch(plogp_grid *g, size_t n_tables, size_t n)
     const BatchRec R((int)n, (int)g->n_s, g->cl_max);
     struct { void **p; size_t bytes; } want[] = {
         {(void **)&b.rec, g->n_m * (size_t)R.slots * sizeof(double)},
-        {(void **)&b.tab, (2 + (n + 1) + 2 * (g->n_s ? g->n_s : 1)) * sizeof(double)},
+        {(void **)&b.tab, (2 + (n + 1) + 2 * (g->n_s ? g->n_s : 1) + 3 * g->n_P) * sizeof(double)},
         {(void **)&g->scratch.batch_ys, (n + 2) * n_tables * 2 * sizeof(double)},
     };
     for (auto &w : want) {

@@ -53,9 +53,10 @@ struct DeviceGrid {
 // k_batch_prep).  Intervals: 0 = below the first sample, i + 1 = from sample i on.
 struct BatchPrep {
     double *rec;      // [n_m][BatchRec::slots]  everything about one message size (see BatchRec)
-    double *tab;      // [2 + (n+1) + 2 n_s]     interval of size 1 and 1 minus its start; widths of
-                      //                         the intervals (the last: +inf); per candidate: s minus
-                      //                         the start of its interval, then that interval
+    double *tab;      // [2 + (n+1) + 2 n_s + 3 n_P]  interval of size 1 and 1 minus its start; widths
+                      //                         of the intervals (the last: +inf); per candidate: s minus
+                      //                         the start of its interval, then that interval; per
+                      //                         process count: P - 1, floor(log2 P), ceil(log2 P)
 };
 
 // Layout of one record of BatchPrep::rec, in 8-byte slots.

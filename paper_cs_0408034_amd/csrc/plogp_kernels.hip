@@ -839,15 +839,13 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
                                              uint32_t s2, double t5, uint32_t s5, double t9,
                                              uint32_t s9)
 {
-    const double R = __builtin_fma(3.0, L, 2.0 * g1);   // rendezvous: 2 g(1) + 3 L
     const double clL = cl * L;
-    Best b = {INFINITY, 0u, 0xFFFFFFFFu};
-    // When R >= L (always, unless g(1) rounds below zero) a rendezvous row is never
-    // below its plain twin, because rounding is monotone; with the twin enabled
-    // (lower id: it also wins ties) the rendezvous row cannot be chosen and is not
-    // evaluated.
-    const bool twin_wins = R >= L;
-    if ((mask & 0x3FFu) == 0x3FFu && twin_wins) {
+    // A rendezvous row adds R - L = 2 g(1) + 2 L to its plain twin's latency term.  Gaps
+    // and latencies are checked to be non-negative when a table is loaded and g(1) is the
+    // first gap (size 1 is never above the first sample), so R >= L, and as rounding is
+    // monotone a rendezvous row is never below its twin; with the twin enabled (lower id:
+    // it also wins ties) the rendezvous row cannot be chosen and is not evaluated.
+    if ((mask & 0x3FFu) == 0x3FFu) {
         // the usual case, every row enabled: rows 0, 2, 3, 5, 6, 7, 9 compete; the running
         // minimum and the id of the first row that attains it
         const double v0 = __builtin_fma(q, gm, L), v3 = q * (gm + L);
@@ -866,11 +864,15 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
         best = min_f64(best, v7);
         id = t9 < best ? 9u : id;
         best = min_f64(best, t9);
+        Best b;
         b.t = best;
         b.id = id;
         b.s = id == 2u ? s2 : (id == 5u ? s5 : (id == 9u ? s9 : 0u));
         return b;
     }
+    const double R = __builtin_fma(3.0, L, 2.0 * g1);   // rendezvous: 2 g(1) + 3 L
+    Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+    const bool twin_wins = true;
     if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
     if ((mask & 2u) && !((mask & 1u) && twin_wins)) consider(b, __builtin_fma(q, gm, R), 1, 0);
     if (mask & (1u << 2)) consider(b, t2, 2, s2);
@@ -1954,7 +1956,7 @@ __global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G
         B.rec[(size_t)mi * R.slots + R.K + si] = (double)((m + sv - 1ull) / sv);   // k = ceil(m / s), exact
     }
     // B.tab: interval of size 1 and 1 minus its start; widths of the intervals; per candidate
-    // s minus the start of its interval, then its interval
+    // s minus the start of its interval, then its interval; per process count three doubles
     for (long e = tid; e < G.n_s; e += stride) {
         int iv;
         double dz;
@@ -1964,6 +1966,14 @@ __global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G
     }
     for (long e = tid; e <= n; e += stride)
         B.tab[2 + e] = e == 0 ? x[0] : (e < n ? x[e] - x[e - 1] : INFINITY);
+    // per process count: P - 1, floor(log2 P), ceil(log2 P) as doubles
+    for (long e = tid; e < G.n_P; e += stride) {
+        double *pt = B.tab + 2 + (n + 1) + 2 * (size_t)G.n_s + 3 * e;
+        const uint32_t P = G.P[e];
+        pt[0] = (double)(P - 1u);
+        pt[1] = (double)floor_log2(P);
+        pt[2] = (double)ceil_log2(P);
+    }
     if (tid == 0) {
         int i1;
         double d1;
@@ -2005,7 +2015,8 @@ __device__ __forceinline__ V uniform_load(const V *p)
     return *(const_ptr)(p);
 }
 constexpr int BATCH_T_WAVES = 16;      // waves of a workgroup; they share the 64 tables
-constexpr int BATCH_T_PC = 4;          // process counts per pass over the candidates
+constexpr int BATCH_T_PC = 4;          // cells of a table written together (64 bytes)
+constexpr int BATCH_T_PS = 12;         // process counts per pass over the candidates
 
 struct BatchDims {
     int n, n_tables, n_m, n_P, n_s, cl_max, n_ops, n_mchunks, m_per_wave;
@@ -2017,7 +2028,7 @@ struct BatchDims {
 // access to a table is one conflict-free LDS read of a whole row.  All other
 // inputs are wave-uniform and come through the scalar cache.  The cells of PC
 // process counts are turned round in LDS so that a store writes 64-byte runs.
-template <int PC>
+template <int PC, int PS>
 __global__ void __launch_bounds__(64 * BATCH_T_WAVES)
 k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
           const double *__restrict__ recs, const double *__restrict__ tab,
@@ -2046,6 +2057,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     __syncthreads();
     const f64x2 *ys = YS + lane;                               // this lane's table: ys[64 i]
     const double *tab_ds = tab + 2 + (n + 1), *tab_is = tab_ds + n_s, *Wd = tab + 2;
+    const double *tab_P = tab_is + n_s;                        // {P - 1, floor log2 P, ceil log2 P}
     for (int si = wave; si < n_s; si += BATCH_T_WAVES) {
         const f64x2 v = ys[64 * (int)uniform_load(tab_is + si)];
         GS[si * 64 + lane] = __builtin_fma(v.y, uniform_load(tab_ds + si), v.x);
@@ -2064,18 +2076,30 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     const int out_p = lane % PC, out_row = lane / PC;
     const size_t plane = (size_t)D.n_m * n_P;
     const size_t table_cells = (size_t)D.n_ops * plane;
-    // first cell this lane writes in a flush, less the (plane, m, p0) part
-    plogp_cell_dev *const o_lane = out + ((size_t)tg * 64 + out_row) * table_cells + out_p;
+    // Where this lane reads the staged cells and where they go: a wave-uniform 64-bit part
+    // (table group, row step, plane, m, p0) plus a per-lane 32-bit byte offset, so that the
+    // stores need no per-lane 64-bit addresses.
+    const uint4 *stage_rd = stage + out_row * (PC + 1) + out_p;
+    const unsigned lane_off = (unsigned)(((size_t)out_row * table_cells + out_p) * sizeof(plogp_cell_dev));
+    char *const o_grp = reinterpret_cast<char *>(out + (size_t)tg * 64 * table_cells);
     const int rows_left = D.n_tables - tg * 64 - out_row;      // rows 'it' with (64 / PC) it < rows_left exist
     auto flush = [&](size_t cell0, int p0) {
         // cell0: index of cell (plane, mi, p0) inside a table
         __builtin_amdgcn_wave_barrier();
         if (p0 + out_p < n_P) {
 #pragma unroll
-            for (int it = 0; it < PC; ++it)
-                if ((64 / PC) * it < rows_left)
-                    *reinterpret_cast<uint4 *>(o_lane + (size_t)(64 / PC) * it * table_cells + cell0) =
-                        stage[(out_row + (64 / PC) * it) * (PC + 1) + out_p];
+            for (int it = 0; it < PC; ++it) {
+                char *ubase = o_grp + ((size_t)(64 / PC) * it * table_cells + cell0) * sizeof(plogp_cell_dev);
+                if ((64 / PC) * it < rows_left) {
+                    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                    const u32x4 cell = reinterpret_cast<const u32x4 *>(stage_rd)[(64 / PC) * it * (PC + 1)];
+                    // wave-uniform base in scalar registers + 32-bit lane offset
+                    asm volatile("global_store_dwordx4 %0, %1, %2"
+                                 :
+                                 : "v"(lane_off), "v"(cell), "s"(ubase)
+                                 : "memory");
+                }
+            }
         }
         __builtin_amdgcn_wave_barrier();
     };
@@ -2108,127 +2132,144 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
             for (int si = 0; si < nvm; ++si)
                 amin = min_f64(amin, gsl[64 * si] * uniform_load(Krow + si));
 
-        for (int p0 = 0; p0 < n_P; p0 += PC) {
-            const size_t cell0 = (size_t)mi * n_P + p0;
-            if (has_s) {
-                // Scatter plane, one process count after the other: the chain sum is walked
-                // along j while P ascends, the binomial sum grows with ceil(log2 P)
-#pragma nounroll
-                for (int p = 0; p < PC; ++p) {
-                    const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
-                    if (want_chain) {
-                        const unsigned target = P - 1u;
-                        while (j_done < target) {
-                            // up to the next process count, block end or interval end
-                            const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
-                            unsigned stop = target < block_end ? target : block_end;
-                            stop = stop < je ? stop : je;
-                            unsigned j = j_done;
-                            for (; j + 4u <= stop; j += 4u) {
+        // PS process counts per pass over the candidates (the per-candidate terms are formed
+        // once for all of them), then PC cells at a time are decided and written
+        for (int q0 = 0; q0 < n_P; q0 += PS) {
+            double b5[PS];
+            int i5[PS];
 #pragma unroll
-                                for (int r = 0; r < 4; ++r) {
-                                    run = run + __builtin_fma(cur.y, d, cur.x);
-                                    d += md;
-                                }
-                            }
-                            for (; j < stop; ++j) {
-                                run = run + __builtin_fma(cur.y, d, cur.x);
-                                d += md;
-                            }
-                            j_done = stop;
-                            if (j_done % SUM_BLOCK == 0u) {
-                                done = done + run;
-                                run = 0.0;
-                            }
-                            while (je <= j_done) {              // the next size lies further on
-                                d -= uniform_load(Wd + ci);
-                                ++ci;
-                                cur = nxt;
-                                je = uniform_load(jend + ci);
-                                nxt = ys[64 * (ci + 1)];
-                            }
-                        }
-                    }
-                    if (want_binom) {
-                        const int cli = ceil_log2(P);
-                        while (cl_done < cli) {
-                            const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
-                            s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
-                            ++cl_done;
-                        }
-                    }
-                    const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
-                                                  done + run, s12);
-                    union { plogp_cell_dev c; uint4 v; } u;
-                    u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
-                    stage[lane * (PC + 1) + p] = u.v;
-                }
-                flush((has_b ? plane : 0) + cell0, p0);
-            }
-            if (!has_b)
-                continue;
-
-            double q[PC], fl[PC], clL[PC], cl[PC], b5[PC];
-            int i5[PC];
-#pragma unroll
-            for (int p = 0; p < PC; ++p) {
-                const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
-                q[p] = (double)(P - 1u);
-                fl[p] = (double)floor_log2(P);
-                cl[p] = (double)ceil_log2(P);
-                clL[p] = cl[p] * L;
+            for (int p = 0; p < PS; ++p) {
                 b5[p] = INFINITY;
                 i5[p] = 0;
             }
-            if (mask & (1u << 5)) {
+            if (has_b && (mask & (1u << 5))) {
+                double q[PS];                                   // wave-uniform
+#pragma unroll
+                for (int p = 0; p < PS; ++p)
+                    q[p] = uniform_load(tab_P + 3 * (q0 + p < n_P ? q0 + p : n_P - 1));
                 for (int si = 0; si < nvm; ++si) {
                     const double gs = gsl[64 * si], k = uniform_load(Krow + si);
                     const double Bv = gs * (k - 1.0), Cv = gs + L;
 #pragma unroll
-                    for (int p = 0; p < PC; ++p) {
+                    for (int p = 0; p < PS; ++p) {
                         const double T5 = __builtin_fma(q[p], Cv, Bv);
                         i5[p] = T5 < b5[p] ? si : i5[p];
                         b5[p] = min_f64(b5[p], T5);
                     }
                 }
             }
-            Best bc[PC];
-            bool any = false;
 #pragma unroll
-            for (int p = 0; p < PC; ++p) {
-                const double t2 = amin < INFINITY ? __builtin_fma(q[p], amin, L) : INFINITY;
-                const double t9 = amin < INFINITY ? __builtin_fma(fl[p], amin, clL[p]) : INFINITY;
-                const uint32_t s5 = b5[p] < INFINITY ? sS[i5[p]] : 0u;
-                bc[p] = decide_bcast(mask, q[p], fl[p], cl[p], gm, L, g1, t2, 0u, b5[p], s5, t9, 0u);
-                any = any || bc[p].id == 2u || bc[p].id == 9u;
-            }
-            if (__ballot(any) != 0) {
-                // a winning row 2 or 9: the first candidate whose value equals the minimum
-                bool open[PC];
-#pragma unroll
-                for (int p = 0; p < PC; ++p)
-                    open[p] = bc[p].id == 2u || bc[p].id == 9u;
-                for (int si = 0; si < nvm; ++si) {
-                    const double A = gsl[64 * si] * uniform_load(Krow + si);
-                    const uint32_t sv = sS[si];
-#pragma unroll
+            for (int g = 0; g < PS / PC; ++g) {
+                const int p0 = q0 + g * PC;
+                if (p0 >= n_P)
+                    break;
+                const size_t cell0 = (size_t)mi * n_P + p0;
+                if (has_s) {
+                    // Scatter plane, one process count after the other: the chain sum is walked
+                    // along j while P ascends, the binomial sum grows with ceil(log2 P)
+#pragma nounroll
                     for (int p = 0; p < PC; ++p) {
-                        const double Tv = bc[p].id == 2u ? __builtin_fma(q[p], A, L)
-                                                         : __builtin_fma(fl[p], A, clL[p]);
-                        if (open[p] && Tv == bc[p].t) {
-                            bc[p].s = sv;
-                            open[p] = false;
+                        const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
+                        if (want_chain) {
+                            const unsigned target = P - 1u;
+                            while (j_done < target) {
+                                // up to the next process count, block end or interval end
+                                const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
+                                unsigned stop = target < block_end ? target : block_end;
+                                stop = stop < je ? stop : je;
+                                unsigned j = j_done;
+                                for (; j + 4u <= stop; j += 4u) {
+#pragma unroll
+                                    for (int r = 0; r < 4; ++r) {
+                                        run = run + __builtin_fma(cur.y, d, cur.x);
+                                        d += md;
+                                    }
+                                }
+                                for (; j < stop; ++j) {
+                                    run = run + __builtin_fma(cur.y, d, cur.x);
+                                    d += md;
+                                }
+                                j_done = stop;
+                                if (j_done % SUM_BLOCK == 0u) {
+                                    done = done + run;
+                                    run = 0.0;
+                                }
+                                while (je <= j_done) {              // the next size lies further on
+                                    d -= uniform_load(Wd + ci);
+                                    ++ci;
+                                    cur = nxt;
+                                    je = uniform_load(jend + ci);
+                                    nxt = ys[64 * (ci + 1)];
+                                }
+                            }
+                        }
+                        if (want_binom) {
+                            const int cli = ceil_log2(P);
+                            while (cl_done < cli) {
+                                const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
+                                s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
+                                ++cl_done;
+                            }
+                        }
+                        const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
+                                                      done + run, s12);
+                        union { plogp_cell_dev c; uint4 v; } u;
+                        u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
+                        stage[lane * (PC + 1) + p] = u.v;
+                    }
+                    flush((has_b ? plane : 0) + cell0, p0);
+                }
+                if (!has_b)
+                    continue;
+                double q[PC], fl[PC], clL[PC], cl[PC];          // q, fl, cl: wave-uniform
+#pragma unroll
+                for (int p = 0; p < PC; ++p) {
+                    const double *pt = tab_P + 3 * (p0 + p < n_P ? p0 + p : n_P - 1);
+                    q[p] = uniform_load(pt);
+                    fl[p] = uniform_load(pt + 1);
+                    cl[p] = uniform_load(pt + 2);
+                    clL[p] = cl[p] * L;
+                }
+                Best bc[PC];
+                bool any = false;
+#pragma unroll
+                for (int p = 0; p < PC; ++p) {
+                    // without a candidate amin is +inf, and so are both values (q, fl >= 1)
+                    const double t2 = __builtin_fma(q[p], amin, L);
+                    const double t9 = __builtin_fma(fl[p], amin, clL[p]);
+                    const double t5 = b5[g * PC + p];
+                    const uint32_t s5 = t5 < INFINITY ? sS[i5[g * PC + p]] : 0u;
+                    bc[p] = decide_bcast(mask, q[p], fl[p], cl[p], gm, L, g1, t2, 0u, t5, s5, t9, 0u);
+                    any = any || bc[p].id == 2u || bc[p].id == 9u;
+                }
+                if (__ballot(any) != 0) {
+                    // a winning row 2 or 9: the first candidate whose value equals the minimum
+                    bool open[PC];
+#pragma unroll
+                    for (int p = 0; p < PC; ++p)
+                        open[p] = bc[p].id == 2u || bc[p].id == 9u;
+                    for (int si = 0; si < nvm; ++si) {
+                        const double A = gsl[64 * si] * uniform_load(Krow + si);
+                        const uint32_t sv = sS[si];
+#pragma unroll
+                        for (int p = 0; p < PC; ++p) {
+                            const double Tv = bc[p].id == 2u ? __builtin_fma(q[p], A, L)
+                                                             : __builtin_fma(fl[p], A, clL[p]);
+                            if (open[p] && Tv == bc[p].t) {
+                                bc[p].s = sv;
+                                open[p] = false;
+                            }
                         }
                     }
                 }
-            }
 #pragma unroll
-            for (int p = 0; p < PC; ++p) {
-                union { plogp_cell_dev c; uint4 v; } u;
-                u.c.time = bc[p].t; u.c.s = bc[p].s; u.c.strategy = bc[p].id;
-                stage[lane * (PC + 1) + p] = u.v;
+                for (int p = 0; p < PC; ++p) {
+                    union { plogp_cell_dev c; uint4 v; } u;
+                    u.c.time = bc[p].t; u.c.s = bc[p].s; u.c.strategy = bc[p].id;
+                    stage[lane * (PC + 1) + p] = u.v;
+                }
+                flush(cell0, p0);
             }
-            flush(cell0, p0);
         }
     }
 }
@@ -2258,7 +2299,7 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
     return e;
 }
@@ -2360,7 +2401,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = n_mchunks; D.m_per_wave = m_per_wave;
         D.mask = G.mask;
         for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_batch_t<BATCH_T_PC>, dim3((unsigned)n_tg * n_mchunks),
+            hipLaunchKernelGGL((k_batch_t<BATCH_T_PC, BATCH_T_PS>), dim3((unsigned)n_tg * n_mchunks),
                                dim3(64 * BATCH_T_WAVES), lds, st, D,
                                reinterpret_cast<const f64x2 *>(S.batch_ys), T.L, S.batch.rec, S.batch.tab,
                                G.P, reinterpret_cast<const u64 *>(G.s), d_out);
