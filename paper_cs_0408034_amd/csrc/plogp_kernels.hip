@@ -360,71 +360,68 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
 
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 
-// The interval after the current one is fetched from LDS when the walk enters
-// the current one and is first looked at one crossing later, so its latency
-// must not be waited for at the point of issue.  The compiler's own wait
-// insertion would do exactly that (the loaded values feed loop-carried
-// registers), so the two reads are issued here, into the registers that carry
-// the values round the loop, and waited for in chain_await(), through which
-// every use of the fetched values passes.
-// w_addr, ys_addr: LDS byte addresses of W[i] and YS[i]; fetched: W[i + 1], YS[i + 1].
-__device__ __forceinline__ void chain_fetch_ahead(unsigned w_addr, unsigned ys_addr, double &nw,
-                                                  f64x2 &nys)
-{
-    asm volatile("ds_read_b64 %0, %2 offset:8\n\tds_read_b128 %1, %3 offset:16"
-                 : "+v"(nw), "+v"(nys)
-                 : "v"(w_addr), "v"(ys_addr)
-                 : "memory");
-}
+// The table as the chain walk sees it, in LDS, as intervals.  Interval 0 is
+// virtual: [0, x_0) with gap y_0 and slope 0 (the clamp below the first
+// sample); interval i + 1 starts at sample i; the last one never ends (its
+// width is +inf) and starts of +inf follow it.
+struct ChainCtx {
+    const f64x2 *YS;      // [n + 2] {gap at the start of the interval, slope}
+    const double *X;      // [n + 6] interval starts
+    const double *W;      // [n + 2] interval widths
+    int n;                // samples of the table
+    int n_blk;
+    size_t n_m;
+    const u64 *blk_mask;
+    const int *blk_off;
+};
 
-// Waits for every fetch issued so far; all registers that a fetch may still be
-// writing pass through here.
+// Intervals of U sizes at once: for each the number of samples not above it
+// (0 = the virtual interval).  The searches run side by side, so that the LDS
+// latencies of one halving step overlap.
 template <int U>
-__device__ __forceinline__ void chain_await(double (&nw)[U], f64x2 (&nys)[U])
+__device__ __forceinline__ void chain_locate(const double *X, int n, const double (&z)[U], int (&i)[U])
 {
-    static_assert(U == 1 || U == 2 || U == 4, "one operand pair per chain");
-    if constexpr (U == 1)
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(nw[0]), "+v"(nys[0]) : : "memory");
-    else if constexpr (U == 2)
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(nw[0]), "+v"(nys[0]), "+v"(nw[1]), "+v"(nys[1])
-                     :
-                     : "memory");
-    else
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(nw[0]), "+v"(nys[0]), "+v"(nw[1]), "+v"(nys[1]), "+v"(nw[2]),
-                       "+v"(nys[2]), "+v"(nw[3]), "+v"(nys[3])
-                     :
-                     : "memory");
-}
-
-// Makes the wait for an ordinary LDS read happen here rather than at a later
-// join of the control flow (where it would also wait for reads fetched ahead).
-__device__ __forceinline__ void settle(double &a, double &b, double &c, double &e)
-{
-    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(e));
+#pragma unroll
+    for (int c = 0; c < U; ++c)
+        i[c] = 0;
+    for (int len = n; len > 1;) {
+        const int half = len >> 1;
+        double xv[U];
+#pragma unroll
+        for (int c = 0; c < U; ++c)
+            xv[c] = X[1 + i[c] + half];
+#pragma unroll
+        for (int c = 0; c < U; ++c)
+            i[c] = xv[c] <= z[c] ? i[c] + half : i[c];
+        len -= half;
+    }
+    const double x_first = X[1];
+#pragma unroll
+    for (int c = 0; c < U; ++c)
+        i[c] += z[c] >= x_first ? 1 : 0;
 }
 
 // Dense part of the table (small j): after moving into interval i the size is
-// still at or past its end (d >= w), i.e. several intervals on.  e = z - end of
-// interval i.  Looks four intervals ahead a few times, then searches the rest
-// of the table for z = xb + e (exact: integers below 2^53).  Leaves i, d, w and
-// the interval's {gap, slope}.
-__device__ __forceinline__ void chain_skip_ahead(const double *X, const f64x2 *YS, const double *W,
-                                                 int n, int &i, double &d, double &w, double &yi,
-                                                 double &si)
+// still at or past its end (d >= w), i.e. several intervals on.  Looks four
+// intervals ahead a few times, then searches the rest of the table for the size
+// itself (exact: integers below 2^53).  Leaves i, d and the interval's terms.
+__device__ __forceinline__ void chain_skip_ahead(const ChainCtx &C, int &i, double &d, double &w,
+                                                 double &yi, double &si)
 {
-    double xb = X[i + 1];
-    double e = d - w;
+    const double *X = C.X;
+    double xb = X[i + 1];         // end of interval i
+    double e = d - w;             // size - end of interval i
     int hops = 0;
     for (;;) {
         const double r1 = X[i + 2] - xb, r2 = X[i + 3] - xb;
         const double r3 = X[i + 4] - xb, r4 = X[i + 5] - xb;
         if (e >= r4) {
             if (++hops == 3) {
-                const double z = xb + e;
-                i = last_not_above(X + 1, n, z) + 1;       // samples not above z
-                d = z - X[i];
+                const double z[1] = {xb + e};
+                int iz[1];
+                chain_locate<1>(X, C.n, z, iz);
+                i = iz[0];
+                d = z[0] - X[i];
                 break;
             }
             i += 4;
@@ -438,37 +435,19 @@ __device__ __forceinline__ void chain_skip_ahead(const double *X, const f64x2 *Y
         i += 1 + c;
         break;
     }
-    const f64x2 ys = YS[i];
-    w = W[i];
+    const f64x2 ys = C.YS[i];
+    w = C.W[i];
     yi = ys.x;
     si = ys.y;
-    settle(d, w, yi, si);
 }
-
-// What a lane needs to know about the blocks of one work item.
-struct ChainCtx {
-    const f64x2 *YS;      // LDS: {gap, slope} per interval
-    const double *X;      // LDS: interval starts
-    const double *W;      // LDS: interval widths
-    unsigned w_lds, ys_lds;
-    int n;                // samples of the table
-    int n_blk;
-    size_t n_m;
-    const u64 *blk_mask;
-    const int *blk_off;
-};
 
 // U consecutive blocks from block b0 on, walked side by side for the size m of
 // this lane.  part: this size's row of in-block partial sums; tot: its column of
-// block totals.  nw, nys: the registers of the fetches ahead (nothing in flight
-// on entry and on return).
+// block totals.
 template <int U>
-__device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, double *part,
-                                           double *tot, double (&nw)[U], f64x2 (&nys)[U])
+__device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, double *part, double *tot)
 {
     const int n = C.n;
-    const double *X = C.X, *W = C.W;
-    const f64x2 *YS = C.YS;
     const int n_act = C.n_blk - b0 < U ? C.n_blk - b0 : U;      // chains that have a block
     const double md = (double)m;
     // per chain (wave-uniform): the points of its block at which some grid P needs the
@@ -481,51 +460,27 @@ __device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, dou
         pi[c] = c < n_act ? C.blk_off[b0 + c] : 0;
         any_wanted |= wanted[c];
     }
-    // interval of each chain's first size: number of samples not above it (0 = the
-    // virtual interval); the searches run side by side.  A chain without a block
-    // repeats the first one and is not stored.
+    // A chain without a block repeats the first one and is not stored.
     double z0[U];
     int i[U];
 #pragma unroll
-    for (int c = 0; c < U; ++c) {
-        const int b = c < n_act ? b0 + c : b0;
-        z0[c] = (double)(((u64)b * SUM_BLOCK + 1) * m);
-        i[c] = 0;
-    }
-    for (int len = n; len > 1;) {
-        const int half = len >> 1;
-        double xv[U];
-#pragma unroll
-        for (int c = 0; c < U; ++c)
-            xv[c] = X[1 + i[c] + half];
-#pragma unroll
-        for (int c = 0; c < U; ++c)
-            i[c] = xv[c] <= z0[c] ? i[c] + half : i[c];
-        len -= half;
-    }
-    const double x_first = X[1];
+    for (int c = 0; c < U; ++c)
+        z0[c] = (double)(((u64)(c < n_act ? b0 + c : b0) * SUM_BLOCK + 1) * m);
+    chain_locate<U>(C.X, n, z0, i);
     double d[U], w[U], yi[U], si[U], run[U];
+    bool beyond = true;         // every chain already above the last sample
 #pragma unroll
     for (int c = 0; c < U; ++c) {
-        i[c] += z0[c] >= x_first ? 1 : 0;
-        d[c] = z0[c] - X[i[c]];           // d = z - start of the interval (exact)
-        w[c] = W[i[c]];                   // width of the interval
-        const f64x2 ys = YS[i[c]];
+        d[c] = z0[c] - C.X[i[c]];         // d = z - start of the interval (exact)
+        w[c] = C.W[i[c]];
+        const f64x2 ys = C.YS[i[c]];
         yi[c] = ys.x;
         si[c] = ys.y;
         run[c] = 0.0;
-    }
-#pragma unroll
-    for (int c = 0; c < U; ++c) {
-        settle(d[c], w[c], yi[c], si[c]);
-        chain_fetch_ahead(C.w_lds + 8u * i[c], C.ys_lds + 16u * i[c], nw[c], nys[c]);
+        beyond = beyond && i[c] == n;
     }
     // Above the last sample nothing is crossed any more: when every size of the wave is
     // there already, the walk needs no comparison at all.
-    bool beyond = true;
-#pragma unroll
-    for (int c = 0; c < U; ++c)
-        beyond = beyond && i[c] == n;
     const bool no_crossing = __ballot(!beyond) == 0;
     int jj = 0;
     for (;;) {
@@ -547,19 +502,18 @@ __device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, dou
                 cross[c] = d[c] >= w[c];
                 any_cross = any_cross || cross[c];
             }
-            if (any_cross) {            // some chain enters its next interval (fetched ahead)
-                chain_await<U>(nw, nys);
+            if (any_cross) {            // some chain enters its next interval
 #pragma unroll
                 for (int c = 0; c < U; ++c) {
                     if (cross[c]) {
                         d[c] -= w[c];
-                        w[c] = nw[c];
-                        yi[c] = nys[c].x;
-                        si[c] = nys[c].y;
                         ++i[c];
+                        const f64x2 ys = C.YS[i[c]];
+                        w[c] = C.W[i[c]];
+                        yi[c] = ys.x;
+                        si[c] = ys.y;
                         if (d[c] >= w[c])
-                            chain_skip_ahead(X, YS, W, n, i[c], d[c], w[c], yi[c], si[c]);
-                        chain_fetch_ahead(C.w_lds + 8u * i[c], C.ys_lds + 16u * i[c], nw[c], nys[c]);
+                            chain_skip_ahead(C, i[c], d[c], w[c], yi[c], si[c]);
                     }
                 }
             }
@@ -584,7 +538,6 @@ __device__ __forceinline__ void chain_walk(const ChainCtx &C, int b0, u64 m, dou
     for (int c = 0; c < U; ++c)
         if (c < n_act && b0 + c < C.n_blk - 1)     // the last block is never complete
             tot[(size_t)(b0 + c) * C.n_m] = run[c];
-    chain_await<U>(nw, nys);              // nothing in flight when the item ends
 }
 
 // One block whose consecutive sizes j m lie many intervals apart (small j on a
@@ -594,38 +547,21 @@ __device__ __forceinline__ void chain_search_block(const ChainCtx &C, int b, u64
                                                    double *tot)
 {
     constexpr int V = 4;
-    const int n = C.n;
-    const double *X = C.X;
-    const f64x2 *YS = C.YS;
     const u64 wanted = C.blk_mask[b];
     int pi = C.blk_off[b];
-    const double x_first = X[1];
     const u64 j0 = (u64)b * SUM_BLOCK + 1;
     double run = 0.0;
     for (int r0 = 0; r0 < SUM_BLOCK; r0 += V) {
         double z[V], g[V];
         int i[V];
 #pragma unroll
-        for (int c = 0; c < V; ++c) {
+        for (int c = 0; c < V; ++c)
             z[c] = (double)((j0 + r0 + c) * m);
-            i[c] = 0;
-        }
-        for (int len = n; len > 1;) {
-            const int half = len >> 1;
-            double xv[V];
-#pragma unroll
-            for (int c = 0; c < V; ++c)
-                xv[c] = X[1 + i[c] + half];
-#pragma unroll
-            for (int c = 0; c < V; ++c)
-                i[c] = xv[c] <= z[c] ? i[c] + half : i[c];
-            len -= half;
-        }
+        chain_locate<V>(C.X, C.n, z, i);
 #pragma unroll
         for (int c = 0; c < V; ++c) {
-            i[c] += z[c] >= x_first ? 1 : 0;
-            const f64x2 ys = YS[i[c]];
-            g[c] = __builtin_fma(ys.y, z[c] - X[i[c]], ys.x);
+            const f64x2 ys = C.YS[i[c]];
+            g[c] = __builtin_fma(ys.y, z[c] - C.X[i[c]], ys.x);
         }
 #pragma unroll
         for (int c = 0; c < V; ++c) {
@@ -658,12 +594,8 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     __shared__ unsigned next_item;
     const int t = blockIdx.x / wg_per_table, wg = blockIdx.x % wg_per_table;
     const int n = T.n;
-    // Table as intervals (written by k_terms): YS[0..n+1] = {gap, slope}, X[0..n+2] =
-    // interval starts.  Interval 0 is virtual: [0, x_0) with gap y_0 and slope 0
-    // (the clamp below the first sample); interval i+1 starts at sample i;
-    // X[n+1] = X[n+2] = +inf.  Copied to LDS together with the widths W[i] =
-    // X[i+1] - X[i] (W[n] = W[n+1] = +inf); each interval is fetched from there one
-    // crossing before it is needed.
+    // the table as intervals (written by k_terms): cys[0..n+1] = {gap, slope}, cx[0..n+2] =
+    // interval starts (0, the samples, +inf, +inf)
     f64x2 *YS = reinterpret_cast<f64x2 *>(chain_lds);              // n + 2 entries
     double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries, +inf from n + 1 on
     double *W = X + (n + 6);                                       // n + 2 entries
@@ -692,20 +624,11 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     C.YS = YS;
     C.X = X;
     C.W = W;
-    C.w_lds = (unsigned)(uintptr_t)W;
-    C.ys_lds = (unsigned)(uintptr_t)YS;
     C.n = n;
     C.n_blk = G.n_blk;
     C.n_m = (size_t)G.n_m;
     C.blk_mask = G.blk_mask;
     C.blk_off = G.blk_off;
-    double nw[CHAIN_U];                   // the next interval of each chain, fetched ahead
-    f64x2 nys[CHAIN_U];
-#pragma unroll
-    for (int c = 0; c < CHAIN_U; ++c) {
-        nw[c] = 0.0;
-        nys[c] = f64x2{0.0, 0.0};
-    }
     for (;;) {
         unsigned k = 0;
         if (lane == 0)
@@ -724,17 +647,12 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
         const u64 m = G.m[mi];
         double *part = S.part + ((size_t)t * C.n_m + mi) * G.n_P;     // [m][P index]
         double *tot = S.blk + (size_t)t * G.n_blk * C.n_m + mi;       // [block][m]
-        if (!single) {
-            chain_walk<CHAIN_U>(C, n_single + u * CHAIN_U, m, part, tot, nw, nys);
-        } else if (u < n_search) {
+        if (!single)
+            chain_walk<CHAIN_U>(C, n_single + u * CHAIN_U, m, part, tot);
+        else if (u < n_search)
             chain_search_block(C, u, m, part, tot);
-        } else {
-            double nw1[1] = {nw[0]};
-            f64x2 nys1[1] = {nys[0]};
-            chain_walk<1>(C, u, m, part, tot, nw1, nys1);
-            nw[0] = nw1[0];
-            nys[0] = nys1[0];
-        }
+        else
+            chain_walk<1>(C, u, m, part, tot);
     }
 }
 
