@@ -4,6 +4,7 @@
 #include "../../include/plogp.h"
 #include "plogp_internal.hpp"
 
+#include <algorithm>
 #include <math.h>
 #include <new>
 #include <vector>
@@ -75,8 +76,10 @@ struct plogp_grid {
     uint64_t s_cap = 0;
     uint32_t mask = 0;
     int n_ops = 0, n_blk = 0, last_terms = 0, cl_max = 0;
-    uint64_t *d_m = nullptr, *d_s = nullptr;
+    uint64_t *d_m = nullptr, *d_s = nullptr, *d_mu = nullptr;
     uint32_t *d_P = nullptr;
+    int *d_m_map = nullptr;
+    size_t n_mu = 0;
     int *d_blk_off = nullptr;
     unsigned long long *d_blk_mask = nullptr;
     // scratch, sized for scratch_tables tables
@@ -92,6 +95,7 @@ struct plogp_grid {
     {
         DeviceGrid g;
         g.m = d_m; g.P = d_P; g.s = d_s; g.blk_off = d_blk_off; g.blk_mask = d_blk_mask;
+        g.mu = d_mu; g.m_map = d_m_map; g.n_mu = (int)n_mu;
         g.n_m = (int)n_m; g.n_P = (int)n_P; g.n_s = (int)n_s;
         g.n_blk = n_blk; g.last_terms = last_terms; g.cl_max = cl_max;
         g.s_cap = s_cap; g.mask = mask; g.n_ops = n_ops;
@@ -137,6 +141,8 @@ struct plogp_grid {
         free_batch_scratch();
         free_cut_scratch();
         if (d_m) (void)hipFree(d_m);
+        if (d_mu) (void)hipFree(d_mu);
+        if (d_m_map) (void)hipFree(d_m_map);
         if (d_s) (void)hipFree(d_s);
         if (d_P) (void)hipFree(d_P);
         if (d_blk_off) (void)hipFree(d_blk_off);
@@ -306,9 +312,20 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
         bmask[(d->P[i] - 1) / SUM_BLOCK] |= 1ull << ((d->P[i] - 1) % SUM_BLOCK);
     }
     for (int b = 0; b < g->n_blk; ++b) off[b + 1] += off[b];
+    // the distinct message sizes (index metadata: grids of log-spaced sizes rounded to the
+    // datatype repeat small sizes, and equal sizes have equal Scatter-chain sums)
+    std::vector<uint64_t> mu(d->m, d->m + d->n_m);
+    std::sort(mu.begin(), mu.end());
+    mu.erase(std::unique(mu.begin(), mu.end()), mu.end());
+    std::vector<int> m_map(d->n_m);
+    for (size_t i = 0; i < d->n_m; ++i)
+        m_map[i] = (int)(std::lower_bound(mu.begin(), mu.end(), d->m[i]) - mu.begin());
+    g->n_mu = mu.size();
 
     hipError_t e;
     if ((e = hipMalloc((void **)&g->d_m, d->n_m * sizeof(uint64_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->d_mu, mu.size() * sizeof(uint64_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->d_m_map, d->n_m * sizeof(int))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_P, d->n_P * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_s, (d->n_s ? d->n_s : 1) * sizeof(uint64_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_blk_off, off.size() * sizeof(int))) != hipSuccess ||
@@ -318,6 +335,8 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
         return device_error(e);
     }
     if ((e = hipMemcpy(g->d_m, d->m, d->n_m * sizeof(uint64_t), hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(g->d_mu, mu.data(), mu.size() * sizeof(uint64_t), hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(g->d_m_map, m_map.data(), d->n_m * sizeof(int), hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(g->d_P, d->P, d->n_P * sizeof(uint32_t), hipMemcpyHostToDevice)) != hipSuccess ||
         (d->n_s && (e = hipMemcpy(g->d_s, d->s, d->n_s * sizeof(uint64_t), hipMemcpyHostToDevice)) != hipSuccess) ||
         (e = hipMemcpy(g->d_blk_off, off.data(), off.size() * sizeof(int), hipMemcpyHostToDevice)) != hipSuccess ||

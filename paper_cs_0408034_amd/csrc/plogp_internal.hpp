@@ -33,11 +33,15 @@ struct DeviceTables {
 // Device-resident grid plus the index metadata of the Scatter-chain blocks.
 struct DeviceGrid {
     const uint64_t *m;    // [n_m]
+    const uint64_t *mu;   // [n_mu] the distinct message sizes, ascending (the Scatter-chain sums are
+                          //        formed once per distinct size)
+    const int *m_map;     // [n_m] index into mu of each message size
     const uint32_t *P;    // [n_P] strictly ascending
     const uint64_t *s;    // [n_s] strictly ascending
     const int *blk_off;   // [n_blk + 1] P-index range whose (P-1)/SUM_BLOCK equals the block
     const unsigned long long *blk_mask;  // [n_blk] bit r set: a grid P has P-1 == SUM_BLOCK*b + r
     int n_m, n_P, n_s;
+    int n_mu;
     int n_blk;            // (Pmax-1)/SUM_BLOCK + 1 blocks; the last one may be partial
     int last_terms;       // number of terms of the last block: (Pmax-1) - SUM_BLOCK*(n_blk-1)
     int cl_max;           // ceil(log2 Pmax)

@@ -615,7 +615,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     }
     __syncthreads();
     const int lane = threadIdx.x & 63;
-    const int n_mg = (G.n_m + 63) / 64;
+    const int n_mg = (G.n_mu + 63) / 64;      // groups of 64 distinct sizes
     const unsigned n_single_items = (unsigned)n_single * (unsigned)n_mg;
     const unsigned n_units = (unsigned)((G.n_blk - n_single + CHAIN_U - 1) / CHAIN_U);
     const unsigned n_items = n_single_items + n_units * (unsigned)n_mg;
@@ -626,7 +626,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     C.W = W;
     C.n = n;
     C.n_blk = G.n_blk;
-    C.n_m = (size_t)G.n_m;
+    C.n_m = (size_t)G.n_mu;
     C.blk_mask = G.blk_mask;
     C.blk_off = G.blk_off;
     for (;;) {
@@ -642,9 +642,9 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
         const unsigned rest = single ? item : item - n_single_items;
         const int u = (int)(rest / (unsigned)n_mg), mg = (int)(rest % (unsigned)n_mg);
         const int mi = mg * 64 + lane;
-        if (mi >= G.n_m)
+        if (mi >= G.n_mu)
             continue;
-        const u64 m = G.m[mi];
+        const u64 m = G.mu[mi];
         double *part = S.part + ((size_t)t * C.n_m + mi) * G.n_P;     // [m][P index]
         double *tot = S.blk + (size_t)t * G.n_blk * C.n_m + mi;       // [block][m]
         if (!single)
@@ -672,8 +672,8 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
     const int ml = tid % PFX_M, br = tid / PFX_M;        // br: 0 .. 256 / PFX_M - 1
     constexpr int ROWS = 256 / PFX_M;                    // rows of the tile loaded per pass
     const int mi = mg * PFX_M + ml;
-    const bool active = mi < G.n_m;
-    const size_t n_m = (size_t)G.n_m;
+    const bool active = mi < G.n_mu;
+    const size_t n_m = (size_t)G.n_mu;       // rows: the distinct sizes
     const double *src = S.blk + (size_t)t * G.n_blk * n_m + (active ? mi : 0);
     const int full = G.n_blk - 1;                        // blocks that have a total
     double done = 0.0;
@@ -703,7 +703,7 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
 #pragma unroll 4
             for (int mm = 0; mm < PFX_M; ++mm) {
                 const int m2 = mg * PFX_M + mm;
-                if (m2 < G.n_m)
+                if (m2 < G.n_mu)
                     S.pre[((size_t)t * n_m + m2) * G.n_blk + b0 + tid] = tile[tid * (PFX_M + 1) + mm];
             }
         }
@@ -820,7 +820,8 @@ __device__ __forceinline__ Best decide_scatter(uint32_t mask, double q, double c
 __device__ __forceinline__ double chain_sum_of(const DeviceGrid &G, const Scratch &S, int t, int mi,
                                                int pi, uint32_t P)
 {
-    const size_t n_m = (size_t)G.n_m;
+    const size_t n_m = (size_t)G.n_mu;      // the chain sums are kept per distinct size
+    mi = G.m_map[mi];
     const int blk = (int)((P - 1u) / SUM_BLOCK);
     double done;
     if (G.blk_is_prefix) {
@@ -977,10 +978,12 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
 #pragma unroll
     for (int p = 0; p < PC; ++p)
         done[p] = 0.0;
+    const size_t n_mu = (size_t)G.n_mu;      // the chain sums are kept per distinct size
+    const int um = G.m_map[mi];
     if (mask & (1u << 11)) {
-        const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
+        const double *tot = S.blk + (size_t)t * G.n_blk * n_mu + um;
         if (G.blk_is_prefix) {
-            const double *pre = S.pre + ((size_t)t * n_m + mi) * G.n_blk;
+            const double *pre = S.pre + ((size_t)t * n_mu + um) * G.n_blk;
 #pragma unroll
             for (int p = 0; p < PC; ++p)
                 done[p] = pre[(Pv[p] - 1u) / SUM_BLOCK];
@@ -999,7 +1002,7 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
                 double tv[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
-                    tv[u] = b0 + u < last ? tot[(size_t)(b0 + u) * n_m] : 0.0;
+                    tv[u] = b0 + u < last ? tot[(size_t)(b0 + u) * n_mu] : 0.0;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     if (b0 + u < last) {
@@ -1018,7 +1021,7 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
         const int pi = pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1;
         s11[p] = s12[p] = 0.0;
         if (mask & (1u << 11))
-            s11[p] = done[p] + S.part[((size_t)t * n_m + mi) * G.n_P + pi];
+            s11[p] = done[p] + S.part[((size_t)t * n_mu + um) * G.n_P + pi];
         if (mask & (1u << 12))
             s12[p] = S.sum2[((size_t)t * n_m + mi) * (G.cl_max + 1) + ceil_log2(Pv[p])];
         s5[p] = b5[p] < INFINITY ? (uint32_t)sS[i5[p]] : 0u;
@@ -1164,6 +1167,9 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     // what is fetched one size ahead
     double fA[NSV], fB[NSV], f_part = 0.0, f_s12 = 0.0, f_done = 0.0, f_gm;
     int f_nv;
+    // row of the chain sums (kept per distinct size) of the size fetched next: read one size
+    // earlier still, so that the fetch does not wait for it
+    int um_next = chain ? G.m_map[w] : 0;
     auto fetch = [&](int mi) {
         const size_t row = (size_t)t * n_m + mi;
         f_gm = S.gm[row];
@@ -1177,11 +1183,14 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
             }
         }
         if (chain) {
-            f_part = S.part[row * n_P + (active ? pi : n_P - 1)];
+            const int um = um_next;
+            um_next = G.m_map[mi + n_w < (int)n_m ? mi + n_w : mi];
+            const size_t urow = (size_t)t * G.n_mu + um;
+            f_part = S.part[urow * n_P + (active ? pi : n_P - 1)];
             if (G.blk_is_prefix)
-                f_done = S.pre[row * n_blk + blk];
+                f_done = S.pre[urow * n_blk + blk];
             else                       // few blocks: lane b holds the total of block b
-                f_done = lane < n_blk - 1 ? S.blk[((size_t)t * n_blk + lane) * n_m + mi] : 0.0;
+                f_done = lane < n_blk - 1 ? S.blk[((size_t)t * n_blk + lane) * G.n_mu + um] : 0.0;
         }
         if (binom)
             f_s12 = S.sum2[row * (G.cl_max + 1) + cli];
@@ -2362,7 +2371,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
         const bool big = chain_lds > 32768;
         const int threads = big ? 1024 : 256;
-        const int n_mg = (G.n_m + 63) / 64;
+        const int n_mg = (G.n_mu + 63) / 64;
         // leading blocks that are items of their own: the dense part of a table with many
         // samples (its first blocks search per term), or every block when the whole sum is
         // too small to fill the chip with units of CHAIN_U blocks
@@ -2381,7 +2390,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
-            const int n_mgroups = (G.n_m + PFX_M - 1) / PFX_M;
+            const int n_mgroups = (G.n_mu + PFX_M - 1) / PFX_M;
             for (int r = 0; r < reps; ++r)
                 hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256),
                                    0, st, G, S, n_mgroups);
