@@ -65,12 +65,19 @@ def describe(wl):
 # FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
 # kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
 MEASURED_TRAFFIC = {
-    2: {"terms": 0.139e6 + 0.662e6, "chain_blocks": 0.075e6 + 8.503e6, "sweep": 9.790e6 + 33.546e6},
-    3: {"terms": 0.169e6 + 0.318e6, "chain_blocks": 0.079e6 + 1.081e6,
-        "chain_prefix": 0.577e6 + 0.524e6, "sweep": 3.653e6 + 2.294e6},
-    4: {"sweep": 12.066e6 + 2378.371e6},
-    5: {"terms": 0.761e6 + 3.491e6, "chain_blocks": 0.971e6 + 62.343e6,
-        "chain_prefix": 33.583e6 + 33.554e6, "sweep": 80.749e6 + 93.323e6},
+    2: {"terms": 0.139e6 + 0.662e6, "chain_blocks": 0.156e6 + 7.484e6, "sweep": 8.706e6 + 33.548e6},
+    3: {"terms": 0.178e6 + 0.318e6, "chain_blocks": 0.127e6 + 1.122e6,
+        "chain_prefix": 0.576e6 + 0.524e6, "sweep": 3.699e6 + 2.294e6},
+    4: {"terms": 87.398e6 + 10.560e6 + 0.140e6 + 0.176e6, "sweep": 86.162e6 + 2002.824e6},
+    5: {"terms": 0.761e6 + 3.491e6, "chain_blocks": 1.427e6 + 71.282e6,
+        "chain_prefix": 50.915e6 + 26.337e6, "sweep": 68.478e6 + 93.321e6},
+}
+# the same for the three kernels of the cut-over extraction (mark, scan1 + scan2, emit)
+MEASURED_CUT_TRAFFIC = {
+    2: 34.230e6 + 2.095e6 + 0.563e6 + 0.526e6 + 0.006e6 + 0.001e6 + 9.287e6 + 0.486e6,
+    3: 2.382e6 + 0.141e6 + 0.060e6 + 0.035e6 + 0.006e6 + 1.725e6 + 0.982e6,
+    4: 1993.065e6 + 61.707e6 + 30.755e6 + 30.840e6 + 0.035e6 + 0.030e6 + 297.978e6 + 52.551e6,
+    5: 96.891e6 + 5.867e6 + 1.497e6 + 1.464e6 + 0.007e6 + 0.001e6 + 26.707e6 + 0.865e6,
 }
 
 
@@ -126,6 +133,8 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
               for _ in range(5)]
     stage_ms = dict(zip(STAGES, np.median(np.array(rounds), axis=0).tolist()))
     cut = run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps) if with_cut else None
+    if cut is not None and wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16:
+        cut["roofline"]["traffic"] = MEASURED_CUT_TRAFFIC.get(int(wl.name[3:]))
     del out
     grid.free()
     tab.free()
