@@ -106,7 +106,7 @@ struct plogp_grid {
     {
         double **all[] = {&scratch.g1, &scratch.gs, &scratch.gm, &scratch.sum2, &scratch.blk,
                           &scratch.pre, &scratch.part, &scratch.rcp, &scratch.cx, &scratch.cys,
-                          &scratch.segC, &scratch.segA, &scratch.segB};
+                          &scratch.segC, &scratch.segA, &scratch.segB, &scratch.amin};
         for (double **p : all) {
             if (*p) (void)hipFree(*p);
             *p = nullptr;
@@ -388,6 +388,7 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
         {&g->scratch.segC, n_tables * (g->n_s ? g->n_s : 1)},
         {&g->scratch.segA, pairs ? n_tables * g->n_m * g->n_s : 1},
         {&g->scratch.segB, pairs ? n_tables * g->n_m * g->n_s : 1},
+        {&g->scratch.amin, pairs ? n_tables * g->n_m : 1},
     };
     for (auto &w : want) {
         hipError_t e = hipMalloc((void **)w.p, w.count * sizeof(double));

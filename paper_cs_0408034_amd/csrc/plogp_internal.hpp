@@ -98,6 +98,7 @@ struct Scratch {
     double *segC;     // [n_tables][n_s]                  C = g(s) + L
     double *segA;     // [n_tables][n_m][n_s]             A = g(s) ceil(m/s), +inf where s does not compete
     double *segB;     // [n_tables][n_m][n_s]             B = g(s) (ceil(m/s) - 1)   (both: n_s <= SWEEP_M_MAX_S only)
+    double *amin;     // [n_tables][n_m]                  min over s of A (with segA, segB)
     int *nv;          // [n_m]                            candidates s <= min(m, s_cap)
     BatchPrep batch;  // shared sample sizes only
     double *batch_ys; // [n+2][n_tables][2]               {gap, slope} by interval (shared sample sizes only)

@@ -127,6 +127,15 @@ __device__ __forceinline__ void segment_terms(double md, double sd, double rcp_s
     C = gs + L;
 }
 
+// Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
+// adds a canonicalising v_max_f64 per operand in IEEE mode).
+__device__ __forceinline__ double min_f64(double a, double b)
+{
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // ---------------------------------------------------------------- slopes (table load)
 
 __global__ void __launch_bounds__(256) k_slopes(DeviceTables T)
@@ -226,6 +235,20 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
 
 // ---------------------------------------------------------------- tune, step 1: per-table and per-m terms
 
+constexpr int TERMS_ROWS = 64;       // rows of (m, s) pairs whose minimum of A is formed together
+
+// An image of a double (no NaN) as an unsigned integer that orders the same way.
+__device__ __forceinline__ unsigned long long ordered_bits(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    return (b >> 63) ? ~b : b | 0x8000000000000000ull;
+}
+
+__device__ __forceinline__ double from_ordered_bits(unsigned long long k)
+{
+    return __longlong_as_double((long long)((k >> 63) ? k & 0x7FFFFFFFFFFFFFFFull : ~k));
+}
+
 // One workgroup per (table, chunk of blockDim items); a lane takes one m and
 // one s.  Computes the interval slopes from the raw samples (chunk 0 publishes
 // them, and the table as intervals for the chain-sum walk), g(m), the number of
@@ -271,6 +294,17 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     }
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
+    // for the sweep that runs its lanes over P: g(s) and 1/s of every candidate, for this
+    // workgroup's own use below
+    double *gs_l = lds + 3 * n, *rcp_l = gs_l + G.n_s;
+    if (with_pairs) {
+        for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
+            const double sd = (double)G.s[si];
+            gs_l[si] = gap_at(tab, sd);
+            rcp_l[si] = 1.0 / sd;
+        }
+        __syncthreads();
+    }
 
     // per message size: g(m), the number of candidates, the prefix of g(2^j m).  Groups
     // of 64 sizes are dealt to the waves of this table's workgroups.
@@ -281,14 +315,15 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
             continue;
         const u64 m = G.m[mi];
         S.gm[(size_t)t * G.n_m + mi] = gap_at(tab, (double)m);
-        if (t == 0) {                  // candidates s <= min(m, s_cap): the list ascends
+        {                              // candidates s <= min(m, s_cap): the list ascends
             const u64 lim = m < G.s_cap ? m : G.s_cap;
             int lo = 0, hi = G.n_s;
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
                 if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
             }
-            S.nv[mi] = lo;
+            if (t == 0)
+                S.nv[mi] = lo;
         }
         if (G.mask & (1u << 12)) {
             double *o = S.sum2 + ((size_t)t * G.n_m + mi) * (G.cl_max + 1);   // [m][d]
@@ -325,22 +360,38 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
             S.rcp[si] = 1.0 / sd;
     }
     // per (m, s): A = g(s) k and B = g(s)(k-1) for the sweep that runs its lanes over P
-    // (there they are wave-uniform); +inf where s does not compete
+    // (there they are wave-uniform), +inf where s does not compete; per m the minimum of A
+    // over the candidates (rows 2 and 9 of Table 1 are monotone in A).  A chunk takes whole
+    // rows of (m, s) pairs, TERMS_ROWS at a time, and forms the minima in LDS on an
+    // order-preserving integer image of the doubles.
     if (with_pairs) {
-        const long n_pairs = (long)G.n_m * G.n_s;
-        for (long id = (long)chunk * blockDim.x + threadIdx.x; id < n_pairs;
-             id += (long)n_chunks * blockDim.x) {
-            const int mi = (int)(id / G.n_s), si = (int)(id % G.n_s);
-            const u64 m = G.m[mi], sv = G.s[si];
-            const u64 lim = m < G.s_cap ? m : G.s_cap;
-            double A = INFINITY, B = INFINITY, C;
-            if (sv <= lim) {
-                const double sd = (double)sv;
-                segment_terms((double)m, sd, 1.0 / sd, gap_at(tab, sd), L, A, B, C);
+        __shared__ unsigned long long amin_l[TERMS_ROWS];
+        const int rows = (G.n_m + n_chunks - 1) / n_chunks;        // rows of a chunk
+        for (int r0 = chunk * rows; r0 < (chunk + 1) * rows && r0 < G.n_m; r0 += TERMS_ROWS) {
+            int nr = (chunk + 1) * rows - r0;
+            nr = nr < TERMS_ROWS ? nr : TERMS_ROWS;
+            nr = nr < G.n_m - r0 ? nr : G.n_m - r0;
+            if ((int)threadIdx.x < TERMS_ROWS)
+                amin_l[threadIdx.x] = ordered_bits(INFINITY);
+            __syncthreads();
+            for (int e = threadIdx.x; e < nr * G.n_s; e += blockDim.x) {
+                const int ml = e / G.n_s, si = e % G.n_s;
+                const int mi = r0 + ml;
+                const u64 m = G.m[mi], sv = G.s[si];
+                const u64 lim = m < G.s_cap ? m : G.s_cap;
+                double A = INFINITY, B = INFINITY, C;
+                if (sv <= lim) {
+                    segment_terms((double)m, (double)sv, rcp_l[si], gs_l[si], L, A, B, C);
+                    atomicMin(&amin_l[ml], ordered_bits(A));
+                }
+                const size_t o = ((size_t)t * G.n_m + mi) * G.n_s + si;
+                S.segA[o] = A;
+                S.segB[o] = B;
             }
-            const size_t o = ((size_t)t * G.n_m + mi) * G.n_s + si;
-            S.segA[o] = A;
-            S.segB[o] = B;
+            __syncthreads();
+            if ((int)threadIdx.x < nr)
+                S.amin[(size_t)t * G.n_m + r0 + threadIdx.x] = from_ordered_bits(amin_l[threadIdx.x]);
+            __syncthreads();
         }
     }
 }
@@ -740,15 +791,6 @@ __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
     *reinterpret_cast<uint4 *>(p) = u.v;
 }
 
-// Minimum of two doubles that are never NaN: a single v_min_f64 (the builtin
-// adds a canonicalising v_max_f64 per operand in IEEE mode).
-__device__ __forceinline__ double min_f64(double a, double b)
-{
-    double r;
-    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
 // Broadcast: the ten rows of Table 1 in id order, strict '<' (ties: lowest id).
 // t2/t5/t9 are the minima over s of the segmented rows (+inf if none), s2/s5/s9
 // the segment sizes that attain them.
@@ -1119,7 +1161,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     constexpr int ROW = 64 * NSV + 8;
     __shared__ double sC[ROW];                       // g(s) + L (0 past the end)
     __shared__ uint32_t sSv[ROW];                    // s
-    __shared__ double rowA[4][ROW], rowB[4][ROW];    // A, B of the current size (+inf past the end)
+    __shared__ double rowB[4][ROW];                  // B of the current size (+inf past the end)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int bid = blockIdx.x;
@@ -1134,7 +1176,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         if (si >= 64 * NSV) {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                rowA[k][si] = rowB[k][si] = INFINITY;
+                rowB[k][si] = INFINITY;
         }
     }
     __syncthreads();
@@ -1165,7 +1207,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     plogp_cell_dev *const obase = out + (size_t)t * G.n_ops * plane + pi;
 
     // what is fetched one size ahead
-    double fA[NSV], fB[NSV], f_part = 0.0, f_s12 = 0.0, f_done = 0.0, f_gm;
+    double fB[NSV], f_part = 0.0, f_s12 = 0.0, f_done = 0.0, f_gm, f_amin = INFINITY;
     int f_nv;
     // row of the chain sums (kept per distinct size) of the size fetched next: read one size
     // earlier still, so that the fetch does not wait for it
@@ -1175,10 +1217,10 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         f_gm = S.gm[row];
         f_nv = S.nv[mi];
         if (seg) {
+            f_amin = S.amin[row];
 #pragma unroll
             for (int k = 0; k < NSV; ++k) {
                 const int si = lane + 64 * k;
-                fA[k] = si < n_s ? S.segA[row * n_s + si] : INFINITY;
                 fB[k] = si < n_s ? S.segB[row * n_s + si] : INFINITY;
             }
         }
@@ -1199,26 +1241,27 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     for (int mi = w; mi < (int)n_m; mi += n_w) {
         const double gm = f_gm, part = f_part, s12 = f_s12, dn = f_done;
         const int nv = f_nv;
-        double a_lane = INFINITY;
+        const double amin = f_amin;      // min over s of A = g(s) k, from k_terms
+        const size_t row_now = (size_t)t * n_m + mi;
         if (seg) {
 #pragma unroll
-            for (int k = 0; k < NSV; ++k) {
-                rowA[wave][lane + 64 * k] = fA[k];
+            for (int k = 0; k < NSV; ++k)
                 rowB[wave][lane + 64 * k] = fB[k];
-                a_lane = min_f64(a_lane, fA[k]);
-            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         if (mi + n_w < (int)n_m)
             fetch(mi + n_w);
 
-        // row 5: min over s of fma(q, C, B), first candidate that attains it
+        // row 5: min over s of fma(q, C, B) and the first candidate that attains it.  The
+        // loop keeps the minimum and in which batch of eight candidates it first appeared;
+        // that batch is evaluated once more for the candidate itself.
         double b5 = INFINITY;
         int i5 = 0;
         if (mask & 0x20u) {
             // eight candidates per round trip to LDS; past the last competing one B is
             // +inf (and C is finite), so the value is +inf and never taken
+            int batch5 = 0;
             for (int s0 = 0; s0 < nv; s0 += 8) {
                 double Bv[8], Cv[8];
 #pragma unroll
@@ -1226,15 +1269,25 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                     Bv[u] = rowB[wave][s0 + u];
                     Cv[u] = sC[s0 + u];
                 }
+                double cur = INFINITY;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    cur = min_f64(cur, __builtin_fma(q, Cv[u], Bv[u]));
+                batch5 = cur < b5 ? s0 : batch5;
+                b5 = min_f64(b5, cur);
+            }
+            if (__ballot(b5 < INFINITY) != 0) {
+                // lanes differ in their batch: per-lane LDS reads of the eight candidates
+                bool open = true;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const double T5 = __builtin_fma(q, Cv[u], Bv[u]);
-                    i5 = T5 < b5 ? s0 + u : i5;
-                    b5 = min_f64(b5, T5);
+                    const double T5 = __builtin_fma(q, sC[batch5 + u], rowB[wave][batch5 + u]);
+                    const bool hit = open && T5 == b5;
+                    i5 = hit ? batch5 + u : i5;
+                    open = open && !hit;
                 }
             }
         }
-        const double amin = seg ? wave_min(a_lane) : INFINITY;
         const uint32_t s5 = b5 < INFINITY ? sSv[i5] : 0u;
 
         plogp_cell_dev *o = obase + (size_t)mi * n_P;
@@ -1252,7 +1305,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                     uint32_t Sv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        Av[u] = rowA[wave][s0 + u];
+                        Av[u] = s0 + u < n_s ? S.segA[row_now * n_s + s0 + u] : INFINITY;
                         Sv[u] = sSv[s0 + u];
                     }
 #pragma unroll
@@ -2205,7 +2258,8 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
 
 // ---------------------------------------------------------------- launch wrappers
 
-static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 96;
+static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 96 +
+                                   (size_t)2 * SWEEP_M_MAX_S * sizeof(double);   // + g(s), 1/s in k_terms
 static const size_t kMaxChainLds = (size_t)4 * 4096 * sizeof(double) + 112;   // + interval widths
 
 hipError_t kernels_init()
@@ -2360,8 +2414,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
     for (int r = 0; r < reps; ++r)
-        hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), tab_lds, st, T,
-                           G, S, n_chunks, lanes_p ? 1 : 0);
+        hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256),
+                           tab_lds + (lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0), st, T, G, S,
+                           n_chunks, lanes_p ? 1 : 0);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(1);
 

@@ -259,6 +259,24 @@ def test_largest_sizes_before_the_range_limit():
     assert assert_tables_equal(gpu_tune(wl), want, "largest sizes")
 
 
+def test_message_sizes_in_any_order_with_repeats():
+    # the Scatter-chain sums are kept per distinct size: a grid whose sizes are shuffled and
+    # repeated must give each cell the row of its own size
+    base = make_workload(2, P_subset=[2, 3, 64, 65, 66, 700, 1024])
+    rng = np.random.default_rng(9)
+    m = rng.permutation(np.concatenate([base.m[::9], base.m[::31], base.m[5:9]]))
+    wl = Workload("shuffled", base.sizes, base.gaps, base.L, m, base.P, base.s, base.s_cap,
+                  base.strategy_mask)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "shuffled sizes")
+    big = make_workload(5, P_subset=[2, 65, 4097, 40000, 65536])
+    m5 = rng.permutation(np.concatenate([big.m[::41], big.m[100:140]]))
+    wl5 = Workload("shuffled5", big.sizes, big.gaps, big.L, m5, big.P, big.s, big.s_cap,
+                   big.strategy_mask)
+    want5, _ = oracle.tune_workload(wl5)
+    assert assert_tables_equal(gpu_tune(wl5), want5, "shuffled sizes, big table")
+
+
 def test_batch_of_tables_matches_one_by_one():
     wl = make_workload(4, n_tables=37, table_offset=1000)
     want, _ = oracle.tune_workload(wl)
