@@ -1153,7 +1153,7 @@ __device__ __forceinline__ double wave_min(double v)
 // n_w apart, so every wave meets the same mix of short and long candidate lists;
 // the loads for the next size are issued before the current one is worked on.
 // NSV: candidates per lane when a row of (m, s) terms is moved (n_s <= 64 NSV).
-template <int NSV>
+template <int NSV, bool ALL>
 __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, Scratch S,
                                                  plogp_cell_dev *out, int n_pg, int n_w)
 {
@@ -1170,21 +1170,9 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     bid /= n_wq;
     const int pg = bid % n_pg;
     const int t = bid / n_pg;
-    for (int si = threadIdx.x; si < ROW; si += blockDim.x) {
-        sC[si] = si < G.n_s ? S.segC[(size_t)t * G.n_s + si] : 0.0;
-        sSv[si] = si < G.n_s ? (uint32_t)G.s[si] : 0u;
-        if (si >= 64 * NSV) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                rowB[k][si] = INFINITY;
-        }
-    }
-    __syncthreads();
     const int w = wq * 4 + wave;
-    if (w >= n_w || w >= G.n_m)
-        return;
-
-    const uint32_t mask = G.mask;
+    const bool has_work = w < n_w && w < G.n_m;
+    const uint32_t mask = ALL ? 0x1FFFu : G.mask;      // ALL: every strategy competes
     const int n_P = G.n_P, n_s = G.n_s, n_blk = G.n_blk;
     const size_t n_m = (size_t)G.n_m;
     const int pi = pg * 64 + lane;
@@ -1211,7 +1199,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     int f_nv;
     // row of the chain sums (kept per distinct size) of the size fetched next: read one size
     // earlier still, so that the fetch does not wait for it
-    int um_next = chain ? G.m_map[w] : 0;
+    int um_next = chain && has_work ? G.m_map[w] : 0;
     auto fetch = [&](int mi) {
         const size_t row = (size_t)t * n_m + mi;
         f_gm = S.gm[row];
@@ -1237,7 +1225,21 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         if (binom)
             f_s12 = S.sum2[row * (G.cl_max + 1) + cli];
     };
-    fetch(w);
+    // the first size's inputs are on their way while the candidates go to LDS
+    if (has_work)
+        fetch(w);
+    for (int si = threadIdx.x; si < ROW; si += blockDim.x) {
+        sC[si] = si < G.n_s ? S.segC[(size_t)t * G.n_s + si] : 0.0;
+        sSv[si] = si < G.n_s ? (uint32_t)G.s[si] : 0u;
+        if (si >= 64 * NSV) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                rowB[k][si] = INFINITY;
+        }
+    }
+    __syncthreads();
+    if (!has_work)
+        return;
     for (int mi = w; mi < (int)n_m; mi += n_w) {
         const double gm = f_gm, part = f_part, s12 = f_s12, dn = f_done;
         const int nv = f_nv;
@@ -2410,7 +2412,10 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (lanes_p && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
     long n_chunks_l = (n_items + 255) / 256;
-    const long chunk_cap = 512 / T.n_tables > 1 ? 512 / T.n_tables : 1;
+    // a workgroup stages the whole table: with a big table one workgroup fits a CU, so no
+    // more workgroups than CUs
+    const long wg_cap = tab_lds > 65536 ? 256 : 512;
+    const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
     for (int r = 0; r < reps; ++r)
@@ -2482,12 +2487,16 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             if (n_w < 1) n_w = 1;
             n_w = (n_w + 3) / 4 * 4;
             const unsigned blocks = (unsigned)(T.n_tables * (long)n_pg * (n_w / 4));
-            if (G.n_s <= 64)
-                hipLaunchKernelGGL(k_sweep_p<1>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
-                                   (int)n_w);
+            const bool all = G.mask == 0x1FFFu;
+            if (G.n_s <= 64 && all)
+                hipLaunchKernelGGL((k_sweep_p<1, true>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
+                                   n_pg, (int)n_w);
+            else if (G.n_s <= 64)
+                hipLaunchKernelGGL((k_sweep_p<1, false>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
+                                   n_pg, (int)n_w);
             else
-                hipLaunchKernelGGL(k_sweep_p<4>, dim3(blocks), dim3(256), 0, st, T, G, S, d_out, n_pg,
-                                   (int)n_w);
+                hipLaunchKernelGGL((k_sweep_p<4, false>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
+                                   n_pg, (int)n_w);
         } else {
             constexpr int PC = 4;
             const int n_mg = (G.n_m + 63) / 64;
