@@ -19,6 +19,9 @@ _SRC = _HERE / "plogp_oracle.c"
 _LIB = _HERE / "libplogp_oracle.so"
 
 CELL_DTYPE = np.dtype([("time", "<f8"), ("s", "<u4"), ("strategy", "<u4")])
+VERDICT_DTYPE = np.dtype([("regret", "<f8"), ("pred_best", "<u4"), ("meas_best", "<u4")])
+SCORE_DTYPE = np.dtype([("sum_abs_err", "<f8"), ("max_abs_err", "<f8"), ("count", "<u8"),
+                        ("reserved", "<u8")])
 
 _lib = None
 
@@ -55,6 +58,12 @@ def _load():
             ctypes.POINTER(ctypes.c_uint64), ctypes.c_size_t,
             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_int]
         lib.plogp_oracle_tune.restype = ctypes.c_int
+        lib.plogp_oracle_score.argtypes = [
+            dp, dp, ctypes.c_size_t, ctypes.c_double,
+            ctypes.POINTER(ctypes.c_uint64), ctypes.c_size_t,
+            ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t, ctypes.c_uint32,
+            dp, ctypes.POINTER(ctypes.c_uint32), dp, ctypes.c_void_p, ctypes.c_void_p]
+        lib.plogp_oracle_score.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -117,3 +126,33 @@ def tune_grid(sizes, gaps, L, m, P, s, s_cap: int, strategy_mask: int, n_threads
 def tune_workload(wl, n_threads: int = 0):
     return tune_grid(wl.sizes, wl.gaps, wl.L, wl.m, wl.P, wl.s, wl.s_cap,
                      wl.strategy_mask, n_threads)
+
+
+def strategy_ids(strategy_mask: int):
+    """The enabled strategy ids, ascending (the row order of measurements and predictions)."""
+    return [i for i in range(13) if (strategy_mask >> i) & 1]
+
+
+def score_grid(x, y, L, m, P, strategy_mask: int, meas, seg):
+    """Prediction against measurement (see plogp_oracle_score): returns
+    (pred [n_ids, n_m, n_P], verdict [n_ops, n_m, n_P], score [n_ids])."""
+    x = _f64(x); y = _f64(y)
+    m = np.ascontiguousarray(m, dtype=np.uint64)
+    P = np.ascontiguousarray(P, dtype=np.uint32)
+    n_ids = len(strategy_ids(strategy_mask))
+    meas = np.ascontiguousarray(meas, dtype=np.float64)
+    seg = np.ascontiguousarray(seg, dtype=np.uint32)
+    assert meas.shape == (n_ids, m.size, P.size) and seg.shape == meas.shape
+    n_ops = (1 if strategy_mask & 0x3FF else 0) + (1 if strategy_mask & 0x1C00 else 0)
+    pred = np.empty_like(meas)
+    verdict = np.zeros((n_ops, m.size, P.size), dtype=VERDICT_DTYPE)
+    score = np.zeros(n_ids, dtype=SCORE_DTYPE)
+    rc = _load().plogp_oracle_score(
+        _dptr(x), _dptr(y), x.size, float(L),
+        m.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), m.size,
+        P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), P.size, ctypes.c_uint32(int(strategy_mask)),
+        _dptr(meas), seg.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _dptr(pred),
+        verdict.ctypes.data_as(ctypes.c_void_p), score.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("bad argument to the oracle")
+    return pred, verdict, score

@@ -325,3 +325,109 @@ int plogp_oracle_tune(const double *x, const double *y, size_t n, const double *
     }
     return used;
 }
+
+/* ---- prediction against measurement ---------------------------------------
+ *
+ * The step after the tuning in the paper (Section 4): each implementation is
+ * measured, the measured completion times are set against the model's
+ * predictions, and the question is whether the technique the models choose
+ * is the one that is fastest in the measurement.  Here, for one table and a
+ * grid of (m, P), with `meas` the measured time of every enabled strategy at
+ * every (m, P) and `seg` the segment size it was measured with (read for the
+ * segmented ids 2, 5, 9 only; 0 < s <= m):
+ *
+ *   pred[r][m][P]     the model at the measured point (r: rank of the strategy
+ *                     id among the enabled ones, ascending)
+ *   verdict[op][m][P] pred_best = the enabled strategy of the operation with
+ *                     the smallest prediction, meas_best = the one with the
+ *                     smallest measured time (strict '<' in ascending id: ties
+ *                     to the lowest id), regret = meas[pred_best] /
+ *                     meas[meas_best] - 1 (0 when the decision survives)
+ *   score[r]          over all (m, P): e = |(pred - meas) / meas|; count;
+ *                     max e; sum e, added per m in ascending P from +0.0 and
+ *                     the per-m sums added in ascending m from +0.0
+ *
+ * Operations present as in plogp_oracle_tune.  Returns 0, or -1 on a bad
+ * argument.
+ */
+typedef struct {
+    double regret;
+    uint32_t pred_best;
+    uint32_t meas_best;
+} oracle_verdict;
+
+typedef struct {
+    double sum_abs_err;
+    double max_abs_err;
+    uint64_t count;
+    uint64_t reserved;
+} oracle_score;
+
+int plogp_oracle_score(const double *x, const double *y, size_t n, double L, const uint64_t *m,
+                       size_t n_m, const uint32_t *P, size_t n_P, uint32_t mask,
+                       const double *meas, const uint32_t *seg, double *pred,
+                       oracle_verdict *verdict, oracle_score *score)
+{
+    if (n < 2 || n_m == 0 || n_P == 0 || (mask & 0x1FFFu) == 0)
+        return -1;
+    int ids[N_STRATEGIES], n_ids = 0;
+    for (int id = 0; id < N_STRATEGIES; ++id)
+        if ((mask >> id) & 1u)
+            ids[n_ids++] = id;
+    const int has_b = (mask & 0x3FFu) != 0;
+    oracle_table t;
+    double *slope = (double *)malloc(n * sizeof(double));
+    t.x = x; t.y = y; t.n = n; t.L = L; t.slope = slope;
+    plogp_oracle_slopes(x, y, n, slope);
+    const size_t plane = n_m * n_P;
+    for (size_t mi = 0; mi < n_m; ++mi) {
+        for (size_t pi = 0; pi < n_P; ++pi) {
+            if (P[pi] < 2 || m[mi] == 0) { free(slope); return -1; }
+            for (int r = 0; r < n_ids; ++r) {
+                const size_t at = (size_t)r * plane + mi * n_P + pi;
+                const uint64_t s = is_segmented(ids[r]) ? seg[at] : 0;
+                if (is_segmented(ids[r]) && (s == 0 || s > m[mi])) { free(slope); return -1; }
+                pred[at] = model(&t, ids[r], m[mi], P[pi], s, NAN);
+            }
+            for (int op = 0; op < 2; ++op) {
+                const int lo = op == 0 ? 0 : 10, hi = op == 0 ? 9 : 12;
+                double best_p = INFINITY, best_m = INFINITY, meas_of_pred_best = NAN;
+                uint32_t id_p = 0xFFFFFFFFu, id_m = 0xFFFFFFFFu;
+                int any = 0;
+                for (int r = 0; r < n_ids; ++r) {
+                    if (ids[r] < lo || ids[r] > hi)
+                        continue;
+                    any = 1;
+                    const size_t at = (size_t)r * plane + mi * n_P + pi;
+                    if (pred[at] < best_p) { best_p = pred[at]; id_p = (uint32_t)ids[r]; meas_of_pred_best = meas[at]; }
+                    if (meas[at] < best_m) { best_m = meas[at]; id_m = (uint32_t)ids[r]; }
+                }
+                if (!any)
+                    continue;
+                oracle_verdict *v = verdict + (size_t)(op == 0 ? 0 : has_b) * plane + mi * n_P + pi;
+                v->pred_best = id_p;
+                v->meas_best = id_m;
+                v->regret = meas_of_pred_best / best_m - 1.0;
+            }
+        }
+    }
+    for (int r = 0; r < n_ids; ++r) {
+        double total = 0.0, worst = 0.0;
+        for (size_t mi = 0; mi < n_m; ++mi) {
+            double row = 0.0;
+            for (size_t pi = 0; pi < n_P; ++pi) {
+                const size_t at = (size_t)r * plane + mi * n_P + pi;
+                const double e = fabs((pred[at] - meas[at]) / meas[at]);
+                row = row + e;
+                if (e > worst) worst = e;
+            }
+            total = total + row;
+        }
+        score[r].sum_abs_err = total;
+        score[r].max_abs_err = worst;
+        score[r].count = (uint64_t)plane;
+        score[r].reserved = 0;
+    }
+    free(slope);
+    return 0;
+}
