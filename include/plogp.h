@@ -246,6 +246,70 @@ int plogp_cutovers_profile(plogp_grid *g, size_t n_tables, const plogp_cell *d_c
                            uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity,
                            void *stream, int reps, float *stage_ms_out);
 
+/*
+ * Prediction against measurement -- paper Section 4: every implementation is
+ * measured, the measured completion times are set against the predictions of
+ * Tables 1 and 2, and the question is whether the technique the models choose
+ * is the fastest one in the measurement.  For ONE table and the (m, P) of grid
+ * g (its candidate list and cap are not used), with r running over the
+ * strategies enabled in the grid's mask in ascending id:
+ *   pred[r][m][P]     the model at the measured point;
+ *   verdict[op][m][P] pred_best: the enabled strategy of the operation with the
+ *                     smallest prediction; meas_best: the one with the smallest
+ *                     measured time (ties to the lowest id in both);
+ *                     regret = meas[pred_best] / meas[meas_best] - 1, i.e. 0
+ *                     when the decision survives;
+ *   scores[r]         over all (m, P): e = |(pred - meas) / meas|: count,
+ *                     maximum, and sum (added per m in ascending P, then over
+ *                     ascending m, so that it is reproducible bit for bit).
+ */
+typedef struct {
+    double regret;       /* how much slower the predicted choice was measured  */
+    uint32_t pred_best;  /* strategy id with the smallest prediction           */
+    uint32_t meas_best;  /* strategy id with the smallest measured time        */
+} plogp_verdict;         /* 16 bytes */
+
+typedef struct {
+    double sum_abs_err;  /* sum of |(pred - meas) / meas|                      */
+    double max_abs_err;  /* its maximum                                        */
+    uint64_t count;      /* points                                             */
+    uint64_t reserved;   /* 0                                                  */
+} plogp_strategy_score;  /* 32 bytes */
+
+/* Strategies enabled in the grid's mask: the rows of meas, seg, pred, scores. */
+size_t plogp_score_strategies(const plogp_grid *g);
+
+/*
+ * plogp_score_grid -- all DEVICE pointers:
+ *   d_meas    [rows][n_m][n_P] doubles, measured times (> 0);
+ *   d_seg     [rows][n_m][n_P] uint32, the segment size each point was measured
+ *             with; read for ids 2, 5, 9 only (0 < s <= m, else the prediction
+ *             is NaN); may be NULL when none of them is enabled;
+ *   d_pred    [rows][n_m][n_P] doubles (out);
+ *   d_verdict [operation planes][n_m][n_P] records (out), planes as in
+ *             plogp_tune_grid, 16-byte aligned;
+ *   d_scores  [rows] records (out), 16-byte aligned.
+ * Enqueued on `stream`.  Uses the grid handle's scratch like plogp_tune_grid:
+ * calls on one grid handle must not overlap.
+ * Errors: EINVAL (null, misaligned, bad table index), ENOMEM, EDEVICE.
+ */
+int plogp_score_grid(const plogp_table *t, size_t table_index, plogp_grid *g, const double *d_meas,
+                     const uint32_t *d_seg, double *d_pred, plogp_verdict *d_verdict,
+                     plogp_strategy_score *d_scores, void *stream);
+
+/*
+ * plogp_score_grid_profile -- the same work, measured: each of its three steps
+ * (g(m), g(1) and the Scatter sums; predictions and verdicts; statistics) is
+ * launched `reps` times back to back between two HIP events; waits and returns
+ * the mean milliseconds per launch in stage_ms_out[0..2].  Synchronous.
+ * Errors: as plogp_score_grid, plus EINVAL for a null stage_ms_out or reps
+ * outside [1, 10000].
+ */
+int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_grid *g,
+                             const double *d_meas, const uint32_t *d_seg, double *d_pred,
+                             plogp_verdict *d_verdict, plogp_strategy_score *d_scores, void *stream,
+                             int reps, float *stage_ms_out);
+
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);
 /* HIP error code of the calling thread's most recent PLOGP_EDEVICE (0 if none). */

@@ -87,6 +87,8 @@ struct plogp_grid {
     Scratch scratch = {};
     // scratch of the path for batches with shared sample sizes
     size_t batch_tables = 0, batch_samples = 0;
+    // scratch of the scoring: 2 doubles per (strategy, m)
+    double *score_rows = nullptr;
     // scratch of the cut-over extraction, sized for cut_tables tables
     size_t cut_tables = 0;
     CutScratch cut = {};
@@ -140,6 +142,7 @@ struct plogp_grid {
         free_scratch();
         free_batch_scratch();
         free_cut_scratch();
+        if (score_rows) (void)hipFree(score_rows);
         if (d_m) (void)hipFree(d_m);
         if (d_mu) (void)hipFree(d_mu);
         if (d_m_map) (void)hipFree(d_m_map);
@@ -575,6 +578,80 @@ int plogp_cutovers_profile(plogp_grid *g, size_t n_tables, const plogp_cell *d_c
     if (e != hipSuccess) return device_error(e);
     for (int i = 0; i < 3; ++i) stage_ms_out[i] = ms[i];
     return PLOGP_OK;
+}
+
+static int score_common(const plogp_table *t, size_t table_index, plogp_grid *g, const double *d_meas,
+                        const uint32_t *d_seg, double *d_pred, plogp_verdict *d_verdict,
+                        plogp_strategy_score *d_scores, void *stream, int reps, float *stage_ms_out)
+{
+    if (!t || !g || !d_meas || !d_pred || !d_verdict || !d_scores) return PLOGP_EINVAL;
+    if (table_index >= t->n_tables) return PLOGP_EINVAL;
+    if ((g->mask & 0x224u) != 0 && !d_seg) return PLOGP_EINVAL;
+    if (((uintptr_t)d_verdict & 15u) != 0 || ((uintptr_t)d_scores & 15u) != 0 ||
+        ((uintptr_t)d_meas & 7u) != 0 || ((uintptr_t)d_pred & 7u) != 0 || ((uintptr_t)d_seg & 3u) != 0)
+        return PLOGP_EINVAL;
+    int rc = ensure_init();
+    if (rc != PLOGP_OK) return rc;
+    if ((rc = ensure_scratch(g, 1, t->n)) != PLOGP_OK) return rc;
+    if (!g->score_rows) {
+        hipError_t e = hipMalloc((void **)&g->score_rows, (size_t)PLOGP_N_STRATEGIES * g->n_m * 2 * sizeof(double));
+        if (e != hipSuccess) {
+            g->score_rows = nullptr;
+            if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return PLOGP_ENOMEM; }
+            return device_error(e);
+        }
+    }
+    DeviceTables T1 = t->view();            // the one table
+    T1.x += table_index * t->n;
+    T1.y += table_index * t->n;
+    T1.slope += table_index * t->n;
+    T1.L += table_index;
+    T1.n_tables = 1;
+    T1.shared_x = 0;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipError_t e = hipSuccess;
+    if (stage_ms_out)
+        for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+    if (e == hipSuccess)
+        e = launch_score(T1, g->view(), g->scratch, g->score_rows, d_meas, d_seg, d_pred, d_verdict,
+                         d_scores, (hipStream_t)stream, stage_ms_out ? ev : nullptr, reps);
+    if (stage_ms_out) {
+        if (e == hipSuccess) e = hipEventSynchronize(ev[3]);
+        for (int i = 0; i < 3 && e == hipSuccess; ++i) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+            stage_ms_out[i] = ms / (float)reps;
+        }
+        for (int i = 0; i < 4; ++i)
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+    }
+    if (e != hipSuccess) return device_error(e);
+    return PLOGP_OK;
+}
+
+size_t plogp_score_strategies(const plogp_grid *g)
+{
+    size_t n = 0;
+    if (g)
+        for (int id = 0; id < PLOGP_N_STRATEGIES; ++id) n += (g->mask >> id) & 1u;
+    return n;
+}
+
+int plogp_score_grid(const plogp_table *t, size_t table_index, plogp_grid *g, const double *d_meas,
+                     const uint32_t *d_seg, double *d_pred, plogp_verdict *d_verdict,
+                     plogp_strategy_score *d_scores, void *stream)
+{
+    return score_common(t, table_index, g, d_meas, d_seg, d_pred, d_verdict, d_scores, stream, 1, nullptr);
+}
+
+int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_grid *g,
+                             const double *d_meas, const uint32_t *d_seg, double *d_pred,
+                             plogp_verdict *d_verdict, plogp_strategy_score *d_scores, void *stream,
+                             int reps, float *stage_ms_out)
+{
+    if (!stage_ms_out || reps < 1 || reps > 10000) return PLOGP_EINVAL;
+    return score_common(t, table_index, g, d_meas, d_seg, d_pred, d_verdict, d_scores, stream, reps,
+                        stage_ms_out);
 }
 
 }  // extern "C"

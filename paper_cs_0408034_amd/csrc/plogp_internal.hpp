@@ -144,6 +144,13 @@ hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_d
                            const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
                            uint64_t capacity, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
 
+// Prediction against measurement for one table (T1: a view of that table alone).  rows:
+// scratch of 2 doubles per (enabled strategy, m).  ev: nullptr, or 4 events recorded
+// before the first kernel and after the terms, the scoring and the statistics.
+hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scratch &S, double *rows,
+                        const double *d_meas, const uint32_t *d_seg, double *d_pred, void *d_verdict,
+                        void *d_scores, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
 bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G);

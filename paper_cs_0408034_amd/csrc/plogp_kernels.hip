@@ -2256,6 +2256,152 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     }
 }
 
+// ---- prediction against measurement ------------------------------------------
+//
+// The step after the tuning in the paper (Section 4): every implementation is
+// measured, the measurements are set against the predictions of Tables 1 and
+// 2, and the question is whether the technique the models choose is the one
+// that is fastest in the measurement.  k_score: one thread per (m, P), lanes
+// along P (the measured times meas[r][m][P] and the predictions are read and
+// written coalesced); r runs over the enabled strategies in ascending id.
+// g(m), g(1) and the two Scatter sums come from the tuning's own first stages.
+
+struct plogp_verdict_dev {
+    double regret;
+    uint32_t pred_best;
+    uint32_t meas_best;
+};
+
+__global__ void __launch_bounds__(256) k_score(DeviceTables T, DeviceGrid G, Scratch S,
+                                               const double *meas, const uint32_t *seg, double *pred,
+                                               plogp_verdict_dev *verdict, int n_pchunks)
+{
+    extern __shared__ double lds[];
+    const uint32_t mask = G.mask;
+    const bool any_seg = (mask & 0x224u) != 0;
+    LdsTable tab = {nullptr, nullptr, nullptr, T.n};
+    if (any_seg)
+        tab = stage_table(lds, T, 0);                 // for g(s) at the measured segment sizes
+    const int mi = blockIdx.x / n_pchunks;
+    const int pi = (blockIdx.x % n_pchunks) * blockDim.x + threadIdx.x;
+    if (pi >= G.n_P)
+        return;
+    const u64 m = G.m[mi];
+    const uint32_t P = G.P[pi];
+    const double L = T.L[0];
+    const double q = (double)(P - 1), fl = (double)floor_log2(P), cl = (double)ceil_log2(P);
+    const double gm = S.gm[mi], g1 = S.g1[0];
+    const double R = __builtin_fma(3.0, L, 2.0 * g1);
+    const size_t plane = (size_t)G.n_m * G.n_P;
+    const size_t cell = (size_t)mi * G.n_P + pi;
+    double best_p[2] = {INFINITY, INFINITY}, best_m[2] = {INFINITY, INFINITY};
+    double meas_of_pred_best[2] = {NAN, NAN};
+    uint32_t id_p[2] = {0xFFFFFFFFu, 0xFFFFFFFFu}, id_m[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+    int r = 0;
+    for (int id = 0; id < 13; ++id) {
+        if (!((mask >> id) & 1u))
+            continue;
+        const size_t at = (size_t)r * plane + cell;
+        ++r;
+        double gs = 0.0, k = 0.0;
+        bool ok = true;
+        if (id == 2 || id == 5 || id == 9) {
+            const u64 s = seg[at];
+            ok = s > 0 && s <= m;
+            if (ok) {
+                gs = gap_at(tab, (double)s);
+                k = segments(m, s);
+            }
+        }
+        double v;
+        switch (id) {
+        case 0: case 10: v = __builtin_fma(q, gm, L); break;
+        case 1: v = __builtin_fma(q, gm, R); break;
+        case 2: v = __builtin_fma(q, gs * k, L); break;
+        case 3: v = q * (gm + L); break;
+        case 4: v = q * (gm + R); break;
+        case 5: v = __builtin_fma(q, gs + L, gs * (k - 1.0)); break;
+        case 6: v = cl * __builtin_fma(2.0, gm, L); break;
+        case 7: v = __builtin_fma(fl, gm, cl * L); break;
+        case 8: v = __builtin_fma(fl, gm, cl * R); break;
+        case 9: v = __builtin_fma(fl, gs * k, cl * L); break;
+        case 11: v = __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P)); break;
+        default: v = __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]); break;
+        }
+        if (!ok)
+            v = NAN;
+        pred[at] = v;
+        const double tm = meas[at];
+        const int op = id < 10 ? 0 : 1;
+        if (v < best_p[op]) {
+            best_p[op] = v;
+            id_p[op] = (uint32_t)id;
+            meas_of_pred_best[op] = tm;
+        }
+        if (tm < best_m[op]) {
+            best_m[op] = tm;
+            id_m[op] = (uint32_t)id;
+        }
+    }
+    plogp_verdict_dev *o = verdict + cell;
+    for (int op = 0; op < 2; ++op) {
+        if (!(mask & (op == 0 ? 0x3FFu : 0x1C00u)))
+            continue;
+        plogp_verdict_dev vd;
+        vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
+        vd.pred_best = id_p[op];
+        vd.meas_best = id_m[op];
+        *o = vd;
+        o += plane;
+    }
+}
+
+// e = |(pred - meas) / meas| per point; per (strategy row r, m): the sum over P in
+// ascending order from +0.0 and the maximum.  rows[(r * n_m + mi) * 2] = {sum, max}.
+__global__ void __launch_bounds__(256) k_score_rows(DeviceGrid G, int n_ids, const double *meas,
+                                                    const double *pred, double *rows)
+{
+    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (long)n_ids * G.n_m)
+        return;
+    const double *pm = meas + (size_t)e * G.n_P, *pp = pred + (size_t)e * G.n_P;
+    double sum = 0.0, worst = 0.0;
+    for (int pi = 0; pi < G.n_P; ++pi) {
+        const double err = fabs((pp[pi] - pm[pi]) / pm[pi]);
+        sum = sum + err;
+        worst = err > worst ? err : worst;
+    }
+    rows[2 * e] = sum;
+    rows[2 * e + 1] = worst;
+}
+
+struct plogp_score_dev {
+    double sum_abs_err;
+    double max_abs_err;
+    unsigned long long count;
+    unsigned long long reserved;
+};
+
+// Per strategy row: the per-m sums added in ascending m from +0.0.
+__global__ void k_score_final(DeviceGrid G, int n_ids, const double *rows, plogp_score_dev *score)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_ids)
+        return;
+    double total = 0.0, worst = 0.0;
+    for (int mi = 0; mi < G.n_m; ++mi) {
+        total = total + rows[2 * ((size_t)r * G.n_m + mi)];
+        const double w = rows[2 * ((size_t)r * G.n_m + mi) + 1];
+        worst = w > worst ? w : worst;
+    }
+    plogp_score_dev sc;
+    sc.sum_abs_err = total;
+    sc.max_abs_err = worst;
+    sc.count = (unsigned long long)G.n_m * (unsigned long long)G.n_P;
+    sc.reserved = 0ull;
+    score[r] = sc;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launch wrappers
@@ -2280,6 +2426,9 @@ hipError_t kernels_init()
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChainLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS>),
@@ -2354,7 +2503,8 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     } while (0)
 
     PLOGP_MARK(0);
-    if (use_table_lane_path(T, G)) {
+    const bool terms_only = d_out == nullptr;      // the staged terms and sums, no sweep
+    if (!terms_only && use_table_lane_path(T, G)) {
         // tables by interval and the per-m facts, then everything else in one kernel
         const long stage_items = (long)(T.n + 2) * T.n_tables;
         for (int r = 0; r < reps; ++r) {
@@ -2392,7 +2542,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(4);
         return hipSuccess;
     }
-    if (use_fused_path(T, G)) {
+    if (!terms_only && use_fused_path(T, G)) {
         PLOGP_MARK(1);
         PLOGP_MARK(2);
         PLOGP_MARK(3);
@@ -2407,7 +2557,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     // which sweep runs: lanes over s for many candidates, else lanes over P if the grid
     // has enough process counts to fill a wave, else lanes over m
     const bool lanes_s = G.n_s > SWEEP_M_MAX_S;
-    const bool lanes_p = !lanes_s && G.n_P >= 32;
+    const bool lanes_p = !terms_only && !lanes_s && G.n_P >= 32;
     long n_items = G.n_m > G.n_s ? G.n_m : G.n_s;          // a lane takes one m and one s ...
     if (lanes_p && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
@@ -2462,6 +2612,10 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         PLOGP_MARK(3);
     }
 
+    if (terms_only) {
+        PLOGP_MARK(4);
+        return hipSuccess;
+    }
     for (int r = 0; r < reps; ++r) {
         if (lanes_s) {
             // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
@@ -2508,6 +2662,38 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(4);
 #undef PLOGP_MARK
+    return hipSuccess;
+}
+
+hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scratch &S, double *rows,
+                        const double *d_meas, const uint32_t *d_seg, double *d_pred, void *d_verdict,
+                        void *d_scores, hipStream_t st, hipEvent_t *ev, int reps)
+{
+    hipError_t e;
+    if (reps < 1) reps = 1;
+    int n_ids = 0;
+    for (int id = 0; id < 13; ++id) n_ids += (G.mask >> id) & 1u;
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
+    // g(m), g(1), the Scatter sums: the first stages of the tuning
+    if ((e = launch_tune(T1, G, S, nullptr, st, nullptr, reps)) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
+    const int n_pchunks = (G.n_P + 255) / 256;
+    const size_t lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(k_score, dim3((unsigned)G.n_m * n_pchunks), dim3(256), lds, st, T1, G, S,
+                           d_meas, d_seg, d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict),
+                           n_pchunks);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
+    const long n_rows = (long)n_ids * G.n_m;
+    for (int r = 0; r < reps; ++r) {
+        hipLaunchKernelGGL(k_score_rows, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, G,
+                           n_ids, d_meas, d_pred, rows);
+        hipLaunchKernelGGL(k_score_final, dim3(1), dim3(64), 0, st, G, n_ids, rows,
+                           reinterpret_cast<plogp_score_dev *>(d_scores));
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
     return hipSuccess;
 }
 

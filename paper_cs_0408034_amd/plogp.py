@@ -25,6 +25,9 @@ MAX_SAMPLES = 4096
 CELL_DTYPE = np.dtype([("time", "<f8"), ("s", "<u4"), ("strategy", "<u4")])
 RUN_DTYPE = np.dtype([("m_from", "<u8"), ("s", "<u4"), ("strategy", "<u4")])
 KEY_STRATEGY, KEY_STRATEGY_AND_SEGMENT = 0, 1
+VERDICT_DTYPE = np.dtype([("regret", "<f8"), ("pred_best", "<u4"), ("meas_best", "<u4")])
+SCORE_DTYPE = np.dtype([("sum_abs_err", "<f8"), ("max_abs_err", "<f8"), ("count", "<u8"),
+                        ("reserved", "<u8")])
 
 
 class PlogpError(RuntimeError):
@@ -73,6 +76,10 @@ def _load_library():
         "plogp_cutovers": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, sz, vp]),
         "plogp_cutovers_profile": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, sz, vp, ctypes.c_int,
                                                   ctypes.POINTER(ctypes.c_float)]),
+        "plogp_score_strategies": (sz, [vp]),
+        "plogp_score_grid": (ctypes.c_int, [vp, sz, vp, vp, vp, vp, vp, vp, vp]),
+        "plogp_score_grid_profile": (ctypes.c_int, [vp, sz, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int,
+                                                    ctypes.POINTER(ctypes.c_float)]),
         "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "plogp_last_hip_error": (ctypes.c_int, []),
     }
@@ -234,4 +241,26 @@ def plogp_cutovers_profile(grid: Grid, n_tables: int, d_cells: int, key_mode: in
     _check(_lib.plogp_cutovers_profile(grid._h, n_tables, d_cells, key_mode, d_row_offsets,
                                        d_runs or None, runs_capacity, stream, reps, ms),
            "plogp_cutovers_profile")
+    return [float(v) for v in ms]
+
+
+def plogp_score_strategies(grid: Grid) -> int:
+    return int(_lib.plogp_score_strategies(grid._h))
+
+
+def plogp_score_grid(table: Table, table_index: int, grid: Grid, d_meas: int, d_seg: int, d_pred: int,
+                     d_verdict: int, d_scores: int, stream: int = 0):
+    _check(_lib.plogp_score_grid(table._h, table_index, grid._h, d_meas, d_seg or None, d_pred,
+                                 d_verdict, d_scores, stream), "plogp_score_grid")
+
+
+def plogp_score_grid_profile(table: Table, table_index: int, grid: Grid, d_meas: int, d_seg: int,
+                             d_pred: int, d_verdict: int, d_scores: int, stream: int = 0,
+                             reps: int = 1):
+    """Each step launched reps times between two events; mean ms per launch of the terms,
+    the scoring, the statistics."""
+    ms = (ctypes.c_float * 3)()
+    _check(_lib.plogp_score_grid_profile(table._h, table_index, grid._h, d_meas, d_seg or None,
+                                         d_pred, d_verdict, d_scores, stream, reps, ms),
+           "plogp_score_grid_profile")
     return [float(v) for v in ms]

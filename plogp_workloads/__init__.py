@@ -15,6 +15,7 @@ from .configs import (  # noqa: F401
     Workload,
     SplitMix64,
     make_workload,
+    make_measurements,
     log_spaced_sizes,
     STRATEGY_NAMES,
     BCAST_IDS,

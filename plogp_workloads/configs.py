@@ -271,3 +271,25 @@ def make_workload(cfg: int, *, n_tables: Optional[int] = None, n_m: Optional[int
     wl.gaps = np.ascontiguousarray(wl.gaps, dtype=np.float64)
     wl.L = np.ascontiguousarray(wl.L, dtype=np.float64)
     return wl
+
+
+def make_measurements(wl, seed: int = 1):
+    """Synthetic "measured" completion times for the scoring step, [n_ids, n_m, n_P], and the
+    segment sizes they were taken with (same shape, uint32).  No model of the method enters:
+    a plain positive curve in (strategy rank, m, P) with 20 % seeded noise, a constant offset
+    and a delay of the small messages (the two error modes the paper reports), so that the
+    arrays have the shape and scale of real ones.  seg: the largest power of two <= min(m, 8192)."""
+    ids = [i for i in range(13) if (wl.strategy_mask >> i) & 1]
+    m = np.asarray(wl.m, dtype=np.float64)
+    P = np.asarray(wl.P, dtype=np.float64)
+    rng = SplitMix64(408034000000 + 777 * seed)
+    noise = np.array([rng.uniform() for _ in range(len(ids) * m.size * P.size)]).reshape(
+        len(ids), m.size, P.size)
+    rank = (1.0 + np.arange(len(ids)) / 13.0)[:, None, None]
+    base = (40.0 + m / 11.5)[None, :, None] * np.log2(P + 1.0)[None, None, :] * rank
+    meas = base * (1.0 + 0.2 * noise) + 200.0
+    meas = np.where(m[None, :, None] < 1024.0, meas * 1.5, meas)
+    cap = np.minimum(np.asarray(wl.m, dtype=np.uint64), 8192)
+    seg1 = (1 << (np.floor(np.log2(cap.astype(np.float64))).astype(np.uint64))).astype(np.uint32)
+    seg = np.broadcast_to(seg1[None, :, None], meas.shape).copy()
+    return meas, seg

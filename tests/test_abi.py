@@ -125,6 +125,13 @@ def test_null_handles_are_refused(plogp):
     assert lib.plogp_cutovers(None, 1, None, 0, None, None, 0, None) == plogp.EINVAL
     assert lib.plogp_cutovers_profile(None, 1, None, 0, None, None, 0, None, 1, None) == plogp.EINVAL
     assert lib.plogp_cutover_rows(3, None) == 0
+    assert lib.plogp_score_grid(None, 0, None, None, None, None, None, None, None) == plogp.EINVAL
+    assert lib.plogp_score_grid_profile(None, 0, None, None, None, None, None, None, None, 1, None) == plogp.EINVAL
+    assert lib.plogp_score_strategies(None) == 0
+
+
+def test_verdict_and_score_records(plogp):
+    assert plogp.VERDICT_DTYPE.itemsize == 16 and plogp.SCORE_DTYPE.itemsize == 32
 
 
 def test_run_is_sixteen_bytes(plogp):

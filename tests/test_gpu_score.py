@@ -1,0 +1,153 @@
+"""GPU parity of the scoring step (prediction against measurement, paper Section 4):
+plogp_score_grid through the C ABI against the CPU oracle on the same inputs.  Predictions,
+verdicts and statistics follow a fixed rounding and summation order, so everything is
+compared bit for bit; the tolerance of the sweep (1e-12 relative) is asserted as well."""
+import numpy as np
+import pytest
+
+import oracle
+from plogp_workloads import Workload, make_measurements, make_workload
+from tests.gpu_util import REL_TOL, stream_handle, torch_cuda
+
+pytestmark = pytest.mark.gpu
+
+
+def _plogp():
+    from paper_cs_0408034_amd import plogp
+    return plogp
+
+
+def gpu_score(wl, meas, seg, table_index=0, with_seg=True):
+    torch = torch_cuda()
+    plogp = _plogp()
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, wl.dtype_size, wl.strategy_mask)
+    n_ids = plogp.plogp_score_strategies(grid)
+    assert meas.shape == (n_ids, len(wl.m), len(wl.P))
+    n_ops = grid.ops
+    d_meas = torch.from_numpy(np.ascontiguousarray(meas)).cuda()
+    d_seg = torch.from_numpy(np.ascontiguousarray(seg).view(np.int32)).cuda() if with_seg else None
+    d_pred = torch.full(meas.shape, float("nan"), dtype=torch.float64, device="cuda")
+    d_ver = torch.full((n_ops * meas.shape[1] * meas.shape[2] * 16,), 0xAB, dtype=torch.uint8, device="cuda")
+    d_sc = torch.full((n_ids * 32,), 0xAB, dtype=torch.uint8, device="cuda")
+    plogp.plogp_score_grid(tab, table_index, grid, d_meas.data_ptr(),
+                           d_seg.data_ptr() if with_seg else 0, d_pred.data_ptr(), d_ver.data_ptr(),
+                           d_sc.data_ptr(), stream_handle())
+    torch.cuda.synchronize()
+    pred = d_pred.cpu().numpy()
+    ver = d_ver.cpu().numpy().view(plogp.VERDICT_DTYPE).reshape(n_ops, meas.shape[1], meas.shape[2])
+    sc = d_sc.cpu().numpy().view(plogp.SCORE_DTYPE)
+    grid.free()
+    tab.free()
+    return pred, ver, sc
+
+
+def same_bits(a, b):
+    return (np.ascontiguousarray(a).view(np.uint64) == np.ascontiguousarray(b).view(np.uint64)).all()
+
+
+def check(wl, meas, seg, table_index=0):
+    x, y, L = wl.sizes[table_index], wl.gaps[table_index], float(wl.L[table_index])
+    want_p, want_v, want_s = oracle.score_grid(x, y, L, wl.m, wl.P, wl.strategy_mask, meas, seg)
+    pred, ver, sc = gpu_score(wl, meas, seg, table_index)
+    assert (np.abs(pred - want_p) <= REL_TOL * np.abs(want_p)).all()
+    assert same_bits(pred, want_p)
+    assert (ver["pred_best"] == want_v["pred_best"]).all()
+    assert (ver["meas_best"] == want_v["meas_best"]).all()
+    assert same_bits(ver["regret"], want_v["regret"])
+    assert (sc["count"] == want_s["count"]).all() and (sc["reserved"] == 0).all()
+    assert same_bits(sc["max_abs_err"], want_s["max_abs_err"])
+    assert same_bits(sc["sum_abs_err"], want_s["sum_abs_err"])
+    return want_p, want_v
+
+
+def from_predictions(wl, seg, seed, table_index=0):
+    """Measurements in the paper's two error modes around the oracle's predictions:
+    a constant offset, a delay of the small messages, and seeded noise."""
+    x, y, L = wl.sizes[table_index], wl.gaps[table_index], float(wl.L[table_index])
+    ones = np.ones(seg.shape)
+    pred, _, _ = oracle.score_grid(x, y, L, wl.m, wl.P, wl.strategy_mask, ones, seg)
+    rng = np.random.default_rng(seed)
+    meas = pred * (1.0 + 0.1 * rng.standard_normal(pred.shape).clip(-3, 3)) + 120.0
+    small = np.asarray(wl.m)[None, :, None] < 4096
+    return np.where(small, meas * 1.4, meas)
+
+
+@pytest.mark.parametrize("cfg,kw", [
+    (1, {}),
+    (2, dict(m_slice=slice(0, 1024, 13), P_subset=[2, 3, 4, 7, 64, 65, 66, 129, 700, 1023, 1024])),
+    (5, dict(m_slice=slice(0, 4096, 37), P_subset=[2, 65, 66, 4097, 40000, 65536])),
+    (3, dict(m_slice=slice(0, 1024, 111), s_subset=slice(0, 8192, 4096))),
+])
+def test_configs_against_the_oracle(cfg, kw):
+    wl = make_workload(cfg, **kw)
+    _, seg = make_measurements(wl)
+    meas = from_predictions(wl, seg, cfg)
+    _, verdict = check(wl, meas, seg)
+    # the noise flips some decisions but not all of them
+    agree = (verdict["pred_best"] == verdict["meas_best"]).mean()
+    assert 0.05 < agree < 1.0
+
+
+def test_model_free_measurements_and_many_process_counts():
+    # the generator the benchmark uses (no model in it); 300 process counts: ragged chunks
+    base = make_workload(2, m_slice=slice(0, 1024, 41))
+    P = np.arange(2, 302, dtype=np.uint32)
+    wl = Workload("score", base.sizes, base.gaps, base.L, base.m, P, base.s, base.s_cap,
+                  base.strategy_mask)
+    meas, seg = make_measurements(wl, seed=3)
+    check(wl, meas, seg)
+
+
+@pytest.mark.parametrize("mask", [0x3FF, 0x1C00, (1 << 0) | (1 << 3) | (1 << 7), (1 << 11), (1 << 5) | (1 << 12)])
+def test_masks_and_planes(mask):
+    base = make_workload(2, m_slice=slice(5, 1024, 101), P_subset=[2, 5, 64, 65, 200])
+    wl = Workload("score", base.sizes, base.gaps, base.L, base.m, base.P, base.s, base.s_cap, mask)
+    meas, seg = make_measurements(wl, seed=mask)
+    check(wl, meas, seg)
+
+
+def test_second_table_of_a_batch_and_no_segment_array():
+    wl4 = make_workload(4, n_tables=3, n_m=20)
+    mask = (1 << 0) | (1 << 6) | (1 << 10) | (1 << 11) | (1 << 12)       # no segmented id
+    wl = Workload("score", wl4.sizes, wl4.gaps, wl4.L, wl4.m, wl4.P, wl4.s, wl4.s_cap, mask)
+    meas, seg = make_measurements(wl, seed=8)
+    x, y, L = wl.sizes[2], wl.gaps[2], float(wl.L[2])
+    want_p, want_v, want_s = oracle.score_grid(x, y, L, wl.m, wl.P, mask, meas, seg)
+    pred, ver, sc = gpu_score(wl, meas, seg, table_index=2, with_seg=False)
+    assert same_bits(pred, want_p) and (ver == want_v).all()
+    assert same_bits(sc["sum_abs_err"], want_s["sum_abs_err"])
+
+
+def test_segment_size_outside_the_domain_gives_nan_for_that_point_only():
+    wl = make_workload(1)
+    meas, seg = make_measurements(wl, seed=5)
+    ids = oracle.strategy_ids(wl.strategy_mask)
+    r5 = ids.index(5)
+    good_p, _, _ = gpu_score(wl, meas, seg)
+    bad = seg.copy()
+    bad[r5, 3, 4] = 0
+    bad[r5, 0, 0] = np.uint32(int(wl.m[0]) * 2)
+    pred, ver, _ = gpu_score(wl, meas, bad)
+    assert np.isnan(pred[r5, 3, 4]) and np.isnan(pred[r5, 0, 0])
+    mask = np.ones(pred.shape, dtype=bool)
+    mask[r5, 3, 4] = mask[r5, 0, 0] = False
+    assert same_bits(pred[mask], good_p[mask])
+    assert ver["pred_best"][0, 3, 4] != 5            # a NaN prediction is never the best one
+
+
+def test_bad_arguments_are_refused():
+    torch = torch_cuda()
+    plogp = _plogp()
+    wl = make_workload(1)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, wl.dtype_size, wl.strategy_mask)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    p = buf.data_ptr()
+    lib = plogp._lib
+    assert lib.plogp_score_grid(tab._h, 1, grid._h, p, p, p, p, p, None) == plogp.EINVAL      # table index
+    assert lib.plogp_score_grid(tab._h, 0, grid._h, p, None, p, p, p, None) == plogp.EINVAL   # id 5 needs seg
+    assert lib.plogp_score_grid(tab._h, 0, grid._h, p, p, p, p + 8, p, None) == plogp.EINVAL  # misaligned
+    assert lib.plogp_score_grid(tab._h, 0, grid._h, None, p, p, p, p, None) == plogp.EINVAL
+    grid.free()
+    tab.free()
