@@ -135,13 +135,75 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     cut = run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps) if with_cut else None
     if cut is not None and wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16:
         cut["roofline"]["traffic"] = MEASURED_CUT_TRAFFIC.get(int(wl.name[3:]))
+    score = run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps) if with_cut else None
     del out
     grid.free()
     tab.free()
-    return ms_per_step, stage_ms, cut
+    return ms_per_step, stage_ms, cut, score
 
 
 CUT_STAGES = ("mark", "scan", "emit")
+SCORE_STAGES = ("terms", "score", "statistics")
+
+
+def run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps):
+    """Prediction against measurement for table 0 of the workload on its (m, P) grid:
+    synthetic measured times of every enabled strategy, already resident."""
+    from plogp_workloads import make_measurements
+    sh = stream.cuda_stream
+    meas, seg = make_measurements(wl)
+    rows, n_m, n_P = meas.shape
+    assert rows == plogp.plogp_score_strategies(grid)
+    d_meas = torch.from_numpy(meas).cuda()
+    d_seg = torch.from_numpy(seg.view(np.int32)).cuda()
+    d_pred = torch.empty_like(d_meas)
+    d_ver = torch.empty(grid.ops * n_m * n_P * 16, dtype=torch.uint8, device="cuda")
+    d_sc = torch.empty(rows * 32, dtype=torch.uint8, device="cuda")
+    args = (tab, 0, grid, d_meas.data_ptr(), d_seg.data_ptr(), d_pred.data_ptr(), d_ver.data_ptr(),
+            d_sc.data_ptr(), sh)
+    for _ in range(3):
+        plogp.plogp_score_grid(*args)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        plogp.plogp_score_grid(*args)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
+    rounds = [plogp.plogp_score_grid_profile(*args, profile_reps) for _ in range(5)]
+    stage_ms = dict(zip(SCORE_STAGES, np.median(np.array(rounds), axis=0).tolist()))
+    # what the scoring has to move: every measured time read once, the segment size of the
+    # segmented strategies' points, every prediction and every verdict written once (the
+    # statistics could in principle be formed from values already in registers)
+    points = n_m * n_P
+    n_seg = sum(1 for i in (2, 5, 9) if (wl.strategy_mask >> i) & 1)
+    alg_bytes = points * (8 * rows + 4 * n_seg + 8 * rows + 16 * grid.ops) + 32 * rows
+    k_ms = stage_ms["score"] + stage_ms["statistics"]
+    ach = alg_bytes / (k_ms * 1e-3) / 1e9
+    return {"ms_per_call": ms, "points_per_s": rows * points / (ms * 1e-3), "strategies": rows,
+            "points": points, "stage_ms": stage_ms,
+            "roofline": {"kernel": "score+statistics", "bound": "hbm", "achieved": ach,
+                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9),
+                         "traffic": None, "algorithmic_bytes": alg_bytes, "avg_ms": k_ms}}
+
+
+def score_cpu(sample):
+    """The scoring oracle (one thread) on table 0 of the sample."""
+    import oracle
+    from plogp_workloads import make_measurements
+    meas, seg = make_measurements(sample)
+    a = (sample.sizes[0], sample.gaps[0], float(sample.L[0]), sample.m, sample.P, sample.strategy_mask,
+         meas, seg)
+    runs, dt = 0, 0.0
+    while dt < 1.0 and runs < 20:
+        t0 = time.perf_counter()
+        oracle.score_grid(*a)
+        dt += time.perf_counter() - t0
+        runs += 1
+    return {"value": runs * meas.size / dt, "unit": "points/s", "cores": 1, "kind": "oracle",
+            "seconds": dt}
 
 
 def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps):
@@ -233,7 +295,7 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
     if mask is not None:
         wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
-    ms, stage_ms, cut = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    ms, stage_ms, cut, score = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
     traffic = MEASURED_TRAFFIC.get(cfg, {}) if mask is None else {}
     if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
         # the single-kernel batch path did every stage inside one launch
@@ -257,11 +319,16 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
     }
     if cut is not None:
         res["cutover_extraction"] = cut
+    if score is not None:
+        res["prediction_scoring"] = score
     if with_cpu:
         res["cpu_baseline"] = run_cpu(cfg, wl)
         if cut is not None:
             sample, what = cpu_sample(cfg, wl)
             cut["cpu_baseline"] = dict(cut_cpu(sample), sample=what)
+        if score is not None:
+            sample, what = cpu_sample(cfg, wl)
+            score["cpu_baseline"] = dict(score_cpu(sample), sample="table 0 of: " + what)
     return res
 
 
@@ -320,6 +387,8 @@ def main():
         line["cpu_baseline"] = head["cpu_baseline"]
     if "cutover_extraction" in head:
         line["cutover_extraction"] = head["cutover_extraction"]
+    if "prediction_scoring" in head:
+        line["prediction_scoring"] = head["prediction_scoring"]
     extras = [] if args.extra in ("", "none") else [int(v) for v in args.extra.split(",")]
     if extras:
         line["workloads"] = {}

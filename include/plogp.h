@@ -284,7 +284,9 @@ size_t plogp_score_strategies(const plogp_grid *g);
  *   d_meas    [rows][n_m][n_P] doubles, measured times (> 0);
  *   d_seg     [rows][n_m][n_P] uint32, the segment size each point was measured
  *             with; read for ids 2, 5, 9 only (0 < s <= m, else the prediction
- *             is NaN); may be NULL when none of them is enabled;
+ *             is NaN: it is never pred_best, the maximum skips it and that
+ *             strategy's sum becomes NaN); may be NULL when none of them is
+ *             enabled;
  *   d_pred    [rows][n_m][n_P] doubles (out);
  *   d_verdict [operation planes][n_m][n_P] records (out), planes as in
  *             plogp_tune_grid, 16-byte aligned;

@@ -2272,9 +2272,15 @@ struct plogp_verdict_dev {
     uint32_t meas_best;
 };
 
-__global__ void __launch_bounds__(256) k_score(DeviceTables T, DeviceGrid G, Scratch S,
-                                               const double *meas, const uint32_t *seg, double *pred,
-                                               plogp_verdict_dev *verdict, int n_pchunks)
+// Workgroups walk the (m, chunk of P) items with a stride, so that a big table is
+// staged once per workgroup; the measured times and segment sizes of a point are
+// fetched before any arithmetic (13 + 3 independent loads per lane in flight).
+__global__ void __launch_bounds__(1024) k_score(DeviceTables T, DeviceGrid G, Scratch S,
+                                                const double *__restrict__ meas,
+                                                const uint32_t *__restrict__ seg,
+                                                double *__restrict__ pred,
+                                                plogp_verdict_dev *__restrict__ verdict, int n_pchunks,
+                                                int n_items)
 {
     extern __shared__ double lds[];
     const uint32_t mask = G.mask;
@@ -2282,97 +2288,190 @@ __global__ void __launch_bounds__(256) k_score(DeviceTables T, DeviceGrid G, Scr
     LdsTable tab = {nullptr, nullptr, nullptr, T.n};
     if (any_seg)
         tab = stage_table(lds, T, 0);                 // for g(s) at the measured segment sizes
-    const int mi = blockIdx.x / n_pchunks;
-    const int pi = (blockIdx.x % n_pchunks) * blockDim.x + threadIdx.x;
-    if (pi >= G.n_P)
-        return;
-    const u64 m = G.m[mi];
-    const uint32_t P = G.P[pi];
     const double L = T.L[0];
-    const double q = (double)(P - 1), fl = (double)floor_log2(P), cl = (double)ceil_log2(P);
-    const double gm = S.gm[mi], g1 = S.g1[0];
+    const double g1 = S.g1[0];
     const double R = __builtin_fma(3.0, L, 2.0 * g1);
     const size_t plane = (size_t)G.n_m * G.n_P;
-    const size_t cell = (size_t)mi * G.n_P + pi;
-    double best_p[2] = {INFINITY, INFINITY}, best_m[2] = {INFINITY, INFINITY};
-    double meas_of_pred_best[2] = {NAN, NAN};
-    uint32_t id_p[2] = {0xFFFFFFFFu, 0xFFFFFFFFu}, id_m[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
-    int r = 0;
-    for (int id = 0; id < 13; ++id) {
-        if (!((mask >> id) & 1u))
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int mi = item / n_pchunks;
+        const int pi = (item % n_pchunks) * blockDim.x + threadIdx.x;
+        if (pi >= G.n_P)
             continue;
-        const size_t at = (size_t)r * plane + cell;
-        ++r;
-        double gs = 0.0, k = 0.0;
-        bool ok = true;
-        if (id == 2 || id == 5 || id == 9) {
-            const u64 s = seg[at];
-            ok = s > 0 && s <= m;
-            if (ok) {
-                gs = gap_at(tab, (double)s);
-                k = segments(m, s);
+        const size_t cell = (size_t)mi * G.n_P + pi;
+        double tm[13];
+        uint32_t sv[3] = {0u, 0u, 0u};
+        {
+            int r = 0;
+#pragma unroll
+            for (int id = 0; id < 13; ++id) {
+                tm[id] = 0.0;
+                if ((mask >> id) & 1u) {
+                    const size_t at = (size_t)r * plane + cell;
+                    tm[id] = meas[at];
+                    if (id == 2) sv[0] = seg[at];
+                    if (id == 5) sv[1] = seg[at];
+                    if (id == 9) sv[2] = seg[at];
+                    ++r;
+                }
             }
         }
-        double v;
-        switch (id) {
-        case 0: case 10: v = __builtin_fma(q, gm, L); break;
-        case 1: v = __builtin_fma(q, gm, R); break;
-        case 2: v = __builtin_fma(q, gs * k, L); break;
-        case 3: v = q * (gm + L); break;
-        case 4: v = q * (gm + R); break;
-        case 5: v = __builtin_fma(q, gs + L, gs * (k - 1.0)); break;
-        case 6: v = cl * __builtin_fma(2.0, gm, L); break;
-        case 7: v = __builtin_fma(fl, gm, cl * L); break;
-        case 8: v = __builtin_fma(fl, gm, cl * R); break;
-        case 9: v = __builtin_fma(fl, gs * k, cl * L); break;
-        case 11: v = __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P)); break;
-        default: v = __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]); break;
+        const u64 m = G.m[mi];
+        const uint32_t P = G.P[pi];
+        const double q = (double)(P - 1), fl = (double)floor_log2(P), cl = (double)ceil_log2(P);
+        const double gm = S.gm[mi];
+        double gs[3] = {0.0, 0.0, 0.0}, k[3] = {0.0, 0.0, 0.0};
+        bool ok[3] = {true, true, true};
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            if (!((mask >> (u == 0 ? 2 : u == 1 ? 5 : 9)) & 1u))
+                continue;
+            const u64 sz = sv[u];
+            ok[u] = sz > 0 && sz <= m;
+            if (ok[u]) {
+                gs[u] = gap_at(tab, (double)sz);
+                k[u] = segments(m, sz);
+            }
         }
-        if (!ok)
-            v = NAN;
-        pred[at] = v;
-        const double tm = meas[at];
-        const int op = id < 10 ? 0 : 1;
-        if (v < best_p[op]) {
-            best_p[op] = v;
-            id_p[op] = (uint32_t)id;
-            meas_of_pred_best[op] = tm;
+        double best_p[2] = {INFINITY, INFINITY}, best_m[2] = {INFINITY, INFINITY};
+        double meas_of_pred_best[2] = {NAN, NAN};
+        uint32_t id_p[2] = {0xFFFFFFFFu, 0xFFFFFFFFu}, id_m[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+        int r = 0;
+#pragma unroll
+        for (int id = 0; id < 13; ++id) {
+            if (!((mask >> id) & 1u))
+                continue;
+            const size_t at = (size_t)r * plane + cell;
+            ++r;
+            double v;
+            switch (id) {
+            case 0: case 10: v = __builtin_fma(q, gm, L); break;
+            case 1: v = __builtin_fma(q, gm, R); break;
+            case 2: v = ok[0] ? __builtin_fma(q, gs[0] * k[0], L) : NAN; break;
+            case 3: v = q * (gm + L); break;
+            case 4: v = q * (gm + R); break;
+            case 5: v = ok[1] ? __builtin_fma(q, gs[1] + L, gs[1] * (k[1] - 1.0)) : NAN; break;
+            case 6: v = cl * __builtin_fma(2.0, gm, L); break;
+            case 7: v = __builtin_fma(fl, gm, cl * L); break;
+            case 8: v = __builtin_fma(fl, gm, cl * R); break;
+            case 9: v = ok[2] ? __builtin_fma(fl, gs[2] * k[2], cl * L) : NAN; break;
+            case 11: v = __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P)); break;
+            default: v = __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]); break;
+            }
+            pred[at] = v;
+            const double t_meas = tm[id];
+            const int op = id < 10 ? 0 : 1;
+            if (v < best_p[op]) {
+                best_p[op] = v;
+                id_p[op] = (uint32_t)id;
+                meas_of_pred_best[op] = t_meas;
+            }
+            if (t_meas < best_m[op]) {
+                best_m[op] = t_meas;
+                id_m[op] = (uint32_t)id;
+            }
         }
-        if (tm < best_m[op]) {
-            best_m[op] = tm;
-            id_m[op] = (uint32_t)id;
+        plogp_verdict_dev *o = verdict + cell;
+#pragma unroll
+        for (int op = 0; op < 2; ++op) {
+            if (!(mask & (op == 0 ? 0x3FFu : 0x1C00u)))
+                continue;
+            plogp_verdict_dev vd;
+            vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
+            vd.pred_best = id_p[op];
+            vd.meas_best = id_m[op];
+            *o = vd;
+            o += plane;
         }
-    }
-    plogp_verdict_dev *o = verdict + cell;
-    for (int op = 0; op < 2; ++op) {
-        if (!(mask & (op == 0 ? 0x3FFu : 0x1C00u)))
-            continue;
-        plogp_verdict_dev vd;
-        vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
-        vd.pred_best = id_p[op];
-        vd.meas_best = id_m[op];
-        *o = vd;
-        o += plane;
     }
 }
 
 // e = |(pred - meas) / meas| per point; per (strategy row r, m): the sum over P in
 // ascending order from +0.0 and the maximum.  rows[(r * n_m + mi) * 2] = {sum, max}.
-__global__ void __launch_bounds__(256) k_score_rows(DeviceGrid G, int n_ids, const double *meas,
-                                                    const double *pred, double *rows)
+// A wave takes SCORE_RT rows of n_P points: per chunk of 64 process counts every lane
+// loads one point of each row (coalesced) and leaves e in LDS; then lane i < SCORE_RT
+// adds the 64 values of row i in order, while the loads of the next chunk are in
+// flight.  The running sums stay in those lanes.
+constexpr int SCORE_RT = 8;
+constexpr int SCORE_WAVES = 4;
+
+__global__ void __launch_bounds__(64 * SCORE_WAVES) k_score_rows(DeviceGrid G, int n_ids,
+                                                                  const double *__restrict__ meas,
+                                                                  const double *__restrict__ pred,
+                                                                  double *__restrict__ rows)
 {
-    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= (long)n_ids * G.n_m)
+    __shared__ double tile[SCORE_WAVES][SCORE_RT][65];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const long n_rows = (long)n_ids * G.n_m;
+    const long row0 = ((long)blockIdx.x * SCORE_WAVES + w) * SCORE_RT;
+    if (row0 >= n_rows)
         return;
-    const double *pm = meas + (size_t)e * G.n_P, *pp = pred + (size_t)e * G.n_P;
-    double sum = 0.0, worst = 0.0;
-    for (int pi = 0; pi < G.n_P; ++pi) {
-        const double err = fabs((pp[pi] - pm[pi]) / pm[pi]);
-        sum = sum + err;
-        worst = err > worst ? err : worst;
+    const int n_here = n_rows - row0 < SCORE_RT ? (int)(n_rows - row0) : SCORE_RT;
+    const int n_P = G.n_P;
+    double vp[SCORE_RT], vm[SCORE_RT];
+    auto fetch = [&](int p0) {
+        const int pi = p0 + lane;
+#pragma unroll
+        for (int i = 0; i < SCORE_RT; ++i) {
+            vp[i] = 1.0;                  // padding: e = 0, below every real maximum
+            vm[i] = 1.0;
+            if (i < n_here && pi < n_P) {
+                vp[i] = pred[(size_t)(row0 + i) * n_P + pi];
+                vm[i] = meas[(size_t)(row0 + i) * n_P + pi];
+            }
+        }
+    };
+    fetch(0);
+    // the maximum does not depend on the order: every lane keeps its own per row and the
+    // lanes are combined once at the end, so that only the sum is a serial chain
+    double sum = 0.0;
+    double wmax[SCORE_RT];
+#pragma unroll
+    for (int i = 0; i < SCORE_RT; ++i)
+        wmax[i] = 0.0;
+    for (int p0 = 0; p0 < n_P; p0 += 64) {
+#pragma unroll
+        for (int i = 0; i < SCORE_RT; ++i) {
+            const double err = fabs((vp[i] - vm[i]) / vm[i]);
+            wmax[i] = err > wmax[i] ? err : wmax[i];
+            tile[w][i][lane] = err;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (p0 + 64 < n_P)
+            fetch(p0 + 64);
+        if (lane < n_here) {
+            const int cnt = n_P - p0 < 64 ? n_P - p0 : 64;
+            int j = 0;
+            for (; j + 16 <= cnt; j += 16) {           // 16 LDS reads in flight, added in order
+                double err[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    err[u] = tile[w][lane][j + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    sum = sum + err[u];
+            }
+            for (; j < cnt; ++j)
+                sum = sum + tile[w][lane][j];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
-    rows[2 * e] = sum;
-    rows[2 * e + 1] = worst;
+#pragma unroll
+    for (int i = 0; i < SCORE_RT; ++i)
+        tile[w][i][lane] = wmax[i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane < n_here) {
+        double worst = 0.0;
+#pragma unroll 16
+        for (int j = 0; j < 64; ++j) {
+            const double v = tile[w][lane][j];
+            worst = v > worst ? v : worst;
+        }
+        rows[2 * (row0 + lane)] = sum;
+        rows[2 * (row0 + lane) + 1] = worst;
+    }
 }
 
 struct plogp_score_dev {
@@ -2382,24 +2481,68 @@ struct plogp_score_dev {
     unsigned long long reserved;
 };
 
-// Per strategy row: the per-m sums added in ascending m from +0.0.
-__global__ void k_score_final(DeviceGrid G, int n_ids, const double *rows, plogp_score_dev *score)
+// Per strategy row: the per-m sums added in ascending m from +0.0.  One workgroup
+// per row: 1024 per-m results are loaded side by side into LDS and thread 0 adds them
+// in order while the next 1024 are in flight.
+__global__ void __launch_bounds__(1024) k_score_final(DeviceGrid G, int n_ids, const double *rows,
+                                                      plogp_score_dev *score)
 {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= n_ids)
-        return;
-    double total = 0.0, worst = 0.0;
-    for (int mi = 0; mi < G.n_m; ++mi) {
-        total = total + rows[2 * ((size_t)r * G.n_m + mi)];
-        const double w = rows[2 * ((size_t)r * G.n_m + mi) + 1];
-        worst = w > worst ? w : worst;
+    __shared__ double part[1024];
+    __shared__ double wave_max[16];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const double *mine = rows + 2 * (size_t)r * G.n_m;
+    double total = 0.0, worst = 0.0;        // worst: this thread's own maximum
+    double a = 0.0, b = 0.0;
+    if (tid < G.n_m) {
+        a = mine[2 * tid];
+        b = mine[2 * tid + 1];
     }
-    plogp_score_dev sc;
-    sc.sum_abs_err = total;
-    sc.max_abs_err = worst;
-    sc.count = (unsigned long long)G.n_m * (unsigned long long)G.n_P;
-    sc.reserved = 0ull;
-    score[r] = sc;
+    for (int m0 = 0; m0 < G.n_m; m0 += 1024) {
+        part[tid] = a;
+        worst = b > worst ? b : worst;
+        __syncthreads();
+        const int nxt = m0 + 1024 + tid;
+        b = 0.0;
+        if (nxt < G.n_m) {
+            a = mine[2 * (size_t)nxt];
+            b = mine[2 * (size_t)nxt + 1];
+        }
+        if (tid == 0) {
+            const int cnt = G.n_m - m0 < 1024 ? G.n_m - m0 : 1024;
+            int j = 0;
+            for (; j + 16 <= cnt; j += 16) {           // 16 LDS reads in flight, added in order
+                double sv[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    sv[u] = part[j + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    total = total + sv[u];
+            }
+            for (; j < cnt; ++j)
+                total = total + part[j];
+        }
+        __syncthreads();
+    }
+    // the maximum over all threads (any order gives the same value)
+    for (int off = 32; off > 0; off >>= 1) {
+        const double o = __shfl_xor(worst, off, 64);
+        worst = o > worst ? o : worst;
+    }
+    if ((tid & 63) == 0)
+        wave_max[tid >> 6] = worst;
+    __syncthreads();
+    if (tid == 0) {
+        double top = 0.0;
+        for (int i = 0; i < 16; ++i)
+            top = wave_max[i] > top ? wave_max[i] : top;
+        plogp_score_dev sc;
+        sc.sum_abs_err = total;
+        sc.max_abs_err = top;
+        sc.count = (unsigned long long)G.n_m * (unsigned long long)G.n_P;
+        sc.reserved = 0ull;
+        score[r] = sc;
+    }
 }
 
 }  // namespace
@@ -2677,19 +2820,31 @@ hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scrat
     // g(m), g(1), the Scatter sums: the first stages of the tuning
     if ((e = launch_tune(T1, G, S, nullptr, st, nullptr, reps)) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
-    const int n_pchunks = (G.n_P + 255) / 256;
     const size_t lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
+    // a small table is staged by every workgroup of 256; a big one by at most one or
+    // two workgroups of 1024 per CU, which then walk the items with a stride
+    const bool big = lds > 16384;
+    const int threads = big ? 1024 : 256;
+    const int n_pchunks = (G.n_P + threads - 1) / threads;
+    const long n_items = (long)G.n_m * n_pchunks;
+    long n_wg = n_items;
+    if (big) {
+        const long fit = 256L * (long)((160 * 1024) / lds);
+        if (n_wg > fit) n_wg = fit;
+    }
+    if (n_items > 0x7FFFFFFFL) return hipErrorInvalidValue;
     for (int r = 0; r < reps; ++r)
-        hipLaunchKernelGGL(k_score, dim3((unsigned)G.n_m * n_pchunks), dim3(256), lds, st, T1, G, S,
-                           d_meas, d_seg, d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict),
-                           n_pchunks);
+        hipLaunchKernelGGL(k_score, dim3((unsigned)n_wg), dim3(threads), lds, st, T1, G, S, d_meas, d_seg,
+                           d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict), n_pchunks,
+                           (int)n_items);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
     const long n_rows = (long)n_ids * G.n_m;
+    const long row_wg = (n_rows + SCORE_RT * SCORE_WAVES - 1) / (SCORE_RT * SCORE_WAVES);
     for (int r = 0; r < reps; ++r) {
-        hipLaunchKernelGGL(k_score_rows, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, G,
-                           n_ids, d_meas, d_pred, rows);
-        hipLaunchKernelGGL(k_score_final, dim3(1), dim3(64), 0, st, G, n_ids, rows,
+        hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids,
+                           d_meas, d_pred, rows);
+        hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, n_ids, rows,
                            reinterpret_cast<plogp_score_dev *>(d_scores));
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
