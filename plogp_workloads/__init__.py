@@ -16,6 +16,7 @@ from .configs import (  # noqa: F401
     SplitMix64,
     make_workload,
     make_measurements,
+    make_perturbed,
     log_spaced_sizes,
     STRATEGY_NAMES,
     BCAST_IDS,

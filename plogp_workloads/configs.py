@@ -293,3 +293,18 @@ def make_measurements(wl, seed: int = 1):
     seg1 = (1 << (np.floor(np.log2(cap.astype(np.float64))).astype(np.uint64))).astype(np.uint32)
     seg = np.broadcast_to(seg1[None, :, None], meas.shape).copy()
     return meas, seg
+
+
+def make_perturbed(wl: Workload, n_copies: int, eps: float, seed: int = 1) -> Workload:
+    """A batch for the robustness check: table 0 of `wl` as it is, followed by n_copies copies in
+    which every gap sample and the latency are scaled by independent factors uniform in
+    [1 - eps, 1 + eps] (the sample sizes stay), over the same grid."""
+    rng = SplitMix64(_seed(6) + 7919 * seed)
+    n = wl.sizes.shape[1]
+    u = rng.uniforms(n_copies * (n + 1)).reshape(n_copies, n + 1)
+    f = 1.0 + eps * (2.0 * u - 1.0)
+    sizes = np.repeat(wl.sizes[:1], n_copies + 1, axis=0)
+    gaps = np.concatenate([wl.gaps[:1], wl.gaps[:1] * f[:, :n]], axis=0)
+    L = np.concatenate([wl.L[:1], wl.L[0] * f[:, n]])
+    return Workload(wl.name + "_perturbed", sizes, gaps, L, wl.m, wl.P, wl.s, wl.s_cap,
+                    wl.strategy_mask, wl.dtype_size)
