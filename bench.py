@@ -136,6 +136,9 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     if cut is not None and wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16:
         cut["roofline"]["traffic"] = MEASURED_CUT_TRAFFIC.get(int(wl.name[3:]))
     score = run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps) if with_cut else None
+    if score is not None and tab.count > 1:
+        score["robustness"] = run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps,
+                                             profile_reps)
     del out
     grid.free()
     tab.free()
@@ -187,6 +190,53 @@ def run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps):
             "roofline": {"kernel": "score+statistics", "bound": "hbm", "achieved": ach,
                          "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9),
                          "traffic": None, "algorithmic_bytes": alg_bytes, "avg_ms": k_ms}}
+
+
+def run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps, profile_reps):
+    """The robustness summary over the batch just tuned (table 0 against all the others)."""
+    sh = stream.cuda_stream
+    nt = tab.count
+    per_table = nbytes // 16 // nt
+    d_agree = torch.empty(per_table, dtype=torch.int32, device="cuda")
+    d_dev = torch.empty(per_table, dtype=torch.float64, device="cuda")
+    d_tab = torch.empty(nt, dtype=torch.int32, device="cuda")
+    args = (grid, nt, out.data_ptr(), plogp.KEY_STRATEGY_AND_SEGMENT, d_agree.data_ptr(),
+            d_dev.data_ptr(), d_tab.data_ptr(), sh)
+    for _ in range(3):
+        plogp.plogp_robustness(*args)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        plogp.plogp_robustness(*args)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
+    k_ms = float(np.median([plogp.plogp_robustness_profile(*args, profile_reps) for _ in range(5)]))
+    # every 16-byte record of every table read once; 12 bytes per cell position and 4 per table out
+    alg_bytes = nbytes + 12 * per_table + 4 * nt
+    ach = alg_bytes / (k_ms * 1e-3) / 1e9
+    return {"ms_per_call": ms, "cells_per_s": (nbytes // 16) / (ms * 1e-3), "tables": nt,
+            "mean_fraction_kept": float(d_agree.double().mean().item()) / max(nt - 1, 1),
+            "roofline": {"kernel": "k_robust", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9,
+                         "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9), "traffic": None,
+                         "algorithmic_bytes": alg_bytes, "avg_ms": k_ms}}
+
+
+def robust_cpu(sample):
+    """The robustness oracle (array operations, one thread) on the oracle's tables of the sample."""
+    import oracle
+    from oracle import plogp_robust as orb
+    cells, _ = oracle.tune_workload(sample)
+    runs, dt = 0, 0.0
+    while dt < 1.0 and runs < 20:
+        t0 = time.perf_counter()
+        orb.robustness(cells, 1)
+        dt += time.perf_counter() - t0
+        runs += 1
+    return {"value": runs * cells.size / dt, "unit": "cells/s", "cores": 1, "kind": "oracle",
+            "seconds": dt}
 
 
 def score_cpu(sample):
@@ -329,6 +379,8 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
         if score is not None:
             sample, what = cpu_sample(cfg, wl)
             score["cpu_baseline"] = dict(score_cpu(sample), sample="table 0 of: " + what)
+            if "robustness" in score:
+                score["robustness"]["cpu_baseline"] = dict(robust_cpu(sample), sample=what)
     return res
 
 

@@ -312,6 +312,40 @@ int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_gri
                              plogp_verdict *d_verdict, plogp_strategy_score *d_scores, void *stream,
                              int reps, float *stage_ms_out);
 
+/*
+ * Decision robustness -- paper Section 4 and the conclusion: the deviations
+ * between prediction and reality did not change which technique the models
+ * select.  For a batch of n_tables decision tables over grid g, laid out as
+ * plogp_tune_grid writes them ([table][operation plane][m][P]), table 0 tuned
+ * from the parameters as measured and tables 1.. from perturbed copies:
+ *   d_agree       [planes][n_m][n_P] uint32 (out): how many of the tables 1..
+ *                 hold the decision of table 0 in that cell (the fraction that
+ *                 keeps it is d_agree / (n_tables - 1));
+ *   d_max_dev     same shape, doubles (out), or NULL: the largest
+ *                 abs(T_t - T_0) / T_0 of the cell's predicted time over those
+ *                 tables (0 for one table; a NaN quotient is skipped);
+ *   d_table_agree [n_tables] uint32 (out), or NULL: in how many cells table t
+ *                 holds the decision of table 0 (entry 0 = number of cells).
+ * key_mode as in plogp_cutovers: the decision is the strategy, or the strategy
+ * and its segment size.  All DEVICE pointers; d_cells 16-byte aligned.
+ * Enqueued on `stream`; uses no scratch memory.
+ * Errors: EINVAL (null, misaligned, bad key_mode, n_tables = 0 or above 2^24),
+ * ERANGE (more than 2^32 - 256 cells per table), EDEVICE.
+ */
+int plogp_robustness(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                     uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree, void *stream);
+
+/*
+ * plogp_robustness_profile -- the same work launched `reps` times back to back
+ * between two HIP events on `stream`; waits and returns the mean milliseconds
+ * per launch (clearing the outputs included) in *ms_out.  Synchronous.
+ * Errors: as plogp_robustness, plus EINVAL for a null ms_out or reps outside
+ * [1, 10000].
+ */
+int plogp_robustness_profile(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells,
+                             int key_mode, uint32_t *d_agree, double *d_max_dev,
+                             uint32_t *d_table_agree, void *stream, int reps, float *ms_out);
+
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);
 /* HIP error code of the calling thread's most recent PLOGP_EDEVICE (0 if none). */

@@ -8,7 +8,8 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libplogp.so"
-SOURCES = [CSRC / "plogp_api.hip", CSRC / "plogp_kernels.hip", CSRC / "plogp_cutover.hip"]
+SOURCES = [CSRC / "plogp_api.hip", CSRC / "plogp_kernels.hip", CSRC / "plogp_cutover.hip",
+           CSRC / "plogp_robust.hip"]
 HEADERS = [CSRC / "plogp_internal.hpp", PKG.parent / "include" / "plogp.h"]
 
 HIPCC_FLAGS = [

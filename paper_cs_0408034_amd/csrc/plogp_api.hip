@@ -654,4 +654,54 @@ int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_gri
                         stage_ms_out);
 }
 
+static int robust_common(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                         uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree, void *stream,
+                         int reps, float *ms_out)
+{
+    if (!g || !d_cells || !d_agree || n_tables < 1 || n_tables > (1u << 24)) return PLOGP_EINVAL;
+    if (key_mode != PLOGP_KEY_STRATEGY && key_mode != PLOGP_KEY_STRATEGY_AND_SEGMENT) return PLOGP_EINVAL;
+    if (((uintptr_t)d_cells & 15u) != 0 || ((uintptr_t)d_agree & 3u) != 0 ||
+        ((uintptr_t)d_max_dev & 7u) != 0 || ((uintptr_t)d_table_agree & 3u) != 0)
+        return PLOGP_EINVAL;
+    const size_t cells = (size_t)g->n_ops * g->n_m * g->n_P;
+    // one thread per cell position (a launch dimension), counts in 32 bits
+    if (cells == 0 || cells > ((size_t)1 << 32) - 256) return PLOGP_ERANGE;
+    int rc = ensure_init();
+    if (rc != PLOGP_OK) return rc;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    hipError_t e = hipSuccess;
+    if (ms_out)
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+    if (e == hipSuccess)
+        e = launch_robustness(cells, (int)n_tables, reinterpret_cast<const plogp_cell_dev *>(d_cells),
+                              key_mode, d_agree, d_max_dev, d_table_agree, (hipStream_t)stream,
+                              ms_out ? ev : nullptr, reps);
+    if (ms_out) {
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+        for (int i = 0; i < 2; ++i)
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+        if (e == hipSuccess) *ms_out = ms / (float)reps;
+    }
+    if (e != hipSuccess) return device_error(e);
+    return PLOGP_OK;
+}
+
+int plogp_robustness(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
+                     uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree, void *stream)
+{
+    return robust_common(g, n_tables, d_cells, key_mode, d_agree, d_max_dev, d_table_agree, stream, 1,
+                         nullptr);
+}
+
+int plogp_robustness_profile(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells,
+                             int key_mode, uint32_t *d_agree, double *d_max_dev,
+                             uint32_t *d_table_agree, void *stream, int reps, float *ms_out)
+{
+    if (!ms_out || reps < 1 || reps > 10000) return PLOGP_EINVAL;
+    return robust_common(g, n_tables, d_cells, key_mode, d_agree, d_max_dev, d_table_agree, stream, reps,
+                         ms_out);
+}
+
 }  // extern "C"

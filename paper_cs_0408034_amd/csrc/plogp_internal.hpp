@@ -151,6 +151,13 @@ hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scrat
                         const double *d_meas, const uint32_t *d_seg, double *d_pred, void *d_verdict,
                         void *d_scores, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
 
+// Robustness summary of n_tables decision tables of `cells` records each (table 0 is the
+// reference).  d_max_dev and d_table_agree may be null.  ev: nullptr, or 2 events around
+// the work.  cells < 2^40 and n_tables >= 1 are the caller's to check.
+hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
+                             uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree,
+                             hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
 bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G);

@@ -80,6 +80,9 @@ def _load_library():
         "plogp_score_grid": (ctypes.c_int, [vp, sz, vp, vp, vp, vp, vp, vp, vp]),
         "plogp_score_grid_profile": (ctypes.c_int, [vp, sz, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int,
                                                     ctypes.POINTER(ctypes.c_float)]),
+        "plogp_robustness": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, vp, vp]),
+        "plogp_robustness_profile": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
+                                                    ctypes.POINTER(ctypes.c_float)]),
         "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "plogp_last_hip_error": (ctypes.c_int, []),
     }
@@ -264,3 +267,20 @@ def plogp_score_grid_profile(table: Table, table_index: int, grid: Grid, d_meas:
                                          d_pred, d_verdict, d_scores, stream, reps, ms),
            "plogp_score_grid_profile")
     return [float(v) for v in ms]
+
+
+def plogp_robustness(grid: Grid, n_tables: int, d_cells: int, key_mode: int, d_agree: int,
+                     d_max_dev: int = 0, d_table_agree: int = 0, stream: int = 0):
+    _check(_lib.plogp_robustness(grid._h, n_tables, d_cells, key_mode, d_agree, d_max_dev or None,
+                                 d_table_agree or None, stream), "plogp_robustness")
+
+
+def plogp_robustness_profile(grid: Grid, n_tables: int, d_cells: int, key_mode: int, d_agree: int,
+                             d_max_dev: int = 0, d_table_agree: int = 0, stream: int = 0,
+                             reps: int = 1) -> float:
+    """The work launched reps times between two events; mean ms per launch."""
+    ms = ctypes.c_float()
+    _check(_lib.plogp_robustness_profile(grid._h, n_tables, d_cells, key_mode, d_agree,
+                                         d_max_dev or None, d_table_agree or None, stream, reps,
+                                         ctypes.byref(ms)), "plogp_robustness_profile")
+    return float(ms.value)

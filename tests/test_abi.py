@@ -128,6 +128,8 @@ def test_null_handles_are_refused(plogp):
     assert lib.plogp_score_grid(None, 0, None, None, None, None, None, None, None) == plogp.EINVAL
     assert lib.plogp_score_grid_profile(None, 0, None, None, None, None, None, None, None, 1, None) == plogp.EINVAL
     assert lib.plogp_score_strategies(None) == 0
+    assert lib.plogp_robustness(None, 1, None, 0, None, None, None, None) == plogp.EINVAL
+    assert lib.plogp_robustness_profile(None, 1, None, 0, None, None, None, None, 1, None) == plogp.EINVAL
 
 
 def test_verdict_and_score_records(plogp):
