@@ -107,7 +107,7 @@ struct plogp_grid {
     void free_scratch()
     {
         double **all[] = {&scratch.g1, &scratch.gs, &scratch.gm, &scratch.sum2, &scratch.blk,
-                          &scratch.pre, &scratch.part, &scratch.rcp, &scratch.cx, &scratch.cys,
+                          &scratch.pre, &scratch.part, &scratch.rcp,
                           &scratch.segC, &scratch.segA, &scratch.segB, &scratch.amin};
         for (double **p : all) {
             if (*p) (void)hipFree(*p);
@@ -385,8 +385,6 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
         {&g->scratch.blk, chain ? n_tables * (size_t)g->n_blk * g->n_m : 1},
         {&g->scratch.part, chain ? n_tables * g->n_m * g->n_P : 1},
         {&g->scratch.rcp, g->n_s ? g->n_s : 1},
-        {&g->scratch.cx, chain ? n_tables * (n_samples + 3) : 1},
-        {&g->scratch.cys, chain ? n_tables * (n_samples + 2) * 2 : 1},
         {&g->scratch.pre, chain && g->n_blk > 32 ? n_tables * g->n_m * (size_t)g->n_blk : 1},
         {&g->scratch.segC, n_tables * (g->n_s ? g->n_s : 1)},
         {&g->scratch.segA, pairs ? n_tables * g->n_m * g->n_s : 1},

@@ -93,8 +93,6 @@ struct Scratch {
     double *pre;      // [n_tables][n_m][n_blk]           their exclusive prefix (more than 32 blocks only)
     double *part;     // [n_tables][n_m][n_P]             in-block partial sums at the grid's P
     double *rcp;      // [n_s]                            1/s, rounded
-    double *cx;       // [n_tables][n+3]                  table as intervals: starts (0, samples, inf, inf)
-    double *cys;      // [n_tables][n+2][2]               {gap, slope} per interval
     double *segC;     // [n_tables][n_s]                  C = g(s) + L
     double *segA;     // [n_tables][n_m][n_s]             A = g(s) ceil(m/s), +inf where s does not compete
     double *segB;     // [n_tables][n_m][n_s]             B = g(s) (ceil(m/s) - 1)   (both: n_s <= SWEEP_M_MAX_S only)

@@ -255,11 +255,11 @@ __device__ __forceinline__ double from_ordered_bits(unsigned long long k)
 // candidates that compete for m and the prefix sums over j of g(2^j m) for its
 // rows, g(s) for its candidates and (first table only) the reciprocals 1/s used
 // to get k = ceil(m/s) without a division per (m, s); chunk 0 also g(1).
-__global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks,
-                                               int with_pairs)
+__device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
+                                           int n_chunks, int with_pairs, int block_id, double *lds)
 {
-    extern __shared__ double lds[];
-    const int t = blockIdx.x / n_chunks, chunk = blockIdx.x % n_chunks;
+    const int t = block_id / n_chunks, chunk = block_id % n_chunks;
+    const int waves = (int)(blockDim.x >> 6);
     const int n = T.n;
     double *x = lds, *y = lds + n, *sl = lds + 2 * n;
     const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
@@ -271,26 +271,8 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const double v = interval_slope(x, y, n, i);
         sl[i] = v;
-        if (chunk == 0) {
+        if (chunk == 0)
             T.slope[(size_t)t * n + i] = v;
-            if (G.mask & (1u << 11)) {      // the table as intervals, for the chain-sum walk
-                S.cx[(size_t)t * (n + 3) + i + 1] = x[i];
-                double *ys = S.cys + ((size_t)t * (n + 2) + i + 1) * 2;
-                ys[0] = y[i];
-                ys[1] = v;
-            }
-        }
-    }
-    if (chunk == 0 && threadIdx.x == 0 && (G.mask & (1u << 11))) {
-        double *cx = S.cx + (size_t)t * (n + 3);
-        double *ys = S.cys + (size_t)t * (n + 2) * 2;
-        cx[0] = 0.0;
-        cx[n + 1] = INFINITY;
-        cx[n + 2] = INFINITY;
-        ys[0] = y[0];
-        ys[1] = 0.0;
-        ys[2 * (n + 1)] = 0.0;
-        ys[2 * (n + 1) + 1] = 0.0;
     }
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
@@ -309,7 +291,7 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
     // per message size: g(m), the number of candidates, the prefix of g(2^j m).  Groups
     // of 64 sizes are dealt to the waves of this table's workgroups.
     const int n_mw = (G.n_m + 63) / 64;
-    for (int mw = chunk * 4 + (int)(threadIdx.x >> 6); mw < n_mw; mw += n_chunks * 4) {
+    for (int mw = chunk * waves + (int)(threadIdx.x >> 6); mw < n_mw; mw += n_chunks * waves) {
         const int mi = mw * 64 + (int)(threadIdx.x & 63);
         if (mi >= G.n_m)
             continue;
@@ -394,6 +376,13 @@ __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scr
             __syncthreads();
         }
     }
+}
+
+__global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks,
+                                               int with_pairs)
+{
+    extern __shared__ double lds[];
+    terms_body(T, G, S, n_chunks, with_pairs, (int)blockIdx.x, lds);
 }
 
 // ---------------------------------------------------------------- tune, step 2: Scatter-chain sum
@@ -638,27 +627,31 @@ __device__ __forceinline__ void chain_search_block(const ChainCtx &C, int b, u64
 // sizes cross an interval.
 constexpr int CHAIN_U = 4;           // blocks walked side by side by a lane in the sparse part
 
-__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
-                               int n_single, int n_search)
+__device__ __forceinline__ void chain_body(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
+                                           int wg_per_table, int n_single, int n_search, int block_id,
+                                           double *chain_lds)
 {
-    extern __shared__ __align__(16) double chain_lds[];
     __shared__ unsigned next_item;
-    const int t = blockIdx.x / wg_per_table, wg = blockIdx.x % wg_per_table;
+    const int t = block_id / wg_per_table, wg = block_id % wg_per_table;
     const int n = T.n;
-    // the table as intervals (written by k_terms): cys[0..n+1] = {gap, slope}, cx[0..n+2] =
-    // interval starts (0, the samples, +inf, +inf)
+    // the table as intervals, built from the raw samples (the slopes are those of the
+    // tuning's first step: the same expression): YS[0..n+1] = {gap, slope}, X[0..n+5] =
+    // interval starts (0, the samples, +inf ...), W = widths
     f64x2 *YS = reinterpret_cast<f64x2 *>(chain_lds);              // n + 2 entries
     double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries, +inf from n + 1 on
     double *W = X + (n + 6);                                       // n + 2 entries
     {
-        const f64x2 *gys = reinterpret_cast<const f64x2 *>(S.cys) + (size_t)t * (n + 2);
-        const double *gx = S.cx + (size_t)t * (n + 3);
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
         for (int i = threadIdx.x; i < n + 6; i += blockDim.x) {
-            const double x0 = i < n + 1 ? gx[i] : INFINITY;
+            // interval i starts at sample i - 1; interval 0 is the clamp below the first sample
+            const double x0 = i == 0 ? 0.0 : i <= n ? gx[i - 1] : INFINITY;
             X[i] = x0;
             if (i < n + 2) {
-                YS[i] = gys[i];
-                W[i] = i < n ? gx[i + 1] - x0 : INFINITY;
+                f64x2 ys;
+                ys.x = i == 0 ? gy[0] : i <= n ? gy[i - 1] : 0.0;
+                ys.y = (i == 0 || i > n) ? 0.0 : interval_slope(gx, gy, n, i - 1);
+                YS[i] = ys;
+                W[i] = i < n ? gx[i] - x0 : INFINITY;
             }
         }
         if (threadIdx.x == 0)
@@ -705,6 +698,28 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
         else
             chain_walk<1>(C, u, m, part, tot);
     }
+}
+
+__global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
+                               int n_single, int n_search)
+{
+    extern __shared__ __align__(16) double chain_lds[];
+    chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, chain_lds);
+}
+
+// Both first steps in one launch: they do not depend on each other (each stages the
+// table from the raw samples), so the workgroups of the chain sums (the longer job, first
+// in the grid) and those of the terms run side by side.  For tables small enough that
+// workgroups of both kinds share a CU.
+__global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid G, Scratch S, int n_chain_wg,
+                                                     int wg_per_table, int n_single, int n_search,
+                                                     int n_chunks, int with_pairs)
+{
+    extern __shared__ __align__(16) double both_lds[];
+    if ((int)blockIdx.x < n_chain_wg)
+        chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, both_lds);
+    else
+        terms_body(T, G, S, n_chunks, with_pairs, (int)blockIdx.x - n_chain_wg, both_lds);
 }
 
 // Turns the block totals of PFX_M message sizes into their exclusive prefix in
@@ -2568,6 +2583,9 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_chain_blocks),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChainLds);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_terms_chain),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+    if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
@@ -2711,18 +2729,23 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
-    for (int r = 0; r < reps; ++r)
-        hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256),
-                           tab_lds + (lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0), st, T, G, S,
-                           n_chunks, lanes_p ? 1 : 0);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t terms_lds = tab_lds + (lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0);
+    const bool chain = (G.mask & (1u << 11)) != 0;
+    // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
+    // stays for its whole share of the work (the table is staged once)
+    const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
+    const bool big = chain_lds > 32768;
+    // small tables: the terms and the chain sums in one launch, side by side
+    const bool together = chain && !big;
+    if (!together) {
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), terms_lds, st, T,
+                               G, S, n_chunks, lanes_p ? 1 : 0);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     PLOGP_MARK(1);
 
-    if (G.mask & (1u << 11)) {
-        // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
-        // stays for its whole share of the work (the table is staged once)
-        const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
-        const bool big = chain_lds > 32768;
+    if (chain) {
         const int threads = big ? 1024 : 256;
         const int n_mg = (G.n_mu + 63) / 64;
         // leading blocks that are items of their own: the dense part of a table with many
@@ -2737,9 +2760,16 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)(T.n_tables * wg)), dim3(threads),
-                               chain_lds, st, T, G, S, (int)wg, n_single, n_search);
+        const int n_chain_wg = (int)(T.n_tables * wg);
+        for (int r = 0; r < reps; ++r) {
+            if (together)
+                hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)(n_chain_wg + T.n_tables * n_chunks)),
+                                   dim3(256), chain_lds > terms_lds ? chain_lds : terms_lds, st, T, G, S,
+                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, lanes_p ? 1 : 0);
+            else
+                hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
+                                   T, G, S, (int)wg, n_single, n_search);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
         if (G.blk_is_prefix) {
