@@ -700,6 +700,93 @@ __device__ __forceinline__ void chain_body(const DeviceTables &T, const DeviceGr
     }
 }
 
+// The same sums for a small job (few samples, about a million terms or fewer), where the
+// walk above is bound by the latency of one lane's 64 dependent steps and the chip is
+// nearly idle: a workgroup takes one (block, 64 sizes) item at a time; its four waves
+// evaluate the 64 x 64 terms side by side, each by a search of its own (the same
+// expression, so the same gaps), into LDS; one wave then adds the terms of each size in
+// order, leaving the sum before every term in place; all waves write the wanted partial
+// sums, a row of the output per store.
+constexpr int SMALL_LD = 65;          // row stride of the 64 x 64 tile of terms
+
+__device__ __forceinline__ void chain_small_body(const DeviceTables &T, const DeviceGrid &G,
+                                                 const Scratch &S, int wg_per_table, int block_id,
+                                                 double *chain_lds)
+{
+    const int t = block_id / wg_per_table, wg = block_id % wg_per_table;
+    const int n = T.n;
+    f64x2 *YS = reinterpret_cast<f64x2 *>(chain_lds);              // n + 2 entries
+    double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries
+    double *gl = X + (n + 6);                                      // 64 rows of SMALL_LD
+    {
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
+        for (int i = threadIdx.x; i < n + 6; i += blockDim.x) {
+            X[i] = i == 0 ? 0.0 : i <= n ? gx[i - 1] : INFINITY;
+            if (i < n + 2) {
+                f64x2 ys;
+                ys.x = i == 0 ? gy[0] : i <= n ? gy[i - 1] : 0.0;
+                ys.y = (i == 0 || i > n) ? 0.0 : interval_slope(gx, gy, n, i - 1);
+                YS[i] = ys;
+            }
+        }
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = (int)(threadIdx.x >> 6);
+    const int n_mu = G.n_mu;
+    const int n_mg = (n_mu + 63) / 64;
+    const int n_items = G.n_blk * n_mg;
+    for (int item = wg; item < n_items; item += wg_per_table) {
+        const int b = item / n_mg, mg = item % n_mg;
+        const int mi = mg * 64 + lane;
+        const u64 m = G.mu[mi < n_mu ? mi : n_mu - 1];
+        const u64 j0 = (u64)b * SUM_BLOCK + 1 + (u64)wave * 16;     // this wave's 16 terms
+#pragma unroll
+        for (int r0 = 0; r0 < 16; r0 += 4) {
+            double z[4];
+            int i[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                z[c] = (double)((j0 + r0 + c) * m);
+            chain_locate<4>(X, n, z, i);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const f64x2 ys = YS[i[c]];
+                gl[(wave * 16 + r0 + c) * SMALL_LD + lane] = __builtin_fma(ys.y, z[c] - X[i[c]], ys.x);
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            double run = 0.0;
+            for (int r0 = 0; r0 < SUM_BLOCK; r0 += 8) {
+                double g[8];
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    g[c] = gl[(r0 + c) * SMALL_LD + lane];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    gl[(r0 + c) * SMALL_LD + lane] = run;          // the sum before term r0 + c
+                    run = run + g[c];
+                }
+            }
+            if (mi < n_mu && b < G.n_blk - 1)
+                S.blk[((size_t)t * G.n_blk + b) * n_mu + mi] = run;
+        }
+        __syncthreads();
+        {
+            // lane r holds term r's place: bit r of the mask = the sum before term r is wanted
+            const u64 wanted = G.blk_mask[b];
+            const bool want = ((wanted >> lane) & 1ull) != 0;
+            const int at = G.blk_off[b] + __popcll(wanted & ((1ull << lane) - 1ull));
+            for (int row = wave; row < 64; row += 4) {
+                const int mrow = mg * 64 + row;
+                if (mrow < n_mu && want)
+                    S.part[((size_t)t * n_mu + mrow) * G.n_P + at] = gl[lane * SMALL_LD + row];
+            }
+        }
+        __syncthreads();
+    }
+}
+
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
                                int n_single, int n_search)
 {
@@ -716,9 +803,12 @@ __global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid 
                                                      int n_chunks, int with_pairs)
 {
     extern __shared__ __align__(16) double both_lds[];
-    if ((int)blockIdx.x < n_chain_wg)
-        chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, both_lds);
-    else
+    if ((int)blockIdx.x < n_chain_wg) {
+        if (n_single < 0)                 // a small job: terms by search, side by side
+            chain_small_body(T, G, S, wg_per_table, (int)blockIdx.x, both_lds);
+        else
+            chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, both_lds);
+    } else
         terms_body(T, G, S, n_chunks, with_pairs, (int)blockIdx.x - n_chain_wg, both_lds);
 }
 
@@ -2760,11 +2850,23 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
+        // a small job (the walk would be bound by one lane's latency): every term by a search
+        const long n_terms = (long)T.n_tables * G.n_mu * G.n_blk * SUM_BLOCK;
+        const bool small = together && n_single == G.n_blk && n_terms <= (3L << 20);
+        size_t both_lds = chain_lds > terms_lds ? chain_lds : terms_lds;
+        if (small) {
+            const size_t small_lds = ((size_t)3 * T.n + 10 + 64 * SMALL_LD) * sizeof(double);
+            if (small_lds > both_lds) both_lds = small_lds;
+            n_single = -1;
+            wg = (long)n_mg * G.n_blk;
+            if (wg > 512 / T.n_tables) wg = 512 / T.n_tables;
+            if (wg < 1) wg = 1;
+        }
         const int n_chain_wg = (int)(T.n_tables * wg);
         for (int r = 0; r < reps; ++r) {
             if (together)
                 hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)(n_chain_wg + T.n_tables * n_chunks)),
-                                   dim3(256), chain_lds > terms_lds ? chain_lds : terms_lds, st, T, G, S,
+                                   dim3(256), both_lds, st, T, G, S,
                                    n_chain_wg, (int)wg, n_single, n_search, n_chunks, lanes_p ? 1 : 0);
             else
                 hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
