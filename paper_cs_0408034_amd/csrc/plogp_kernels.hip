@@ -278,12 +278,18 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
     const LdsTable tab = {x, y, sl, n};
     // for the sweep that runs its lanes over P: g(s) and 1/s of every candidate, for this
     // workgroup's own use below
+    const bool pairs = (with_pairs & 1) != 0, stage_s = (with_pairs & 2) != 0;
     double *gs_l = lds + 3 * n, *rcp_l = gs_l + G.n_s;
-    if (with_pairs) {
+    double *sd_l = lds + 3 * n + (pairs ? 2 * G.n_s : 0);      // the candidates (exact as doubles)
+    if (pairs || stage_s) {
         for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
             const double sd = (double)G.s[si];
-            gs_l[si] = gap_at(tab, sd);
-            rcp_l[si] = 1.0 / sd;
+            if (pairs) {
+                gs_l[si] = gap_at(tab, sd);
+                rcp_l[si] = 1.0 / sd;
+            }
+            if (stage_s)
+                sd_l[si] = sd;
         }
         __syncthreads();
     }
@@ -300,9 +306,17 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
         {                              // candidates s <= min(m, s_cap): the list ascends
             const u64 lim = m < G.s_cap ? m : G.s_cap;
             int lo = 0, hi = G.n_s;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
+            if (stage_s) {             // from LDS: a step is not a round trip to memory
+                const double limd = (double)lim;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (sd_l[mid] <= limd) lo = mid + 1; else hi = mid;
+                }
+            } else {
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (G.s[mid] <= lim) lo = mid + 1; else hi = mid;
+                }
             }
             if (t == 0)
                 S.nv[mi] = lo;
@@ -346,7 +360,7 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
     // over the candidates (rows 2 and 9 of Table 1 are monotone in A).  A chunk takes whole
     // rows of (m, s) pairs, TERMS_ROWS at a time, and forms the minima in LDS on an
     // order-preserving integer image of the doubles.
-    if (with_pairs) {
+    if (pairs) {
         __shared__ unsigned long long amin_l[TERMS_ROWS];
         const int rows = (G.n_m + n_chunks - 1) / n_chunks;        // rows of a chunk
         for (int r0 = chunk * rows; r0 < (chunk + 1) * rows && r0 < G.n_m; r0 += TERMS_ROWS) {
@@ -1305,30 +1319,44 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     // row of the chain sums (kept per distinct size) of the size fetched next: read one size
     // earlier still, so that the fetch does not wait for it
     int um_next = chain && has_work ? G.m_map[w] : 0;
+    // the sizes of a wave lie n_w apart: the rows of the per-size arrays are reached by adding
+    // a stride to running pointers (no multiplications per size); the chain sums are kept per
+    // distinct size and go through the row map
+    const double *p_gm = S.gm + (size_t)t * n_m + w;
+    const double *p_amin = S.amin + (size_t)t * n_m + w;
+    const int *p_nv = S.nv + w;
+    const double *p_B = S.segB + ((size_t)t * n_m + w) * n_s + lane;
+    const double *p_s12 = S.sum2 + ((size_t)t * n_m + w) * (G.cl_max + 1) + cli;
+    const size_t stride_B = (size_t)n_w * n_s, stride_s12 = (size_t)n_w * (G.cl_max + 1);
+    const double *const part_t = S.part + (size_t)t * G.n_mu * n_P + (active ? pi : n_P - 1);
+    const double *const pre_t = S.pre + (size_t)t * G.n_mu * n_blk + blk;
+    const double *const blk_t = S.blk + ((size_t)t * n_blk + lane) * G.n_mu;
     auto fetch = [&](int mi) {
-        const size_t row = (size_t)t * n_m + mi;
-        f_gm = S.gm[row];
-        f_nv = S.nv[mi];
+        f_gm = *p_gm;
+        f_nv = *p_nv;
+        p_gm += n_w;
+        p_nv += n_w;
         if (seg) {
-            f_amin = S.amin[row];
+            f_amin = *p_amin;
+            p_amin += n_w;
 #pragma unroll
-            for (int k = 0; k < NSV; ++k) {
-                const int si = lane + 64 * k;
-                fB[k] = si < n_s ? S.segB[row * n_s + si] : INFINITY;
-            }
+            for (int k = 0; k < NSV; ++k)
+                fB[k] = lane + 64 * k < n_s ? p_B[64 * k] : INFINITY;
+            p_B += stride_B;
         }
         if (chain) {
-            const int um = um_next;
+            const uint32_t um = (uint32_t)um_next;
             um_next = G.m_map[mi + n_w < (int)n_m ? mi + n_w : mi];
-            const size_t urow = (size_t)t * G.n_mu + um;
-            f_part = S.part[urow * n_P + (active ? pi : n_P - 1)];
+            f_part = part_t[(u64)um * (uint32_t)n_P];
             if (G.blk_is_prefix)
-                f_done = S.pre[urow * n_blk + blk];
+                f_done = pre_t[(u64)um * (uint32_t)n_blk];
             else                       // few blocks: lane b holds the total of block b
-                f_done = lane < n_blk - 1 ? S.blk[((size_t)t * n_blk + lane) * G.n_mu + um] : 0.0;
+                f_done = lane < n_blk - 1 ? blk_t[um] : 0.0;
         }
-        if (binom)
-            f_s12 = S.sum2[row * (G.cl_max + 1) + cli];
+        if (binom) {
+            f_s12 = *p_s12;
+            p_s12 += stride_s12;
+        }
     };
     // the first size's inputs are on their way while the candidates go to LDS
     if (has_work)
@@ -1383,25 +1411,29 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                 batch5 = cur < b5 ? s0 : batch5;
                 b5 = min_f64(b5, cur);
             }
-            if (__ballot(b5 < INFINITY) != 0) {
-                // lanes differ in their batch: per-lane LDS reads of the eight candidates
-                bool open = true;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const double T5 = __builtin_fma(q, sC[batch5 + u], rowB[wave][batch5 + u]);
-                    const bool hit = open && T5 == b5;
-                    i5 = hit ? batch5 + u : i5;
-                    open = open && !hit;
-                }
-            }
+            i5 = batch5;
         }
-        const uint32_t s5 = b5 < INFINITY ? sSv[i5] : 0u;
 
         plogp_cell_dev *o = obase + (size_t)mi * n_P;
         if (mask & 0x3FFu) {
             const double t2 = amin < INFINITY ? __builtin_fma(q, amin, L) : INFINITY;
             const double t9 = amin < INFINITY ? __builtin_fma(fl, amin, clL) : INFINITY;
-            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, s5, t9, 0u);
+            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, 0u, t9, 0u);
+            // a winning row 5: the first candidate of the remembered batch that attains the
+            // minimum (lanes differ in their batch: per-lane LDS reads of its eight candidates)
+            if (__ballot(active && bc.id == 5u) != 0) {
+                bool open5 = true;
+                int at5 = i5;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const double T5 = __builtin_fma(q, sC[i5 + u], rowB[wave][i5 + u]);
+                    const bool hit = open5 && T5 == b5;
+                    at5 = hit ? i5 + u : at5;
+                    open5 = open5 && !hit;
+                }
+                if (bc.id == 5u)
+                    bc.s = sSv[at5];
+            }
             // a winning row 2 or 9: the first candidate whose value equals the minimum
             bool open = active && (bc.id == 2u || bc.id == 9u);
             if (__ballot(open) != 0) {
@@ -2813,13 +2845,17 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (lanes_p && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
     long n_chunks_l = (n_items + 255) / 256;
+    // the candidates go to LDS too (for the count per m) if they fit beside the table
+    const size_t pair_lds = lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0;
+    const bool stage_s = G.n_s > 0 && tab_lds + pair_lds + (size_t)G.n_s * sizeof(double) <= kMaxTableLds;
+    const int terms_mode = (lanes_p ? 1 : 0) | (stage_s ? 2 : 0);
+    const size_t terms_lds = tab_lds + pair_lds + (stage_s ? (size_t)G.n_s * sizeof(double) : 0);
     // a workgroup stages the whole table: with a big table one workgroup fits a CU, so no
     // more workgroups than CUs
-    const long wg_cap = tab_lds > 65536 ? 256 : 512;
+    const long wg_cap = terms_lds > 65536 ? 256 : 512;
     const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
-    const size_t terms_lds = tab_lds + (lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0);
     const bool chain = (G.mask & (1u << 11)) != 0;
     // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
     // stays for its whole share of the work (the table is staged once)
@@ -2830,7 +2866,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (!together) {
         for (int r = 0; r < reps; ++r)
             hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), terms_lds, st, T,
-                               G, S, n_chunks, lanes_p ? 1 : 0);
+                               G, S, n_chunks, terms_mode);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     PLOGP_MARK(1);
@@ -2867,7 +2903,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             if (together)
                 hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)(n_chain_wg + T.n_tables * n_chunks)),
                                    dim3(256), both_lds, st, T, G, S,
-                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, lanes_p ? 1 : 0);
+                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, terms_mode);
             else
                 hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
                                    T, G, S, (int)wg, n_single, n_search);
@@ -2911,7 +2947,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             // as many waves as the chip holds at four per SIMD, shared out over the tables and
             // the groups of 64 process counts; each walks over every n_w-th message size
             const int n_pg = (G.n_P + 63) / 64;
-            long n_w = 4096 / ((long)T.n_tables * n_pg);
+            long n_w = 8192 / ((long)T.n_tables * n_pg);
             if (n_w > G.n_m) n_w = G.n_m;
             if (n_w < 1) n_w = 1;
             n_w = (n_w + 3) / 4 * 4;
