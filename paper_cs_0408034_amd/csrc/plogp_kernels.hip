@@ -1274,7 +1274,7 @@ __device__ __forceinline__ double wave_min(double v)
 // NSV: candidates per lane when a row of (m, s) terms is moved (n_s <= 64 NSV).
 template <int NSV, bool ALL>
 __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, Scratch S,
-                                                 plogp_cell_dev *out, int n_pg, int n_w)
+                                                 plogp_cell_dev *out, int t0, int n_w)
 {
     // the loops below read up to 7 entries past the last candidate: rows are 8 longer
     constexpr int ROW = 64 * NSV + 8;
@@ -1283,12 +1283,8 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     __shared__ double rowB[4][ROW];                  // B of the current size (+inf past the end)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    int bid = blockIdx.x;
-    const int n_wq = (n_w + 3) / 4;
-    const int wq = bid % n_wq;
-    bid /= n_wq;
-    const int pg = bid % n_pg;
-    const int t = bid / n_pg;
+    // grid: x = group of four waves, y = group of 64 process counts, z = table (from t0)
+    const int wq = (int)blockIdx.x, pg = (int)blockIdx.y, t = t0 + (int)blockIdx.z;
     const int w = wq * 4 + wave;
     const bool has_work = w < n_w && w < G.n_m;
     const uint32_t mask = ALL ? 0x1FFFu : G.mask;      // ALL: every strategy competes
@@ -2840,7 +2836,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     // which sweep runs: lanes over s for many candidates, else lanes over P if the grid
     // has enough process counts to fill a wave, else lanes over m
     const bool lanes_s = G.n_s > SWEEP_M_MAX_S;
-    const bool lanes_p = !terms_only && !lanes_s && G.n_P >= 32;
+    const bool lanes_p = !terms_only && !lanes_s && G.n_P >= 32 && G.n_P <= 65535 * 64;   // grid.y
     long n_items = G.n_m > G.n_s ? G.n_m : G.n_s;          // a lane takes one m and one s ...
     if (lanes_p && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
@@ -2951,17 +2947,20 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             if (n_w > G.n_m) n_w = G.n_m;
             if (n_w < 1) n_w = 1;
             n_w = (n_w + 3) / 4 * 4;
-            const unsigned blocks = (unsigned)(T.n_tables * (long)n_pg * (n_w / 4));
             const bool all = G.mask == 0x1FFFu;
-            if (G.n_s <= 64 && all)
-                hipLaunchKernelGGL((k_sweep_p<1, true>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
-                                   n_pg, (int)n_w);
-            else if (G.n_s <= 64)
-                hipLaunchKernelGGL((k_sweep_p<1, false>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
-                                   n_pg, (int)n_w);
-            else
-                hipLaunchKernelGGL((k_sweep_p<4, false>), dim3(blocks), dim3(256), 0, st, T, G, S, d_out,
-                                   n_pg, (int)n_w);
+            for (int t0 = 0; t0 < T.n_tables; t0 += 65535) {
+                const int nt = T.n_tables - t0 < 65535 ? T.n_tables - t0 : 65535;
+                const dim3 blocks((unsigned)(n_w / 4), (unsigned)n_pg, (unsigned)nt);
+                if (G.n_s <= 64 && all)
+                    hipLaunchKernelGGL((k_sweep_p<1, true>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                                       (int)n_w);
+                else if (G.n_s <= 64)
+                    hipLaunchKernelGGL((k_sweep_p<1, false>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                                       (int)n_w);
+                else
+                    hipLaunchKernelGGL((k_sweep_p<4, false>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                                       (int)n_w);
+            }
         } else {
             constexpr int PC = 4;
             const int n_mg = (G.n_m + 63) / 64;
