@@ -65,20 +65,29 @@ def describe(wl):
 # FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
 # kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
 MEASURED_TRAFFIC = {
-    2: {"terms": 0.139e6 + 0.662e6, "chain_blocks": 0.156e6 + 7.484e6, "sweep": 8.706e6 + 33.548e6},
-    3: {"terms": 0.178e6 + 0.318e6, "chain_blocks": 0.127e6 + 1.122e6,
-        "chain_prefix": 0.576e6 + 0.524e6, "sweep": 3.699e6 + 2.294e6},
-    4: {"terms": 87.398e6 + 10.560e6 + 0.140e6 + 0.176e6, "sweep": 86.162e6 + 2002.824e6},
-    5: {"terms": 0.761e6 + 3.491e6, "chain_blocks": 1.427e6 + 71.282e6,
-        "chain_prefix": 50.915e6 + 26.337e6, "sweep": 68.478e6 + 93.321e6},
+    2: {"chain_blocks": 0.239e6 + 7.688e6, "sweep": 8.595e6 + 33.633e6},
+    3: {"chain_blocks": 0.753e6 + 1.438e6, "chain_prefix": 0.576e6 + 0.524e6, "sweep": 3.682e6 + 2.294e6},
+    4: {"terms": 88.252e6 + 10.560e6 + 0.146e6 + 0.176e6, "sweep": 86.178e6 + 2004.747e6},
+    5: {"terms": 0.671e6 + 1.986e6, "chain_blocks": 1.181e6 + 71.299e6,
+        "chain_prefix": 50.916e6 + 26.337e6, "sweep": 79.698e6 + 93.323e6},
 }
 # the same for the three kernels of the cut-over extraction (mark, scan1 + scan2, emit)
 MEASURED_CUT_TRAFFIC = {
-    2: 34.230e6 + 2.095e6 + 0.563e6 + 0.526e6 + 0.006e6 + 0.001e6 + 9.287e6 + 0.486e6,
+    2: 34.219e6 + 2.095e6 + 0.563e6 + 0.526e6 + 0.006e6 + 0.001e6 + 9.287e6 + 0.486e6,
     3: 2.382e6 + 0.141e6 + 0.060e6 + 0.035e6 + 0.006e6 + 1.725e6 + 0.982e6,
-    4: 1993.065e6 + 61.707e6 + 30.755e6 + 30.840e6 + 0.035e6 + 0.030e6 + 297.978e6 + 52.551e6,
-    5: 96.891e6 + 5.867e6 + 1.497e6 + 1.464e6 + 0.007e6 + 0.001e6 + 26.707e6 + 0.865e6,
+    4: 1993.133e6 + 61.704e6 + 30.754e6 + 30.840e6 + 0.035e6 + 0.030e6 + 297.974e6 + 52.548e6,
+    5: 96.910e6 + 5.859e6 + 1.497e6 + 1.464e6 + 0.007e6 + 0.001e6 + 26.708e6 + 0.865e6,
 }
+# the scoring kernels (k_score, k_score_rows, k_score_final) and the robustness summary
+# (k_robust_clear, k_robust; its per-table counts are one atomic per wave and table, which the
+# write counter sees as 86 MB)
+MEASURED_SCORE_TRAFFIC = {
+    2: 139.182e6 + 144.107e6 + 221.466e6 + 0.213e6 + 0.256e6,
+    3: 11.925e6 + 9.961e6 + 14.767e6 + 0.213e6 + 0.256e6,
+    4: 1.516e6 + 0.836e6 + 1.350e6 + 0.053e6 + 0.096e6,
+    5: 401.050e6 + 400.357e6 + 623.124e6 + 0.852e6 + 0.895e6,
+}
+MEASURED_ROBUST_TRAFFIC = {4: 0.021e6 + 0.187e6 + 1967.171e6 + 86.391e6}
 
 
 def roofline_of(stage, work, ms, traffic=None):
@@ -136,9 +145,14 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     if cut is not None and wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16:
         cut["roofline"]["traffic"] = MEASURED_CUT_TRAFFIC.get(int(wl.name[3:]))
     score = run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps) if with_cut else None
+    full = wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16
+    if score is not None and full and wl.strategy_mask == 0x1FFF:
+        score["roofline"]["traffic"] = MEASURED_SCORE_TRAFFIC.get(int(wl.name[3:]))
     if score is not None and tab.count > 1:
         score["robustness"] = run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps,
                                              profile_reps)
+        if full:
+            score["robustness"]["roofline"]["traffic"] = MEASURED_ROBUST_TRAFFIC.get(int(wl.name[3:]))
     del out
     grid.free()
     tab.free()

@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
     const u64 base_key = key_of(base, R.strict);
     const double base_time = base.x;
     uint32_t cnt = 0;
-    double worst = 0.0;
+    double worst = 0.0;               // largest abs(T_t - T_0) of this slice (a NaN is skipped)
     const f64x2_t *p = cells + (u64)t0 * R.cells + cc;
     int t = t0;
     constexpr int U = 8;                              // records of eight tables in flight
@@ -73,7 +73,7 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
         for (int u = 0; u < U; ++u) {
             const bool same = live && key_of(r[u], R.strict) == base_key;
             cnt += same ? 1u : 0u;
-            const double dev = fabs(r[u].x - base_time) / base_time;
+            const double dev = fabs(r[u].x - base_time);
             worst = dev > worst ? dev : worst;
             if (PER_TABLE) {
                 const u64 votes = __ballot(same);
@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
         p += R.cells;
         const bool same = live && key_of(r, R.strict) == base_key;
         cnt += same ? 1u : 0u;
-        const double dev = fabs(r.x - base_time) / base_time;
+        const double dev = fabs(r.x - base_time);
         worst = dev > worst ? dev : worst;
         if (PER_TABLE) {
             const u64 votes = __ballot(same);
@@ -98,8 +98,11 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
     if (live) {
         if (cnt)
             atomicAdd(agree + c, cnt);
-        if (max_dev && worst > 0.0)
-            atomicMax(max_dev + c, (u64)__double_as_longlong(worst));
+        // the quotient is monotone in the difference (the divisor is the same for every
+        // table), so the largest quotient is the quotient of the largest difference
+        const double top = worst / base_time;
+        if (max_dev && top > 0.0)
+            atomicMax(max_dev + c, (u64)__double_as_longlong(top));
     }
 }
 
