@@ -1272,7 +1272,7 @@ __device__ __forceinline__ double wave_min(double v)
 // n_w apart, so every wave meets the same mix of short and long candidate lists;
 // the loads for the next size are issued before the current one is worked on.
 // NSV: candidates per lane when a row of (m, s) terms is moved (n_s <= 64 NSV).
-template <int NSV, bool ALL>
+template <int NSV, bool ALL, int PPL>
 __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, Scratch S,
                                                  plogp_cell_dev *out, int t0, int n_w)
 {
@@ -1283,35 +1283,48 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     __shared__ double rowB[4][ROW];                  // B of the current size (+inf past the end)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // grid: x = group of four waves, y = group of 64 process counts, z = table (from t0)
+    // grid: x = group of four waves, y = group of 64 PPL process counts, z = table (from t0)
     const int wq = (int)blockIdx.x, pg = (int)blockIdx.y, t = t0 + (int)blockIdx.z;
     const int w = wq * 4 + wave;
     const bool has_work = w < n_w && w < G.n_m;
     const uint32_t mask = ALL ? 0x1FFFu : G.mask;      // ALL: every strategy competes
     const int n_P = G.n_P, n_s = G.n_s, n_blk = G.n_blk;
     const size_t n_m = (size_t)G.n_m;
-    const int pi = pg * 64 + lane;
-    const bool active = pi < n_P;
-    const uint32_t Pv = G.P[active ? pi : n_P - 1];
-    const double q = (double)(Pv - 1u);
-    const int cli = ceil_log2(Pv);
-    const double fl = (double)floor_log2(Pv), cl = (double)cli;
-    const int blk = (int)((Pv - 1u) / SUM_BLOCK);
     const double L = T.L[t];
-    const double clL = cl * L;
     const double g1 = S.g1[t];
     const bool chain = (mask & (1u << 11)) != 0, binom = (mask & (1u << 12)) != 0;
     const bool seg = (mask & 0x224u) != 0 && n_s > 0;
-    // the largest block index among the lanes (the P of the grid ascend)
-    const int last_lane = (n_P - pg * 64 < 64 ? n_P - pg * 64 : 64) - 1;
-    const int bmax = __builtin_amdgcn_readlane(blk, last_lane);
-    const int bmin = __builtin_amdgcn_readfirstlane(blk);
     const size_t plane = n_m * n_P;
-    plogp_cell_dev *const obase = out + (size_t)t * G.n_ops * plane + pi;
+    // a lane takes PPL process counts, 64 apart (so that every store of a wave is one run)
+    int pi[PPL], cli[PPL], blk[PPL], bmin[PPL], bmax[PPL];
+    bool active[PPL];
+    double q[PPL], fl[PPL], cl[PPL], clL[PPL];
+#pragma unroll
+    for (int h = 0; h < PPL; ++h) {
+        const int base = (pg * PPL + h) * 64;
+        pi[h] = base + lane;
+        active[h] = pi[h] < n_P;
+        const uint32_t Pv = G.P[active[h] ? pi[h] : n_P - 1];
+        q[h] = (double)(Pv - 1u);
+        cli[h] = ceil_log2(Pv);
+        fl[h] = (double)floor_log2(Pv);
+        cl[h] = (double)cli[h];
+        clL[h] = cl[h] * L;
+        blk[h] = (int)((Pv - 1u) / SUM_BLOCK);
+        // the smallest and the largest block index among the lanes (the P of the grid ascend;
+        // an empty half repeats the last P of the grid)
+        const int here = n_P - base < 64 ? n_P - base : 64;
+        bmin[h] = __builtin_amdgcn_readfirstlane(blk[h]);
+        bmax[h] = __builtin_amdgcn_readlane(blk[h], here > 0 ? here - 1 : 0);
+    }
+    plogp_cell_dev *const obase = out + (size_t)t * G.n_ops * plane + pi[0];
 
     // what is fetched one size ahead
-    double fB[NSV], f_part = 0.0, f_s12 = 0.0, f_done = 0.0, f_gm, f_amin = INFINITY;
+    double fB[NSV], f_part[PPL], f_s12[PPL], f_done[PPL], f_gm, f_amin = INFINITY;
     int f_nv;
+#pragma unroll
+    for (int h = 0; h < PPL; ++h)
+        f_part[h] = f_s12[h] = f_done[h] = 0.0;
     // row of the chain sums (kept per distinct size) of the size fetched next: read one size
     // earlier still, so that the fetch does not wait for it
     int um_next = chain && has_work ? G.m_map[w] : 0;
@@ -1322,10 +1335,10 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     const double *p_amin = S.amin + (size_t)t * n_m + w;
     const int *p_nv = S.nv + w;
     const double *p_B = S.segB + ((size_t)t * n_m + w) * n_s + lane;
-    const double *p_s12 = S.sum2 + ((size_t)t * n_m + w) * (G.cl_max + 1) + cli;
+    const double *p_s12 = S.sum2 + ((size_t)t * n_m + w) * (G.cl_max + 1);
     const size_t stride_B = (size_t)n_w * n_s, stride_s12 = (size_t)n_w * (G.cl_max + 1);
-    const double *const part_t = S.part + (size_t)t * G.n_mu * n_P + (active ? pi : n_P - 1);
-    const double *const pre_t = S.pre + (size_t)t * G.n_mu * n_blk + blk;
+    const double *const part_t = S.part + (size_t)t * G.n_mu * n_P;
+    const double *const pre_t = S.pre + (size_t)t * G.n_mu * n_blk;
     const double *const blk_t = S.blk + ((size_t)t * n_blk + lane) * G.n_mu;
     auto fetch = [&](int mi) {
         f_gm = *p_gm;
@@ -1343,14 +1356,23 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         if (chain) {
             const uint32_t um = (uint32_t)um_next;
             um_next = G.m_map[mi + n_w < (int)n_m ? mi + n_w : mi];
-            f_part = part_t[(u64)um * (uint32_t)n_P];
-            if (G.blk_is_prefix)
-                f_done = pre_t[(u64)um * (uint32_t)n_blk];
-            else                       // few blocks: lane b holds the total of block b
-                f_done = lane < n_blk - 1 ? blk_t[um] : 0.0;
+            const double *row = part_t + (u64)um * (uint32_t)n_P;
+#pragma unroll
+            for (int h = 0; h < PPL; ++h)
+                f_part[h] = row[active[h] ? pi[h] : n_P - 1];
+            if (G.blk_is_prefix) {
+                const double *prow = pre_t + (u64)um * (uint32_t)n_blk;
+#pragma unroll
+                for (int h = 0; h < PPL; ++h)
+                    f_done[h] = prow[blk[h]];
+            } else {                   // few blocks: lane b holds the total of block b
+                f_done[0] = lane < n_blk - 1 ? blk_t[um] : 0.0;
+            }
         }
         if (binom) {
-            f_s12 = *p_s12;
+#pragma unroll
+            for (int h = 0; h < PPL; ++h)
+                f_s12[h] = p_s12[cli[h]];
             p_s12 += stride_s12;
         }
     };
@@ -1370,7 +1392,14 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     if (!has_work)
         return;
     for (int mi = w; mi < (int)n_m; mi += n_w) {
-        const double gm = f_gm, part = f_part, s12 = f_s12, dn = f_done;
+        const double gm = f_gm;
+        double part[PPL], s12[PPL], dn[PPL];
+#pragma unroll
+        for (int h = 0; h < PPL; ++h) {
+            part[h] = f_part[h];
+            s12[h] = f_s12[h];
+            dn[h] = f_done[h];
+        }
         const int nv = f_nv;
         const double amin = f_amin;      // min over s of A = g(s) k, from k_terms
         const size_t row_now = (size_t)t * n_m + mi;
@@ -1384,15 +1413,19 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
         if (mi + n_w < (int)n_m)
             fetch(mi + n_w);
 
-        // row 5: min over s of fma(q, C, B) and the first candidate that attains it.  The
-        // loop keeps the minimum and in which batch of eight candidates it first appeared;
-        // that batch is evaluated once more for the candidate itself.
-        double b5 = INFINITY;
-        int i5 = 0;
+        // row 5: min over s of fma(q, C, B).  The loop keeps the minimum and in which batch of
+        // eight candidates it first appeared; the candidate itself is looked for afterwards,
+        // and only where row 5 wins the cell.
+        double b5[PPL];
+        int i5[PPL];
+#pragma unroll
+        for (int h = 0; h < PPL; ++h) {
+            b5[h] = INFINITY;
+            i5[h] = 0;
+        }
         if (mask & 0x20u) {
             // eight candidates per round trip to LDS; past the last competing one B is
             // +inf (and C is finite), so the value is +inf and never taken
-            int batch5 = 0;
             for (int s0 = 0; s0 < nv; s0 += 8) {
                 double Bv[8], Cv[8];
 #pragma unroll
@@ -1400,89 +1433,110 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                     Bv[u] = rowB[wave][s0 + u];
                     Cv[u] = sC[s0 + u];
                 }
-                double cur = INFINITY;
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    cur = min_f64(cur, __builtin_fma(q, Cv[u], Bv[u]));
-                batch5 = cur < b5 ? s0 : batch5;
-                b5 = min_f64(b5, cur);
+                for (int h = 0; h < PPL; ++h) {
+                    double cur = INFINITY;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        cur = min_f64(cur, __builtin_fma(q[h], Cv[u], Bv[u]));
+                    i5[h] = cur < b5[h] ? s0 : i5[h];
+                    b5[h] = min_f64(b5[h], cur);
+                }
             }
-            i5 = batch5;
         }
 
         plogp_cell_dev *o = obase + (size_t)mi * n_P;
         if (mask & 0x3FFu) {
-            const double t2 = amin < INFINITY ? __builtin_fma(q, amin, L) : INFINITY;
-            const double t9 = amin < INFINITY ? __builtin_fma(fl, amin, clL) : INFINITY;
-            Best bc = decide_bcast(mask, q, fl, cl, gm, L, g1, t2, 0u, b5, 0u, t9, 0u);
-            // a winning row 5: the first candidate of the remembered batch that attains the
-            // minimum (lanes differ in their batch: per-lane LDS reads of its eight candidates)
-            if (__ballot(active && bc.id == 5u) != 0) {
-                bool open5 = true;
-                int at5 = i5;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const double T5 = __builtin_fma(q, sC[i5 + u], rowB[wave][i5 + u]);
-                    const bool hit = open5 && T5 == b5;
-                    at5 = hit ? i5 + u : at5;
-                    open5 = open5 && !hit;
-                }
-                if (bc.id == 5u)
-                    bc.s = sSv[at5];
-            }
-            // a winning row 2 or 9: the first candidate whose value equals the minimum
-            bool open = active && (bc.id == 2u || bc.id == 9u);
-            if (__ballot(open) != 0) {
-                const double mul = bc.id == 2u ? q : fl, add = bc.id == 2u ? L : clL;
-                uint32_t found = 0u;
-                for (int s0 = 0; s0 < nv; s0 += 4) {     // past the last candidate A is +inf
-                    double Av[4];
-                    uint32_t Sv[4];
+            for (int h = 0; h < PPL; ++h) {
+                const double t2 = amin < INFINITY ? __builtin_fma(q[h], amin, L) : INFINITY;
+                const double t9 = amin < INFINITY ? __builtin_fma(fl[h], amin, clL[h]) : INFINITY;
+                Best bc = decide_bcast(mask, q[h], fl[h], cl[h], gm, L, g1, t2, 0u, b5[h], 0u, t9, 0u);
+                // a winning row 5: the first candidate of the remembered batch that attains the
+                // minimum (lanes differ in their batch: per-lane LDS reads of its eight candidates)
+                if (__ballot(active[h] && bc.id == 5u) != 0) {
+                    bool open5 = true;
+                    int at5 = i5[h];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        Av[u] = s0 + u < n_s ? S.segA[row_now * n_s + s0 + u] : INFINITY;
-                        Sv[u] = sSv[s0 + u];
+                    for (int u = 0; u < 8; ++u) {
+                        const double T5 = __builtin_fma(q[h], sC[i5[h] + u], rowB[wave][i5[h] + u]);
+                        const bool hit = open5 && T5 == b5[h];
+                        at5 = hit ? i5[h] + u : at5;
+                        open5 = open5 && !hit;
                     }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const bool hit = open && __builtin_fma(mul, Av[u], add) == bc.t;
-                        found = hit ? Sv[u] : found;
-                        open = open && !hit;
-                    }
-                    if (__ballot(open) == 0)
-                        break;
+                    if (bc.id == 5u)
+                        bc.s = sSv[at5];
                 }
-                if (bc.id == 2u || bc.id == 9u)
-                    bc.s = found;
+                // a winning row 2 or 9: the first candidate whose value equals the minimum
+                bool open = active[h] && (bc.id == 2u || bc.id == 9u);
+                if (__ballot(open) != 0) {
+                    const double mul = bc.id == 2u ? q[h] : fl[h], add = bc.id == 2u ? L : clL[h];
+                    uint32_t found = 0u;
+                    for (int s0 = 0; s0 < nv; s0 += 4) {     // past the last candidate A is +inf
+                        double Av[4];
+                        uint32_t Sv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            Av[u] = s0 + u < n_s ? S.segA[row_now * n_s + s0 + u] : INFINITY;
+                            Sv[u] = sSv[s0 + u];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const bool hit = open && __builtin_fma(mul, Av[u], add) == bc.t;
+                            found = hit ? Sv[u] : found;
+                            open = open && !hit;
+                        }
+                        if (__ballot(open) == 0)
+                            break;
+                    }
+                    if (bc.id == 2u || bc.id == 9u)
+                        bc.s = found;
+                }
+                if (active[h])
+                    store_cell(o + 64 * h, bc);
             }
-            if (active)
-                store_cell(o, bc);
             o += plane;
         }
         if (mask & 0x1C00u) {
-            double s11 = 0.0;
+            double s11[PPL];
+#pragma unroll
+            for (int h = 0; h < PPL; ++h)
+                s11[h] = 0.0;
             if (chain) {
-                double done = dn;
+                double done[PPL];
                 if (!G.blk_is_prefix) {
-                    // the finished blocks are added in ascending order, the same sum in
-                    // every lane; a lane keeps the value that belongs to its own block
+                    // the finished blocks are added in ascending order, the same sum in every
+                    // lane; a lane keeps, per process count, the value that belongs to its block
+                    const double tot = dn[0];
                     double acc = 0.0;
-                    for (int b = 0; b < bmin; ++b)
+                    for (int b = 0; b < bmin[0]; ++b)
                         acc = acc + __hiloint2double(
-                                        __builtin_amdgcn_readlane(__double2hiint(dn), b),
-                                        __builtin_amdgcn_readlane(__double2loint(dn), b));
-                    done = acc;                  // lanes of block bmin
-                    for (int b = bmin; b < bmax; ++b) {
+                                        __builtin_amdgcn_readlane(__double2hiint(tot), b),
+                                        __builtin_amdgcn_readlane(__double2loint(tot), b));
+#pragma unroll
+                    for (int h = 0; h < PPL; ++h)
+                        done[h] = acc;               // lanes of block bmin[0]
+                    for (int b = bmin[0]; b < bmax[PPL - 1]; ++b) {
                         acc = acc + __hiloint2double(
-                                        __builtin_amdgcn_readlane(__double2hiint(dn), b),
-                                        __builtin_amdgcn_readlane(__double2loint(dn), b));
-                        done = blk == b + 1 ? acc : done;
+                                        __builtin_amdgcn_readlane(__double2hiint(tot), b),
+                                        __builtin_amdgcn_readlane(__double2loint(tot), b));
+#pragma unroll
+                        for (int h = 0; h < PPL; ++h)
+                            done[h] = blk[h] == b + 1 ? acc : done[h];
                     }
+                } else {
+#pragma unroll
+                    for (int h = 0; h < PPL; ++h)
+                        done[h] = dn[h];
                 }
-                s11 = done + part;
+#pragma unroll
+                for (int h = 0; h < PPL; ++h)
+                    s11[h] = done[h] + part[h];
             }
-            if (active)
-                store_cell(o, decide_scatter(mask, q, cl, gm, L, s11, s12));
+#pragma unroll
+            for (int h = 0; h < PPL; ++h)
+                if (active[h])
+                    store_cell(o + 64 * h, decide_scatter(mask, q[h], cl[h], gm, L, s11[h], s12[h]));
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -2942,23 +2996,28 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         } else if (lanes_p) {
             // as many waves as the chip holds at four per SIMD, shared out over the tables and
             // the groups of 64 process counts; each walks over every n_w-th message size
-            const int n_pg = (G.n_P + 63) / 64;
-            long n_w = 8192 / ((long)T.n_tables * n_pg);
+            // two process counts per lane when the grid has at least 512 of them
+            const bool all = G.mask == 0x1FFFu;
+            const int ppl = G.n_P >= 512 && G.n_s <= 64 && all ? 2 : 1;
+            const int n_pg = (G.n_P + 64 * ppl - 1) / (64 * ppl);
+            long n_w = 8192 / ppl / ((long)T.n_tables * n_pg);
             if (n_w > G.n_m) n_w = G.n_m;
             if (n_w < 1) n_w = 1;
             n_w = (n_w + 3) / 4 * 4;
-            const bool all = G.mask == 0x1FFFu;
             for (int t0 = 0; t0 < T.n_tables; t0 += 65535) {
                 const int nt = T.n_tables - t0 < 65535 ? T.n_tables - t0 : 65535;
                 const dim3 blocks((unsigned)(n_w / 4), (unsigned)n_pg, (unsigned)nt);
-                if (G.n_s <= 64 && all)
-                    hipLaunchKernelGGL((k_sweep_p<1, true>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                if (G.n_s <= 64 && all && ppl == 2)
+                    hipLaunchKernelGGL((k_sweep_p<1, true, 2>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                                       (int)n_w);
+                else if (G.n_s <= 64 && all)
+                    hipLaunchKernelGGL((k_sweep_p<1, true, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
                                        (int)n_w);
                 else if (G.n_s <= 64)
-                    hipLaunchKernelGGL((k_sweep_p<1, false>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                    hipLaunchKernelGGL((k_sweep_p<1, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
                                        (int)n_w);
                 else
-                    hipLaunchKernelGGL((k_sweep_p<4, false>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
+                    hipLaunchKernelGGL((k_sweep_p<4, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
                                        (int)n_w);
             }
         } else {

@@ -174,7 +174,10 @@ def test_each_strategy_alone_over_a_ragged_grid(sid):
     assert assert_tables_equal(gpu_tune(wl), want, "only id %d" % sid)
 
 
-@pytest.mark.parametrize("n_P,n_m", [(1, 1), (7, 3), (255, 2), (256, 5), (257, 4), (1500, 3)])
+# from 512 process counts on a lane of the sweep takes two of them, 64 apart: 512 and 640 fill
+# their groups, 513 and 520 leave the second half of the last group empty, 600 and 1500 ragged
+@pytest.mark.parametrize("n_P,n_m", [(1, 1), (7, 3), (255, 2), (256, 5), (257, 4), (512, 2), (513, 3),
+                                     (520, 9), (600, 2), (640, 5), (1500, 3)])
 def test_tile_shapes(n_P, n_m):
     rng = np.random.default_rng(n_P * 10 + n_m)
     base = make_workload(2)
@@ -184,6 +187,17 @@ def test_tile_shapes(n_P, n_m):
                   ALL_STRATEGIES_MASK)
     want, _ = oracle.tune_workload(wl)
     assert assert_tables_equal(gpu_tune(wl), want, "tiles %d x %d" % (n_P, n_m))
+
+
+@pytest.mark.parametrize("n_P", [512, 520, 577, 700])
+def test_two_process_counts_per_lane_with_few_blocks(n_P):
+    # consecutive process counts up to 2 + n_P: at most 32 blocks of the chain sum, so the sweep
+    # adds the finished blocks itself; the last group's second half is empty, ragged or full
+    base = make_workload(2, m_slice=slice(3, 1024, 97))
+    wl = Workload("two", base.sizes, base.gaps, base.L, base.m, np.arange(2, 2 + n_P, dtype=np.uint32),
+                  base.s, base.s_cap, ALL_STRATEGIES_MASK)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "two per lane, %d P" % n_P)
 
 
 def test_many_candidates_span_several_lds_passes():
