@@ -256,9 +256,17 @@ __device__ __forceinline__ double from_ordered_bits(unsigned long long k)
 // rows, g(s) for its candidates and (first table only) the reciprocals 1/s used
 // to get k = ceil(m/s) without a division per (m, s); chunk 0 also g(1).
 __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
-                                           int n_chunks, int with_pairs, int block_id, double *lds)
+                                           int n_chunks, int n_mchunks, int with_pairs, int block_id,
+                                           double *lds)
 {
-    const int t = block_id / n_chunks, chunk = block_id % n_chunks;
+    // per table: n_chunks workgroups for the candidates and the (m, s) pairs, then n_mchunks
+    // that only do the per-size part (0: the first kind does that part as well); the two
+    // parts are about equally long chains of dependent steps, side by side they halve
+    const int per_table = n_chunks + n_mchunks;
+    const int t = block_id / per_table, c_in = block_id % per_table;
+    const bool m_role = c_in >= n_chunks;
+    const int chunk = m_role ? c_in - n_chunks : c_in;
+    const bool first = chunk == 0 && !m_role;
     const int waves = (int)(blockDim.x >> 6);
     const int n = T.n;
     double *x = lds, *y = lds + n, *sl = lds + 2 * n;
@@ -271,16 +279,16 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         const double v = interval_slope(x, y, n, i);
         sl[i] = v;
-        if (chunk == 0)
+        if (first)
             T.slope[(size_t)t * n + i] = v;
     }
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
     // for the sweep that runs its lanes over P: g(s) and 1/s of every candidate, for this
     // workgroup's own use below
-    const bool pairs = (with_pairs & 1) != 0, stage_s = (with_pairs & 2) != 0;
+    const bool pairs = (with_pairs & 1) != 0 && !m_role, stage_s = (with_pairs & 2) != 0;
     double *gs_l = lds + 3 * n, *rcp_l = gs_l + G.n_s;
-    double *sd_l = lds + 3 * n + (pairs ? 2 * G.n_s : 0);      // the candidates (exact as doubles)
+    double *sd_l = lds + 3 * n + ((with_pairs & 1) ? 2 * G.n_s : 0);   // the candidates (exact as doubles)
     if (pairs || stage_s) {
         for (int si = threadIdx.x; si < G.n_s; si += blockDim.x) {
             const double sd = (double)G.s[si];
@@ -297,7 +305,9 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
     // per message size: g(m), the number of candidates, the prefix of g(2^j m).  Groups
     // of 64 sizes are dealt to the waves of this table's workgroups.
     const int n_mw = (G.n_m + 63) / 64;
-    for (int mw = chunk * waves + (int)(threadIdx.x >> 6); mw < n_mw; mw += n_chunks * waves) {
+    const int m_step = (n_mchunks > 0 ? n_mchunks : n_chunks) * waves;
+    const int m_first = n_mchunks > 0 && !m_role ? n_mw : chunk * waves + (int)(threadIdx.x >> 6);
+    for (int mw = m_first; mw < n_mw; mw += m_step) {
         const int mi = mw * 64 + (int)(threadIdx.x & 63);
         if (mi >= G.n_m)
             continue;
@@ -343,8 +353,10 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
             }
         }
     }
-    if (chunk == 0 && threadIdx.x == 0)
+    if (first && threadIdx.x == 0)
         S.g1[t] = gap_at(tab, 1.0);
+    if (m_role)
+        return;
     // per candidate: g(s), 1/s, C = g(s) + L; shared out over the chunks of this table
     const double L = T.L[t];
     for (int si = chunk * blockDim.x + threadIdx.x; si < G.n_s; si += n_chunks * blockDim.x) {
@@ -393,10 +405,10 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
 }
 
 __global__ void __launch_bounds__(256) k_terms(DeviceTables T, DeviceGrid G, Scratch S, int n_chunks,
-                                               int with_pairs)
+                                               int n_mchunks, int with_pairs)
 {
     extern __shared__ double lds[];
-    terms_body(T, G, S, n_chunks, with_pairs, (int)blockIdx.x, lds);
+    terms_body(T, G, S, n_chunks, n_mchunks, with_pairs, (int)blockIdx.x, lds);
 }
 
 // ---------------------------------------------------------------- tune, step 2: Scatter-chain sum
@@ -732,6 +744,19 @@ __device__ __forceinline__ void chain_small_body(const DeviceTables &T, const De
     f64x2 *YS = reinterpret_cast<f64x2 *>(chain_lds);              // n + 2 entries
     double *X = chain_lds + 2 * (n + 2);                           // n + 6 entries
     double *gl = X + (n + 6);                                      // 64 rows of SMALL_LD
+    const int lane = threadIdx.x & 63, wave = (int)(threadIdx.x >> 6);
+    const int n_mu = G.n_mu;
+    const int n_mg = (n_mu + 63) / 64;
+    const int n_items = G.n_blk * n_mg;
+    // the first item's size, block mask and offset are on their way while the table is staged
+    u64 m_next = 0, wanted_next = 0;
+    int off_next = 0;
+    if (wg < n_items) {
+        const int mi0 = (wg % n_mg) * 64 + lane;
+        m_next = G.mu[mi0 < n_mu ? mi0 : n_mu - 1];
+        wanted_next = G.blk_mask[wg / n_mg];
+        off_next = G.blk_off[wg / n_mg];
+    }
     {
         const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
         for (int i = threadIdx.x; i < n + 6; i += blockDim.x) {
@@ -745,25 +770,29 @@ __device__ __forceinline__ void chain_small_body(const DeviceTables &T, const De
         }
     }
     __syncthreads();
-    const int lane = threadIdx.x & 63, wave = (int)(threadIdx.x >> 6);
-    const int n_mu = G.n_mu;
-    const int n_mg = (n_mu + 63) / 64;
-    const int n_items = G.n_blk * n_mg;
     for (int item = wg; item < n_items; item += wg_per_table) {
         const int b = item / n_mg, mg = item % n_mg;
         const int mi = mg * 64 + lane;
-        const u64 m = G.mu[mi < n_mu ? mi : n_mu - 1];
+        const u64 m = m_next, wanted = wanted_next;
+        const int off = off_next;
+        if (item + wg_per_table < n_items) {
+            const int nxt = item + wg_per_table;
+            const int mi1 = (nxt % n_mg) * 64 + lane;
+            m_next = G.mu[mi1 < n_mu ? mi1 : n_mu - 1];
+            wanted_next = G.blk_mask[nxt / n_mg];
+            off_next = G.blk_off[nxt / n_mg];
+        }
         const u64 j0 = (u64)b * SUM_BLOCK + 1 + (u64)wave * 16;     // this wave's 16 terms
 #pragma unroll
-        for (int r0 = 0; r0 < 16; r0 += 4) {
-            double z[4];
-            int i[4];
+        for (int r0 = 0; r0 < 16; r0 += 8) {                        // eight searches side by side
+            double z[8];
+            int i[8];
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
+            for (int c = 0; c < 8; ++c)
                 z[c] = (double)((j0 + r0 + c) * m);
-            chain_locate<4>(X, n, z, i);
+            chain_locate<8>(X, n, z, i);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
+            for (int c = 0; c < 8; ++c) {
                 const f64x2 ys = YS[i[c]];
                 gl[(wave * 16 + r0 + c) * SMALL_LD + lane] = __builtin_fma(ys.y, z[c] - X[i[c]], ys.x);
             }
@@ -788,9 +817,8 @@ __device__ __forceinline__ void chain_small_body(const DeviceTables &T, const De
         __syncthreads();
         {
             // lane r holds term r's place: bit r of the mask = the sum before term r is wanted
-            const u64 wanted = G.blk_mask[b];
             const bool want = ((wanted >> lane) & 1ull) != 0;
-            const int at = G.blk_off[b] + __popcll(wanted & ((1ull << lane) - 1ull));
+            const int at = off + __popcll(wanted & ((1ull << lane) - 1ull));
             for (int row = wave; row < 64; row += 4) {
                 const int mrow = mg * 64 + row;
                 if (mrow < n_mu && want)
@@ -814,7 +842,7 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
 // workgroups of both kinds share a CU.
 __global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid G, Scratch S, int n_chain_wg,
                                                      int wg_per_table, int n_single, int n_search,
-                                                     int n_chunks, int with_pairs)
+                                                     int n_chunks, int n_mchunks, int with_pairs)
 {
     extern __shared__ __align__(16) double both_lds[];
     if ((int)blockIdx.x < n_chain_wg) {
@@ -823,7 +851,7 @@ __global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid 
         else
             chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, both_lds);
     } else
-        terms_body(T, G, S, n_chunks, with_pairs, (int)blockIdx.x - n_chain_wg, both_lds);
+        terms_body(T, G, S, n_chunks, n_mchunks, with_pairs, (int)blockIdx.x - n_chain_wg, both_lds);
 }
 
 // Turns the block totals of PFX_M message sizes into their exclusive prefix in
@@ -2906,6 +2934,14 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     const int n_chunks = (int)n_chunks_l;
+    // small tables: the per-size part in workgroups of its own, beside the others
+    int n_mchunks = 0;
+    if (terms_lds <= 16384) {
+        n_mchunks = ((G.n_m + 63) / 64 + 3) / 4;
+        const int cap = 256 / T.n_tables > 1 ? 256 / T.n_tables : 1;
+        if (n_mchunks > cap) n_mchunks = cap;
+    }
+    const unsigned terms_wg = (unsigned)T.n_tables * (unsigned)(n_chunks + n_mchunks);
     const bool chain = (G.mask & (1u << 11)) != 0;
     // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
     // stays for its whole share of the work (the table is staged once)
@@ -2915,8 +2951,8 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const bool together = chain && !big;
     if (!together) {
         for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_terms, dim3((unsigned)T.n_tables * n_chunks), dim3(256), terms_lds, st, T,
-                               G, S, n_chunks, terms_mode);
+            hipLaunchKernelGGL(k_terms, dim3(terms_wg), dim3(256), terms_lds, st, T, G, S, n_chunks,
+                               n_mchunks, terms_mode);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     PLOGP_MARK(1);
@@ -2951,9 +2987,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         const int n_chain_wg = (int)(T.n_tables * wg);
         for (int r = 0; r < reps; ++r) {
             if (together)
-                hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)(n_chain_wg + T.n_tables * n_chunks)),
+                hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)n_chain_wg + terms_wg),
                                    dim3(256), both_lds, st, T, G, S,
-                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, terms_mode);
+                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, n_mchunks, terms_mode);
             else
                 hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
                                    T, G, S, (int)wg, n_single, n_search);
