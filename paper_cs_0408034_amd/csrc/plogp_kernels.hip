@@ -1483,17 +1483,18 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
                 // a winning row 5: the first candidate of the remembered batch that attains the
                 // minimum (lanes differ in their batch: per-lane LDS reads of its eight candidates)
                 if (__ballot(active[h] && bc.id == 5u) != 0) {
-                    bool open5 = true;
-                    int at5 = i5[h];
+                    double Bv[8], Cv[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        const double T5 = __builtin_fma(q[h], sC[i5[h] + u], rowB[wave][i5[h] + u]);
-                        const bool hit = open5 && T5 == b5[h];
-                        at5 = hit ? i5[h] + u : at5;
-                        open5 = open5 && !hit;
+                        Bv[u] = rowB[wave][i5[h] + u];
+                        Cv[u] = sC[i5[h] + u];
                     }
-                    if (bc.id == 5u)
-                        bc.s = sSv[at5];
+                    int at5 = i5[h];
+#pragma unroll
+                    for (int u = 7; u >= 0; --u)        // descending: the first match stays
+                        at5 = __builtin_fma(q[h], Cv[u], Bv[u]) == b5[h] ? i5[h] + u : at5;
+                    const uint32_t s_at = sSv[at5];
+                    bc.s = bc.id == 5u ? s_at : bc.s;
                 }
                 // a winning row 2 or 9: the first candidate whose value equals the minimum
                 bool open = active[h] && (bc.id == 2u || bc.id == 9u);
