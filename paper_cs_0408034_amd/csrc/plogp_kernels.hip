@@ -875,24 +875,37 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
     const double *src = S.blk + (size_t)t * G.n_blk * n_m + (active ? mi : 0);
     const int full = G.n_blk - 1;                        // blocks that have a total
     double done = 0.0;
-    for (int b0 = 0; b0 < G.n_blk; b0 += PFX_TILE) {
-        double v[PFX_TILE / ROWS];
+    double v[PFX_TILE / ROWS];
+    auto load_tile = [&](int b0) {
 #pragma unroll
         for (int k = 0; k < PFX_TILE / ROWS; ++k) {
             const int b = b0 + br + ROWS * k;
             v[k] = (active && b < full) ? src[(size_t)b * n_m] : 0.0;
         }
+    };
+    load_tile(0);
+    for (int b0 = 0; b0 < G.n_blk; b0 += PFX_TILE) {
 #pragma unroll
         for (int k = 0; k < PFX_TILE / ROWS; ++k)
             tile[(br + ROWS * k) * (PFX_M + 1) + ml] = v[k];
         __syncthreads();
+        // the next tile's totals are on their way while this one is scanned and written
+        if (b0 + PFX_TILE < G.n_blk)
+            load_tile(b0 + PFX_TILE);
         if (tid < PFX_M) {
+            // sixteen totals at a time: read, add in order, write the sums before each (rows
+            // past the last block hold zeros and are not written out below)
             const int nb = G.n_blk - b0 < PFX_TILE ? G.n_blk - b0 : PFX_TILE;
-#pragma unroll 8
-            for (int bb = 0; bb < nb; ++bb) {
-                const double tot = tile[bb * (PFX_M + 1) + tid];
-                tile[bb * (PFX_M + 1) + tid] = done;
-                done = done + tot;
+            for (int bb = 0; bb < nb; bb += 16) {
+                double tot[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    tot[u] = tile[(bb + u) * (PFX_M + 1) + tid];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    tile[(bb + u) * (PFX_M + 1) + tid] = done;
+                    done = done + tot[u];
+                }
             }
         }
         __syncthreads();
