@@ -383,3 +383,90 @@ def test_repeated_calls_on_a_side_stream_give_the_same_table():
         arr = o.cpu().numpy().view(plogp.CELL_DTYPE).reshape(want.shape)
         assert assert_tables_equal(arr, want, "repeat")
     grid.free(); tab.free()
+
+
+def _random_problem(rng):
+    """A small random tuning job: table (possibly non-monotone), sizes with repeats in any
+    order, ascending process counts, ascending candidates, cap, mask, one to four tables."""
+    n = int(rng.choice([2, 3, 5, 17, 64, 65, 130, 300]))
+    steps = rng.integers(1, 2000, size=n).astype(np.float64)
+    x = np.cumsum(steps)
+    x[0] = float(rng.integers(1, 64))
+    x = np.maximum.accumulate(x + 0.0)
+    x = np.unique(np.floor(x))
+    n = len(x)
+    if n < 2:
+        x = np.array([1.0, 9.0])
+        n = 2
+    n_tables = int(rng.choice([1, 1, 1, 2, 4]))
+    gaps = np.empty((n_tables, n))
+    for t in range(n_tables):
+        y = 30.0 + x * rng.uniform(0.01, 0.2) * (1.0 + 0.3 * rng.standard_normal(n))
+        if rng.random() < 0.5:
+            y = np.maximum.accumulate(np.abs(y))
+        gaps[t] = np.abs(y)
+    L = rng.uniform(0.0, 200.0, size=n_tables)
+    top = float(x[-1]) * float(rng.choice([0.5, 1.0, 40.0]))
+    n_m = int(rng.choice([1, 3, 30, 64, 65, 129]))
+    m = (np.floor(np.exp(rng.uniform(np.log(8.0), np.log(max(top, 64.0)), size=n_m)) / 8.0) * 8.0)
+    m = np.maximum(m, 8.0).astype(np.uint64)
+    if rng.random() < 0.5:
+        m = np.concatenate([m, m[: max(1, n_m // 3)]])
+    p_hi = int(rng.choice([9, 70, 700, 2500, 5000]))
+    n_P = int(min(p_hi - 2, rng.choice([1, 2, 31, 32, 64, 65, 300, 513, 640])))
+    P = np.sort(rng.choice(np.arange(2, p_hi), size=max(n_P, 1), replace=False)).astype(np.uint32)
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        s = np.array([], dtype=np.uint64)
+    elif kind == 1:
+        s = np.unique((rng.integers(1, 4000, size=int(rng.choice([1, 5, 34, 64, 65, 200]))) * 8)).astype(np.uint64)
+    else:
+        s = (np.arange(1, int(rng.choice([300, 1100])) + 1) * 8).astype(np.uint64)
+    s_cap = int(rng.choice([NO_CAP, 4096, 64]))
+    mask = int(rng.choice([ALL_STRATEGIES_MASK, ALL_STRATEGIES_MASK, 0x3FF, 0x1C00, 0x0A25, 0x1224,
+                           int(rng.integers(1, 1 << 13))]))
+    return Workload("random", np.repeat(x[None, :], n_tables, axis=0), gaps, L, m, P, s, s_cap, mask)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_problems(seed):
+    """Eight random problems per seed: every launch path and tile shape that the sizes select."""
+    rng = np.random.default_rng(1000 + seed)
+    for k in range(8):
+        wl = _random_problem(rng)
+        want, _ = oracle.tune_workload(wl)
+        what = "random %d/%d: n=%d tables=%d m=%d P=%d s=%d cap=%d mask=%#x" % (
+            seed, k, wl.sizes.shape[1], wl.n_tables, len(wl.m), len(wl.P), len(wl.s), wl.s_cap & 0xFFFFFFFF,
+            wl.strategy_mask)
+        print(what, flush=True)
+        assert_tables_equal(gpu_tune(wl), want, what)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_batches(seed):
+    """Batches big enough for the single-kernel paths (at least 8192 (table, m) rows), with and
+    without shared sample sizes, few or many candidates, short or long chain sums."""
+    rng = np.random.default_rng(2000 + seed)
+    n = int(rng.choice([2, 9, 40, 64]))
+    n_tables = int(rng.choice([64, 65, 100, 130]))
+    n_m = -(-8192 // n_tables) + int(rng.integers(0, 40))
+    x = np.unique(np.floor(np.cumsum(rng.integers(1, 3000, size=n).astype(np.float64))))
+    while len(x) < 2:
+        x = np.append(x, x[-1] + 7.0)
+    sizes = np.repeat(x[None, :], n_tables, axis=0)
+    if seed % 2 == 1:                               # tables with sample sizes of their own
+        sizes = sizes + np.floor(rng.integers(0, 3, size=sizes.shape).cumsum(axis=1))
+    gaps = 20.0 + sizes * rng.uniform(0.02, 0.1, size=(n_tables, 1)) * (1.0 + 0.2 * rng.random(sizes.shape))
+    L = rng.uniform(1.0, 90.0, size=n_tables)
+    m = (np.floor(np.exp(rng.uniform(np.log(8.0), np.log(float(x[-1]) * 20.0), size=n_m)) / 8.0) * 8.0)
+    m = np.maximum(m, 8.0).astype(np.uint64)
+    p_hi = int(rng.choice([40, 600, 2300]))
+    P = np.sort(rng.choice(np.arange(2, p_hi), size=int(rng.choice([3, 24, 37])), replace=False)).astype(np.uint32)
+    s = np.unique(rng.integers(1, 3000, size=int(rng.choice([0, 7, 21, 40]))) * 8).astype(np.uint64)
+    mask = int(rng.choice([ALL_STRATEGIES_MASK, ALL_STRATEGIES_MASK, 0x3FF, 0x1C00, 0x0E24]))
+    wl = Workload("batch", sizes, gaps, L, m, P, s, int(rng.choice([NO_CAP, 2048])), mask)
+    want, _ = oracle.tune_workload(wl)
+    what = "batch %d: n=%d tables=%d m=%d P=%d (up to %d) s=%d mask=%#x" % (
+        seed, sizes.shape[1], n_tables, n_m, len(P), int(P[-1]), len(s), mask)
+    print(what, flush=True)
+    assert_tables_equal(gpu_tune(wl), want, what)
