@@ -151,3 +151,18 @@ def test_bad_arguments_are_refused():
     assert lib.plogp_score_grid(tab._h, 0, grid._h, None, p, p, p, p, None) == plogp.EINVAL
     grid.free()
     tab.free()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_problems(seed):
+    """Random tables, sizes (any order, repeats), process counts and masks; a random table of
+    the batch is scored."""
+    from tests.test_gpu_parity import _random_problem
+    rng = np.random.default_rng(3000 + seed)
+    for k in range(6):
+        wl = _random_problem(rng)
+        meas, seg = make_measurements(wl, seed=seed * 10 + k)
+        ti = int(rng.integers(0, wl.n_tables))
+        print("random %d/%d: n=%d table %d of %d, m=%d P=%d mask=%#x" % (
+            seed, k, wl.sizes.shape[1], ti, wl.n_tables, len(wl.m), len(wl.P), wl.strategy_mask), flush=True)
+        check(wl, meas, seg, table_index=ti)
