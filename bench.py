@@ -407,8 +407,8 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="headline workload (1..5)")
     ap.add_argument("--extra", type=str, default="3,4,5", help="other configs to time, or 'none'")
     ap.add_argument("--no-cpu", action="store_true")
