@@ -65,11 +65,11 @@ def describe(wl):
 # FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
 # kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
 MEASURED_TRAFFIC = {
-    2: {"chain_blocks": 0.239e6 + 7.688e6, "sweep": 8.595e6 + 33.633e6},
-    3: {"chain_blocks": 0.753e6 + 1.438e6, "chain_prefix": 0.576e6 + 0.524e6, "sweep": 3.682e6 + 2.294e6},
-    4: {"terms": 88.252e6 + 10.560e6 + 0.146e6 + 0.176e6, "sweep": 86.178e6 + 2004.747e6},
-    5: {"terms": 0.671e6 + 1.986e6, "chain_blocks": 1.181e6 + 71.299e6,
-        "chain_prefix": 50.916e6 + 26.337e6, "sweep": 79.698e6 + 93.323e6},
+    2: {"chain_blocks": 0.247e6 + 7.689e6, "sweep": 8.523e6 + 33.585e6},
+    3: {"chain_blocks": 0.741e6 + 1.438e6, "chain_prefix": 0.584e6 + 0.524e6, "sweep": 3.694e6 + 2.294e6},
+    4: {"terms": 87.335e6 + 10.560e6 + 0.131e6 + 0.176e6, "sweep": 86.168e6 + 2005.225e6},
+    5: {"terms": 0.672e6 + 1.986e6, "chain_blocks": 1.165e6 + 71.265e6,
+        "chain_prefix": 50.923e6 + 26.336e6, "sweep": 63.403e6 + 93.320e6},
 }
 # the same for the three kernels of the cut-over extraction (mark, scan1 + scan2, emit)
 MEASURED_CUT_TRAFFIC = {
