@@ -385,7 +385,7 @@ static int ensure_scratch(plogp_grid *g, size_t n_tables, size_t n_samples)
         {&g->scratch.blk, chain ? n_tables * (size_t)g->n_blk * g->n_m : 1},
         {&g->scratch.part, chain ? n_tables * g->n_m * g->n_P : 1},
         {&g->scratch.rcp, g->n_s ? g->n_s : 1},
-        {&g->scratch.pre, chain && g->n_blk > 32 ? n_tables * g->n_m * (size_t)g->n_blk : 1},
+        {&g->scratch.pre, chain && g->n_blk > 32 ? n_tables * g->n_m * g->n_P : 1},
         {&g->scratch.segC, n_tables * (g->n_s ? g->n_s : 1)},
         {&g->scratch.segA, pairs ? n_tables * g->n_m * g->n_s : 1},
         {&g->scratch.segB, pairs ? n_tables * g->n_m * g->n_s : 1},

@@ -90,7 +90,7 @@ struct Scratch {
     double *gm;       // [n_tables][n_m]                  g(m)
     double *sum2;     // [n_tables][n_m][cl_max+1]        prefix over j of g(2^j m)
     double *blk;      // [n_tables][n_blk][n_m]           totals of the blocks of the chain sum
-    double *pre;      // [n_tables][n_m][n_blk]           their exclusive prefix (more than 32 blocks only)
+    double *pre;      // [n_tables][n_m][n_P]             sum of the blocks finished before each grid P (more than 32 blocks only)
     double *part;     // [n_tables][n_m][n_P]             in-block partial sums at the grid's P
     double *rcp;      // [n_s]                            1/s, rounded
     double *segC;     // [n_tables][n_s]                  C = g(s) + L

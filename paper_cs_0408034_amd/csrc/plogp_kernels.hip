@@ -856,7 +856,8 @@ __global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid 
 
 // Turns the block totals of PFX_M message sizes into their exclusive prefix in
 // ascending block order (the sum of all finished blocks before block b) and
-// writes it transposed, pre[m][b], which is how the sweeps read it.  The sum is
+// writes, per process count of the grid, the prefix of the block it ends in:
+// pre[m][P index], which the sweeps read side by side with the partial sums.  The sum is
 // sequential per m; the workgroup moves tiles of PFX_TILE blocks through LDS
 // (every thread 16 loads in flight) and the first PFX_M lanes scan a tile there.
 constexpr int PFX_TILE = 256;
@@ -909,13 +910,19 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
             }
         }
         __syncthreads();
-        // thread tid writes block b0 + tid of every m: runs of up to 2 KB per m
-        if (b0 + tid < G.n_blk) {
+        // only the blocks in which some process count of the grid ends are wanted: the sums
+        // go out per process count, pre[m][P index], a run of the output per m and store
+        {
+            const int b_end = b0 + PFX_TILE < G.n_blk ? b0 + PFX_TILE : G.n_blk;
+            const int pi_end = G.blk_off[b_end];
+            for (int pi = G.blk_off[b0] + tid; pi < pi_end; pi += 256) {
+                const int bb = (int)((G.P[pi] - 1u) / SUM_BLOCK) - b0;
 #pragma unroll 4
-            for (int mm = 0; mm < PFX_M; ++mm) {
-                const int m2 = mg * PFX_M + mm;
-                if (m2 < G.n_mu)
-                    S.pre[((size_t)t * n_m + m2) * G.n_blk + b0 + tid] = tile[tid * (PFX_M + 1) + mm];
+                for (int mm = 0; mm < PFX_M; ++mm) {
+                    const int m2 = mg * PFX_M + mm;
+                    if (m2 < G.n_mu)
+                        S.pre[((size_t)t * n_m + m2) * G.n_P + pi] = tile[bb * (PFX_M + 1) + mm];
+                }
             }
         }
         __syncthreads();
@@ -1027,7 +1034,7 @@ __device__ __forceinline__ double chain_sum_of(const DeviceGrid &G, const Scratc
     const int blk = (int)((P - 1u) / SUM_BLOCK);
     double done;
     if (G.blk_is_prefix) {
-        done = S.pre[((size_t)t * n_m + mi) * G.n_blk + blk];
+        done = S.pre[((size_t)t * n_m + mi) * G.n_P + pi];
     } else {                           // few blocks: add the finished ones here, in ascending order
         const double *tot = S.blk + (size_t)t * G.n_blk * n_m + mi;
         done = 0.0;
@@ -1185,10 +1192,10 @@ __global__ void __launch_bounds__(256) k_sweep_m(DeviceTables T, DeviceGrid G, S
     if (mask & (1u << 11)) {
         const double *tot = S.blk + (size_t)t * G.n_blk * n_mu + um;
         if (G.blk_is_prefix) {
-            const double *pre = S.pre + ((size_t)t * n_mu + um) * G.n_blk;
+            const double *pre = S.pre + ((size_t)t * n_mu + um) * G.n_P;
 #pragma unroll
             for (int p = 0; p < PC; ++p)
-                done[p] = pre[(Pv[p] - 1u) / SUM_BLOCK];
+                done[p] = pre[pc * PC + p < G.n_P ? pc * PC + p : G.n_P - 1];
         } else {
             // few blocks (at most 32): the totals are added here, in ascending order; the
             // P of the chunk ascend, so one pass over the blocks serves all of them, and
@@ -1379,7 +1386,7 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
     const double *p_s12 = S.sum2 + ((size_t)t * n_m + w) * (G.cl_max + 1);
     const size_t stride_B = (size_t)n_w * n_s, stride_s12 = (size_t)n_w * (G.cl_max + 1);
     const double *const part_t = S.part + (size_t)t * G.n_mu * n_P;
-    const double *const pre_t = S.pre + (size_t)t * G.n_mu * n_blk;
+    const double *const pre_t = S.pre + (size_t)t * G.n_mu * n_P;
     const double *const blk_t = S.blk + ((size_t)t * n_blk + lane) * G.n_mu;
     auto fetch = [&](int mi) {
         f_gm = *p_gm;
@@ -1402,10 +1409,10 @@ __global__ void __launch_bounds__(256) k_sweep_p(DeviceTables T, DeviceGrid G, S
             for (int h = 0; h < PPL; ++h)
                 f_part[h] = row[active[h] ? pi[h] : n_P - 1];
             if (G.blk_is_prefix) {
-                const double *prow = pre_t + (u64)um * (uint32_t)n_blk;
+                const double *prow = pre_t + (u64)um * (uint32_t)n_P;
 #pragma unroll
                 for (int h = 0; h < PPL; ++h)
-                    f_done[h] = prow[blk[h]];
+                    f_done[h] = prow[active[h] ? pi[h] : n_P - 1];
             } else {                   // few blocks: lane b holds the total of block b
                 f_done[0] = lane < n_blk - 1 ? blk_t[um] : 0.0;
             }
