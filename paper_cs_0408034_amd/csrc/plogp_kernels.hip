@@ -2954,14 +2954,19 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const long wg_cap = terms_lds > 65536 ? 256 : 512;
     const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
-    const int n_chunks = (int)n_chunks_l;
-    // small tables: the per-size part in workgroups of its own, beside the others
+    // the per-size part in workgroups of its own, beside the others: freely for small tables;
+    // for a big table (one workgroup per CU) out of the same budget of workgroups
     int n_mchunks = 0;
     if (terms_lds <= 16384) {
         n_mchunks = ((G.n_m + 63) / 64 + 3) / 4;
         const int cap = 256 / T.n_tables > 1 ? 256 / T.n_tables : 1;
         if (n_mchunks > cap) n_mchunks = cap;
+    } else if (T.n_tables == 1 && n_chunks_l >= 64) {
+        n_mchunks = ((G.n_m + 63) / 64 + 3) / 4;
+        if (n_mchunks > n_chunks_l / 8) n_mchunks = (int)(n_chunks_l / 8);
+        if (n_chunks_l + n_mchunks > chunk_cap) n_chunks_l = chunk_cap - n_mchunks;
     }
+    const int n_chunks = (int)n_chunks_l;
     const unsigned terms_wg = (unsigned)T.n_tables * (unsigned)(n_chunks + n_mchunks);
     const bool chain = (G.mask & (1u << 11)) != 0;
     // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
