@@ -3007,7 +3007,11 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
             if (small_lds > both_lds) both_lds = small_lds;
             n_single = -1;
             wg = (long)n_mg * G.n_blk;
-            if (wg > 512 / T.n_tables) wg = 512 / T.n_tables;
+            // the chain workgroups come first in the grid: they must leave the terms
+            // workgroups room on the chip, or those would only start when these are done
+            long room = 256L * (long)((160 * 1024) / (both_lds + 512)) - (long)terms_wg;
+            if (room > 512) room = 512;
+            if (wg > room / T.n_tables) wg = room / T.n_tables;
             if (wg < 1) wg = 1;
         }
         const int n_chain_wg = (int)(T.n_tables * wg);
