@@ -1726,104 +1726,156 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     if (!has_work)
         return;
 
-    // per process count of the group: the best segmented row, its time and its s
+    // per process count of the group: the best segmented row and its time (lane p keeps those
+    // of process count p0 + p)
     const double Aw = (mask & 0x204u) ? wave_min(amin) : INFINITY;
     const bool haveA = Aw < INFINITY;
-    // candidate si of this lane re-evaluated: value of the row given by (mul, add, use_chain)
-    auto value_at = [&](int si, double mul, double add, bool chain_row) {
-        double A, B, C;
-        segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
-        return chain_row ? __builtin_fma(mul, C, B) : __builtin_fma(mul, A, add);
-    };
-    double segT = INFINITY;       // kept by lane p for process count p0 + p
-    uint32_t segId = 0xFFFFFFFFu, segS = 0;
+    double segT = INFINITY;
+    uint32_t segId = 0xFFFFFFFFu;
 #pragma unroll
     for (int p = 0; p < GP; ++p) {
-        const uint32_t Pv = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
-        const double flp = (double)floor_log2(Pv);
-        const double clLp = (double)ceil_log2(Pv) * L;
+        const uint32_t Pp = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
+        const double flp = (double)floor_log2(Pp);
+        const double clLp = (double)ceil_log2(Pp) * L;
         const double V2 = ((mask & (1u << 2)) && haveA) ? __builtin_fma(q[p], Aw, L) : INFINITY;
         const double V9 = ((mask & (1u << 9)) && haveA) ? __builtin_fma(flp, Aw, clLp) : INFINITY;
         const double c5 = (mask & (1u << 5)) ? best5[p] : INFINITY;
         const double V5 = wave_min(c5);
         const double V = __builtin_fmin(__builtin_fmin(V2, V5), V9);
-        if (!(V < INFINITY))
-            continue;                                  // wave-uniform
-        const int id = V2 == V ? 2 : (V5 == V ? 5 : 9);
-        int first = 0x7FFFFFFF;
-        if (id == 5) {
-            // every lane that holds V names the pass it first saw it in; lanes 0..15
-            // re-evaluate that lane's 16 candidates of the pass
-            unsigned long long holders = __ballot(c5 == V);
-            while (holders != 0) {
-                const int l = __builtin_ctzll(holders);
-                holders &= holders - 1;
-                const int c = __builtin_amdgcn_readlane(blk5[p], l);
-                const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
-                const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
-                                 value_at(si, q[p], 0.0, true) == V;
-                const unsigned long long hits = __ballot(hit);
-                if (hits != 0) {
-                    const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
-                    first = cand < first ? cand : first;
-                }
-            }
-        } else {
-            // rows 2 and 9: the first pass whose minimum of A already gives V holds the
-            // smallest such s; walk that pass in ascending order, 64 candidates at a time
-            const double mul = id == 2 ? q[p] : flp;
-            const double add = id == 2 ? L : clLp;
-            int c0 = 0;
-            const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
-            while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
-                ++c0;
-            for (int base = c0 * SWEEP_S_CHUNK; base < nv && first == 0x7FFFFFFF; base += 256) {
-                // four groups of 64 candidates per round trip to memory
-                double sdv[4], rcv[4], gsv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int si = base + 64 * u + lane;
-                    const int idx = si < nv ? si : nv - 1;
-                    sdv[u] = (double)G.s[idx];
-                    rcv[u] = S.rcp[idx];
-                    gsv[u] = gs[idx];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    double A, B, C;
-                    segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
-                    const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
-                    const unsigned long long hits = __ballot(hit);
-                    if (hits != 0 && first == 0x7FFFFFFF)
-                        first = base + 64 * u + __builtin_ctzll(hits);
-                }
-            }
-        }
-        if (lane == p) {
+        if (V < INFINITY && lane == p) {
             segT = V;
-            segId = (uint32_t)id;
-            segS = first < nv ? (uint32_t)G.s[first] : 0u;
+            segId = V2 == V ? 2u : (V5 == V ? 5u : 9u);
         }
     }
 
-    // lanes 0..GP-1 finish one cell each: unsegmented rows, arg-min, store
+    // lanes 0..GP-1 decide one Broadcast cell each: unsegmented rows, arg-min.  The segment
+    // size is looked for afterwards, and only in the cells that a segmented row wins.
     const int pi = p0 + lane;
-    if (lane >= GP || pi >= G.n_P)
-        return;
-    const uint32_t Pv = G.P[pi];
+    const bool mine = lane < GP && pi < G.n_P;
+    const uint32_t Pv = G.P[mine ? pi : G.n_P - 1];
     const double qv = (double)(Pv - 1);
     const int fli = floor_log2(Pv), cli = ceil_log2(Pv);
     const double gm = S.gm[(size_t)t * G.n_m + mi];
     const size_t plane = (size_t)G.n_m * G.n_P;
-    plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + pi;
+    plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + (mine ? pi : 0);
+    Best bc = {INFINITY, 0u, 0xFFFFFFFFu};
     if (mask & 0x3FFu) {
         const double g1 = S.g1[t];
-        store_cell(o, decide_bcast(mask, qv, (double)fli, (double)cli, gm, L, g1,
-                                   segId == 2 ? segT : INFINITY, segS,
-                                   segId == 5 ? segT : INFINITY, segS,
-                                   segId == 9 ? segT : INFINITY, segS));
+        bc = decide_bcast(mask, qv, (double)fli, (double)cli, gm, L, g1,
+                          segId == 2u ? segT : INFINITY, 0u, segId == 5u ? segT : INFINITY, 0u,
+                          segId == 9u ? segT : INFINITY, 0u);
+        const unsigned long long need =
+            __ballot(mine && (bc.id == 2u || bc.id == 5u || bc.id == 9u));
+        if (need != 0) {
+            // Row 5: every lane that holds the minimum V of process count p names the pass it
+            // first saw it in; lanes 0..15 re-evaluate that lane's 16 candidates of the pass.
+            // For the first such lane of every process count the candidates are fetched
+            // together, before any of them is used.
+            int hl[GP], hc[GP];
+            unsigned long long rest[GP];
+            double r_s[GP], r_rcp[GP], r_gs[GP];
+#pragma unroll
+            for (int p = 0; p < GP; ++p) {
+                hl[p] = hc[p] = 0;
+                rest[p] = 0;
+                r_s[p] = r_rcp[p] = r_gs[p] = 1.0;
+                if (!((need >> p) & 1ull) || __builtin_amdgcn_readlane((int)bc.id, p) != 5)
+                    continue;                              // wave-uniform
+                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
+                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
+                const unsigned long long holders = __ballot(best5[p] == V);
+                hl[p] = __builtin_ctzll(holders);
+                rest[p] = holders & (holders - 1);
+                hc[p] = __builtin_amdgcn_readlane(blk5[p], hl[p]);
+                const int si = hc[p] * SWEEP_S_CHUNK + 64 * (lane & 15) + hl[p];
+                const int idx = si < nv ? si : nv - 1;
+                r_s[p] = (double)G.s[idx];
+                r_rcp[p] = S.rcp[idx];
+                r_gs[p] = gs[idx];
+            }
+            // candidate si of this lane re-evaluated: value of the row given by (mul, add)
+            auto value_at = [&](int si, double mul, double add, bool chain_row) {
+                double A, B, C;
+                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
+                return chain_row ? __builtin_fma(mul, C, B) : __builtin_fma(mul, A, add);
+            };
+#pragma unroll
+            for (int p = 0; p < GP; ++p) {
+                if (!((need >> p) & 1ull))
+                    continue;                              // wave-uniform
+                const int id = __builtin_amdgcn_readlane((int)bc.id, p);
+                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
+                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
+                int first = 0x7FFFFFFF;
+                if (id == 5) {
+                    {
+                        const int si = hc[p] * SWEEP_S_CHUNK + 64 * lane + hl[p];
+                        double A, B, C;
+                        segment_terms(md, r_s[p], r_rcp[p], r_gs[p], L, A, B, C);
+                        const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
+                                         __builtin_fma(q[p], C, B) == V;
+                        const unsigned long long hits = __ballot(hit);
+                        if (hits != 0)
+                            first = hc[p] * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + hl[p];
+                    }
+                    unsigned long long holders = rest[p];  // further lanes that hold V (ties)
+                    while (holders != 0) {
+                        const int l = __builtin_ctzll(holders);
+                        holders &= holders - 1;
+                        const int c = __builtin_amdgcn_readlane(blk5[p], l);
+                        const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
+                        const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
+                                         value_at(si < nv ? si : nv - 1, q[p], 0.0, true) == V;
+                        const unsigned long long hits = __ballot(hit);
+                        if (hits != 0) {
+                            const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
+                            first = cand < first ? cand : first;
+                        }
+                    }
+                } else {
+                    // rows 2 and 9: the first pass whose minimum of A already gives V holds the
+                    // smallest such s; walk that pass in ascending order, 64 candidates at a time
+                    const uint32_t Pp = G.P[p0 + p];
+                    const double flp = (double)floor_log2(Pp);
+                    const double clLp = (double)ceil_log2(Pp) * L;
+                    const double mul = id == 2 ? q[p] : flp;
+                    const double add = id == 2 ? L : clLp;
+                    int c0 = 0;
+                    const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
+                    while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
+                        ++c0;
+                    for (int base = c0 * SWEEP_S_CHUNK; base < nv && first == 0x7FFFFFFF; base += 256) {
+                        // four groups of 64 candidates per round trip to memory
+                        double sdv[4], rcv[4], gsv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int si = base + 64 * u + lane;
+                            const int idx = si < nv ? si : nv - 1;
+                            sdv[u] = (double)G.s[idx];
+                            rcv[u] = S.rcp[idx];
+                            gsv[u] = gs[idx];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            double A, B, C;
+                            segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
+                            const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
+                            const unsigned long long hits = __ballot(hit);
+                            if (hits != 0 && first == 0x7FFFFFFF)
+                                first = base + 64 * u + __builtin_ctzll(hits);
+                        }
+                    }
+                }
+                if (lane == p)
+                    bc.s = first < nv ? (uint32_t)G.s[first] : 0u;
+            }
+        }
+        if (mine)
+            store_cell(o, bc);
         o += plane;
     }
+    if (!mine)
+        return;
     if (mask & 0x1C00u) {
         const double s11 = (mask & (1u << 11)) ? chain_sum_of(G, S, t, mi, pi, Pv) : 0.0;
         const double s12 = (mask & (1u << 12))
