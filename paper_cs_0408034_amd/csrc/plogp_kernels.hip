@@ -999,17 +999,16 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
     }
     const double R = __builtin_fma(3.0, L, 2.0 * g1);   // rendezvous: 2 g(1) + 3 L
     Best b = {INFINITY, 0u, 0xFFFFFFFFu};
-    const bool twin_wins = true;
+    // a rendezvous row (1, 4, 8) is evaluated only when its plain twin (0, 3, 7) is masked out
     if (mask & (1u << 0)) consider(b, __builtin_fma(q, gm, L), 0, 0);
-    if ((mask & 2u) && !((mask & 1u) && twin_wins)) consider(b, __builtin_fma(q, gm, R), 1, 0);
+    if ((mask & 3u) == 2u) consider(b, __builtin_fma(q, gm, R), 1, 0);
     if (mask & (1u << 2)) consider(b, t2, 2, s2);
     if (mask & (1u << 3)) consider(b, q * (gm + L), 3, 0);
-    if ((mask & 0x10u) && !((mask & 8u) && twin_wins)) consider(b, q * (gm + R), 4, 0);
+    if ((mask & 0x18u) == 0x10u) consider(b, q * (gm + R), 4, 0);
     if (mask & (1u << 5)) consider(b, t5, 5, s5);
     if (mask & (1u << 6)) consider(b, cl * __builtin_fma(2.0, gm, L), 6, 0);
     if (mask & (1u << 7)) consider(b, __builtin_fma(fl, gm, clL), 7, 0);
-    if ((mask & 0x100u) && !((mask & 0x80u) && twin_wins))
-        consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
+    if ((mask & 0x180u) == 0x100u) consider(b, __builtin_fma(fl, gm, cl * R), 8, 0);
     if (mask & (1u << 9)) consider(b, t9, 9, s9);
     return b;
 }
