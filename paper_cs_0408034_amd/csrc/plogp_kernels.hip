@@ -1770,28 +1770,8 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
             // first saw it in; lanes 0..15 re-evaluate that lane's 16 candidates of the pass.
             // For the first such lane of every process count the candidates are fetched
             // together, before any of them is used.
-            int hl[GP], hc[GP];
-            unsigned long long rest[GP];
-            double r_s[GP], r_rcp[GP], r_gs[GP];
-#pragma unroll
-            for (int p = 0; p < GP; ++p) {
-                hl[p] = hc[p] = 0;
-                rest[p] = 0;
-                r_s[p] = r_rcp[p] = r_gs[p] = 1.0;
-                if (!((need >> p) & 1ull) || __builtin_amdgcn_readlane((int)bc.id, p) != 5)
-                    continue;                              // wave-uniform
-                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
-                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
-                const unsigned long long holders = __ballot(best5[p] == V);
-                hl[p] = __builtin_ctzll(holders);
-                rest[p] = holders & (holders - 1);
-                hc[p] = __builtin_amdgcn_readlane(blk5[p], hl[p]);
-                const int si = hc[p] * SWEEP_S_CHUNK + 64 * (lane & 15) + hl[p];
-                const int idx = si < nv ? si : nv - 1;
-                r_s[p] = (double)G.s[idx];
-                r_rcp[p] = S.rcp[idx];
-                r_gs[p] = gs[idx];
-            }
+            // (GB process counts at a time, to bound the registers that the fetched candidates take)
+            constexpr int GB = 6;
             // candidate si of this lane re-evaluated: value of the row given by (mul, add)
             auto value_at = [&](int si, double mul, double add, bool chain_row) {
                 double A, B, C;
@@ -1799,7 +1779,31 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 return chain_row ? __builtin_fma(mul, C, B) : __builtin_fma(mul, A, add);
             };
 #pragma unroll
-            for (int p = 0; p < GP; ++p) {
+            for (int g0 = 0; g0 < GP; g0 += GB) {
+            int hl[GB], hc[GB];
+            unsigned long long rest[GB];
+            double r_s[GB], r_rcp[GB], r_gs[GB];
+#pragma unroll
+            for (int p = g0; p < g0 + GB && p < GP; ++p) {
+                hl[p - g0] = hc[p - g0] = 0;
+                rest[p - g0] = 0;
+                r_s[p - g0] = r_rcp[p - g0] = r_gs[p - g0] = 1.0;
+                if (!((need >> p) & 1ull) || __builtin_amdgcn_readlane((int)bc.id, p) != 5)
+                    continue;                              // wave-uniform
+                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
+                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
+                const unsigned long long holders = __ballot(best5[p] == V);
+                hl[p - g0] = __builtin_ctzll(holders);
+                rest[p - g0] = holders & (holders - 1);
+                hc[p - g0] = __builtin_amdgcn_readlane(blk5[p], hl[p - g0]);
+                const int si = hc[p - g0] * SWEEP_S_CHUNK + 64 * (lane & 15) + hl[p - g0];
+                const int idx = si < nv ? si : nv - 1;
+                r_s[p - g0] = (double)G.s[idx];
+                r_rcp[p - g0] = S.rcp[idx];
+                r_gs[p - g0] = gs[idx];
+            }
+#pragma unroll
+            for (int p = g0; p < g0 + GB && p < GP; ++p) {
                 if (!((need >> p) & 1ull))
                     continue;                              // wave-uniform
                 const int id = __builtin_amdgcn_readlane((int)bc.id, p);
@@ -1808,16 +1812,16 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 int first = 0x7FFFFFFF;
                 if (id == 5) {
                     {
-                        const int si = hc[p] * SWEEP_S_CHUNK + 64 * lane + hl[p];
+                        const int si = hc[p - g0] * SWEEP_S_CHUNK + 64 * lane + hl[p - g0];
                         double A, B, C;
-                        segment_terms(md, r_s[p], r_rcp[p], r_gs[p], L, A, B, C);
+                        segment_terms(md, r_s[p - g0], r_rcp[p - g0], r_gs[p - g0], L, A, B, C);
                         const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
                                          __builtin_fma(q[p], C, B) == V;
                         const unsigned long long hits = __ballot(hit);
                         if (hits != 0)
-                            first = hc[p] * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + hl[p];
+                            first = hc[p - g0] * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + hl[p - g0];
                     }
-                    unsigned long long holders = rest[p];  // further lanes that hold V (ties)
+                    unsigned long long holders = rest[p - g0];  // further lanes that hold V (ties)
                     while (holders != 0) {
                         const int l = __builtin_ctzll(holders);
                         holders &= holders - 1;
@@ -1867,6 +1871,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 }
                 if (lane == p)
                     bc.s = first < nv ? (uint32_t)G.s[first] : 0u;
+            }
             }
         }
         if (mine)
@@ -2771,7 +2776,7 @@ struct plogp_score_dev {
 // Per strategy row: the per-m sums added in ascending m from +0.0.  One workgroup
 // per row: 1024 per-m results are loaded side by side into LDS and thread 0 adds them
 // in order while the next 1024 are in flight.
-__global__ void __launch_bounds__(1024) k_score_final(DeviceGrid G, int n_ids, const double *rows,
+__global__ void __launch_bounds__(1024) k_score_final(DeviceGrid G, const double *rows,
                                                       plogp_score_dev *score)
 {
     __shared__ double part[1024];
@@ -3187,7 +3192,7 @@ hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scrat
     for (int r = 0; r < reps; ++r) {
         hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids,
                            d_meas, d_pred, rows);
-        hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, n_ids, rows,
+        hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, rows,
                            reinterpret_cast<plogp_score_dev *>(d_scores));
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
