@@ -1725,30 +1725,39 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     if (!has_work)
         return;
 
-    // per process count of the group: the best segmented row and its time (lane p keeps those
-    // of process count p0 + p)
+    // The minimum of row 5 over the lanes, for all process counts of the group at once: the
+    // lanes leave their minima in LDS (the candidate buffers are free now, every wave has
+    // passed the last barrier), lane p reads the 64 minima of process count p0 + p (skewed,
+    // so that the lanes hit different banks) and keeps their minimum.
     const double Aw = (mask & 0x204u) ? wave_min(amin) : INFINITY;
     const bool haveA = Aw < INFINITY;
-    double segT = INFINITY;
-    uint32_t segId = 0xFFFFFFFFu;
+    double V5 = INFINITY;
+    if (mask & (1u << 5)) {
+        static_assert(GP <= 12, "columns of the reduction buffer");
+        double *lo = reinterpret_cast<double *>(&AB[0][0]) + wave * 512;     // columns 0..7
+        double *hi = &Cs[0][0] + wave * 256;                                 // columns 8..11
 #pragma unroll
-    for (int p = 0; p < GP; ++p) {
-        const uint32_t Pp = (p0 + p < G.n_P) ? G.P[p0 + p] : 2u;
-        const double flp = (double)floor_log2(Pp);
-        const double clLp = (double)ceil_log2(Pp) * L;
-        const double V2 = ((mask & (1u << 2)) && haveA) ? __builtin_fma(q[p], Aw, L) : INFINITY;
-        const double V9 = ((mask & (1u << 9)) && haveA) ? __builtin_fma(flp, Aw, clLp) : INFINITY;
-        const double c5 = (mask & (1u << 5)) ? best5[p] : INFINITY;
-        const double V5 = wave_min(c5);
-        const double V = __builtin_fmin(__builtin_fmin(V2, V5), V9);
-        if (V < INFINITY && lane == p) {
-            segT = V;
-            segId = V2 == V ? 2u : (V5 == V ? 5u : 9u);
+        for (int p = 0; p < GP; ++p)
+            (p < 8 ? lo + 64 * p : hi + 64 * (p - 8))[lane] = best5[p];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < GP) {
+            const double *col = lane < 8 ? lo + 64 * lane : hi + 64 * (lane - 8);
+            for (int j0 = 0; j0 < 64; j0 += 16) {
+                double v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    v[u] = col[(j0 + u + lane) & 63];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    V5 = min_f64(V5, v[u]);
+            }
         }
     }
 
-    // lanes 0..GP-1 decide one Broadcast cell each: unsegmented rows, arg-min.  The segment
-    // size is looked for afterwards, and only in the cells that a segmented row wins.
+    // lanes 0..GP-1 decide one Broadcast cell each: the segmented rows' minima, the
+    // unsegmented rows, arg-min.  The segment size is looked for afterwards, and only in
+    // the cells that a segmented row wins.
     const int pi = p0 + lane;
     const bool mine = lane < GP && pi < G.n_P;
     const uint32_t Pv = G.P[mine ? pi : G.n_P - 1];
@@ -1760,9 +1769,10 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     Best bc = {INFINITY, 0u, 0xFFFFFFFFu};
     if (mask & 0x3FFu) {
         const double g1 = S.g1[t];
-        bc = decide_bcast(mask, qv, (double)fli, (double)cli, gm, L, g1,
-                          segId == 2u ? segT : INFINITY, 0u, segId == 5u ? segT : INFINITY, 0u,
-                          segId == 9u ? segT : INFINITY, 0u);
+        const double t2 = ((mask & (1u << 2)) && haveA) ? __builtin_fma(qv, Aw, L) : INFINITY;
+        const double t9 = ((mask & (1u << 9)) && haveA)
+                              ? __builtin_fma((double)fli, Aw, (double)cli * L) : INFINITY;
+        bc = decide_bcast(mask, qv, (double)fli, (double)cli, gm, L, g1, t2, 0u, V5, 0u, t9, 0u);
         const unsigned long long need =
             __ballot(mine && (bc.id == 2u || bc.id == 5u || bc.id == 9u));
         if (need != 0) {
