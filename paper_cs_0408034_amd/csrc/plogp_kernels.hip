@@ -1727,27 +1727,30 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 
     // The minimum of row 5 over the lanes, for all process counts of the group at once: the
     // lanes leave their minima in LDS (the candidate buffers are free now, every wave has
-    // passed the last barrier), lane p reads the 64 minima of process count p0 + p (skewed,
-    // so that the lanes hit different banks) and keeps their minimum.
+    // passed the last barrier), lane p reads the 64 minima of process count p0 + p (the
+    // columns are 65 apart where they fit, so that the lanes hit different banks) and keeps
+    // their minimum.
     const double Aw = (mask & 0x204u) ? wave_min(amin) : INFINITY;
     const bool haveA = Aw < INFINITY;
     double V5 = INFINITY;
     if (mask & (1u << 5)) {
         static_assert(GP <= 12, "columns of the reduction buffer");
-        double *lo = reinterpret_cast<double *>(&AB[0][0]) + wave * 512;     // columns 0..7
-        double *hi = &Cs[0][0] + wave * 256;                                 // columns 8..11
+        // per wave 512 doubles of AB and 256 of Cs: 7 + 3 padded columns, or 8 + 4 plain ones
+        constexpr int LD = GP <= 10 ? 65 : 64, NLO = GP <= 10 ? 7 : 8;
+        double *lo = reinterpret_cast<double *>(&AB[0][0]) + wave * 512;
+        double *hi = &Cs[0][0] + wave * 256;
 #pragma unroll
         for (int p = 0; p < GP; ++p)
-            (p < 8 ? lo + 64 * p : hi + 64 * (p - 8))[lane] = best5[p];
+            (p < NLO ? lo + LD * p : hi + LD * (p - NLO))[lane] = best5[p];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         if (lane < GP) {
-            const double *col = lane < 8 ? lo + 64 * lane : hi + 64 * (lane - 8);
+            const double *col = lane < NLO ? lo + LD * lane : hi + LD * (lane - NLO);
             for (int j0 = 0; j0 < 64; j0 += 16) {
                 double v[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u)
-                    v[u] = col[(j0 + u + lane) & 63];
+                    v[u] = col[j0 + u];
 #pragma unroll
                 for (int u = 0; u < 16; ++u)
                     V5 = min_f64(V5, v[u]);
