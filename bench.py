@@ -66,7 +66,7 @@ def describe(wl):
 # kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
 MEASURED_TRAFFIC = {
     2: {"chain_blocks": 0.247e6 + 7.689e6, "sweep": 8.523e6 + 33.585e6},
-    3: {"chain_blocks": 0.741e6 + 1.438e6, "chain_prefix": 0.589e6 + 0.565e6, "sweep": 4.040e6 + 2.294e6},
+    3: {"chain_blocks": 0.741e6 + 1.438e6, "chain_prefix": 0.589e6 + 0.565e6, "sweep": 4.001e6 + 2.294e6},
     4: {"terms": 87.335e6 + 10.560e6 + 0.131e6 + 0.176e6, "sweep": 86.168e6 + 2005.225e6},
     5: {"terms": 0.683e6 + 1.988e6, "chain_blocks": 1.164e6 + 71.274e6,
         "chain_prefix": 50.954e6 + 18.569e6, "sweep": 54.130e6 + 93.323e6},
