@@ -136,6 +136,29 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = max(wall_ms, ev_ms) / steps
+    # the same call captured once in a HIP graph and replayed (what a caller with a launch-bound
+    # loop would do); reported beside the eager figure, never as `value`
+    graph_ms = None
+    if with_cut:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, side.cuda_stream)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        g0.record(stream)
+        for _ in range(steps):
+            graph.replay()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        graph_ms = max((time.perf_counter() - t0) * 1e3, g0.elapsed_time(g1)) / steps
+        del graph
     # per-kernel durations: every kernel launched profile_reps times back to back between two
     # HIP events on the launch stream; the median of five such rounds
     rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, profile_reps)
@@ -156,7 +179,7 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     del out
     grid.free()
     tab.free()
-    return ms_per_step, stage_ms, cut, score
+    return ms_per_step, stage_ms, cut, score, graph_ms
 
 
 CUT_STAGES = ("mark", "scan", "emit")
@@ -363,7 +386,7 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
     if mask is not None:
         wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
-    ms, stage_ms, cut, score = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
+    ms, stage_ms, cut, score, graph_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
     traffic = MEASURED_TRAFFIC.get(cfg, {}) if mask is None else {}
     if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
         # the single-kernel batch path did every stage inside one launch
@@ -386,6 +409,7 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
         "cells_per_s": c["cells"] / (ms * 1e-3),
         "scatter_chain_interps_per_s": c["scatter_chain_interps"] / (ms * 1e-3),
         "steps": steps,
+        "graph_replay_ms_per_step": graph_ms,
         "stage_ms": stage_ms,
         "roofline": roofline_of(dominant, work, stage_ms[dominant], traffic.get(dominant)),
         "stage_rooflines": {k: roofline_of(k, work, stage_ms[k], traffic.get(k))
@@ -456,6 +480,7 @@ def main():
         "config": {"workload": head["workload"]},
         "cells_per_s": head["cells_per_s"],
         "effective_evals_per_s": head["effective_evals_per_s"],
+        "graph_replay_ms_per_step": head["graph_replay_ms_per_step"],
         "stage_ms": head["stage_ms"],
         "roofline": head["roofline"],
         "stage_rooflines": head["stage_rooflines"],
