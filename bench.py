@@ -497,7 +497,7 @@ def main():
         for cfg in extras:
             if cfg == args.config:
                 continue
-            steps = 20
+            steps = 50
             line["workloads"]["cfg%d" % cfg] = bench_config(cfg, steps, 2, not args.no_cpu)
     print(json.dumps(line))
 
