@@ -24,8 +24,7 @@
  * enter a formula (m, s, k, P-1, floor/ceil log2 P, j*m, 2^j*m) are exact in
  * binary64 (callers keep them below 2^53).
  *
- * Readings of points the paper leaves open (each is a convention, stated
- * here and in the repository's design notes):
+ * Readings of points the paper leaves open (each is a convention):
  *   - g between samples: piecewise linear; below the first sample: clamped to
  *     the first gap; above the last sample: the last interval's line goes on.
  *   - k = ceil(m / s)  (the paper says "k segments"; with s | m this equals
