@@ -5,7 +5,11 @@ A step is one pass of the whole hot path (table terms, Scatter sums, sweep
 over s, arg-min over strategies, decision-table write: one plogp_tune_grid
 call) over one synthetic workload whose tables and grid are already resident
 in HBM.  The headline workload is config 2; configs 3-5 are timed too and
-reported under "workloads" in the same JSON line.
+reported under "workloads" in the same JSON line.  Beside the step, per
+workload: the same call replayed from a HIP graph, the cut-over extraction of
+the table just tuned, the scoring of predictions against synthetic
+measurements and (batches) the robustness summary, each with its own roofline
+and the oracle timed on the host.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--extra 3,4,5] [--no-cpu]
 """
