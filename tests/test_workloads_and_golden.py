@@ -67,3 +67,33 @@ def test_stored_config1_values():
         c = out[0, 0, mi, int(P) - 2]
         assert int(wl.m[mi]) == mb
         assert (int(c["strategy"]), int(c["s"]), float(c["time"])) == (sid, s, float.fromhex(r[5]))
+
+
+def test_measurement_and_perturbation_generators_are_seeded_and_model_free():
+    """The synthetic measured times and the perturbed parameter sets: reproducible, of the
+    stated shapes and ranges, and built without any of the method's arithmetic."""
+    from plogp_workloads import make_measurements, make_perturbed
+    wl = make_workload(1)
+    meas, seg = make_measurements(wl, seed=4)
+    meas2, seg2 = make_measurements(wl, seed=4)
+    n_ids = bin(wl.strategy_mask).count("1")
+    assert meas.shape == seg.shape == (n_ids, len(wl.m), len(wl.P))
+    assert meas.dtype == np.float64 and seg.dtype == np.uint32
+    assert (meas == meas2).all() and (seg == seg2).all()
+    assert not (make_measurements(wl, seed=5)[0] == meas).all()
+    assert (meas > 0).all() and np.isfinite(meas).all()
+    m = wl.m.astype(np.uint64)[None, :, None]
+    assert (seg >= 1).all() and (seg <= m).all() and (seg <= 8192).all()
+    assert ((seg & (seg - 1)) == 0).all()                       # powers of two
+    pw = make_perturbed(wl, 5, 0.1, seed=2)
+    pw2 = make_perturbed(wl, 5, 0.1, seed=2)
+    assert pw.n_tables == 6 and (pw.gaps == pw2.gaps).all() and (pw.L == pw2.L).all()
+    assert (pw.sizes == wl.sizes[0]).all() and (pw.gaps[0] == wl.gaps[0]).all() and pw.L[0] == wl.L[0]
+    ratio = pw.gaps[1:] / wl.gaps[0]
+    assert ratio.min() >= 0.9 and ratio.max() <= 1.1 and len(np.unique(ratio)) > 50
+    assert (pw.m == wl.m).all() and (pw.P == wl.P).all() and (pw.s == wl.s).all()
+    # no model inside the generator: the measured times do not depend on the table at all
+    other = make_workload(1)
+    other.gaps = other.gaps * 3.0
+    other.L = other.L * 0.5
+    assert (make_measurements(other, seed=4)[0] == meas).all()
