@@ -20,7 +20,9 @@
  * Pointers are HOST pointers unless the name starts with d_ (DEVICE).
  * Calls that enqueue work take the HIP stream as a void* (hipStream_t; NULL
  * is the default stream) and are asynchronous with respect to the host unless
- * stated otherwise.  Handles may be used from one host thread at a time.
+ * stated otherwise.  Handles may be used from one host thread at a time, and
+ * belong to the device that was current when they were created: call with
+ * that device current.
  *
  * Strategy ids (the order of the rows of Table 1, then Table 2):
  *    0 Broadcast flat tree                 7 Broadcast binomial tree

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -32,9 +33,11 @@ constexpr double kTwo53 = 9007199254740992.0;
 constexpr uint64_t kTwo53u = 1ull << 53;
 
 bool g_init_done = false;
+std::mutex g_init_mutex;
 
 int ensure_init()
 {
+    std::lock_guard<std::mutex> lock(g_init_mutex);
     if (!g_init_done) {
         int count = 0;
         HIP_TRY(hipGetDeviceCount(&count));
