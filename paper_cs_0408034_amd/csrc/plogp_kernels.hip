@@ -2302,8 +2302,13 @@ __device__ __forceinline__ V uniform_load(const V *p)
     return *(const_ptr)(p);
 }
 constexpr int BATCH_T_WAVES = 16;      // waves of a workgroup; they share the 64 tables
-constexpr int BATCH_T_PC = 4;          // cells of a table written together (64 bytes)
-constexpr int BATCH_T_PS = 12;         // process counts per pass over the candidates
+constexpr int BATCH_T_PC = 4;          // process counts decided together (in registers)
+constexpr int BATCH_T_PS = 8;          // process counts per pass over the candidates, and the
+                                       // cells of a table written together (128 bytes)
+// Output staging of a wave, used in turn as 64 rows of 8 times + 8 one-byte ids (Scatter)
+// and as 32 rows of 8 cells padded to 9 (Broadcast).
+constexpr int BATCH_T_STAGE = 64 * 72;
+static_assert(BATCH_T_STAGE >= 32 * (BATCH_T_PS + 1) * 16 && BATCH_T_STAGE % 16 == 0, "both layouts fit");
 
 struct BatchDims {
     int n, n_tables, n_m, n_P, n_s, cl_max, n_ops, n_mchunks, m_per_wave;
@@ -2313,8 +2318,13 @@ struct BatchDims {
 // A workgroup stages its 64 tables by interval in LDS (YS[i][lane] = {gap, slope}
 // of interval i of the lane's table) together with their g(s); every later
 // access to a table is one conflict-free LDS read of a whole row.  All other
-// inputs are wave-uniform and come through the scalar cache.  The cells of PC
-// process counts are turned round in LDS so that a store writes 64-byte runs.
+// inputs are wave-uniform and come through the scalar cache.  The cells of PS = 8
+// process counts are turned round in LDS so that eight neighbouring lanes store
+// the 128 contiguous bytes of one table (whole cache lines when n_P is a multiple
+// of 8: measured 5.2 TB/s against 3.3 TB/s for 64-byte runs).  LDS has room for
+// 4.5 KB of staging per wave, not for 64 rows of 8 cells: a Scatter cell is staged
+// as its time and a one-byte id (s is 0), the Broadcast cells go out in two halves
+// of 32 tables, the second half waiting in registers.
 template <int PC, int PS>
 __global__ void __launch_bounds__(64 * BATCH_T_WAVES)
 k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
@@ -2328,8 +2338,8 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     f64x2 *YS = reinterpret_cast<f64x2 *>(batch_lds);          // [n + 2][64]
     double *GS = batch_lds + (size_t)2 * (n + 2) * 64;         // [n_s][64]
     // per wave: the PC cells of 64 tables on their way out, rows padded by one cell
-    uint4 *stage_all = reinterpret_cast<uint4 *>(GS + (size_t)(n_s ? n_s : 1) * 64);
-    uint32_t *sS = reinterpret_cast<uint32_t *>(stage_all + (size_t)BATCH_T_WAVES * 64 * (PC + 1));   // [n_s]
+    char *stage_all = reinterpret_cast<char *>(GS + (size_t)(n_s ? n_s : 1) * 64);
+    uint32_t *sS = reinterpret_cast<uint32_t *>(stage_all + (size_t)BATCH_T_WAVES * BATCH_T_STAGE);   // [n_s]
     const int tg = blockIdx.x / D.n_mchunks, mc = blockIdx.x % D.n_mchunks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -2356,39 +2366,65 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     }
     __syncthreads();
     const double *gsl = GS + lane;                             // g(s) of this lane's table: gsl[64 si]
-    uint4 *stage = stage_all + (size_t)wave * 64 * (PC + 1);
-    // A store instruction writes the PC cells (PC x 16 contiguous bytes) of 64 / PC tables:
-    // lane l takes cell l % PC of table row l / PC + (64 / PC) it, it = 0 .. PC - 1.
-    static_assert(PC == 4, "64-byte runs");
-    const int out_p = lane % PC, out_row = lane / PC;
+    char *stage = stage_all + (size_t)wave * BATCH_T_STAGE;
+    // A store instruction writes the PS cells (PS x 16 contiguous bytes) of 64 / PS tables:
+    // lane l takes cell l % PS of table row l / PS + (64 / PS) it.
+    static_assert(PC == 4 && PS == 8, "128-byte runs, decided four at a time");
+    const int out_p = lane % PS, out_row = lane / PS;
     const size_t plane = (size_t)D.n_m * n_P;
     const size_t table_cells = (size_t)D.n_ops * plane;
-    // Where this lane reads the staged cells and where they go: a wave-uniform 64-bit part
-    // (table group, row step, plane, m, p0) plus a per-lane 32-bit byte offset, so that the
-    // stores need no per-lane 64-bit addresses.
-    const uint4 *stage_rd = stage + out_row * (PC + 1) + out_p;
+    // Where the staged cells go: a wave-uniform 64-bit part (table group, row step, plane, m,
+    // first process count) plus a per-lane 32-bit byte offset, so that the stores need no
+    // per-lane 64-bit addresses (the host checks that the offset fits).
     const unsigned lane_off = (unsigned)(((size_t)out_row * table_cells + out_p) * sizeof(plogp_cell_dev));
     char *const o_grp = reinterpret_cast<char *>(out + (size_t)tg * 64 * table_cells);
-    const int rows_left = D.n_tables - tg * 64 - out_row;      // rows 'it' with (64 / PC) it < rows_left exist
-    auto flush = [&](size_t cell0, int p0) {
-        // cell0: index of cell (plane, mi, p0) inside a table
+    const int rows_left = D.n_tables - tg * 64 - out_row;      // table rows r0 + out_row with r0 < rows_left exist
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    auto store_run = [&](int r0, size_t cell0, u32x4 cell) {
+        // wave-uniform base in scalar registers + 32-bit lane offset
+        char *ubase = o_grp + ((size_t)r0 * table_cells + cell0) * sizeof(plogp_cell_dev);
+        asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(cell), "s"(ubase) : "memory");
+    };
+    // cell0: index of cell (plane, mi, p0) inside a table.  Scatter layout: row r of the stage
+    // holds 8 times, then 8 ids as signed bytes (-1 = no strategy).
+    auto flush_times = [&](size_t cell0, int p0) {
         __builtin_amdgcn_wave_barrier();
         if (p0 + out_p < n_P) {
 #pragma unroll
-            for (int it = 0; it < PC; ++it) {
-                char *ubase = o_grp + ((size_t)(64 / PC) * it * table_cells + cell0) * sizeof(plogp_cell_dev);
-                if ((64 / PC) * it < rows_left) {
-                    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-                    const u32x4 cell = reinterpret_cast<const u32x4 *>(stage_rd)[(64 / PC) * it * (PC + 1)];
-                    // wave-uniform base in scalar registers + 32-bit lane offset
-                    asm volatile("global_store_dwordx4 %0, %1, %2"
-                                 :
-                                 : "v"(lane_off), "v"(cell), "s"(ubase)
-                                 : "memory");
+            for (int it = 0; it < 64 / PS; ++it) {
+                if ((64 / PS) * it < rows_left) {
+                    const char *row = stage + ((64 / PS) * it + out_row) * 72;
+                    const double tv = *reinterpret_cast<const double *>(row + 8 * out_p);
+                    const int id = *reinterpret_cast<const signed char *>(row + 64 + out_p);
+                    u32x4 cell;
+                    cell.x = (unsigned)__double2loint(tv);
+                    cell.y = (unsigned)__double2hiint(tv);
+                    cell.z = 0u;
+                    cell.w = (unsigned)id;
+                    store_run((64 / PS) * it, cell0, cell);
                 }
             }
         }
         __builtin_amdgcn_wave_barrier();
+    };
+    // Broadcast layout: row r of the stage holds the 8 cells of table 32 half + r, padded to 9.
+    auto flush_cells = [&](int half, size_t cell0, int p0) {
+        __builtin_amdgcn_wave_barrier();
+        if (p0 + out_p < n_P) {
+#pragma unroll
+            for (int it = 0; it < 32 / PS; ++it) {
+                const int r0 = 32 * half + (64 / PS) * it;
+                if (r0 < rows_left)
+                    store_run(r0, cell0,
+                              reinterpret_cast<const u32x4 *>(stage)[((64 / PS) * it + out_row) * (PS + 1) + out_p]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto pack = [](const Best &b) {
+        union { plogp_cell_dev c; uint4 v; } u;
+        u.c.time = b.t; u.c.s = b.s; u.c.strategy = b.id;
+        return u.v;
     };
     const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
     const bool has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
@@ -2445,69 +2481,67 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                     }
                 }
             }
-#pragma unroll
-            for (int g = 0; g < PS / PC; ++g) {
-                const int p0 = q0 + g * PC;
-                if (p0 >= n_P)
-                    break;
-                const size_t cell0 = (size_t)mi * n_P + p0;
-                if (has_s) {
-                    // Scatter plane, one process count after the other: the chain sum is walked
-                    // along j while P ascends, the binomial sum grows with ceil(log2 P)
+            const size_t cell0 = (size_t)mi * n_P + q0;
+            if (has_s) {
+                // Scatter plane, one process count after the other: the chain sum is walked
+                // along j while P ascends, the binomial sum grows with ceil(log2 P)
 #pragma nounroll
-                    for (int p = 0; p < PC; ++p) {
-                        const uint32_t P = uniform_load(p_P + (p0 + p < n_P ? p0 + p : n_P - 1));
-                        if (want_chain) {
-                            const unsigned target = P - 1u;
-                            while (j_done < target) {
-                                // up to the next process count, block end or interval end
-                                const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
-                                unsigned stop = target < block_end ? target : block_end;
-                                stop = stop < je ? stop : je;
-                                unsigned j = j_done;
-                                for (; j + 4u <= stop; j += 4u) {
+                for (int p = 0; p < PS; ++p) {
+                    const uint32_t P = uniform_load(p_P + (q0 + p < n_P ? q0 + p : n_P - 1));
+                    if (want_chain) {
+                        const unsigned target = P - 1u;
+                        while (j_done < target) {
+                            // up to the next process count, block end or interval end
+                            const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
+                            unsigned stop = target < block_end ? target : block_end;
+                            stop = stop < je ? stop : je;
+                            unsigned j = j_done;
+                            for (; j + 4u <= stop; j += 4u) {
 #pragma unroll
-                                    for (int r = 0; r < 4; ++r) {
-                                        run = run + __builtin_fma(cur.y, d, cur.x);
-                                        d += md;
-                                    }
-                                }
-                                for (; j < stop; ++j) {
+                                for (int r = 0; r < 4; ++r) {
                                     run = run + __builtin_fma(cur.y, d, cur.x);
                                     d += md;
                                 }
-                                j_done = stop;
-                                if (j_done % SUM_BLOCK == 0u) {
-                                    done = done + run;
-                                    run = 0.0;
-                                }
-                                while (je <= j_done) {              // the next size lies further on
-                                    d -= uniform_load(Wd + ci);
-                                    ++ci;
-                                    cur = nxt;
-                                    je = uniform_load(jend + ci);
-                                    nxt = ys[64 * (ci + 1)];
-                                }
+                            }
+                            for (; j < stop; ++j) {
+                                run = run + __builtin_fma(cur.y, d, cur.x);
+                                d += md;
+                            }
+                            j_done = stop;
+                            if (j_done % SUM_BLOCK == 0u) {
+                                done = done + run;
+                                run = 0.0;
+                            }
+                            while (je <= j_done) {              // the next size lies further on
+                                d -= uniform_load(Wd + ci);
+                                ++ci;
+                                cur = nxt;
+                                je = uniform_load(jend + ci);
+                                nxt = ys[64 * (ci + 1)];
                             }
                         }
-                        if (want_binom) {
-                            const int cli = ceil_log2(P);
-                            while (cl_done < cli) {
-                                const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
-                                s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
-                                ++cl_done;
-                            }
-                        }
-                        const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
-                                                      done + run, s12);
-                        union { plogp_cell_dev c; uint4 v; } u;
-                        u.c.time = r.t; u.c.s = r.s; u.c.strategy = r.id;
-                        stage[lane * (PC + 1) + p] = u.v;
                     }
-                    flush((has_b ? plane : 0) + cell0, p0);
+                    if (want_binom) {
+                        const int cli = ceil_log2(P);
+                        while (cl_done < cli) {
+                            const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
+                            s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
+                            ++cl_done;
+                        }
+                    }
+                    const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
+                                                  done + run, s12);
+                    *reinterpret_cast<double *>(stage + lane * 72 + 8 * p) = r.t;
+                    *reinterpret_cast<signed char *>(stage + lane * 72 + 64 + p) = (signed char)r.id;
                 }
-                if (!has_b)
-                    continue;
+                flush_times((has_b ? plane : 0) + cell0, q0);
+            }
+            if (!has_b)
+                continue;
+            Best held[PC];                                      // the first four cells of tables 32..63
+#pragma unroll
+            for (int g = 0; g < PS / PC; ++g) {
+                const int p0 = q0 + g * PC;                     // may lie past the end: indices are clamped
                 double q[PC], fl[PC], clL[PC], cl[PC];          // q, fl, cl: wave-uniform
 #pragma unroll
                 for (int p = 0; p < PC; ++p) {
@@ -2549,13 +2583,32 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                         }
                     }
                 }
+                uint4 *rows = reinterpret_cast<uint4 *>(stage);
+                if (g == 0) {
+                    if (lane < 32) {
 #pragma unroll
-                for (int p = 0; p < PC; ++p) {
-                    union { plogp_cell_dev c; uint4 v; } u;
-                    u.c.time = bc[p].t; u.c.s = bc[p].s; u.c.strategy = bc[p].id;
-                    stage[lane * (PC + 1) + p] = u.v;
+                        for (int p = 0; p < PC; ++p)
+                            rows[lane * (PS + 1) + p] = pack(bc[p]);
+                    }
+#pragma unroll
+                    for (int p = 0; p < PC; ++p)
+                        held[p] = bc[p];
+                } else {
+                    if (lane < 32) {
+#pragma unroll
+                        for (int p = 0; p < PC; ++p)
+                            rows[lane * (PS + 1) + PC + p] = pack(bc[p]);
+                    }
+                    flush_cells(0, cell0, q0);
+                    if (lane >= 32) {
+#pragma unroll
+                        for (int p = 0; p < PC; ++p) {
+                            rows[(lane - 32) * (PS + 1) + p] = pack(held[p]);
+                            rows[(lane - 32) * (PS + 1) + PC + p] = pack(bc[p]);
+                        }
+                    }
+                    flush_cells(1, cell0, q0);
                 }
-                flush(cell0, p0);
             }
         }
     }
@@ -2929,15 +2982,17 @@ bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
 static size_t batch_t_lds(int n, int n_s)
 {
     return ((size_t)2 * (n + 2) + (n_s ? n_s : 1)) * 64 * sizeof(double) +
-           (size_t)BATCH_T_WAVES * 64 * (BATCH_T_PC + 1) * 16 + (size_t)(n_s ? n_s : 1) * 4;
+           (size_t)BATCH_T_WAVES * BATCH_T_STAGE + (size_t)(n_s ? n_s : 1) * 4;
 }
 
 // Batches whose tables share their sample sizes, with enough tables to fill waves and
 // few enough samples and candidates for the LDS staging: lanes over tables.
 bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G)
 {
+    // a lane's byte offset inside a store (up to 7 tables + 7 cells on) is kept in 32 bits
+    const size_t table_cells = (size_t)G.n_ops * G.n_m * G.n_P;
     return T.shared_x && T.n_tables >= 64 && (long)T.n_tables * G.n_m >= 8192 &&
-           batch_t_lds(T.n, G.n_s) <= BATCH_T_LDS_MAX;
+           table_cells <= ((size_t)1 << 24) && batch_t_lds(T.n, G.n_s) <= BATCH_T_LDS_MAX;
 }
 
 hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,

@@ -335,6 +335,20 @@ def test_table_lane_path_ragged_many_blocks_and_masks():
         assert assert_tables_equal(gpu_tune(wl), want, "lanes over tables, mask %x" % mask)
 
 
+@pytest.mark.parametrize("n_tables,n_P", [(96, 8), (97, 3), (97, 9), (129, 12), (65, 21)])
+def test_table_lane_path_half_groups_and_short_runs(n_tables, n_P):
+    # the cells leave in runs of 8 process counts, 32 tables at a time: table counts that
+    # end at, just after and in the middle of a half group, process counts that leave the
+    # last run short or its second half empty
+    base = make_workload(4, n_tables=n_tables, table_offset=900, n_m=130)
+    P = np.unique(np.random.default_rng(n_P).integers(2, 700, size=64).astype(np.uint32))[:n_P]
+    assert len(P) == n_P
+    wl = Workload("halves", base.sizes, base.gaps, base.L, base.m, P, base.s, base.s_cap,
+                  base.strategy_mask)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "lanes over tables, %d tables x %d P" % (n_tables, n_P))
+
+
 def test_batch_whose_tables_do_not_share_sample_sizes():
     # one table of 128 sampled elsewhere: the batch must not take the path that assumes
     # shared sample sizes
