@@ -51,6 +51,7 @@ extern "C" {
 #define PLOGP_NO_STRATEGY 0xFFFFFFFFu
 #define PLOGP_MAX_SAMPLES 4096        /* largest table that fits the LDS staging */
 #define PLOGP_NO_CAP UINT64_MAX
+#define PLOGP_MAX_TIME 6.668014432879854e+240  /* 2^800: largest gap or latency of a table */
 
 enum {
     PLOGP_OK = 0,
@@ -95,8 +96,10 @@ typedef struct {
  * clamped to the first gap, above the last sample the last line continues).
  *   sizes [n_tables][n]: sample sizes in bytes, integers in [1, 2^53), strictly
  *                        increasing within a table;
- *   gaps  [n_tables][n]: g at those sizes, finite, >= 0 (need not be monotone);
- *   L     [n_tables]   : latency, finite, >= 0;
+ *   gaps  [n_tables][n]: g at those sizes, in [0, PLOGP_MAX_TIME] (need not be monotone);
+ *   L     [n_tables]   : latency, in [0, PLOGP_MAX_TIME];
+ *                        (with this bound no model value can overflow: a predicted time is
+ *                        +infinity only where no segment size competes)
  *   2 <= n <= PLOGP_MAX_SAMPLES, n_tables >= 1.
  * Synchronous.  Inputs are copied; the handle owns host and device copies and
  * is released with plogp_free_table.  Errors: EINVAL, ENOMEM, EDEVICE.

@@ -179,12 +179,12 @@ int plogp_load_tables(const double *sizes, const double *gaps, size_t n, const d
     if (!sizes || !gaps || !L || !out) return PLOGP_EINVAL;
     if (n < 2 || n > PLOGP_MAX_SAMPLES || n_tables < 1 || n_tables > (1u << 24)) return PLOGP_EINVAL;
     for (size_t t = 0; t < n_tables; ++t) {
-        if (!(isfinite(L[t]) && L[t] >= 0.0)) return PLOGP_EINVAL;
+        if (!(L[t] >= 0.0 && L[t] <= PLOGP_MAX_TIME)) return PLOGP_EINVAL;
         const double *x = sizes + t * n, *y = gaps + t * n;
         for (size_t i = 0; i < n; ++i) {
             if (!(x[i] >= 1.0 && x[i] < kTwo53) || x[i] != floor(x[i])) return PLOGP_EINVAL;
             if (i > 0 && !(x[i] > x[i - 1])) return PLOGP_EINVAL;
-            if (!(isfinite(y[i]) && y[i] >= 0.0)) return PLOGP_EINVAL;
+            if (!(y[i] >= 0.0 && y[i] <= PLOGP_MAX_TIME)) return PLOGP_EINVAL;
         }
     }
     int rc = ensure_init();

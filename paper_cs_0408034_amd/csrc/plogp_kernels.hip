@@ -102,10 +102,8 @@ __device__ __forceinline__ LdsTable stage_table(double *lds, const DeviceTables 
 // ---------------------------------------------------------------- integer terms
 
 __device__ __forceinline__ int floor_log2(uint32_t P) { return 31 - __clz((int)P); }
-__device__ __forceinline__ int ceil_log2(uint32_t P)
-{
-    return floor_log2(P) + ((P & (P - 1)) != 0 ? 1 : 0);
-}
+// P >= 1: the bit length of P - 1 (__clz(0) is 32)
+__device__ __forceinline__ int ceil_log2(uint32_t P) { return 32 - __clz((int)(P - 1u)); }
 
 // k = ceil(m / s) for integers below 2^53: the rounded quotient of two such
 // integers cannot reach or cross an integer it is not equal to (its error is
@@ -973,24 +971,20 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
     // monotone a rendezvous row is never below its twin; with the twin enabled (lower id:
     // it also wins ties) the rendezvous row cannot be chosen and is not evaluated.
     if ((mask & 0x3FFu) == 0x3FFu) {
-        // the usual case, every row enabled: rows 0, 2, 3, 5, 6, 7, 9 compete; the running
-        // minimum and the id of the first row that attains it
+        // the usual case, every row enabled: rows 0, 2, 3, 5, 6, 7, 9 compete; the minimum,
+        // then the lowest id that attains it (the compares do not depend on one another and
+        // no partial minimum stays live)
         const double v0 = __builtin_fma(q, gm, L), v3 = q * (gm + L);
         const double v6 = cl * __builtin_fma(2.0, gm, L), v7 = __builtin_fma(fl, gm, clL);
-        double best = v0;
-        uint32_t id = 0u;
-        id = t2 < best ? 2u : id;
-        best = min_f64(best, t2);
-        id = v3 < best ? 3u : id;
-        best = min_f64(best, v3);
-        id = t5 < best ? 5u : id;
-        best = min_f64(best, t5);
-        id = v6 < best ? 6u : id;
-        best = min_f64(best, v6);
-        id = v7 < best ? 7u : id;
-        best = min_f64(best, v7);
-        id = t9 < best ? 9u : id;
-        best = min_f64(best, t9);
+        const double best =
+            min_f64(min_f64(min_f64(v0, t2), min_f64(v3, t5)), min_f64(min_f64(v6, v7), t9));
+        uint32_t id = 9u;
+        id = v7 == best ? 7u : id;
+        id = v6 == best ? 6u : id;
+        id = t5 == best ? 5u : id;
+        id = v3 == best ? 3u : id;
+        id = t2 == best ? 2u : id;
+        id = v0 == best ? 0u : id;
         Best b;
         b.t = best;
         b.id = id;
@@ -1017,6 +1011,16 @@ __device__ __forceinline__ Best decide_bcast(uint32_t mask, double q, double fl,
 __device__ __forceinline__ Best decide_scatter(uint32_t mask, double q, double cl, double gm,
                                                double L, double s11, double s12)
 {
+    if ((mask & 0x1C00u) == 0x1C00u) {
+        // every row enabled: the minimum, then the lowest id that attains it
+        const double v10 = __builtin_fma(q, gm, L), v11 = __builtin_fma(q, L, s11);
+        const double v12 = __builtin_fma(cl, L, s12);
+        Best b;
+        b.t = min_f64(min_f64(v10, v11), v12);
+        b.s = 0u;
+        b.id = v10 == b.t ? 10u : (v11 == b.t ? 11u : 12u);
+        return b;
+    }
     Best b = {INFINITY, 0u, 0xFFFFFFFFu};
     if (mask & (1u << 10)) consider(b, __builtin_fma(q, gm, L), 10, 0);
     if (mask & (1u << 11)) consider(b, __builtin_fma(q, L, s11), 11, 0);
@@ -2325,7 +2329,8 @@ struct BatchDims {
 // 4.5 KB of staging per wave, not for 64 rows of 8 cells: a Scatter cell is staged
 // as its time and a one-byte id (s is 0), the Broadcast cells go out in two halves
 // of 32 tables, the second half waiting in registers.
-template <int PC, int PS>
+// ALL: every strategy is enabled (the mask is a compile-time constant).
+template <int PC, int PS, bool ALL>
 __global__ void __launch_bounds__(64 * BATCH_T_WAVES)
 k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
           const double *__restrict__ recs, const double *__restrict__ tab,
@@ -2346,7 +2351,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     const int t = tg * 64 + lane;
     const int tc = t < D.n_tables ? t : D.n_tables - 1;
     const double L = Lt[tc];
-    const uint32_t mask = D.mask;
+    const uint32_t mask = ALL ? 0x1FFFu : D.mask;
     for (int si = threadIdx.x; si < n_s; si += blockDim.x)
         sS[si] = (uint32_t)p_s[si];
     for (int i = wave; i < n + 2; i += BATCH_T_WAVES)
@@ -2458,29 +2463,6 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         // PS process counts per pass over the candidates (the per-candidate terms are formed
         // once for all of them), then PC cells at a time are decided and written
         for (int q0 = 0; q0 < n_P; q0 += PS) {
-            double b5[PS];
-            int i5[PS];
-#pragma unroll
-            for (int p = 0; p < PS; ++p) {
-                b5[p] = INFINITY;
-                i5[p] = 0;
-            }
-            if (has_b && (mask & (1u << 5))) {
-                double q[PS];                                   // wave-uniform
-#pragma unroll
-                for (int p = 0; p < PS; ++p)
-                    q[p] = uniform_load(tab_P + 3 * (q0 + p < n_P ? q0 + p : n_P - 1));
-                for (int si = 0; si < nvm; ++si) {
-                    const double gs = gsl[64 * si], k = uniform_load(Krow + si);
-                    const double Bv = gs * (k - 1.0), Cv = gs + L;
-#pragma unroll
-                    for (int p = 0; p < PS; ++p) {
-                        const double T5 = __builtin_fma(q[p], Cv, Bv);
-                        i5[p] = T5 < b5[p] ? si : i5[p];
-                        b5[p] = min_f64(b5[p], T5);
-                    }
-                }
-            }
             const size_t cell0 = (size_t)mi * n_P + q0;
             if (has_s) {
                 // Scatter plane, one process count after the other: the chain sum is walked
@@ -2538,6 +2520,29 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
             }
             if (!has_b)
                 continue;
+            double b5[PS];
+            int i5[PS];
+#pragma unroll
+            for (int p = 0; p < PS; ++p) {
+                b5[p] = INFINITY;
+                i5[p] = 0;
+            }
+            if (has_b && (mask & (1u << 5))) {
+                double q[PS];                                   // wave-uniform
+#pragma unroll
+                for (int p = 0; p < PS; ++p)
+                    q[p] = uniform_load(tab_P + 3 * (q0 + p < n_P ? q0 + p : n_P - 1));
+                for (int si = 0; si < nvm; ++si) {
+                    const double gs = gsl[64 * si], k = uniform_load(Krow + si);
+                    const double Bv = gs * (k - 1.0), Cv = gs + L;
+#pragma unroll
+                    for (int p = 0; p < PS; ++p) {
+                        const double T5 = __builtin_fma(q[p], Cv, Bv);
+                        i5[p] = T5 < b5[p] ? si : i5[p];
+                        b5[p] = min_f64(b5[p], T5);
+                    }
+                }
+            }
             Best held[PC];                                      // the first four cells of tables 32..63
 #pragma unroll
             for (int g = 0; g < PS / PC; ++g) {
@@ -2935,7 +2940,10 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
     return e;
 }
@@ -3039,8 +3047,10 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
         D.n = T.n; D.n_tables = T.n_tables; D.n_m = G.n_m; D.n_P = G.n_P; D.n_s = G.n_s;
         D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = n_mchunks; D.m_per_wave = m_per_wave;
         D.mask = G.mask;
+        const auto kern = G.mask == 0x1FFFu ? k_batch_t<BATCH_T_PC, BATCH_T_PS, true>
+                                            : k_batch_t<BATCH_T_PC, BATCH_T_PS, false>;
         for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL((k_batch_t<BATCH_T_PC, BATCH_T_PS>), dim3((unsigned)n_tg * n_mchunks),
+            hipLaunchKernelGGL(kern, dim3((unsigned)n_tg * n_mchunks),
                                dim3(64 * BATCH_T_WAVES), lds, st, D,
                                reinterpret_cast<const f64x2 *>(S.batch_ys), T.L, S.batch.rec, S.batch.tab,
                                G.P, reinterpret_cast<const u64 *>(G.s), d_out);

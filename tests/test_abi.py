@@ -61,6 +61,8 @@ GOOD_Y = [1.0, 2.0, 3.0]
     ([1.0, 8.0], [1.0, float("nan")], 1.0),            # NaN gap
     ([1.0, 8.0], [1.0, -2.0], 1.0),                    # negative gap
     ([1.0, 8.0], [1.0, float("inf")], 1.0),
+    ([1.0, 8.0], [1.0, 2.0 ** 801], 1.0),              # a gap so large that a model could overflow
+    (GOOD_X, GOOD_Y, 2.0 ** 801),
     ([1.0, 1.0], [1.0, 2.0], 1.0),                     # sizes not strictly increasing
     ([8.0, 1.0], [1.0, 2.0], 1.0),
     ([0.0, 8.0], [1.0, 2.0], 1.0),                     # size below one byte
