@@ -54,7 +54,7 @@ struct DeviceGrid {
 
 // Facts about where the grid's sizes fall among the samples, for batches whose
 // tables share their sample sizes (the same for every table; written by
-// k_batch_prep).  Intervals: 0 = below the first sample, i + 1 = from sample i on.
+// k_batch_setup).  Intervals: 0 = below the first sample, i + 1 = from sample i on.
 struct BatchPrep {
     double *rec;      // [n_m][BatchRec::slots]  everything about one message size (see BatchRec)
     double *tab;      // [2 + (n+1) + 2 n_s + 3 n_P]  interval of size 1 and 1 minus its start; widths

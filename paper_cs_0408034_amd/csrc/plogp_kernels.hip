@@ -2178,15 +2178,15 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
 // flow is wave-uniform (no lane ever waits for another lane's interval
 // crossing), the table entries are read as coalesced rows of a copy laid out
 // [interval][table], and the per-m facts come from small tables prepared once
-// per call by k_batch_prep.
+// per call by k_batch_setup.
 
 // One thread per entry of the prepared facts.  Uses table 0's sample sizes.
 // Intervals are numbered as in the chain walk: 0 = [0, x_0) (the clamp: gap y_0,
 // slope 0), i + 1 = [x_i, x_{i+1}), n = [x_{n-1}, inf).  Everything about one
 // message size sits in one record of B.rec (layout: BatchRec).
-__global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G, BatchPrep B)
+__device__ __forceinline__ void batch_prep_body(const DeviceTables &T, const DeviceGrid &G,
+                                                const BatchPrep &B, int block, int n_blocks, double *lds)
 {
-    extern __shared__ double lds[];
     const int n = T.n;
     double *x = lds;                              // samples of table 0
     for (int i = threadIdx.x; i < n; i += blockDim.x)
@@ -2199,8 +2199,8 @@ __global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G
         dz = cnt == 0 ? z : z - x[cnt - 1];
     };
     const BatchRec R(n, G.n_s, G.cl_max);
-    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long stride = (long)gridDim.x * blockDim.x;
+    const long tid = (long)block * blockDim.x + threadIdx.x;
+    const long stride = (long)n_blocks * blockDim.x;
     for (long e = tid; e < G.n_m; e += stride) {
         double *rec = B.rec + (size_t)e * R.slots;
         const u64 m = G.m[e];
@@ -2276,22 +2276,44 @@ __global__ void __launch_bounds__(256) k_batch_prep(DeviceTables T, DeviceGrid G
 
 // The tables laid out by interval: ysT[i][t] = {gap, slope} of interval i of table t
 // (i = 0: the clamp {y_0, 0}; i = n + 1: zeros, only ever fetched ahead).  The slopes
-// are formed here from the raw samples.
-__global__ void __launch_bounds__(256) k_batch_stage(DeviceTables T, f64x2 *ysT)
+// are formed here from the raw samples.  A workgroup takes BATCH_STAGE_TT tables: their
+// gaps are read as whole rows into LDS (rows padded by one), then written with the
+// tables along the lanes.  The sample sizes are those of table 0 (shared by all).
+constexpr int BATCH_STAGE_TT = 32;
+
+__device__ __forceinline__ void batch_stage_body(const DeviceTables &T, f64x2 *ysT, int block, double *lds)
 {
-    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = T.n;
-    const long total = (long)(n + 2) * T.n_tables;
-    if (e >= total)
-        return;
-    const int i = (int)(e / T.n_tables), t = (int)(e % T.n_tables);
-    const double *x = T.x + (size_t)t * n, *y = T.y + (size_t)t * n;
-    f64x2 v = {0.0, 0.0};
-    if (i == 0)
-        v = f64x2{y[0], 0.0};
-    else if (i <= n)
-        v = f64x2{y[i - 1], interval_slope(x, y, n, i - 1)};
-    ysT[e] = v;
+    const int n = T.n, t0 = block * BATCH_STAGE_TT;
+    const int nt = T.n_tables - t0 < BATCH_STAGE_TT ? T.n_tables - t0 : BATCH_STAGE_TT;
+    for (int e = threadIdx.x; e < nt * n; e += blockDim.x) {
+        const int tl = e / n, i = e - tl * n;
+        lds[tl * (n + 1) + i] = T.y[(size_t)(t0 + tl) * n + i];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < (n + 2) * BATCH_STAGE_TT; e += blockDim.x) {
+        const int i = e / BATCH_STAGE_TT, tl = e % BATCH_STAGE_TT;
+        if (tl >= nt)
+            continue;
+        const double *y = lds + tl * (n + 1);
+        f64x2 v = {0.0, 0.0};
+        if (i == 0)
+            v = f64x2{y[0], 0.0};
+        else if (i <= n)
+            v = f64x2{y[i - 1], interval_slope(T.x, y, n, i - 1)};
+        ysT[(size_t)i * T.n_tables + t0 + tl] = v;
+    }
+}
+
+// One launch for both preparations: the first n_stage workgroups lay out the tables, the
+// others prepare the per-size facts.
+__global__ void __launch_bounds__(256) k_batch_setup(DeviceTables T, DeviceGrid G, BatchPrep B,
+                                                     f64x2 *ysT, int n_stage)
+{
+    extern __shared__ double lds[];
+    if ((int)blockIdx.x < n_stage)
+        batch_stage_body(T, ysT, (int)blockIdx.x, lds);
+    else
+        batch_prep_body(T, G, B, (int)blockIdx.x - n_stage, (int)gridDim.x - n_stage, lds);
 }
 
 constexpr size_t BATCH_T_LDS_MAX = 160 * 1024;     // LDS of a compute unit
@@ -2345,7 +2367,10 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     // per wave: the PC cells of 64 tables on their way out, rows padded by one cell
     char *stage_all = reinterpret_cast<char *>(GS + (size_t)(n_s ? n_s : 1) * 64);
     uint32_t *sS = reinterpret_cast<uint32_t *>(stage_all + (size_t)BATCH_T_WAVES * BATCH_T_STAGE);   // [n_s]
-    const int tg = blockIdx.x / D.n_mchunks, mc = blockIdx.x % D.n_mchunks;
+    // the chunks of large sizes (more candidates, the longest) are handed out first, so that
+    // the launch ends with short workgroups
+    const int n_tg = (D.n_tables + 63) / 64;
+    const int tg = blockIdx.x % n_tg, mc = D.n_mchunks - 1 - (int)(blockIdx.x / n_tg);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int t = tg * 64 + lane;
@@ -2385,28 +2410,41 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     char *const o_grp = reinterpret_cast<char *>(out + (size_t)tg * 64 * table_cells);
     const int rows_left = D.n_tables - tg * 64 - out_row;      // table rows r0 + out_row with r0 < rows_left exist
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    auto store_run = [&](int r0, size_t cell0, u32x4 cell) {
-        // wave-uniform base in scalar registers + 32-bit lane offset
-        char *ubase = o_grp + ((size_t)r0 * table_cells + cell0) * sizeof(plogp_cell_dev);
+    // wave-uniform base in scalar registers + 32-bit lane offset
+    auto store_run = [&](char *ubase, u32x4 cell) {
         asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(cell), "s"(ubase) : "memory");
     };
+    const size_t run_step = (size_t)(64 / PS) * table_cells * sizeof(plogp_cell_dev);   // 8 tables on
+    const bool whole_group = tg * 64 + 64 <= D.n_tables;       // wave-uniform: no row of tables is missing
     // cell0: index of cell (plane, mi, p0) inside a table.  Scatter layout: row r of the stage
     // holds 8 times, then 8 ids as signed bytes (-1 = no strategy).
+    auto scatter_cell = [&](int r0) {
+        const char *row = stage + (r0 + out_row) * 72;
+        const double tv = *reinterpret_cast<const double *>(row + 8 * out_p);
+        const int id = *reinterpret_cast<const signed char *>(row + 64 + out_p);
+        u32x4 cell;
+        cell.x = (unsigned)__double2loint(tv);
+        cell.y = (unsigned)__double2hiint(tv);
+        cell.z = 0u;
+        cell.w = (unsigned)id;
+        return cell;
+    };
     auto flush_times = [&](size_t cell0, int p0) {
         __builtin_amdgcn_wave_barrier();
         if (p0 + out_p < n_P) {
+            char *ubase = o_grp + cell0 * sizeof(plogp_cell_dev);
+            if (whole_group) {
 #pragma unroll
-            for (int it = 0; it < 64 / PS; ++it) {
-                if ((64 / PS) * it < rows_left) {
-                    const char *row = stage + ((64 / PS) * it + out_row) * 72;
-                    const double tv = *reinterpret_cast<const double *>(row + 8 * out_p);
-                    const int id = *reinterpret_cast<const signed char *>(row + 64 + out_p);
-                    u32x4 cell;
-                    cell.x = (unsigned)__double2loint(tv);
-                    cell.y = (unsigned)__double2hiint(tv);
-                    cell.z = 0u;
-                    cell.w = (unsigned)id;
-                    store_run((64 / PS) * it, cell0, cell);
+                for (int it = 0; it < 64 / PS; ++it) {
+                    store_run(ubase, scatter_cell((64 / PS) * it));
+                    ubase += run_step;
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 64 / PS; ++it) {
+                    if ((64 / PS) * it < rows_left)
+                        store_run(ubase, scatter_cell((64 / PS) * it));
+                    ubase += run_step;
                 }
             }
         }
@@ -2416,12 +2454,21 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     auto flush_cells = [&](int half, size_t cell0, int p0) {
         __builtin_amdgcn_wave_barrier();
         if (p0 + out_p < n_P) {
+            char *ubase = o_grp + ((size_t)32 * half * table_cells + cell0) * sizeof(plogp_cell_dev);
+            const u32x4 *rows = reinterpret_cast<const u32x4 *>(stage) + out_row * (PS + 1) + out_p;
+            if (whole_group) {
 #pragma unroll
-            for (int it = 0; it < 32 / PS; ++it) {
-                const int r0 = 32 * half + (64 / PS) * it;
-                if (r0 < rows_left)
-                    store_run(r0, cell0,
-                              reinterpret_cast<const u32x4 *>(stage)[((64 / PS) * it + out_row) * (PS + 1) + out_p]);
+                for (int it = 0; it < 32 / PS; ++it) {
+                    store_run(ubase, rows[(64 / PS) * it * (PS + 1)]);
+                    ubase += run_step;
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 32 / PS; ++it) {
+                    if (32 * half + (64 / PS) * it < rows_left)
+                        store_run(ubase, rows[(64 / PS) * it * (PS + 1)]);
+                    ubase += run_step;
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -3020,17 +3067,15 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const bool terms_only = d_out == nullptr;      // the staged terms and sums, no sweep
     if (!terms_only && use_table_lane_path(T, G)) {
         // tables by interval and the per-m facts, then everything else in one kernel
-        const long stage_items = (long)(T.n + 2) * T.n_tables;
-        for (int r = 0; r < reps; ++r) {
-            hipLaunchKernelGGL(k_batch_stage, dim3((unsigned)((stage_items + 255) / 256)), dim3(256), 0,
-                               st, T, reinterpret_cast<f64x2 *>(S.batch_ys));
-            long prep_items = (long)G.n_m * (T.n + 1);
-            if ((long)G.n_m * G.n_s > prep_items) prep_items = (long)G.n_m * G.n_s;
-            long prep_wg = (prep_items + 255) / 256;
-            if (prep_wg > 1024) prep_wg = 1024;
-            hipLaunchKernelGGL(k_batch_prep, dim3((unsigned)prep_wg), dim3(256),
-                               (size_t)T.n * sizeof(double), st, T, G, S.batch);
-        }
+        const int n_stage = (T.n_tables + BATCH_STAGE_TT - 1) / BATCH_STAGE_TT;
+        long prep_items = (long)G.n_m * (T.n + 1);
+        if ((long)G.n_m * G.n_s > prep_items) prep_items = (long)G.n_m * G.n_s;
+        long prep_wg = (prep_items + 255) / 256;
+        if (prep_wg > 1024) prep_wg = 1024;
+        const size_t setup_lds = (size_t)BATCH_STAGE_TT * (T.n + 1) * sizeof(double);
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_batch_setup, dim3((unsigned)(n_stage + prep_wg)), dim3(256), setup_lds,
+                               st, T, G, S.batch, reinterpret_cast<f64x2 *>(S.batch_ys), n_stage);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(1);
         PLOGP_MARK(2);
