@@ -3,7 +3,8 @@
 // neighbouring lanes, so a store instruction covers 64 / RUN tables whose rows lie one
 // whole table apart.  Shape of the batched workload: 157 x 64 tables x 2 operations x
 // 256 sizes x 24 process counts (1.98 GB).  HIP events, best of three launches.  Timing
-// only, values are arbitrary.  Not part of the library:
+// only, values are arbitrary.  Also a contiguous fill under each store cache policy.
+// Not part of the library:
 //   hipcc --offload-arch=gfx950 -O3 -o /tmp/store_patterns paper_cs_0408034_amd/csrc/store_patterns.hip
 //   /tmp/store_patterns
 #include <hip/hip_runtime.h>
@@ -71,6 +72,41 @@ int run(uint4 *d, int m_per_wave, size_t lds_bytes)
     return 0;
 }
 
+template <int POL>
+__global__ void __launch_bounds__(1024) k_contig_pol(uint4 *out, size_t n)
+{
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        u32x4 v = {(unsigned)i, 1u, 2u, 3u};
+        uint4 *p = out + i;
+        if (POL == 0) asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+        if (POL == 1) asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(p), "v"(v) : "memory");
+        if (POL == 2) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+        if (POL == 3) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+        if (POL == 4) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+    }
+}
+
+template <int POL>
+int run_pol(uint4 *d, const char *name)
+{
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    float best = 1e30f;
+    for (int rep = 0; rep < 4; ++rep) {
+        CHECK(hipEventRecord(e0, 0));
+        hipLaunchKernelGGL(k_contig_pol<POL>, dim3(4096), dim3(1024), 0, 0, d, TOTAL_CELLS);
+        CHECK(hipGetLastError());
+        CHECK(hipEventRecord(e1, 0));
+        CHECK(hipEventSynchronize(e1));
+        float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+        if (rep > 0 && ms < best) best = ms;
+    }
+    printf("contiguous, policy %-12s: %.3f ms  %.0f GB/s\n", name, best, TOTAL_CELLS * 16.0 / best * 1e-6);
+    fflush(stdout);
+    return 0;
+}
+
 int main()
 {
     uint4 *d;
@@ -91,6 +127,11 @@ int main()
         printf("contiguous, %d blocks: %.3f ms  %.0f GB/s\n", blocks, best, TOTAL_CELLS * 16.0 / best * 1e-6);
         fflush(stdout);
     }
+    if (run_pol<0>(d, "default")) return 1;
+    if (run_pol<1>(d, "nt")) return 1;
+    if (run_pol<2>(d, "sc0 sc1")) return 1;
+    if (run_pol<3>(d, "sc1")) return 1;
+    if (run_pol<4>(d, "sc0 sc1 nt")) return 1;
     for (size_t lds : {(size_t)0, (size_t)150 * 1024}) {     // 150 KB: one workgroup per CU, as in the library
         for (int mpw : {2, 8}) {
             if (run<4>(d, mpw, lds)) return 1;
