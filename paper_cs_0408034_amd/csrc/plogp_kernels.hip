@@ -2440,9 +2440,13 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                     ubase += run_step;
                 }
             } else {
+                // (the limit is made opaque here: its sixteen compares would otherwise be kept
+                // in scalar registers across the whole kernel)
+                int rl = rows_left;
+                asm volatile("" : "+v"(rl));
 #pragma unroll
                 for (int it = 0; it < 64 / PS; ++it) {
-                    if ((64 / PS) * it < rows_left)
+                    if ((64 / PS) * it < rl)
                         store_run(ubase, scatter_cell((64 / PS) * it));
                     ubase += run_step;
                 }
@@ -2463,9 +2467,11 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                     ubase += run_step;
                 }
             } else {
+                int rl = rows_left;
+                asm volatile("" : "+v"(rl));
 #pragma unroll
                 for (int it = 0; it < 32 / PS; ++it) {
-                    if (32 * half + (64 / PS) * it < rows_left)
+                    if (32 * half + (64 / PS) * it < rl)
                         store_run(ubase, rows[(64 / PS) * it * (PS + 1)]);
                     ubase += run_step;
                 }
