@@ -69,11 +69,11 @@ def describe(wl):
 # FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
 # kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
 MEASURED_TRAFFIC = {
-    2: {"chain_blocks": 0.247e6 + 7.689e6, "sweep": 8.523e6 + 33.585e6},
-    3: {"chain_blocks": 0.741e6 + 1.438e6, "chain_prefix": 0.589e6 + 0.565e6, "sweep": 4.001e6 + 2.294e6},
-    4: {"terms": 87.335e6 + 10.560e6 + 0.131e6 + 0.176e6, "sweep": 86.168e6 + 2005.225e6},
-    5: {"terms": 0.683e6 + 1.988e6, "chain_blocks": 1.164e6 + 71.274e6,
-        "chain_prefix": 50.954e6 + 18.569e6, "sweep": 54.130e6 + 93.323e6},
+    2: {"chain_blocks": 0.258e6 + 7.719e6, "sweep": 8.508e6 + 33.579e6},
+    3: {"chain_blocks": 0.749e6 + 1.438e6, "chain_prefix": 0.599e6 + 0.565e6, "sweep": 3.999e6 + 2.294e6},
+    4: {"terms": 5.283e6 + 10.736e6, "sweep": 88.979e6 + 1966.079e6},
+    5: {"terms": 0.684e6 + 2.139e6, "chain_blocks": 1.169e6 + 71.290e6,
+        "chain_prefix": 50.964e6 + 18.569e6, "sweep": 54.121e6 + 93.322e6},
 }
 # the same for the three kernels of the cut-over extraction (mark, scan1 + scan2, emit)
 MEASURED_CUT_TRAFFIC = {
