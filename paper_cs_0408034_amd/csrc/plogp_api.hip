@@ -444,7 +444,7 @@ static int ensure_batch_scratch(plogp_grid *g, size_t n_tables, size_t n)
 static int ensure_tune_scratch(const plogp_table *t, plogp_grid *g)
 {
     if (use_table_lane_path(t->view(), g->view())) return ensure_batch_scratch(g, t->n_tables, t->n);
-    if (use_fused_path(t->view(), g->view())) return PLOGP_OK;
+    if (use_fused_path(t->view(), g->view()) || use_row_path(t->view(), g->view())) return PLOGP_OK;
     return ensure_scratch(g, t->n_tables, t->n);
 }
 
@@ -489,7 +489,7 @@ int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_o
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     if (e != hipSuccess) return device_error(e);
     const bool table_lanes = use_table_lane_path(t->view(), g->view());
-    const bool fused = table_lanes || use_fused_path(t->view(), g->view());
+    const bool fused = table_lanes || use_fused_path(t->view(), g->view()) || use_row_path(t->view(), g->view());
     const bool chain = (g->mask & (1u << 11)) != 0 && !fused;
     if (fused && !table_lanes) ms[0] = 0.f;
     stage_ms_out[0] = ms[0];

@@ -158,6 +158,7 @@ hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d
 
 hipError_t kernels_init();
 bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
+bool use_row_path(const DeviceTables &T, const DeviceGrid &G);
 bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G);
 
 }  // namespace plogp

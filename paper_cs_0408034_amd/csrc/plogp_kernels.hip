@@ -2167,6 +2167,272 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
     }
 }
 
+// ---- whole path of one (table, m) row in one workgroup ------------------------
+//
+// Few candidates (one per lane of a wave) and few blocks of the Scatter-chain sum:
+// a workgroup takes one (table, m) and does every step for it, with LDS between
+// the steps instead of device memory and launches: the table and its slopes; wave
+// 0 the candidates (g(s), k, A, B, C, min A: one lane each), wave 1 g(m), g(1)
+// and the prefix of g(2^j m); all threads the terms g(j m) of the chain sum, one
+// search each; wave 0 the sums inside the blocks (a lane per block, 64 dependent
+// additions) and then over the blocks; then the waves run their lanes over the
+// process counts as in k_sweep_p: per candidate one fma and one min for row 5 of
+// Table 1, min_s A for rows 2 and 9, the winning candidate looked for only where a
+// segmented row wins, two coalesced stores per cell.
+constexpr int ROW_THREADS = 512;
+constexpr int ROW_MAX_BLK = 32;          // at most 2048 terms of the chain sum
+constexpr int ROW_NS = 64;               // candidates at most
+constexpr int ROW_SPAD = ROW_NS + 8;     // the candidate loops read up to 7 entries past the last
+constexpr int ROW_MAX_N = 512;           // samples at most (LDS per workgroup stays small)
+
+static size_t row_lds_bytes(int n, int n_blk, int n_P)
+{
+    return ((size_t)3 * n + 3 * ROW_SPAD + 36 + 36 + (size_t)n_blk * (SUM_BLOCK + 1) + 2 * ROW_MAX_BLK +
+            ROW_SPAD / 2 + (size_t)(n_P + 1) / 2) * sizeof(double);
+}
+
+// PPL: process counts per lane in the Broadcast plane.
+template <bool ALL, int PPL>
+__global__ void __launch_bounds__(ROW_THREADS) k_row(DeviceTables T, DeviceGrid G, plogp_cell_dev *out)
+{
+    extern __shared__ double lds[];
+    __shared__ double sh_gm, sh_g1, sh_amin;
+    __shared__ int sh_nv;
+    __shared__ unsigned next_group;
+    const int n = T.n, n_s = G.n_s, n_P = G.n_P, n_blk = G.n_blk;
+    const uint32_t mask = ALL ? 0x1FFFu : G.mask;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the rows of large sizes (the most candidates) first when the sizes ascend
+    const int t = (int)blockIdx.x / G.n_m, mi = G.n_m - 1 - (int)blockIdx.x % G.n_m;
+    double *x = lds, *y = x + n, *sl = y + n;
+    double *sA = sl + n, *sB = sA + ROW_SPAD, *sC = sB + ROW_SPAD;     // per candidate
+    double *sum2 = sC + ROW_SPAD, *g2 = sum2 + 36;                     // prefix of g(2^j m); its terms
+    double *pre = g2 + 36;                     // [block][65]: the terms, then the sums before each
+    double *tot = pre + (size_t)n_blk * (SUM_BLOCK + 1), *done = tot + ROW_MAX_BLK;
+    uint32_t *sSv = reinterpret_cast<uint32_t *>(done + ROW_MAX_BLK);  // the candidates
+    uint32_t *sP = sSv + ROW_SPAD;                                     // the process counts
+    // everything that comes from device memory is asked for at once
+    const u64 m = G.m[mi];
+    const double L = T.L[t];
+    const u64 my_s = wave == 0 && lane < n_s ? G.s[lane] : 0ull;
+    {
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
+        for (int i = tid; i < n; i += ROW_THREADS) {
+            x[i] = gx[i];
+            y[i] = gy[i];
+        }
+        for (int i = tid; i < n_P; i += ROW_THREADS)
+            sP[i] = G.P[i];
+        if (tid == 0)
+            next_group = 0u;
+        __syncthreads();
+        for (int i = tid; i < n; i += ROW_THREADS)
+            sl[i] = interval_slope(x, y, n, i);
+        __syncthreads();
+    }
+    const LdsTable tab = {x, y, sl, n};
+    const double md = (double)m;
+    const bool chain = (mask & (1u << 11)) != 0, binom = (mask & (1u << 12)) != 0;
+
+    if (wave == 0) {
+        double A = INFINITY, B = INFINITY, C = 0.0;
+        bool valid = false;
+        if (lane < n_s) {
+            const u64 lim = m < G.s_cap ? m : G.s_cap;
+            const double sd = (double)my_s, gs = gap_at(tab, sd);
+            C = gs + L;
+            valid = my_s <= lim;
+            if (valid) {
+                double Cx;
+                segment_terms(md, sd, 1.0 / sd, gs, L, A, B, Cx);
+            }
+        }
+        sA[lane] = A;
+        sB[lane] = B;
+        sC[lane] = C;
+        sSv[lane] = (uint32_t)my_s;
+        if (lane < ROW_SPAD - ROW_NS) {        // past the end: never taken (B = +inf, C finite)
+            sA[ROW_NS + lane] = INFINITY;
+            sB[ROW_NS + lane] = INFINITY;
+            sC[ROW_NS + lane] = 0.0;
+            sSv[ROW_NS + lane] = 0u;
+        }
+        const double amin = wave_min(A);
+        const int nv = __builtin_popcountll(__ballot(valid));       // the candidates ascend
+        if (lane == 0) {
+            sh_amin = amin;
+            sh_nv = nv;
+        }
+    } else if (wave == 1) {
+        if (binom && lane < G.cl_max)
+            g2[lane] = gap_at(tab, (double)(m << lane));
+        if (lane == 63) {
+            sh_gm = gap_at(tab, md);
+            sh_g1 = gap_at(tab, 1.0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (binom && lane == 0) {
+            double acc = 0.0;
+            sum2[0] = 0.0;
+            for (int j = 0; j < G.cl_max; ++j) {
+                acc = acc + g2[j];
+                sum2[j + 1] = acc;
+            }
+        }
+    }
+    if (chain) {
+        const int n_terms = SUM_BLOCK * (n_blk - 1) + G.last_terms;
+        for (int r = tid; r < n_blk * SUM_BLOCK; r += ROW_THREADS) {
+            double v = 0.0;
+            if (r < n_terms)
+                v = gap_at(tab, (double)((u64)(r + 1) * m));
+            pre[r + r / SUM_BLOCK] = v;
+        }
+    }
+    __syncthreads();
+    // wave 0 adds the chain sums up while the others start on the Broadcast plane, which
+    // does not need them; it joins them afterwards (the groups of 64 process counts are
+    // handed out through a counter)
+    if (chain && wave == 0) {
+        if (lane < n_blk) {
+            // sixteen terms at a time: read, add in order, write the sums before each
+            double *p = pre + lane * (SUM_BLOCK + 1);
+            double run = 0.0;
+            for (int r0 = 0; r0 < SUM_BLOCK; r0 += 16) {
+                double v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    v[u] = p[r0 + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    p[r0 + u] = run;
+                    run = run + v[u];
+                }
+            }
+            tot[lane] = run;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (lane == 0) {
+            double acc = 0.0;
+            for (int b = 0; b < n_blk; ++b) {      // the finished blocks, in ascending order
+                done[b] = acc;
+                acc = acc + tot[b];
+            }
+        }
+    }
+
+    const double gm = sh_gm, g1 = sh_g1, amin = sh_amin;
+    const int nv = sh_nv;
+    const size_t plane = (size_t)G.n_m * n_P;
+    plogp_cell_dev *const orow = out + (size_t)t * G.n_ops * plane + (size_t)mi * n_P;
+    // lane si keeps C of candidate si (lanes past the candidates: 0, never taken as B is +inf)
+    const double c_mine = sC[lane];
+    const int c_lo = __double2loint(c_mine), c_hi = __double2hiint(c_mine);
+    // a lane takes PPL process counts, 64 apart: a candidate read from LDS serves them all
+    const unsigned n_groups = (unsigned)((n_P + 64 * PPL - 1) / (64 * PPL));
+    if (mask & 0x3FFu) {
+        for (;;) {
+            unsigned grp = 0u;
+            if (lane == 0)
+                grp = atomicAdd(&next_group, 1u);
+            grp = __builtin_amdgcn_readfirstlane(grp);
+            if (grp >= n_groups)
+                break;
+            int pi[PPL];
+            bool active[PPL];
+            double q[PPL], fl[PPL], cl[PPL], clL[PPL], b5[PPL];
+            int i5[PPL];
+#pragma unroll
+            for (int h = 0; h < PPL; ++h) {
+                pi[h] = ((int)grp * PPL + h) * 64 + lane;
+                active[h] = pi[h] < n_P;
+                const uint32_t Pv = sP[active[h] ? pi[h] : n_P - 1];
+                q[h] = (double)(Pv - 1u);
+                fl[h] = (double)floor_log2(Pv);
+                cl[h] = (double)ceil_log2(Pv);
+                clL[h] = cl[h] * L;
+                b5[h] = INFINITY;
+                i5[h] = 0;
+            }
+            // row 5: min over s of fma(q, C, B), eight candidates per round trip to LDS; the
+            // batch in which the minimum first appeared is remembered
+            if (mask & 0x20u) {
+                for (int s0 = 0; s0 < nv; s0 += 8) {
+                    // B from LDS (the same address in every lane), C from the lane that holds
+                    // it, through scalar registers: half the LDS traffic
+                    double Bv[8], Cv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        Bv[u] = sB[s0 + u];
+                        Cv[u] = __hiloint2double(__builtin_amdgcn_readlane(c_hi, s0 + u),
+                                                 __builtin_amdgcn_readlane(c_lo, s0 + u));
+                    }
+#pragma unroll
+                    for (int h = 0; h < PPL; ++h) {
+                        double cur = INFINITY;
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            cur = min_f64(cur, __builtin_fma(q[h], Cv[u], Bv[u]));
+                        i5[h] = cur < b5[h] ? s0 : i5[h];
+                        b5[h] = min_f64(b5[h], cur);
+                    }
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < PPL; ++h) {
+                const double t2 = amin < INFINITY ? __builtin_fma(q[h], amin, L) : INFINITY;
+                const double t9 = amin < INFINITY ? __builtin_fma(fl[h], amin, clL[h]) : INFINITY;
+                Best bc = decide_bcast(mask, q[h], fl[h], cl[h], gm, L, g1, t2, 0u, b5[h], 0u, t9, 0u);
+                if (__ballot(active[h] && bc.id == 5u) != 0) {
+                    // the first candidate of the remembered batch that attains the minimum
+                    int at5 = i5[h];
+#pragma unroll
+                    for (int u = 7; u >= 0; --u)        // descending: the first match stays
+                        at5 = __builtin_fma(q[h], sC[i5[h] + u], sB[i5[h] + u]) == b5[h] ? i5[h] + u : at5;
+                    const uint32_t s_at = sSv[at5];
+                    bc.s = bc.id == 5u ? s_at : bc.s;
+                }
+                bool open = active[h] && (bc.id == 2u || bc.id == 9u);
+                if (__ballot(open) != 0) {
+                    // a winning row 2 or 9: the first candidate whose value equals the minimum
+                    const double mul = bc.id == 2u ? q[h] : fl[h], add = bc.id == 2u ? L : clL[h];
+                    uint32_t found = 0u;
+                    for (int s0 = 0; s0 < nv; s0 += 4) {     // past the last candidate A is +inf
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const bool hit = open && __builtin_fma(mul, sA[s0 + u], add) == bc.t;
+                            found = hit ? sSv[s0 + u] : found;
+                            open = open && !hit;
+                        }
+                        if (__ballot(open) == 0)
+                            break;
+                    }
+                    if (bc.id == 2u || bc.id == 9u)
+                        bc.s = found;
+                }
+                if (active[h])
+                    store_cell(orow + pi[h], bc);
+            }
+        }
+    }
+    __syncthreads();                   // the chain sums are complete
+    if (mask & 0x1C00u) {
+        plogp_cell_dev *const srow = orow + ((mask & 0x3FFu) ? plane : 0);
+        for (int pi = tid; pi < n_P; pi += ROW_THREADS) {
+            const uint32_t Pv = sP[pi];
+            const int cli = ceil_log2(Pv), blk = (int)((Pv - 1u) / SUM_BLOCK);
+            const double s11 = chain ? done[blk] + pre[(Pv - 1u) + blk] : 0.0;
+            const double s12 = binom ? sum2[cli] : 0.0;
+            store_cell(srow + pi, decide_scatter(mask, (double)(Pv - 1u), (double)cli, gm, L, s11, s12));
+        }
+    }
+}
+
 // ---- whole path for batches of tables that share their sample sizes ----------
 //
 // Measured tables of many clusters are normally taken at the same list of
@@ -3039,6 +3305,14 @@ bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
     return (long)T.n_tables * G.n_m >= 8192 && G.n_s <= FUSED_NS && G.n_blk <= 32;
 }
 
+// Few tables, few candidates, few blocks of the chain sum and many process counts: one
+// workgroup per (table, m) does the whole path (k_row).
+bool use_row_path(const DeviceTables &T, const DeviceGrid &G)
+{
+    return G.n_s <= ROW_NS && G.n_blk <= ROW_MAX_BLK && T.n <= ROW_MAX_N && G.n_P >= 256 &&
+           (long)T.n_tables * G.n_m >= 256 && (long)T.n_tables * G.n_m <= 65535 * 16;
+}
+
 // LDS of a k_batch_t workgroup: 64 tables by interval, their g(s), the output staging.
 static size_t batch_t_lds(int n, int n_s)
 {
@@ -3105,6 +3379,21 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
                                dim3(64 * BATCH_T_WAVES), lds, st, D,
                                reinterpret_cast<const f64x2 *>(S.batch_ys), T.L, S.batch.rec, S.batch.tab,
                                G.P, reinterpret_cast<const u64 *>(G.s), d_out);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        PLOGP_MARK(4);
+        return hipSuccess;
+    }
+    if (!terms_only && !use_fused_path(T, G) && use_row_path(T, G)) {
+        PLOGP_MARK(1);
+        PLOGP_MARK(2);
+        PLOGP_MARK(3);
+        const bool all = G.mask == 0x1FFFu;
+        // two process counts per lane when there are more groups of 64 than waves
+        const bool two = G.n_P > 64 * (ROW_THREADS / 64);
+        const auto kern = all ? (two ? k_row<true, 2> : k_row<true, 1>) : (two ? k_row<false, 2> : k_row<false, 1>);
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(kern, dim3((unsigned)(T.n_tables * G.n_m)), dim3(ROW_THREADS),
+                               row_lds_bytes(T.n, G.n_blk, G.n_P), st, T, G, d_out);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(4);
         return hipSuccess;

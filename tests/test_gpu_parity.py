@@ -456,6 +456,56 @@ def test_random_small_problems(seed):
         assert_tables_equal(gpu_tune(wl), want, what)
 
 
+def _row_problem(rng):
+    """A job for the path that does a whole (table, m) row in one workgroup: at least 256
+    rows, at least 256 process counts up to 2048 at most (32 blocks of the chain sum), at
+    most 64 candidates, at most 512 samples."""
+    n = int(rng.choice([2, 7, 64, 200, 512]))
+    x = np.unique(np.floor(np.cumsum(rng.integers(1, 3000, size=n).astype(np.float64))))
+    while len(x) < 2:
+        x = np.append(x, x[-1] + 7.0)
+    n = len(x)
+    n_tables = int(rng.choice([1, 1, 2, 5]))
+    gaps = np.empty((n_tables, n))
+    for t in range(n_tables):
+        y = 20.0 + x * rng.uniform(0.01, 0.3) * (1.0 + 0.3 * rng.standard_normal(n))
+        gaps[t] = np.abs(y) if rng.random() < 0.5 else np.maximum.accumulate(np.abs(y))
+    L = rng.uniform(0.0, 100.0, size=n_tables)
+    n_m = -(-256 // n_tables) + int(rng.integers(0, 70))
+    top = float(x[-1]) * float(rng.choice([0.3, 2.0, 50.0]))
+    m = np.maximum(np.floor(np.exp(rng.uniform(np.log(8.0), np.log(max(top, 64.0)), size=n_m)) / 8.0) * 8.0, 8.0)
+    m = m.astype(np.uint64)
+    if rng.random() < 0.5:
+        m = np.sort(m)
+    p_hi = int(rng.choice([300, 1026, 2049]))              # P below p_hi: up to 2048
+    n_P = int(min(p_hi - 2, rng.choice([256, 257, 298, 512, 513, 1000])))
+    P = np.sort(rng.choice(np.arange(2, p_hi), size=n_P, replace=False)).astype(np.uint32)
+    if rng.random() < 0.5:
+        P[-1] = p_hi - 1                                    # the largest process count allowed
+        P = np.unique(P)
+        while len(P) < 256:
+            P = np.unique(np.append(P, rng.integers(2, p_hi - 1))).astype(np.uint32)
+    n_s = int(rng.choice([0, 1, 7, 8, 9, 34, 63, 64]))
+    s = np.unique(rng.integers(1, 6000, size=n_s) * 8).astype(np.uint64) if n_s else np.array([], dtype=np.uint64)
+    s_cap = int(rng.choice([NO_CAP, NO_CAP, 4096, 64]))
+    mask = int(rng.choice([ALL_STRATEGIES_MASK, ALL_STRATEGIES_MASK, 0x3FF, 0x1C00, 0x0A25, 0x1224, 1 << 2,
+                           1 << 9, 1 << 11, 1 << 12, int(rng.integers(1, 1 << 13))]))
+    return Workload("row", np.repeat(x[None, :], n_tables, axis=0), gaps, L, m, P, s, s_cap, mask)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_whole_row_problems(seed):
+    rng = np.random.default_rng(3000 + seed)
+    for k in range(3):
+        wl = _row_problem(rng)
+        want, _ = oracle.tune_workload(wl)
+        what = "row %d/%d: n=%d tables=%d m=%d P=%d (max %d) s=%d cap=%d mask=%#x" % (
+            seed, k, wl.sizes.shape[1], wl.n_tables, len(wl.m), len(wl.P), int(wl.P[-1]), len(wl.s),
+            wl.s_cap & 0xFFFFFFFF, wl.strategy_mask)
+        print(what, flush=True)
+        assert_tables_equal(gpu_tune(wl), want, what)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_batches(seed):
     """Batches big enough for the single-kernel paths (at least 8192 (table, m) rows), with and
