@@ -190,7 +190,8 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
  * A stage that did not run reports 0 (two events with nothing between them may
  * read a fraction of a microsecond).  For tables of up to about 1000 samples
  * the terms and the Scatter-chain block sums are one launch, reported under
- * [1]; the batch paths that do everything in one kernel report it under [3].
+ * [1]; the paths that do everything in one kernel (batches of tables; one
+ * workgroup per (table, m) row) report it under [3].
  * Synchronous.  For measurement only.
  * Errors: as plogp_tune_grid, plus EINVAL for a null stage_ms_out or reps
  * outside [1, 10000].
