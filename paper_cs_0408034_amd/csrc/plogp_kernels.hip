@@ -860,6 +860,7 @@ __global__ void __launch_bounds__(256) k_terms_chain(DeviceTables T, DeviceGrid 
 // (every thread 16 loads in flight) and the first PFX_M lanes scan a tile there.
 constexpr int PFX_TILE = 256;
 constexpr int PFX_M = 16;
+constexpr int PFX_MAX_P = 4096;     // process counts whose block index is kept in LDS
 
 __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, int n_mgroups)
 {
@@ -883,14 +884,30 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
         }
     };
     load_tile(0);
+    // the block of every process count of the grid, kept in LDS when there are few enough:
+    // writing the results out then waits for no load from device memory
+    __shared__ int blk_of[PFX_MAX_P];
+    const bool p_in_lds = G.n_P <= PFX_MAX_P;
+    if (p_in_lds)
+        for (int pi = tid; pi < G.n_P; pi += 256)
+            blk_of[pi] = (int)((G.P[pi] - 1u) / SUM_BLOCK);
+    // the process counts whose sums end in the current tile: P indices [off_lo, off_hi)
+    const int m_valid = G.n_mu - mg * PFX_M < PFX_M ? G.n_mu - mg * PFX_M : PFX_M;   // sizes of this group
+    int off_lo = G.blk_off[0];
+    int off_hi = G.blk_off[PFX_TILE < G.n_blk ? PFX_TILE : G.n_blk];
     for (int b0 = 0; b0 < G.n_blk; b0 += PFX_TILE) {
 #pragma unroll
         for (int k = 0; k < PFX_TILE / ROWS; ++k)
             tile[(br + ROWS * k) * (PFX_M + 1) + ml] = v[k];
+        const int pi_lo = off_lo, pi_hi = off_hi;
         __syncthreads();
-        // the next tile's totals are on their way while this one is scanned and written
-        if (b0 + PFX_TILE < G.n_blk)
+        // the next tile's totals and range are on their way while this one is scanned and
+        // written
+        if (b0 + PFX_TILE < G.n_blk) {
             load_tile(b0 + PFX_TILE);
+            off_lo = off_hi;
+            off_hi = G.blk_off[b0 + 2 * PFX_TILE < G.n_blk ? b0 + 2 * PFX_TILE : G.n_blk];
+        }
         if (tid < PFX_M) {
             // sixteen totals at a time: read, add in order, write the sums before each (rows
             // past the last block hold zeros and are not written out below)
@@ -911,15 +928,18 @@ __global__ void __launch_bounds__(256) k_chain_prefix(DeviceGrid G, Scratch S, i
         // only the blocks in which some process count of the grid ends are wanted: the sums
         // go out per process count, pre[m][P index], a run of the output per m and store
         {
-            const int b_end = b0 + PFX_TILE < G.n_blk ? b0 + PFX_TILE : G.n_blk;
-            const int pi_end = G.blk_off[b_end];
-            for (int pi = G.blk_off[b0] + tid; pi < pi_end; pi += 256) {
-                const int bb = (int)((G.P[pi] - 1u) / SUM_BLOCK) - b0;
-#pragma unroll 4
+            for (int pi = pi_lo + tid; pi < pi_hi; pi += 256) {
+                const int bb = (p_in_lds ? blk_of[pi] : (int)((G.P[pi] - 1u) / SUM_BLOCK)) - b0;
+                // all the sums of the row first (one wait for LDS), then the stores
+                double row[PFX_M];
+#pragma unroll
+                for (int mm = 0; mm < PFX_M; ++mm)
+                    row[mm] = tile[bb * (PFX_M + 1) + mm];
+                double *o = S.pre + ((size_t)t * n_m + (size_t)mg * PFX_M) * G.n_P + pi;
+#pragma unroll
                 for (int mm = 0; mm < PFX_M; ++mm) {
-                    const int m2 = mg * PFX_M + mm;
-                    if (m2 < G.n_mu)
-                        S.pre[((size_t)t * n_m + m2) * G.n_P + pi] = tile[bb * (PFX_M + 1) + mm];
+                    if (mm < m_valid)
+                        o[(size_t)mm * G.n_P] = row[mm];
                 }
             }
         }
