@@ -1674,6 +1674,22 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
         blk5[p] = 0;
     }
     double amin = INFINITY;
+    // What lane p < GP needs at the end to decide its cells is asked for now, so that the end
+    // of the wave does not wait for device memory: its process count, g(m), g(1), the two
+    // Scatter sums.
+    const int pi = p0 + lane;
+    const bool mine = lane < GP && pi < G.n_P;
+    uint32_t Pv = 2u;
+    double gm = 0.0, g1 = 0.0, s11 = 0.0, s12 = 0.0;
+    if (has_work) {
+        Pv = G.P[mine ? pi : G.n_P - 1];
+        gm = S.gm[(size_t)t * G.n_m + mi];
+        g1 = S.g1[t];
+        if (mine && (mask & (1u << 11)))
+            s11 = chain_sum_of(G, S, t, mi, pi, Pv);
+        if (mine && (mask & (1u << 12)))
+            s12 = S.sum2[((size_t)t * G.n_m + mi) * (size_t)(G.cl_max + 1) + ceil_log2(Pv)];
+    }
 
     // Filling a pass: the loads of the per-candidate scalars are issued before the
     // previous pass is consumed, the arithmetic and the LDS stores come after it.
@@ -1785,17 +1801,12 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     // lanes 0..GP-1 decide one Broadcast cell each: the segmented rows' minima, the
     // unsegmented rows, arg-min.  The segment size is looked for afterwards, and only in
     // the cells that a segmented row wins.
-    const int pi = p0 + lane;
-    const bool mine = lane < GP && pi < G.n_P;
-    const uint32_t Pv = G.P[mine ? pi : G.n_P - 1];
     const double qv = (double)(Pv - 1);
     const int fli = floor_log2(Pv), cli = ceil_log2(Pv);
-    const double gm = S.gm[(size_t)t * G.n_m + mi];
     const size_t plane = (size_t)G.n_m * G.n_P;
     plogp_cell_dev *o = out + (size_t)t * G.n_ops * plane + (size_t)mi * G.n_P + (mine ? pi : 0);
     Best bc = {INFINITY, 0u, 0xFFFFFFFFu};
     if (mask & 0x3FFu) {
-        const double g1 = S.g1[t];
         const double t2 = ((mask & (1u << 2)) && haveA) ? __builtin_fma(qv, Aw, L) : INFINITY;
         const double t9 = ((mask & (1u << 9)) && haveA)
                               ? __builtin_fma((double)fli, Aw, (double)cli * L) : INFINITY;
@@ -1847,6 +1858,11 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
                                                   __builtin_amdgcn_readlane(__double2loint(bc.t), p));
                 int first = 0x7FFFFFFF;
+                double s_first = 0.0;                      // the candidate at index `first` (wave-uniform)
+                auto from_lane = [&](double v, int l) {
+                    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                                            __builtin_amdgcn_readlane(__double2loint(v), l));
+                };
                 if (id == 5) {
                     {
                         const int si = hc[p - g0] * SWEEP_S_CHUNK + 64 * lane + hl[p - g0];
@@ -1855,8 +1871,11 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                         const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
                                          __builtin_fma(q[p], C, B) == V;
                         const unsigned long long hits = __ballot(hit);
-                        if (hits != 0)
-                            first = hc[p - g0] * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + hl[p - g0];
+                        if (hits != 0) {
+                            const int l = __builtin_ctzll(hits);
+                            first = hc[p - g0] * SWEEP_S_CHUNK + 64 * l + hl[p - g0];
+                            s_first = from_lane(r_s[p - g0], l);      // already here: no load
+                        }
                     }
                     unsigned long long holders = rest[p - g0];  // further lanes that hold V (ties)
                     while (holders != 0) {
@@ -1869,7 +1888,10 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                         const unsigned long long hits = __ballot(hit);
                         if (hits != 0) {
                             const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
-                            first = cand < first ? cand : first;
+                            if (cand < first) {
+                                first = cand;
+                                s_first = (double)G.s[cand];
+                            }
                         }
                     }
                 } else {
@@ -1901,13 +1923,15 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                             segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
                             const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
                             const unsigned long long hits = __ballot(hit);
-                            if (hits != 0 && first == 0x7FFFFFFF)
+                            if (hits != 0 && first == 0x7FFFFFFF) {
                                 first = base + 64 * u + __builtin_ctzll(hits);
+                                s_first = from_lane(sdv[u], __builtin_ctzll(hits));
+                            }
                         }
                     }
                 }
                 if (lane == p)
-                    bc.s = first < nv ? (uint32_t)G.s[first] : 0u;
+                    bc.s = first < nv ? (uint32_t)s_first : 0u;
             }
             }
         }
@@ -1917,12 +1941,8 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     }
     if (!mine)
         return;
-    if (mask & 0x1C00u) {
-        const double s11 = (mask & (1u << 11)) ? chain_sum_of(G, S, t, mi, pi, Pv) : 0.0;
-        const double s12 = (mask & (1u << 12))
-            ? S.sum2[((size_t)t * G.n_m + mi) * (size_t)(G.cl_max + 1) + cli] : 0.0;
+    if (mask & 0x1C00u)
         store_cell(o, decide_scatter(mask, qv, (double)cli, gm, L, s11, s12));
-    }
 }
 
 // ---- whole path in one kernel, for batches of many tables -----------------
