@@ -1815,124 +1815,116 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
             __ballot(mine && (bc.id == 2u || bc.id == 5u || bc.id == 9u));
         if (need != 0) {
             // Row 5: every lane that holds the minimum V of process count p names the pass it
-            // first saw it in; lanes 0..15 re-evaluate that lane's 16 candidates of the pass.
-            // For the first such lane of every process count the candidates are fetched
-            // together, before any of them is used.
-            // (GB process counts at a time, to bound the registers that the fetched candidates take)
-            constexpr int GB = 6;
-            // candidate si of this lane re-evaluated: value of the row given by (mul, add)
-            auto value_at = [&](int si, double mul, double add, bool chain_row) {
+            // first saw it in; that lane's 16 candidates of the pass are evaluated again, by 16
+            // lanes, and the first that gives V is its earliest.  Four such (process count,
+            // holding lane) queries are worked on at once, one per quarter of the wave; lane p
+            // keeps the smallest index found for process count p and the candidate there.
+            int first_v = 0x7FFFFFFF;
+            double s_v = 0.0;
+            int qc = 0, ql = 0, qp = 0;                    // the query of this lane's quarter
+            double qV = 0.0, qq = 0.0;
+            int nq = 0;                                    // queries waiting (wave-uniform)
+            auto from_lane = [&](double v, int l) {
+                return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                                        __builtin_amdgcn_readlane(__double2loint(v), l));
+            };
+            auto flush = [&]() {
+                const bool live = (lane >> 4) < nq;
+                const int si = qc * SWEEP_S_CHUNK + 64 * (lane & 15) + ql;
+                const int idx = si < nv ? si : nv - 1;
+                const double r_s = (double)G.s[idx];
                 double A, B, C;
-                segment_terms(md, (double)G.s[si], S.rcp[si], gs[si], L, A, B, C);
-                return chain_row ? __builtin_fma(mul, C, B) : __builtin_fma(mul, A, add);
+                segment_terms(md, r_s, S.rcp[idx], gs[idx], L, A, B, C);
+                const bool hit = live && si < nv && __builtin_fma(qq, C, B) == qV;
+                const unsigned long long hits = __ballot(hit);
+                for (int j = 0; j < nq; ++j) {
+                    const unsigned h = (unsigned)(hits >> (16 * j)) & 0xFFFFu;
+                    if (h == 0u)
+                        continue;
+                    const int k = __builtin_ctz(h);
+                    const int cand = __builtin_amdgcn_readlane(qc, 16 * j) * SWEEP_S_CHUNK + 64 * k +
+                                     __builtin_amdgcn_readlane(ql, 16 * j);
+                    const double s_c = from_lane(r_s, 16 * j + k);
+                    if (lane == __builtin_amdgcn_readlane(qp, 16 * j) && cand < first_v) {
+                        first_v = cand;
+                        s_v = s_c;
+                    }
+                }
+                nq = 0;
+            };
+            auto push = [&](int p, int l, int c, double V, double q_p) {
+                const bool slot = (lane >> 4) == nq;
+                qc = slot ? c : qc;
+                ql = slot ? l : ql;
+                qp = slot ? p : qp;
+                qV = slot ? V : qV;
+                qq = slot ? q_p : qq;
+                if (++nq == 4)
+                    flush();
             };
 #pragma unroll
-            for (int g0 = 0; g0 < GP; g0 += GB) {
-            int hl[GB], hc[GB];
-            unsigned long long rest[GB];
-            double r_s[GB], r_rcp[GB], r_gs[GB];
-#pragma unroll
-            for (int p = g0; p < g0 + GB && p < GP; ++p) {
-                hl[p - g0] = hc[p - g0] = 0;
-                rest[p - g0] = 0;
-                r_s[p - g0] = r_rcp[p - g0] = r_gs[p - g0] = 1.0;
+            for (int p = 0; p < GP; ++p) {
                 if (!((need >> p) & 1ull) || __builtin_amdgcn_readlane((int)bc.id, p) != 5)
                     continue;                              // wave-uniform
-                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
-                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
-                const unsigned long long holders = __ballot(best5[p] == V);
-                hl[p - g0] = __builtin_ctzll(holders);
-                rest[p - g0] = holders & (holders - 1);
-                hc[p - g0] = __builtin_amdgcn_readlane(blk5[p], hl[p - g0]);
-                const int si = hc[p - g0] * SWEEP_S_CHUNK + 64 * (lane & 15) + hl[p - g0];
-                const int idx = si < nv ? si : nv - 1;
-                r_s[p - g0] = (double)G.s[idx];
-                r_rcp[p - g0] = S.rcp[idx];
-                r_gs[p - g0] = gs[idx];
+                const double V = from_lane(bc.t, p);
+                unsigned long long holders = __ballot(best5[p] == V);
+                while (holders != 0) {                     // more than one lane only on exact ties
+                    const int l = __builtin_ctzll(holders);
+                    holders &= holders - 1;
+                    push(p, l, __builtin_amdgcn_readlane(blk5[p], l), V, q[p]);
+                }
             }
+            if (nq > 0)
+                flush();
+            if (bc.id == 5u)
+                bc.s = first_v < nv ? (uint32_t)s_v : 0u;
+
+            // Rows 2 and 9: the first pass whose minimum of A already gives V holds the
+            // smallest such s; walk that pass in ascending order, 64 candidates at a time
 #pragma unroll
-            for (int p = g0; p < g0 + GB && p < GP; ++p) {
+            for (int p = 0; p < GP; ++p) {
                 if (!((need >> p) & 1ull))
                     continue;                              // wave-uniform
                 const int id = __builtin_amdgcn_readlane((int)bc.id, p);
-                const double V = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(bc.t), p),
-                                                  __builtin_amdgcn_readlane(__double2loint(bc.t), p));
+                if (id == 5)
+                    continue;
+                const double V = from_lane(bc.t, p);
                 int first = 0x7FFFFFFF;
-                double s_first = 0.0;                      // the candidate at index `first` (wave-uniform)
-                auto from_lane = [&](double v, int l) {
-                    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
-                                            __builtin_amdgcn_readlane(__double2loint(v), l));
-                };
-                if (id == 5) {
-                    {
-                        const int si = hc[p - g0] * SWEEP_S_CHUNK + 64 * lane + hl[p - g0];
+                double s_first = 0.0;                      // the candidate at index `first`
+                const uint32_t Pp = G.P[p0 + p];
+                const double flp = (double)floor_log2(Pp);
+                const double clLp = (double)ceil_log2(Pp) * L;
+                const double mul = id == 2 ? q[p] : flp;
+                const double add = id == 2 ? L : clLp;
+                int c0 = 0;
+                const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
+                while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
+                    ++c0;
+                for (int base = c0 * SWEEP_S_CHUNK; base < nv && first == 0x7FFFFFFF; base += 256) {
+                    // four groups of 64 candidates per round trip to memory
+                    double sdv[4], rcv[4], gsv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int si = base + 64 * u + lane;
+                        const int idx = si < nv ? si : nv - 1;
+                        sdv[u] = (double)G.s[idx];
+                        rcv[u] = S.rcp[idx];
+                        gsv[u] = gs[idx];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
                         double A, B, C;
-                        segment_terms(md, r_s[p - g0], r_rcp[p - g0], r_gs[p - g0], L, A, B, C);
-                        const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
-                                         __builtin_fma(q[p], C, B) == V;
+                        segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
+                        const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
                         const unsigned long long hits = __ballot(hit);
-                        if (hits != 0) {
-                            const int l = __builtin_ctzll(hits);
-                            first = hc[p - g0] * SWEEP_S_CHUNK + 64 * l + hl[p - g0];
-                            s_first = from_lane(r_s[p - g0], l);      // already here: no load
-                        }
-                    }
-                    unsigned long long holders = rest[p - g0];  // further lanes that hold V (ties)
-                    while (holders != 0) {
-                        const int l = __builtin_ctzll(holders);
-                        holders &= holders - 1;
-                        const int c = __builtin_amdgcn_readlane(blk5[p], l);
-                        const int si = c * SWEEP_S_CHUNK + 64 * lane + l;
-                        const bool hit = lane < SWEEP_S_CHUNK / 64 && si < nv &&
-                                         value_at(si < nv ? si : nv - 1, q[p], 0.0, true) == V;
-                        const unsigned long long hits = __ballot(hit);
-                        if (hits != 0) {
-                            const int cand = c * SWEEP_S_CHUNK + 64 * __builtin_ctzll(hits) + l;
-                            if (cand < first) {
-                                first = cand;
-                                s_first = (double)G.s[cand];
-                            }
-                        }
-                    }
-                } else {
-                    // rows 2 and 9: the first pass whose minimum of A already gives V holds the
-                    // smallest such s; walk that pass in ascending order, 64 candidates at a time
-                    const uint32_t Pp = G.P[p0 + p];
-                    const double flp = (double)floor_log2(Pp);
-                    const double clLp = (double)ceil_log2(Pp) * L;
-                    const double mul = id == 2 ? q[p] : flp;
-                    const double add = id == 2 ? L : clLp;
-                    int c0 = 0;
-                    const int known = n_chunks < SWEEP_S_PASSES ? n_chunks : SWEEP_S_PASSES;
-                    while (c0 < known && __builtin_fma(mul, passMinA[c0], add) != V)
-                        ++c0;
-                    for (int base = c0 * SWEEP_S_CHUNK; base < nv && first == 0x7FFFFFFF; base += 256) {
-                        // four groups of 64 candidates per round trip to memory
-                        double sdv[4], rcv[4], gsv[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int si = base + 64 * u + lane;
-                            const int idx = si < nv ? si : nv - 1;
-                            sdv[u] = (double)G.s[idx];
-                            rcv[u] = S.rcp[idx];
-                            gsv[u] = gs[idx];
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            double A, B, C;
-                            segment_terms(md, sdv[u], rcv[u], gsv[u], L, A, B, C);
-                            const bool hit = base + 64 * u + lane < nv && __builtin_fma(mul, A, add) == V;
-                            const unsigned long long hits = __ballot(hit);
-                            if (hits != 0 && first == 0x7FFFFFFF) {
-                                first = base + 64 * u + __builtin_ctzll(hits);
-                                s_first = from_lane(sdv[u], __builtin_ctzll(hits));
-                            }
+                        if (hits != 0 && first == 0x7FFFFFFF) {
+                            first = base + 64 * u + __builtin_ctzll(hits);
+                            s_first = from_lane(sdv[u], __builtin_ctzll(hits));
                         }
                     }
                 }
                 if (lane == p)
                     bc.s = first < nv ? (uint32_t)s_first : 0u;
-            }
             }
         }
         if (mine)
