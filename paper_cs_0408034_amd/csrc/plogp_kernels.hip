@@ -834,6 +834,147 @@ __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_p
     chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, chain_lds);
 }
 
+// The Scatter-chain sums of one (table, distinct m) in one workgroup, for tables of few
+// samples and sums of few blocks: what k_chain_blocks and k_chain_prefix leave in device
+// memory (the in-block sums at the grid's process counts, and the totals of the finished
+// blocks or their prefix), without a lane that walks a block alone.  A thread evaluates 16
+// consecutive terms g(j m) (one search, then a walk: the sizes ascend), into a tile in LDS;
+// a lane per block adds its 64 terms in order and leaves the sum before every term in
+// place; one lane adds the block totals in order; all threads write the sums out, the
+// process counts along the lanes.
+constexpr int CROW_THREADS = 256;
+constexpr int CROW_MAX_BLK = 96;         // 6144 terms at most
+constexpr int CROW_TPT = 16;             // consecutive terms per thread
+constexpr int CROW_LD = SUM_BLOCK + SUM_BLOCK / CROW_TPT + 1;     // 69: a block's row in the tile
+
+// term r (0-based) sits at r + r / 64 + r / 16: rows of 69, so that neither the threads
+// that write runs of 16 nor the lanes that read one row each meet in a bank
+__device__ __forceinline__ int crow_at(int r) { return r + r / SUM_BLOCK + r / CROW_TPT; }
+
+static size_t chain_row_lds(int n, int n_blk)
+{
+    return ((size_t)3 * n + (size_t)n_blk * CROW_LD + 2 * CROW_MAX_BLK) * sizeof(double);
+}
+
+__device__ __forceinline__ void chain_row_body(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
+                                               int block_id, double *lds)
+{
+    const int n = T.n, n_blk = G.n_blk, n_mu = G.n_mu, n_P = G.n_P;
+    const int tid = threadIdx.x;
+    const int t = block_id / n_mu, mu_i = block_id % n_mu;
+    double *x = lds, *y = x + n, *sl = y + n;
+    double *pre = sl + n;                                  // the terms, then the sums before each
+    double *tot = pre + (size_t)n_blk * CROW_LD, *done = tot + CROW_MAX_BLK;
+    const u64 m = G.mu[mu_i];
+    const uint32_t P_first = tid < n_P ? G.P[tid] : 2u;    // asked for now, used at the very end
+    {
+        const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
+        for (int i = tid; i < n; i += CROW_THREADS) {
+            x[i] = gx[i];
+            y[i] = gy[i];
+        }
+        __syncthreads();
+        for (int i = tid; i < n; i += CROW_THREADS)
+            sl[i] = interval_slope(x, y, n, i);
+        __syncthreads();
+    }
+    const double md = (double)m, x0 = x[0];
+    const int n_terms = SUM_BLOCK * (n_blk - 1) + G.last_terms;
+    for (int r0 = tid * CROW_TPT; r0 < n_blk * SUM_BLOCK; r0 += CROW_THREADS * CROW_TPT) {
+        // g((r + 1) m) for r = r0 .. r0 + 15: the same expression as gap_at, with the interval
+        // carried along (i: the last sample not above the size, 0 below the first)
+        double z = (double)((u64)(r0 + 1) * m);
+        int i = last_not_above(x, n, z);
+        double xi = x[i], yi = y[i], si = sl[i];
+        double xn = i + 1 < n ? x[i + 1] : INFINITY;
+#pragma unroll 4
+        for (int k = 0; k < CROW_TPT; ++k) {
+            double v = 0.0;
+            if (r0 + k < n_terms) {
+                while (z >= xn) {
+                    ++i;
+                    xi = xn;
+                    yi = y[i];
+                    si = sl[i];
+                    xn = i + 1 < n ? x[i + 1] : INFINITY;
+                }
+                const double zc = z > x0 ? z : x0;
+                v = __builtin_fma(si, zc - xi, yi);
+            }
+            pre[crow_at(r0 + k)] = v;
+            z += md;                                       // exact: integers below 2^53
+        }
+    }
+    __syncthreads();
+    if (tid < n_blk) {
+        // sixteen terms at a time: read, add in order, write the sums before each
+        double *p = pre + tid * CROW_LD;
+        double run = 0.0;
+        for (int r0 = 0; r0 < SUM_BLOCK; r0 += CROW_TPT) {
+            double v[CROW_TPT];
+            double *q = p + r0 + r0 / CROW_TPT;
+#pragma unroll
+            for (int u = 0; u < CROW_TPT; ++u)
+                v[u] = q[u];
+#pragma unroll
+            for (int u = 0; u < CROW_TPT; ++u) {
+                q[u] = run;
+                run = run + v[u];
+            }
+        }
+        tot[tid] = run;
+    } else if (tid < CROW_MAX_BLK) {
+        tot[tid] = 0.0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // the finished blocks, in ascending order; sixteen totals per round trip to LDS
+        double acc = 0.0;
+        for (int b0 = 0; b0 < n_blk; b0 += 16) {
+            double v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                v[u] = tot[b0 + u];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                done[b0 + u] = acc;
+                acc = acc + v[u];
+            }
+        }
+    }
+    __syncthreads();
+    const size_t row = (size_t)t * n_mu + mu_i;
+    for (int pi = tid; pi < n_P; pi += CROW_THREADS) {
+        const int r = (int)((pi == tid ? P_first : G.P[pi]) - 1u), blk = r / SUM_BLOCK;
+        S.part[row * n_P + pi] = pre[crow_at(r)];
+        if (G.blk_is_prefix)
+            S.pre[row * n_P + pi] = done[blk];
+    }
+    if (!G.blk_is_prefix)
+        for (int b = tid; b < n_blk - 1; b += CROW_THREADS)        // the last block is never complete
+            S.blk[((size_t)t * n_blk + b) * n_mu + mu_i] = tot[b];
+}
+
+__global__ void __launch_bounds__(CROW_THREADS) k_chain_row(DeviceTables T, DeviceGrid G, Scratch S)
+{
+    extern __shared__ double lds[];
+    chain_row_body(T, G, S, (int)blockIdx.x, lds);
+}
+
+// The terms and the sums above in one launch, side by side: both are short chains of
+// dependent steps.  The (few) terms workgroups come first, so that they are on the chip at
+// once.
+__global__ void __launch_bounds__(CROW_THREADS) k_terms_chain_row(DeviceTables T, DeviceGrid G, Scratch S,
+                                                                  int terms_wg, int n_chunks, int n_mchunks,
+                                                                  int with_pairs)
+{
+    extern __shared__ __align__(16) double both_lds[];
+    if ((int)blockIdx.x < terms_wg)
+        terms_body(T, G, S, n_chunks, n_mchunks, with_pairs, (int)blockIdx.x, both_lds);
+    else
+        chain_row_body(T, G, S, (int)blockIdx.x - terms_wg, both_lds);
+}
+
 // Both first steps in one launch: they do not depend on each other (each stages the
 // table from the raw samples), so the workgroups of the chain sums (the longer job, first
 // in the grid) and those of the terms run side by side.  For tables small enough that
@@ -3450,9 +3591,12 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     if (lanes_p && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
     long n_chunks_l = (n_items + 255) / 256;
-    // the candidates go to LDS too (for the count per m) if they fit beside the table
+    // the candidates go to LDS too (for the count per m) if they fit beside the table and are
+    // few: every workgroup stages them all, and for 8192 of them that takes longer (11.8 us)
+    // than the thirteen dependent loads of a search in device memory (6.9 us)
     const size_t pair_lds = lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0;
-    const bool stage_s = G.n_s > 0 && tab_lds + pair_lds + (size_t)G.n_s * sizeof(double) <= kMaxTableLds;
+    const bool stage_s = G.n_s > 0 && G.n_s <= 1024 &&
+                         tab_lds + pair_lds + (size_t)G.n_s * sizeof(double) <= kMaxTableLds;
     const int terms_mode = (lanes_p ? 1 : 0) | (stage_s ? 2 : 0);
     const size_t terms_lds = tab_lds + pair_lds + (stage_s ? (size_t)G.n_s * sizeof(double) : 0);
     // a workgroup stages the whole table: with a big table one workgroup fits a CU, so no
@@ -3479,9 +3623,16 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     // stays for its whole share of the work (the table is staged once)
     const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
     const bool big = chain_lds > 32768;
+    // few samples, few blocks, enough distinct sizes: a workgroup per (table, m) forms all
+    // its sums, the prefix over the blocks included
+    const bool chain_row = chain && T.n <= 512 && G.n_blk <= CROW_MAX_BLK &&
+                           chain_row_lds(T.n, G.n_blk) <= 65536 &&
+                           (long)T.n_tables * G.n_mu >= 128 && (long)T.n_tables * G.n_mu <= (1L << 24);
     // small tables: the terms and the chain sums in one launch, side by side
-    const bool together = chain && !big;
-    if (!together) {
+    const bool together = chain && !big && !chain_row;
+    // (terms beside the per-row chain sums: when the terms need little LDS)
+    const bool row_together = chain_row && terms_lds <= 65536;
+    if (!together && !row_together) {
         for (int r = 0; r < reps; ++r)
             hipLaunchKernelGGL(k_terms, dim3(terms_wg), dim3(256), terms_lds, st, T, G, S, n_chunks,
                                n_mchunks, terms_mode);
@@ -3489,7 +3640,21 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     }
     PLOGP_MARK(1);
 
-    if (chain) {
+    if (chain_row) {
+        const size_t crow_lds = chain_row_lds(T.n, G.n_blk);
+        for (int r = 0; r < reps; ++r) {
+            if (row_together)
+                hipLaunchKernelGGL(k_terms_chain_row, dim3(terms_wg + (unsigned)(T.n_tables * G.n_mu)),
+                                   dim3(CROW_THREADS), crow_lds > terms_lds ? crow_lds : terms_lds, st, T, G,
+                                   S, (int)terms_wg, n_chunks, n_mchunks, terms_mode);
+            else
+                hipLaunchKernelGGL(k_chain_row, dim3((unsigned)(T.n_tables * G.n_mu)), dim3(CROW_THREADS),
+                                   crow_lds, st, T, G, S);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        PLOGP_MARK(2);
+        PLOGP_MARK(3);
+    } else if (chain) {
         const int threads = big ? 1024 : 256;
         const int n_mg = (G.n_mu + 63) / 64;
         // leading blocks that are items of their own: the dense part of a table with many
