@@ -506,6 +506,36 @@ def test_random_whole_row_problems(seed):
         assert_tables_equal(gpu_tune(wl), want, what)
 
 
+@pytest.mark.parametrize("p_max,n_mu,n,n_tables,n_s", [
+    (6145, 128, 64, 1, 300),      # 96 blocks (the most) x 128 distinct sizes (the fewest), many candidates
+    (6146, 140, 64, 1, 300),      # 97 blocks: the walk and the prefix launch instead
+    (4097, 127, 64, 1, 70),       # one distinct size too few
+    (2050, 70, 200, 2, 12),       # two tables share the launch; 33 blocks (a prefix is wanted)
+    (2049, 200, 512, 1, 0),       # 32 blocks (block totals instead of a prefix), 512 samples, no candidates
+    (65, 300, 7, 1, 5),           # two blocks, the second with one term
+])
+def test_chain_sums_per_row_edges(p_max, n_mu, n, n_tables, n_s):
+    # the path that forms all Scatter-chain sums of a (table, m) in one workgroup, at its limits
+    rng = np.random.default_rng(p_max + n_mu)
+    x = np.unique(np.floor(np.cumsum(rng.integers(1, 900, size=n).astype(np.float64))))
+    while len(x) < 2:
+        x = np.append(x, x[-1] + 5.0)
+    gaps = np.abs(25.0 + np.outer(rng.uniform(0.02, 0.2, size=n_tables), x) *
+                  (1.0 + 0.2 * rng.standard_normal((n_tables, len(x)))))
+    L = rng.uniform(1.0, 80.0, size=n_tables)
+    mu = np.unique(rng.integers(1, 4 * int(x[-1]), size=4 * n_mu).astype(np.uint64) * 8)[:n_mu]
+    assert len(mu) == n_mu
+    m = np.concatenate([mu, mu[: n_mu // 3]])              # repeats: fewer distinct sizes than sizes
+    rng.shuffle(m)
+    P = np.unique(np.concatenate([rng.integers(2, p_max, size=40), [2, 3, 64, 65, 66, p_max - 1, p_max]])
+                  ).astype(np.uint32)
+    s = np.unique(rng.integers(1, 3000, size=n_s) * 8).astype(np.uint64) if n_s else np.array([], dtype=np.uint64)
+    wl = Workload("chain rows", np.repeat(x[None, :], n_tables, axis=0), gaps, L, m, P, s, NO_CAP,
+                  ALL_STRATEGIES_MASK)
+    want, _ = oracle.tune_workload(wl)
+    assert_tables_equal(gpu_tune(wl), want, "chain sums per row, Pmax %d" % p_max)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_batches(seed):
     """Batches big enough for the single-kernel paths (at least 8192 (table, m) rows), with and
