@@ -2389,6 +2389,8 @@ __global__ void __launch_bounds__(ROW_THREADS) k_row(DeviceTables T, DeviceGrid 
     const u64 m = G.m[mi];
     const double L = T.L[t];
     const u64 my_s = wave == 0 && lane < n_s ? G.s[lane] : 0ull;
+    // (the division does not wait for the table: it runs while the samples are on their way)
+    const double my_sd = (double)my_s, my_rcp = 1.0 / my_sd;
     {
         const double *gx = T.x + (size_t)t * n, *gy = T.y + (size_t)t * n;
         for (int i = tid; i < n; i += ROW_THREADS) {
@@ -2413,12 +2415,12 @@ __global__ void __launch_bounds__(ROW_THREADS) k_row(DeviceTables T, DeviceGrid 
         bool valid = false;
         if (lane < n_s) {
             const u64 lim = m < G.s_cap ? m : G.s_cap;
-            const double sd = (double)my_s, gs = gap_at(tab, sd);
+            const double sd = my_sd, gs = gap_at(tab, sd);
             C = gs + L;
             valid = my_s <= lim;
             if (valid) {
                 double Cx;
-                segment_terms(md, sd, 1.0 / sd, gs, L, A, B, Cx);
+                segment_terms(md, sd, my_rcp, gs, L, A, B, Cx);
             }
         }
         sA[lane] = A;
