@@ -177,11 +177,55 @@ struct plogp_run_dev {
     uint32_t strategy;
 };
 
+// n_fused > 0: group_before still holds the n_fused (at most CUT_FUSE_MAX) group totals; every
+// workgroup forms their exclusive prefix itself in LDS, workgroup 0 also writes the grand
+// total to *total_out - one launch fewer for the small jobs, which are bound by launches.
+constexpr int CUT_FUSE_MAX = 1024;
+
 __global__ void __launch_bounds__(256) k_cut_emit(CutShape sh, const plogp_cell_dev *cells, const u64 *m,
                                                   const uint32_t *local, const uint32_t *flags,
                                                   const u64 *group_before, u64 *row_offsets,
-                                                  plogp_run_dev *runs, u64 capacity)
+                                                  plogp_run_dev *runs, u64 capacity, int n_fused,
+                                                  u64 *total_out)
 {
+    __shared__ u64 gpre[CUT_FUSE_MAX];
+    __shared__ u64 wsum[4];
+    if (n_fused > 0) {
+        // four totals per thread, in order; scan over the wave, then over the four waves
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        u64 v[4], sum = 0ull;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int g = (int)threadIdx.x * 4 + k;
+            v[k] = g < n_fused ? group_before[g] : 0ull;
+            sum += v[k];
+        }
+        u64 inc = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const u64 up = (u64)__shfl_up((long long)inc, d, 64);
+            if (lane >= d)
+                inc += up;
+        }
+        if (lane == 63)
+            wsum[wave] = inc;
+        __syncthreads();
+        u64 before = 0ull, all = 0ull;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            before += w < wave ? wsum[w] : 0ull;
+            all += wsum[w];
+        }
+        u64 run = before + inc - sum;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            gpre[threadIdx.x * 4 + k] = run;
+            run += v[k];
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0)
+            *total_out = all;
+        __syncthreads();
+    }
     const long item = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (item >= sh.n_items)
         return;
@@ -190,7 +234,7 @@ __global__ void __launch_bounds__(256) k_cut_emit(CutShape sh, const plogp_cell_
         return;
     const size_t row = (size_t)(t * sh.n_ops + op) * sh.n_P + pi;
     const size_t idx = row * sh.n_tiles + tile;
-    u64 at = group_before[idx / CUT_SCAN_WG] + local[idx];
+    u64 at = (n_fused > 0 ? gpre[idx / CUT_SCAN_WG] : group_before[idx / CUT_SCAN_WG]) + local[idx];
     if (tile == 0)
         row_offsets[row] = at;
     uint32_t bits = flags[idx];
@@ -253,12 +297,14 @@ hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_d
                            C.flags);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(1);
+    const bool fuse = n_groups <= (size_t)CUT_FUSE_MAX;     // the prefix of the group totals inside the last step
     for (int r = 0; r < reps; ++r) {
         hipLaunchKernelGGL(k_cut_scan1, dim3((unsigned)n_groups), dim3(CUT_SCAN_THREADS), 0, st,
                            C.counts, C.local, n_counts, reinterpret_cast<u64 *>(C.group_total));
-        hipLaunchKernelGGL(k_cut_scan2, dim3(1), dim3(1024), 0, st,
-                           reinterpret_cast<u64 *>(C.group_total), n_groups,
-                           reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
+        if (!fuse)
+            hipLaunchKernelGGL(k_cut_scan2, dim3(1), dim3(1024), 0, st,
+                               reinterpret_cast<u64 *>(C.group_total), n_groups,
+                               reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(2);
@@ -267,7 +313,8 @@ hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_d
                            reinterpret_cast<const u64 *>(G.m), C.local, C.flags,
                            reinterpret_cast<const u64 *>(C.group_total),
                            reinterpret_cast<u64 *>(d_row_offsets),
-                           reinterpret_cast<plogp_run_dev *>(d_runs), (u64)capacity);
+                           reinterpret_cast<plogp_run_dev *>(d_runs), (u64)capacity, fuse ? (int)n_groups : 0,
+                           reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     PLOGP_MARK(3);
 #undef PLOGP_MARK
