@@ -75,12 +75,12 @@ MEASURED_TRAFFIC = {
     5: {"terms": 0.684e6 + 2.139e6, "chain_blocks": 1.169e6 + 71.290e6,
         "chain_prefix": 50.977e6 + 18.574e6, "sweep": 54.121e6 + 93.322e6},
 }
-# the same for the three kernels of the cut-over extraction (mark, scan1 + scan2, emit)
+# the same for the kernels of the cut-over extraction (mark, scan1 [+ scan2 on config 4], emit)
 MEASURED_CUT_TRAFFIC = {
-    2: 34.219e6 + 2.095e6 + 0.563e6 + 0.526e6 + 0.006e6 + 0.001e6 + 9.287e6 + 0.486e6,
-    3: 2.382e6 + 0.141e6 + 0.060e6 + 0.035e6 + 0.006e6 + 1.725e6 + 0.982e6,
+    2: 34.270e6 + 2.095e6 + 0.563e6 + 0.526e6 + 9.296e6 + 0.486e6,
+    3: 2.387e6 + 0.141e6 + 0.060e6 + 0.035e6 + 1.734e6 + 0.982e6,
     4: 1993.133e6 + 61.704e6 + 30.754e6 + 30.840e6 + 0.035e6 + 0.030e6 + 297.974e6 + 52.548e6,
-    5: 96.910e6 + 5.859e6 + 1.497e6 + 1.464e6 + 0.007e6 + 0.001e6 + 26.708e6 + 0.865e6,
+    5: 97.012e6 + 5.952e6 + 1.497e6 + 1.464e6 + 26.717e6 + 0.865e6,
 }
 # the scoring kernels (k_score, k_score_rows, k_score_final) and the robustness summary
 # (k_robust_clear, k_robust; its per-table counts are one atomic per wave and table, which the
