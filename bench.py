@@ -72,8 +72,8 @@ MEASURED_TRAFFIC = {
     2: {"sweep": 0.336e6 + 33.560e6},
     3: {"chain_blocks": 0.387e6 + 1.496e6, "sweep": 4.016e6 + 2.294e6},
     4: {"terms": 5.283e6 + 10.736e6, "sweep": 88.979e6 + 1966.079e6},
-    5: {"terms": 0.684e6 + 2.139e6, "chain_blocks": 1.169e6 + 71.290e6,
-        "chain_prefix": 50.977e6 + 18.574e6, "sweep": 54.121e6 + 93.322e6},
+    5: {"terms": 0.671e6 + 2.139e6, "chain_blocks": 1.162e6 + 71.265e6,
+        "chain_prefix": 50.977e6 + 18.574e6, "sweep": 44.820e6 + 93.321e6},
 }
 # the same for the kernels of the cut-over extraction (mark, scan1 [+ scan2 on config 4], emit)
 MEASURED_CUT_TRAFFIC = {
