@@ -72,8 +72,8 @@ MEASURED_TRAFFIC = {
     2: {"sweep": 0.336e6 + 33.560e6},
     3: {"chain_blocks": 0.387e6 + 1.496e6, "sweep": 4.016e6 + 2.294e6},
     4: {"terms": 5.283e6 + 10.736e6, "sweep": 88.979e6 + 1966.079e6},
-    5: {"terms": 0.671e6 + 2.139e6, "chain_blocks": 1.162e6 + 71.265e6,
-        "chain_prefix": 50.977e6 + 18.574e6, "sweep": 44.820e6 + 93.321e6},
+    5: {"chain_blocks": 1.839e6 + 73.536e6,
+        "chain_prefix": 50.976e6 + 18.581e6, "sweep": 44.802e6 + 93.321e6},
 }
 # the same for the kernels of the cut-over extraction (mark, scan1 [+ scan2 on config 4], emit)
 MEASURED_CUT_TRAFFIC = {
@@ -399,8 +399,8 @@ def bench_config(cfg, steps, warmup, with_cpu, mask=None):
                 "sweep": {"flops": sum(w["flops"] for w in work.values()),
                           "bytes": sum(w["bytes"] for w in work.values())}}
     elif stage_ms["terms"] < 0.001 < stage_ms["chain_blocks"]:
-        # small tables: the terms and the chain sums run side by side in one launch, timed
-        # under "chain_blocks"
+        # the terms and the chain sums run in one launch (side by side for small tables, the
+        # terms at the end of each workgroup for big ones), timed under "chain_blocks"
         work = dict(work)
         work["chain_blocks"] = {k: work["chain_blocks"][k] + work["terms"][k] for k in ("flops", "bytes")}
         work["terms"] = {"flops": 0, "bytes": 0}

@@ -303,8 +303,11 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
     // per message size: g(m), the number of candidates, the prefix of g(2^j m).  Groups
     // of 64 sizes are dealt to the waves of this table's workgroups.
     const int n_mw = (G.n_m + 63) / 64;
-    const int m_step = (n_mchunks > 0 ? n_mchunks : n_chunks) * waves;
-    const int m_first = n_mchunks > 0 && !m_role ? n_mw : chunk * waves + (int)(threadIdx.x >> 6);
+    // (wave w of chunk c takes group w * chunks + c first: few groups spread over the
+    // workgroups, one wave in each, rather than filling the first of them)
+    const int m_chunks = n_mchunks > 0 ? n_mchunks : n_chunks;
+    const int m_step = m_chunks * waves;
+    const int m_first = n_mchunks > 0 && !m_role ? n_mw : (int)(threadIdx.x >> 6) * m_chunks + chunk;
     for (int mw = m_first; mw < n_mw; mw += m_step) {
         const int mi = mw * 64 + (int)(threadIdx.x & 63);
         if (mi >= G.n_m)
@@ -827,11 +830,19 @@ __device__ __forceinline__ void chain_small_body(const DeviceTables &T, const De
     }
 }
 
+// terms_mode >= 0: a workgroup that has run out of sums goes on with its share of the tuning's
+// first step (as chunk blockIdx.x of wg_per_table per table), in the same LDS: for a big
+// table that step is a few dependent lookups per workgroup, which fit in the time the
+// workgroups wait for the slowest of them anyway, and a launch less.
 __global__ void k_chain_blocks(DeviceTables T, DeviceGrid G, Scratch S, int wg_per_table,
-                               int n_single, int n_search)
+                               int n_single, int n_search, int terms_mode)
 {
     extern __shared__ __align__(16) double chain_lds[];
     chain_body(T, G, S, wg_per_table, n_single, n_search, (int)blockIdx.x, chain_lds);
+    if (terms_mode >= 0) {
+        __syncthreads();                  // every wave is done with the table as intervals
+        terms_body(T, G, S, wg_per_table, 0, terms_mode, (int)blockIdx.x, chain_lds);
+    }
 }
 
 // The Scatter-chain sums of one (table, distinct m) in one workgroup, for tables of few
@@ -3634,7 +3645,9 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
     const bool together = chain && !big && !chain_row;
     // (terms beside the per-row chain sums: when the terms need little LDS)
     const bool row_together = chain_row && terms_lds <= 65536;
-    if (!together && !row_together) {
+    // a big table: the workgroups of the chain sums do the terms when they run out of sums
+    const bool terms_in_chain = chain && big && !chain_row && terms_lds <= chain_lds;
+    if (!together && !row_together && !terms_in_chain) {
         for (int r = 0; r < reps; ++r)
             hipLaunchKernelGGL(k_terms, dim3(terms_wg), dim3(256), terms_lds, st, T, G, S, n_chunks,
                                n_mchunks, terms_mode);
@@ -3695,7 +3708,7 @@ hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch
                                    n_chain_wg, (int)wg, n_single, n_search, n_chunks, n_mchunks, terms_mode);
             else
                 hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
-                                   T, G, S, (int)wg, n_single, n_search);
+                                   T, G, S, (int)wg, n_single, n_search, terms_in_chain ? terms_mode : -1);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         PLOGP_MARK(2);
