@@ -52,6 +52,11 @@ def _load_library():
         raise ImportError(
             "%s is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
             "(or paper_cs_0408034_amd/build.py); there is no CPU fallback" % LIB_PATH)
+    # The callers hand this library device pointers and streams that PyTorch made, so both
+    # must sit on one HIP runtime: PyTorch's is loaded first, and the library binds to it.
+    # (Loaded the other way round, the library takes the system's runtime, PyTorch then its
+    # own, and the library's calls fail with "no device".)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(str(LIB_PATH))
     vp, sz, dp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double)
     pp = ctypes.POINTER(ctypes.c_void_p)
