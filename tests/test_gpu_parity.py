@@ -399,10 +399,10 @@ def test_repeated_calls_on_a_side_stream_give_the_same_table():
     grid.free(); tab.free()
 
 
-def _random_problem(rng):
+def _random_problem(rng, n_choices=(2, 3, 5, 17, 64, 65, 130, 300)):
     """A small random tuning job: table (possibly non-monotone), sizes with repeats in any
     order, ascending process counts, ascending candidates, cap, mask, one to four tables."""
-    n = int(rng.choice([2, 3, 5, 17, 64, 65, 130, 300]))
+    n = int(rng.choice(n_choices))
     steps = rng.integers(1, 2000, size=n).astype(np.float64)
     x = np.cumsum(steps)
     x[0] = float(rng.integers(1, 64))
@@ -450,6 +450,22 @@ def test_random_small_problems(seed):
         wl = _random_problem(rng)
         want, _ = oracle.tune_workload(wl)
         what = "random %d/%d: n=%d tables=%d m=%d P=%d s=%d cap=%d mask=%#x" % (
+            seed, k, wl.sizes.shape[1], wl.n_tables, len(wl.m), len(wl.P), len(wl.s), wl.s_cap & 0xFFFFFFFF,
+            wl.strategy_mask)
+        print(what, flush=True)
+        assert_tables_equal(gpu_tune(wl), want, what)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_problems_with_big_tables(seed):
+    """Tables of more than a thousand samples (one workgroup per CU holds the table; the
+    workgroups of the chain sums also form the per-size and per-candidate terms), one to four
+    of them, with every shape of grid the generator makes."""
+    rng = np.random.default_rng(7000 + seed)
+    for k in range(5):
+        wl = _random_problem(rng, n_choices=(1100, 1500, 2300, 4096))
+        want, _ = oracle.tune_workload(wl)
+        what = "big table %d/%d: n=%d tables=%d m=%d P=%d s=%d cap=%d mask=%#x" % (
             seed, k, wl.sizes.shape[1], wl.n_tables, len(wl.m), len(wl.P), len(wl.s), wl.s_cap & 0xFFFFFFFF,
             wl.strategy_mask)
         print(what, flush=True)
