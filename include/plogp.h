@@ -56,7 +56,8 @@ extern "C" {
 enum {
     PLOGP_OK = 0,
     PLOGP_EINVAL = 1,   /* bad argument (see each function)                          */
-    PLOGP_ERANGE = 2,   /* a size that enters a formula would reach 2^53             */
+    PLOGP_ERANGE = 2,   /* a size that enters a formula would reach 2^53, or a job   */
+                        /* is too large for one launch                               */
     PLOGP_ENOSPC = 3,   /* output buffer too small                                   */
     PLOGP_ENOMEM = 4,   /* host or device allocation failed                          */
     PLOGP_EDEVICE = 5   /* HIP error; plogp_last_hip_error() returns the HIP code    */
@@ -171,33 +172,16 @@ size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g);
  * A cell in which no strategy competed (e.g. only segmented ids enabled and
  * no candidate <= m) is {+inf, 0, PLOGP_NO_STRATEGY}.
  * Enqueued on `stream`; the result is complete when the stream reaches this
- * point.  Scratch memory is owned by the grid handle (allocated on first use,
- * reused afterwards): two tune calls on the same grid handle must not overlap.
- * Errors: EINVAL (null, misaligned d_out), ENOSPC, ENOMEM, EDEVICE.
+ * point.  Scratch memory is owned by the grid handle (one block, allocated on
+ * first use, replaced only when a later call needs a larger one): two calls
+ * that use the same grid handle's scratch (plogp_tune_grid, plogp_score_grid)
+ * must not overlap.  The table handle is only read.
+ * Errors: EINVAL (null, misaligned d_out), ENOSPC, ERANGE (the job would need a
+ * launch of 2^31 workgroups or more: split the batch or the grid), ENOMEM,
+ * EDEVICE.
  */
 int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size_t d_out_bytes,
                     void *stream);
-
-/*
- * plogp_tune_grid_profile -- the same work as plogp_tune_grid, measured: every
- * kernel of the sweep is launched `reps` times back to back (each launch
- * overwrites its outputs with the same values) between two HIP events on
- * `stream`; waits for completion and returns the mean milliseconds per launch
- * of each stage in stage_ms_out[0..3]:
- *   [0] per-table and per-m terms (interval slopes, g(1), g(s), g(m), the
- *       Scatter-binomial prefix sums), [1] Scatter-chain block sums,
- *   [2] Scatter-chain block prefix, [3] sweep + arg-min + decision-table write.
- * A stage that did not run reports 0 (two events with nothing between them may
- * read a fraction of a microsecond).  For tables of up to about 1000 samples
- * the terms and the Scatter-chain block sums are one launch, reported under
- * [1]; the paths that do everything in one kernel (batches of tables; one
- * workgroup per (table, m) row) report it under [3].
- * Synchronous.  For measurement only.
- * Errors: as plogp_tune_grid, plus EINVAL for a null stage_ms_out or reps
- * outside [1, 10000].
- */
-int plogp_tune_grid_profile(const plogp_table *t, plogp_grid *g, plogp_cell *d_out,
-                            size_t d_out_bytes, void *stream, int reps, float *stage_ms_out);
 
 /*
  * Cut-over extraction -- paper Section 3.1 (how the tuned segment size is
@@ -243,18 +227,6 @@ size_t plogp_cutover_rows(size_t n_tables, const plogp_grid *g);
  */
 int plogp_cutovers(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
                    uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity, void *stream);
-
-/*
- * plogp_cutovers_profile -- the same work, measured: each of the three steps
- * (mark run starts, prefix of their counts, write the runs) is launched `reps`
- * times back to back between two HIP events on `stream`; waits and returns
- * the mean milliseconds per launch in stage_ms_out[0..2].  Synchronous.
- * Errors: as plogp_cutovers, plus EINVAL for a null stage_ms_out or reps
- * outside [1, 10000].
- */
-int plogp_cutovers_profile(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
-                           uint64_t *d_row_offsets, plogp_run *d_runs, size_t runs_capacity,
-                           void *stream, int reps, float *stage_ms_out);
 
 /*
  * Prediction against measurement -- paper Section 4: every implementation is
@@ -310,19 +282,6 @@ int plogp_score_grid(const plogp_table *t, size_t table_index, plogp_grid *g, co
                      plogp_strategy_score *d_scores, void *stream);
 
 /*
- * plogp_score_grid_profile -- the same work, measured: each of its three steps
- * (g(m), g(1) and the Scatter sums; predictions and verdicts; statistics) is
- * launched `reps` times back to back between two HIP events; waits and returns
- * the mean milliseconds per launch in stage_ms_out[0..2].  Synchronous.
- * Errors: as plogp_score_grid, plus EINVAL for a null stage_ms_out or reps
- * outside [1, 10000].
- */
-int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_grid *g,
-                             const double *d_meas, const uint32_t *d_seg, double *d_pred,
-                             plogp_verdict *d_verdict, plogp_strategy_score *d_scores, void *stream,
-                             int reps, float *stage_ms_out);
-
-/*
  * Decision robustness -- paper Section 4 and the conclusion: the deviations
  * between prediction and reality did not change which technique the models
  * select.  For a batch of n_tables decision tables over grid g, laid out as
@@ -344,17 +303,6 @@ int plogp_score_grid_profile(const plogp_table *t, size_t table_index, plogp_gri
  */
 int plogp_robustness(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
                      uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree, void *stream);
-
-/*
- * plogp_robustness_profile -- the same work launched `reps` times back to back
- * between two HIP events on `stream`; waits and returns the mean milliseconds
- * per launch (clearing the outputs included) in *ms_out.  Synchronous.
- * Errors: as plogp_robustness, plus EINVAL for a null ms_out or reps outside
- * [1, 10000].
- */
-int plogp_robustness_profile(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells,
-                             int key_mode, uint32_t *d_agree, double *d_max_dev,
-                             uint32_t *d_table_agree, void *stream, int reps, float *ms_out);
 
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);

@@ -9,8 +9,9 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libplogp.so"
 SOURCES = [CSRC / "plogp_api.hip", CSRC / "plogp_kernels.hip", CSRC / "plogp_cutover.hip",
-           CSRC / "plogp_robust.hip"]
-HEADERS = [CSRC / "plogp_internal.hpp", PKG.parent / "include" / "plogp.h"]
+           CSRC / "plogp_robust.hip", CSRC / "plogp_profile.hip"]
+HEADERS = [CSRC / "plogp_internal.hpp", CSRC / "plogp_handles.hpp", PKG.parent / "include" / "plogp.h",
+           PKG.parent / "include" / "plogp_profile.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

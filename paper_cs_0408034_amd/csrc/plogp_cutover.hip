@@ -266,12 +266,10 @@ size_t cutover_items(const DeviceGrid &G, int n_tables)
     return (size_t)n_tables * G.n_ops * G.n_P * n_tiles;
 }
 
-hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
-                           const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
-                           uint64_t capacity, hipStream_t st, hipEvent_t *ev, int reps)
+hipError_t launch_cutovers_stage(int stage, const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells,
+                                 int key_mode, const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
+                                 uint64_t capacity, hipStream_t st)
 {
-    hipError_t e;
-    if (reps < 1) reps = 1;
     CutShape sh;
     sh.n_tables = n_tables;
     sh.n_ops = G.n_ops;
@@ -286,39 +284,29 @@ hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_d
     const size_t n_counts = cutover_items(G, n_tables);
     const size_t n_groups = (n_counts + CUT_SCAN_WG - 1) / CUT_SCAN_WG;
     const size_t n_rows = (size_t)n_tables * G.n_ops * G.n_P;
+    // one thread per (row, tile), padded to whole waves along P: must fit one launch
+    if ((sh.n_items + 255) / 256 > 0x7FFFFFFFL || n_groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)((sh.n_items + 255) / 256);
-#define PLOGP_MARK(i)                                                            \
-    do {                                                                         \
-        if (ev && (e = hipEventRecord(ev[i], st)) != hipSuccess) return e;       \
-    } while (0)
-    PLOGP_MARK(0);
-    for (int r = 0; r < reps; ++r)
+    const bool fuse = n_groups <= (size_t)CUT_FUSE_MAX;     // the prefix of the group totals inside the last step
+    if (stage == 0) {
         hipLaunchKernelGGL(k_cut_mark, dim3(blocks), dim3(256), 0, st, sh, d_cells, key_mode, C.counts,
                            C.flags);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    PLOGP_MARK(1);
-    const bool fuse = n_groups <= (size_t)CUT_FUSE_MAX;     // the prefix of the group totals inside the last step
-    for (int r = 0; r < reps; ++r) {
+    } else if (stage == 1) {
         hipLaunchKernelGGL(k_cut_scan1, dim3((unsigned)n_groups), dim3(CUT_SCAN_THREADS), 0, st,
                            C.counts, C.local, n_counts, reinterpret_cast<u64 *>(C.group_total));
         if (!fuse)
             hipLaunchKernelGGL(k_cut_scan2, dim3(1), dim3(1024), 0, st,
                                reinterpret_cast<u64 *>(C.group_total), n_groups,
                                reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
-    }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    PLOGP_MARK(2);
-    for (int r = 0; r < reps; ++r)
+    } else {
         hipLaunchKernelGGL(k_cut_emit, dim3(blocks), dim3(256), 0, st, sh, d_cells,
                            reinterpret_cast<const u64 *>(G.m), C.local, C.flags,
                            reinterpret_cast<const u64 *>(C.group_total),
                            reinterpret_cast<u64 *>(d_row_offsets),
                            reinterpret_cast<plogp_run_dev *>(d_runs), (u64)capacity, fuse ? (int)n_groups : 0,
                            reinterpret_cast<u64 *>(d_row_offsets) + n_rows);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    PLOGP_MARK(3);
-#undef PLOGP_MARK
-    return hipSuccess;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace plogp

@@ -23,7 +23,7 @@ constexpr int SWEEP_M_MAX_S = 256;
 struct DeviceTables {
     const double *x;      // [n_tables][n] sample sizes
     const double *y;      // [n_tables][n] gaps
-    double *slope;        // [n_tables][n] interval slopes (written by the kernels)
+    const double *slope;  // [n_tables][n] interval slopes (written once, when the tables are loaded)
     const double *L;      // [n_tables]
     int n;                // samples per table
     int n_tables;
@@ -108,18 +108,78 @@ struct plogp_cell_dev {
     uint32_t strategy;
 };
 
+// What the kernels' launch shapes are sized by: read once from the device properties.
+struct DeviceInfo {
+    int n_cu;             // compute units
+    size_t lds_per_cu;    // bytes of LDS of one compute unit
+};
+const DeviceInfo &device_info();
+
+// Where each scratch array of a tune (or scoring) call starts inside one block of device
+// memory, in bytes; every array starts on a 256-byte boundary.  An array the chosen path does
+// not use has offset 0: the first 256 bytes of the block are a spare that nothing reads.
+struct ScratchLayout {
+    size_t g1, gs, gm, sum2, blk, pre, part, rcp, segC, segA, segB, amin, nv;
+    size_t rec, tab, batch_ys;     // table-lane batch path
+    size_t score_rows;             // scoring only: 2 doubles per (strategy, m)
+    size_t total;                  // bytes of the block
+};
+
+enum TunePath : int { TUNE_TABLE_LANES = 0, TUNE_ROW = 1, TUNE_FUSED = 2, TUNE_STAGED = 3 };
+
+// Everything the host decides about one tune call before the first launch: the path, every
+// launch shape, and the scratch each kernel of that path reads or writes (one source for the
+// allocation and for the kernels' index ranges).
+struct TunePlan {
+    int path;                      // TunePath
+    int terms_only;                // the staged terms and sums only (scoring)
+    ScratchLayout lay;
+    // table-lane batch path
+    int n_stage, prep_wg, n_tg, m_per_wave, batch_mchunks;
+    size_t setup_lds, batch_lds;
+    // whole-row path
+    int row_two;
+    size_t row_lds;
+    // lane-per-m batch path
+    int fused_mchunks;
+    // staged path
+    int lanes_s, lanes_p, pairs, terms_mode, n_chunks, n_mchunks, terms_wg;
+    int chain, chain_row, together, row_together, terms_in_chain, chain_threads;
+    int n_single, n_search, chain_wg, n_chain_wg, n_mgroups;
+    size_t terms_lds, chain_lds, both_lds, crow_lds;
+    int sweep_gp, sweep_ptiles;    // lanes over s
+    int ppl, n_pg, n_w;            // lanes over P
+    int n_mg, n_pcg;               // lanes over m
+};
+
+// Stages of a tune call, in launch order; a stage may launch nothing.
+enum { TUNE_STAGE_TERMS = 0, TUNE_STAGE_CHAIN = 1, TUNE_STAGE_PREFIX = 2, TUNE_STAGE_SWEEP = 3,
+       TUNE_STAGES = 4 };
+
+// Fills `plan`.  Returns false if a launch dimension or an index of the chosen path would not
+// fit 31 bits (the job is too large for one call).
+bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, TunePlan &plan);
+// The scratch arrays of a plan inside the block that starts at `base`.
+Scratch bind_scratch(void *base, const ScratchLayout &lay);
+
 // Each returns the hipError_t of the launch (hipGetLastError after it).
-hipError_t launch_slopes(const DeviceTables &T, hipStream_t st);
+hipError_t launch_slopes(const DeviceTables &T, double *slope_out, hipStream_t st);
 hipError_t launch_interp(const DeviceTables &T, int table, const uint64_t *d_z, size_t n,
                          double *d_out, hipStream_t st);
 hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uint64_t *d_m,
                        const uint32_t *d_P, const uint64_t *d_s, size_t n, double *d_out,
                        hipStream_t st);
-// ev: nullptr, or 5 events recorded before the first kernel and after each stage;
-// reps: launches of every stage between its two events (1 outside measurement).
-hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
-                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev = nullptr,
-                       int reps = 1);
+hipError_t launch_tune_stage(const TunePlan &plan, int stage, const DeviceTables &T, const DeviceGrid &G,
+                             const Scratch &S, plogp_cell_dev *d_out, hipStream_t st);
+inline hipError_t launch_tune(const TunePlan &plan, const DeviceTables &T, const DeviceGrid &G,
+                              const Scratch &S, plogp_cell_dev *d_out, hipStream_t st)
+{
+    for (int stage = 0; stage < TUNE_STAGES; ++stage) {
+        const hipError_t e = launch_tune_stage(plan, stage, T, G, S, d_out, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 // ---- cut-over extraction (plogp_cutover.hip)
 constexpr int CUT_TM = 16;                 // message sizes per thread (a tile of one row)
@@ -137,28 +197,27 @@ struct CutScratch {
 
 // Number of (row, tile) entries for n_tables tables over grid G.
 size_t cutover_items(const DeviceGrid &G, int n_tables);
-// ev: nullptr, or 4 events recorded before the first kernel and after mark, scan, emit.
-hipError_t launch_cutovers(const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
-                           const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
-                           uint64_t capacity, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+// Stages: 0 mark the run starts, 1 prefix of their counts, 2 write the runs.
+enum { CUT_STAGES = 3 };
+hipError_t launch_cutovers_stage(int stage, const DeviceGrid &G, int n_tables, const plogp_cell_dev *d_cells,
+                                 int key_mode, const CutScratch &C, uint64_t *d_row_offsets, void *d_runs,
+                                 uint64_t capacity, hipStream_t st);
 
-// Prediction against measurement for one table (T1: a view of that table alone).  rows:
-// scratch of 2 doubles per (enabled strategy, m).  ev: nullptr, or 4 events recorded
-// before the first kernel and after the terms, the scoring and the statistics.
-hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scratch &S, double *rows,
-                        const double *d_meas, const uint32_t *d_seg, double *d_pred, void *d_verdict,
-                        void *d_scores, hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+// Prediction against measurement for one table (T1: a view of that table alone).  plan: the
+// terms-only plan of (T1, G), its scratch bound in S, score_rows among it.  Stages: 0 the
+// terms and sums (the tune's own first stages), 1 predictions and verdicts, 2 statistics.
+enum { SCORE_STAGES = 3 };
+hipError_t launch_score_stage(int stage, const TunePlan &plan, const DeviceTables &T1, const DeviceGrid &G,
+                              const Scratch &S, double *rows, const double *d_meas, const uint32_t *d_seg,
+                              double *d_pred, void *d_verdict, void *d_scores, hipStream_t st);
 
 // Robustness summary of n_tables decision tables of `cells` records each (table 0 is the
-// reference).  d_max_dev and d_table_agree may be null.  ev: nullptr, or 2 events around
-// the work.  cells < 2^40 and n_tables >= 1 are the caller's to check.
+// reference).  d_max_dev and d_table_agree may be null.  cells < 2^40 and n_tables >= 1 are
+// the caller's to check.
 hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
                              uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree,
-                             hipStream_t st, hipEvent_t *ev = nullptr, int reps = 1);
+                             hipStream_t st);
 
 hipError_t kernels_init();
-bool use_fused_path(const DeviceTables &T, const DeviceGrid &G);
-bool use_row_path(const DeviceTables &T, const DeviceGrid &G);
-bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G);
 
 }  // namespace plogp

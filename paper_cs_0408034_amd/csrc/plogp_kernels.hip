@@ -136,12 +136,12 @@ __device__ __forceinline__ double min_f64(double a, double b)
 
 // ---------------------------------------------------------------- slopes (table load)
 
-__global__ void __launch_bounds__(256) k_slopes(DeviceTables T)
+__global__ void __launch_bounds__(256) k_slopes(DeviceTables T, double *slope_out)
 {
     const int t = blockIdx.x, n = T.n;
     const double *x = T.x + (size_t)t * n, *y = T.y + (size_t)t * n;
     for (int i = threadIdx.x; i < n; i += blockDim.x)
-        T.slope[(size_t)t * n + i] = interval_slope(x, y, n, i);
+        slope_out[(size_t)t * n + i] = interval_slope(x, y, n, i);
 }
 
 // ---------------------------------------------------------------- g() at arbitrary sizes
@@ -248,8 +248,8 @@ __device__ __forceinline__ double from_ordered_bits(unsigned long long k)
 }
 
 // One workgroup per (table, chunk of blockDim items); a lane takes one m and
-// one s.  Computes the interval slopes from the raw samples (chunk 0 publishes
-// them, and the table as intervals for the chain-sum walk), g(m), the number of
+// one s.  Computes the interval slopes from the raw samples (into LDS, for its
+// own lookups), g(m), the number of
 // candidates that compete for m and the prefix sums over j of g(2^j m) for its
 // rows, g(s) for its candidates and (first table only) the reciprocals 1/s used
 // to get k = ceil(m/s) without a division per (m, s); chunk 0 also g(1).
@@ -274,12 +274,8 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
         y[i] = gy[i];
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-        const double v = interval_slope(x, y, n, i);
-        sl[i] = v;
-        if (first)
-            T.slope[(size_t)t * n + i] = v;
-    }
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+        sl[i] = interval_slope(x, y, n, i);
     __syncthreads();
     const LdsTable tab = {x, y, sl, n};
     // for the sweep that runs its lanes over P: g(s) and 1/s of every candidate, for this
@@ -3421,9 +3417,24 @@ static const size_t kMaxTableLds = (size_t)3 * 4096 * sizeof(double) + 96 +
                                    (size_t)2 * SWEEP_M_MAX_S * sizeof(double);   // + g(s), 1/s in k_terms
 static const size_t kMaxChainLds = (size_t)4 * 4096 * sizeof(double) + 112;   // + interval widths
 
+static DeviceInfo g_device = {256, (size_t)160 * 1024};
+
+const DeviceInfo &device_info() { return g_device; }
+
 hipError_t kernels_init()
 {
     hipError_t e;
+    {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+        if (prop.multiProcessorCount > 0) g_device.n_cu = prop.multiProcessorCount;
+        // the kernels that fill a compute unit's LDS were laid out for 160 KB; a device that
+        // reports less gets fewer workgroups per unit from the same formulas
+        if (prop.maxSharedMemoryPerMultiProcessor >= (size_t)64 * 1024)
+            g_device.lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    }
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_interp),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
@@ -3453,9 +3464,9 @@ hipError_t kernels_init()
     return e;
 }
 
-hipError_t launch_slopes(const DeviceTables &T, hipStream_t st)
+hipError_t launch_slopes(const DeviceTables &T, double *slope_out, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_slopes, dim3(T.n_tables), dim3(256), 0, st, T);
+    hipLaunchKernelGGL(k_slopes, dim3(T.n_tables), dim3(256), 0, st, T, slope_out);
     return hipGetLastError();
 }
 
@@ -3463,6 +3474,7 @@ hipError_t launch_interp(const DeviceTables &T, int table, const uint64_t *d_z, 
                          double *d_out, hipStream_t st)
 {
     if (n == 0) return hipSuccess;
+    if ((n + 255) / 256 > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const size_t lds = (size_t)3 * T.n * sizeof(double);
     const unsigned blocks = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(k_interp, dim3(blocks), dim3(256), lds, st, T, table,
@@ -3475,6 +3487,7 @@ hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uin
                        hipStream_t st)
 {
     if (n == 0) return hipSuccess;
+    if ((n + 255) / 256 > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const size_t lds = (size_t)3 * T.n * sizeof(double);
     const unsigned blocks = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(k_eval, dim3(blocks), dim3(256), lds, st, T, table, strategy,
@@ -3486,14 +3499,14 @@ hipError_t launch_eval(const DeviceTables &T, int table, int strategy, const uin
 // Batches with enough (table, m) rows to fill the chip, few candidates and a short
 // chain sum go through the single fused kernel; everything else through the
 // staged kernels.
-bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
+static bool use_fused_path(const DeviceTables &T, const DeviceGrid &G)
 {
     return (long)T.n_tables * G.n_m >= 8192 && G.n_s <= FUSED_NS && G.n_blk <= 32;
 }
 
 // Few tables, few candidates, few blocks of the chain sum and many process counts: one
 // workgroup per (table, m) does the whole path (k_row).
-bool use_row_path(const DeviceTables &T, const DeviceGrid &G)
+static bool use_row_path(const DeviceTables &T, const DeviceGrid &G)
 {
     return G.n_s <= ROW_NS && G.n_blk <= ROW_MAX_BLK && T.n <= ROW_MAX_N && G.n_P >= 256 &&
            (long)T.n_tables * G.n_m >= 256 && (long)T.n_tables * G.n_m <= 65535 * 16;
@@ -3508,7 +3521,7 @@ static size_t batch_t_lds(int n, int n_s)
 
 // Batches whose tables share their sample sizes, with enough tables to fill waves and
 // few enough samples and candidates for the LDS staging: lanes over tables.
-bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G)
+static bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G)
 {
     // a lane's byte offset inside a store (up to 7 tables + 7 cells on) is kept in 32 bits
     const size_t table_cells = (size_t)G.n_ops * G.n_m * G.n_P;
@@ -3516,321 +3529,392 @@ bool use_table_lane_path(const DeviceTables &T, const DeviceGrid &G)
            table_cells <= ((size_t)1 << 24) && batch_t_lds(T.n, G.n_s) <= BATCH_T_LDS_MAX;
 }
 
-hipError_t launch_tune(const DeviceTables &T, const DeviceGrid &G, const Scratch &S,
-                       plogp_cell_dev *d_out, hipStream_t st, hipEvent_t *ev, int reps)
-{
-    // reps > 1 (measurement only): every stage is launched reps times back to back
-    // between its two events; each stage overwrites its own outputs with the same values
-    hipError_t e;
-    if (reps < 1) reps = 1;
-    const size_t tab_lds = (size_t)3 * T.n * sizeof(double);
-#define PLOGP_MARK(i)                                                            \
-    do {                                                                         \
-        if (ev && (e = hipEventRecord(ev[i], st)) != hipSuccess) return e;       \
-    } while (0)
+namespace {
 
-    PLOGP_MARK(0);
-    const bool terms_only = d_out == nullptr;      // the staged terms and sums, no sweep
+// Lays the arrays of a plan out one after the other, each on a 256-byte boundary; the first
+// 256 bytes stay free (arrays of size 0 point there).
+struct LayoutBuilder {
+    size_t at = 256;
+    size_t take(size_t bytes)
+    {
+        if (bytes == 0) return 0;
+        const size_t here = at;
+        at += (bytes + 255) & ~(size_t)255;
+        return here;
+    }
+};
+
+constexpr long kMaxLaunch = 0x7FFFFFFFL;      // workgroups of one launch, and int indices inside the kernels
+
+}  // namespace
+
+Scratch bind_scratch(void *base, const ScratchLayout &lay)
+{
+    char *b = static_cast<char *>(base);
+    Scratch S = {};
+    S.g1 = reinterpret_cast<double *>(b + lay.g1);
+    S.gs = reinterpret_cast<double *>(b + lay.gs);
+    S.gm = reinterpret_cast<double *>(b + lay.gm);
+    S.sum2 = reinterpret_cast<double *>(b + lay.sum2);
+    S.blk = reinterpret_cast<double *>(b + lay.blk);
+    S.pre = reinterpret_cast<double *>(b + lay.pre);
+    S.part = reinterpret_cast<double *>(b + lay.part);
+    S.rcp = reinterpret_cast<double *>(b + lay.rcp);
+    S.segC = reinterpret_cast<double *>(b + lay.segC);
+    S.segA = reinterpret_cast<double *>(b + lay.segA);
+    S.segB = reinterpret_cast<double *>(b + lay.segB);
+    S.amin = reinterpret_cast<double *>(b + lay.amin);
+    S.nv = reinterpret_cast<int *>(b + lay.nv);
+    S.batch.rec = reinterpret_cast<double *>(b + lay.rec);
+    S.batch.tab = reinterpret_cast<double *>(b + lay.tab);
+    S.batch_ys = reinterpret_cast<double *>(b + lay.batch_ys);
+    return S;
+}
+
+bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, TunePlan &p)
+{
+    p = TunePlan{};
+    p.terms_only = terms_only ? 1 : 0;
+    const DeviceInfo &dev = device_info();
+    const long n_cu = dev.n_cu;
+    const size_t D = sizeof(double);
+    const size_t nt = (size_t)T.n_tables, n_m = (size_t)G.n_m, n_mu = (size_t)G.n_mu;
+    const size_t n_P = (size_t)G.n_P, n_s = (size_t)G.n_s;
+    LayoutBuilder lb;
     if (!terms_only && use_table_lane_path(T, G)) {
+        p.path = TUNE_TABLE_LANES;
         // tables by interval and the per-m facts, then everything else in one kernel
-        const int n_stage = (T.n_tables + BATCH_STAGE_TT - 1) / BATCH_STAGE_TT;
+        p.n_stage = (T.n_tables + BATCH_STAGE_TT - 1) / BATCH_STAGE_TT;
         long prep_items = (long)G.n_m * (T.n + 1);
         if ((long)G.n_m * G.n_s > prep_items) prep_items = (long)G.n_m * G.n_s;
         long prep_wg = (prep_items + 255) / 256;
         if (prep_wg > 1024) prep_wg = 1024;
-        const size_t setup_lds = (size_t)BATCH_STAGE_TT * (T.n + 1) * sizeof(double);
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_batch_setup, dim3((unsigned)(n_stage + prep_wg)), dim3(256), setup_lds,
-                               st, T, G, S.batch, reinterpret_cast<f64x2 *>(S.batch_ys), n_stage);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(1);
-        PLOGP_MARK(2);
-        PLOGP_MARK(3);
+        p.prep_wg = (int)prep_wg;
+        p.setup_lds = (size_t)BATCH_STAGE_TT * (T.n + 1) * D;
         // a workgroup: 64 tables x (BATCH_T_WAVES waves x m_per_wave sizes)
-        const int n_tg = (T.n_tables + 63) / 64;
+        p.n_tg = (T.n_tables + 63) / 64;
         const int per = BATCH_T_WAVES;
         int m_per_wave = 8;
-        while (m_per_wave > 1 && (long)n_tg * ((G.n_m + per * m_per_wave - 1) / (per * m_per_wave)) < 1024)
+        while (m_per_wave > 1 && (long)p.n_tg * ((G.n_m + per * m_per_wave - 1) / (per * m_per_wave)) < 4 * n_cu)
             m_per_wave >>= 1;
-        const int n_mchunks = (G.n_m + per * m_per_wave - 1) / (per * m_per_wave);
-        const size_t lds = batch_t_lds(T.n, G.n_s);
-        BatchDims D;
-        D.n = T.n; D.n_tables = T.n_tables; D.n_m = G.n_m; D.n_P = G.n_P; D.n_s = G.n_s;
-        D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = n_mchunks; D.m_per_wave = m_per_wave;
-        D.mask = G.mask;
-        const auto kern = G.mask == 0x1FFFu ? k_batch_t<BATCH_T_PC, BATCH_T_PS, true>
-                                            : k_batch_t<BATCH_T_PC, BATCH_T_PS, false>;
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(kern, dim3((unsigned)n_tg * n_mchunks),
-                               dim3(64 * BATCH_T_WAVES), lds, st, D,
-                               reinterpret_cast<const f64x2 *>(S.batch_ys), T.L, S.batch.rec, S.batch.tab,
-                               G.P, reinterpret_cast<const u64 *>(G.s), d_out);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(4);
-        return hipSuccess;
+        p.m_per_wave = m_per_wave;
+        p.batch_mchunks = (G.n_m + per * m_per_wave - 1) / (per * m_per_wave);
+        p.batch_lds = batch_t_lds(T.n, G.n_s);
+        if ((long)p.n_tg * p.batch_mchunks > kMaxLaunch) return false;
+        const BatchRec R(T.n, G.n_s, G.cl_max);
+        p.lay.rec = lb.take(n_m * (size_t)R.slots * D);
+        p.lay.tab = lb.take((2 + ((size_t)T.n + 1) + 2 * (n_s ? n_s : 1) + 3 * n_P) * D);
+        p.lay.batch_ys = lb.take(((size_t)T.n + 2) * nt * 2 * D);
+        p.lay.total = lb.at;
+        return true;
     }
     if (!terms_only && !use_fused_path(T, G) && use_row_path(T, G)) {
-        PLOGP_MARK(1);
-        PLOGP_MARK(2);
-        PLOGP_MARK(3);
-        const bool all = G.mask == 0x1FFFu;
+        p.path = TUNE_ROW;
         // two process counts per lane when there are more groups of 64 than waves
-        const bool two = G.n_P > 64 * (ROW_THREADS / 64);
-        const auto kern = all ? (two ? k_row<true, 2> : k_row<true, 1>) : (two ? k_row<false, 2> : k_row<false, 1>);
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(kern, dim3((unsigned)(T.n_tables * G.n_m)), dim3(ROW_THREADS),
-                               row_lds_bytes(T.n, G.n_blk, G.n_P), st, T, G, d_out);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(4);
-        return hipSuccess;
+        p.row_two = G.n_P > 64 * (ROW_THREADS / 64);
+        p.row_lds = row_lds_bytes(T.n, G.n_blk, G.n_P);
+        p.lay.total = lb.at;
+        return true;
     }
     if (!terms_only && use_fused_path(T, G)) {
-        PLOGP_MARK(1);
-        PLOGP_MARK(2);
-        PLOGP_MARK(3);
-        const int n_mchunks = (G.n_m + 255) / 256;
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * n_mchunks), dim3(256),
-                               tab_lds + 64, st, T, G, d_out, n_mchunks);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(4);
-        return hipSuccess;
+        p.path = TUNE_FUSED;
+        p.fused_mchunks = (G.n_m + 255) / 256;
+        if ((long)T.n_tables * p.fused_mchunks > kMaxLaunch) return false;
+        p.lay.total = lb.at;
+        return true;
     }
+    p.path = TUNE_STAGED;
+    const size_t tab_lds = (size_t)3 * T.n * D;
     // which sweep runs: lanes over s for many candidates, else lanes over P if the grid
     // has enough process counts to fill a wave, else lanes over m
     const bool lanes_s = G.n_s > SWEEP_M_MAX_S;
     const bool lanes_p = !terms_only && !lanes_s && G.n_P >= 32 && G.n_P <= 65535 * 64;   // grid.y
+    // the per-(m, s) terms A, B and min_s A in device memory: only for the sweep that runs its
+    // lanes over P, and only when there is a candidate at all
+    const bool pairs = lanes_p && G.n_s > 0;
+    p.lanes_s = lanes_s;
+    p.lanes_p = lanes_p;
+    p.pairs = pairs;
     long n_items = G.n_m > G.n_s ? G.n_m : G.n_s;          // a lane takes one m and one s ...
-    if (lanes_p && (long)G.n_m * G.n_s > n_items)
+    if (pairs && (long)G.n_m * G.n_s > n_items)
         n_items = (long)G.n_m * G.n_s;                     // ... and one (m, s) pair
     long n_chunks_l = (n_items + 255) / 256;
     // the candidates go to LDS too (for the count per m) if they fit beside the table and are
     // few: every workgroup stages them all, and for 8192 of them that takes longer (11.8 us)
     // than the thirteen dependent loads of a search in device memory (6.9 us)
-    const size_t pair_lds = lanes_p ? (size_t)2 * G.n_s * sizeof(double) : 0;
-    const bool stage_s = G.n_s > 0 && G.n_s <= 1024 &&
-                         tab_lds + pair_lds + (size_t)G.n_s * sizeof(double) <= kMaxTableLds;
-    const int terms_mode = (lanes_p ? 1 : 0) | (stage_s ? 2 : 0);
-    const size_t terms_lds = tab_lds + pair_lds + (stage_s ? (size_t)G.n_s * sizeof(double) : 0);
+    const size_t pair_lds = pairs ? (size_t)2 * G.n_s * D : 0;
+    const bool stage_s = G.n_s > 0 && G.n_s <= 1024 && tab_lds + pair_lds + (size_t)G.n_s * D <= kMaxTableLds;
+    p.terms_mode = (pairs ? 1 : 0) | (stage_s ? 2 : 0);
+    p.terms_lds = tab_lds + pair_lds + (stage_s ? (size_t)G.n_s * D : 0);
     // a workgroup stages the whole table: with a big table one workgroup fits a CU, so no
     // more workgroups than CUs
-    const long wg_cap = terms_lds > 65536 ? 256 : 512;
+    const long wg_cap = p.terms_lds > 65536 ? n_cu : 2 * n_cu;
     const long chunk_cap = wg_cap / T.n_tables > 1 ? wg_cap / T.n_tables : 1;
     if (n_chunks_l > chunk_cap) n_chunks_l = chunk_cap;
     // the per-size part in workgroups of its own, beside the others: freely for small tables;
     // for a big table (one workgroup per CU) out of the same budget of workgroups
     int n_mchunks = 0;
-    if (terms_lds <= 16384) {
+    if (p.terms_lds <= 16384) {
         n_mchunks = ((G.n_m + 63) / 64 + 3) / 4;
-        const int cap = 256 / T.n_tables > 1 ? 256 / T.n_tables : 1;
+        const int cap = n_cu / T.n_tables > 1 ? (int)(n_cu / T.n_tables) : 1;
         if (n_mchunks > cap) n_mchunks = cap;
     } else if (T.n_tables == 1 && n_chunks_l >= 64) {
         n_mchunks = ((G.n_m + 63) / 64 + 3) / 4;
         if (n_mchunks > n_chunks_l / 8) n_mchunks = (int)(n_chunks_l / 8);
         if (n_chunks_l + n_mchunks > chunk_cap) n_chunks_l = chunk_cap - n_mchunks;
     }
-    const int n_chunks = (int)n_chunks_l;
-    const unsigned terms_wg = (unsigned)T.n_tables * (unsigned)(n_chunks + n_mchunks);
+    p.n_chunks = (int)n_chunks_l;
+    p.n_mchunks = n_mchunks;
+    const long terms_wg = (long)T.n_tables * (p.n_chunks + n_mchunks);
+    if (terms_wg > kMaxLaunch) return false;
+    p.terms_wg = (int)terms_wg;
     const bool chain = (G.mask & (1u << 11)) != 0;
+    p.chain = chain;
     // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
     // stays for its whole share of the work (the table is staged once)
-    const size_t chain_lds = (size_t)4 * T.n * sizeof(double) + 112;
-    const bool big = chain_lds > 32768;
+    p.chain_lds = (size_t)4 * T.n * D + 112;
+    const bool big = p.chain_lds > 32768;
     // few samples, few blocks, enough distinct sizes: a workgroup per (table, m) forms all
     // its sums, the prefix over the blocks included
-    const bool chain_row = chain && T.n <= 512 && G.n_blk <= CROW_MAX_BLK &&
-                           chain_row_lds(T.n, G.n_blk) <= 65536 &&
-                           (long)T.n_tables * G.n_mu >= 128 && (long)T.n_tables * G.n_mu <= (1L << 24);
+    p.crow_lds = chain_row_lds(T.n, G.n_blk);
+    p.chain_row = chain && T.n <= 512 && G.n_blk <= CROW_MAX_BLK && p.crow_lds <= 65536 &&
+                  (long)T.n_tables * G.n_mu >= 128 && (long)T.n_tables * G.n_mu <= (1L << 24);
     // small tables: the terms and the chain sums in one launch, side by side
-    const bool together = chain && !big && !chain_row;
+    p.together = chain && !big && !p.chain_row;
     // (terms beside the per-row chain sums: when the terms need little LDS)
-    const bool row_together = chain_row && terms_lds <= 65536;
+    p.row_together = p.chain_row && p.terms_lds <= 65536;
     // a big table: the workgroups of the chain sums do the terms when they run out of sums
-    const bool terms_in_chain = chain && big && !chain_row && terms_lds <= chain_lds;
-    if (!together && !row_together && !terms_in_chain) {
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_terms, dim3(terms_wg), dim3(256), terms_lds, st, T, G, S, n_chunks,
-                               n_mchunks, terms_mode);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    PLOGP_MARK(1);
-
-    if (chain_row) {
-        const size_t crow_lds = chain_row_lds(T.n, G.n_blk);
-        for (int r = 0; r < reps; ++r) {
-            if (row_together)
-                hipLaunchKernelGGL(k_terms_chain_row, dim3(terms_wg + (unsigned)(T.n_tables * G.n_mu)),
-                                   dim3(CROW_THREADS), crow_lds > terms_lds ? crow_lds : terms_lds, st, T, G,
-                                   S, (int)terms_wg, n_chunks, n_mchunks, terms_mode);
-            else
-                hipLaunchKernelGGL(k_chain_row, dim3((unsigned)(T.n_tables * G.n_mu)), dim3(CROW_THREADS),
-                                   crow_lds, st, T, G, S);
-        }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(2);
-        PLOGP_MARK(3);
+    p.terms_in_chain = chain && big && !p.chain_row && p.terms_lds <= p.chain_lds;
+    if (p.chain_row) {
+        if ((long)p.terms_wg + (long)T.n_tables * G.n_mu > kMaxLaunch) return false;
     } else if (chain) {
-        const int threads = big ? 1024 : 256;
+        p.chain_threads = big ? 1024 : 256;
         const int n_mg = (G.n_mu + 63) / 64;
         // leading blocks that are items of their own: the dense part of a table with many
         // samples (its first blocks search per term), or every block when the whole sum is
         // too small to fill the chip with units of CHAIN_U blocks
         int n_single = T.n > 256 ? 32 : 0, n_search = T.n > 256 ? 4 : 0;
-        if ((long)T.n_tables * n_mg * ((G.n_blk + CHAIN_U - 1) / CHAIN_U) < 2048) n_single = G.n_blk;
+        if ((long)T.n_tables * n_mg * ((G.n_blk + CHAIN_U - 1) / CHAIN_U) < 8 * n_cu) n_single = G.n_blk;
         if (n_single > G.n_blk) n_single = G.n_blk;
         if (n_search > n_single) n_search = n_single;
-        const long n_items = (long)n_mg * (n_single + (G.n_blk - n_single + CHAIN_U - 1) / CHAIN_U);
-        long wg = (big ? 256 : 1024) / T.n_tables;
-        const long wg_need = (n_items + threads / 64 - 1) / (threads / 64);
+        const long items = (long)n_mg * (n_single + (G.n_blk - n_single + CHAIN_U - 1) / CHAIN_U);
+        if (items > kMaxLaunch) return false;
+        long wg = (big ? n_cu : 4 * n_cu) / T.n_tables;
+        const long wg_need = (items + p.chain_threads / 64 - 1) / (p.chain_threads / 64);
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
         // a small job (the walk would be bound by one lane's latency): every term by a search
         const long n_terms = (long)T.n_tables * G.n_mu * G.n_blk * SUM_BLOCK;
-        const bool small = together && n_single == G.n_blk && n_terms <= (3L << 20);
-        size_t both_lds = chain_lds > terms_lds ? chain_lds : terms_lds;
+        const bool small = p.together && n_single == G.n_blk && n_terms <= (3L << 20);
+        p.both_lds = p.chain_lds > p.terms_lds ? p.chain_lds : p.terms_lds;
         if (small) {
-            const size_t small_lds = ((size_t)3 * T.n + 10 + 64 * SMALL_LD) * sizeof(double);
-            if (small_lds > both_lds) both_lds = small_lds;
+            const size_t small_lds = ((size_t)3 * T.n + 10 + 64 * SMALL_LD) * D;
+            if (small_lds > p.both_lds) p.both_lds = small_lds;
             n_single = -1;
             wg = (long)n_mg * G.n_blk;
             // the chain workgroups come first in the grid: they must leave the terms
             // workgroups room on the chip, or those would only start when these are done
-            long room = 256L * (long)((160 * 1024) / (both_lds + 512)) - (long)terms_wg;
-            if (room > 512) room = 512;
+            long room = n_cu * (long)(dev.lds_per_cu / (p.both_lds + 512)) - (long)p.terms_wg;
+            if (room > 2 * n_cu) room = 2 * n_cu;
             if (wg > room / T.n_tables) wg = room / T.n_tables;
             if (wg < 1) wg = 1;
         }
-        const int n_chain_wg = (int)(T.n_tables * wg);
-        for (int r = 0; r < reps; ++r) {
-            if (together)
-                hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)n_chain_wg + terms_wg),
-                                   dim3(256), both_lds, st, T, G, S,
-                                   n_chain_wg, (int)wg, n_single, n_search, n_chunks, n_mchunks, terms_mode);
-            else
-                hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)n_chain_wg), dim3(threads), chain_lds, st,
-                                   T, G, S, (int)wg, n_single, n_search, terms_in_chain ? terms_mode : -1);
-        }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        PLOGP_MARK(2);
-        if (G.blk_is_prefix) {
-            const int n_mgroups = (G.n_mu + PFX_M - 1) / PFX_M;
-            for (int r = 0; r < reps; ++r)
-                hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * n_mgroups), dim3(256),
-                                   0, st, G, S, n_mgroups);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        PLOGP_MARK(3);
-    } else {
-        PLOGP_MARK(2);
-        PLOGP_MARK(3);
+        p.n_single = n_single;
+        p.n_search = n_search;
+        p.chain_wg = (int)wg;
+        if ((long)T.n_tables * wg + p.terms_wg > kMaxLaunch) return false;
+        p.n_chain_wg = (int)(T.n_tables * wg);
+        p.n_mgroups = (G.n_mu + PFX_M - 1) / PFX_M;
+        if ((long)T.n_tables * p.n_mgroups > kMaxLaunch) return false;
     }
-
-    if (terms_only) {
-        PLOGP_MARK(4);
-        return hipSuccess;
-    }
-    for (int r = 0; r < reps; ++r) {
+    if (!terms_only) {
         if (lanes_s) {
             // 8 waves per workgroup (two per SIMD, so that two workgroups share a CU); the
             // process counts per wave are chosen so that one workgroup covers all of them if
             // it can
-            const int waves = 8;
-            const unsigned rows = (unsigned)T.n_tables * G.n_m;
-            if (G.n_P <= 6 * waves) {
-                hipLaunchKernelGGL(k_sweep_s<6>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
-            } else if (G.n_P <= 9 * waves) {
-                hipLaunchKernelGGL(k_sweep_s<9>, dim3(rows), dim3(64 * waves), 0, st, T, G, S, d_out, 1);
-            } else {
-                const int n_ptiles = (G.n_P + 12 * waves - 1) / (12 * waves);
-                hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * n_ptiles), dim3(64 * waves), 0, st, T, G, S,
-                                   d_out, n_ptiles);
-            }
+            const int waves = SWEEP_S_MAX_WAVES;
+            p.sweep_gp = G.n_P <= 6 * waves ? 6 : (G.n_P <= 9 * waves ? 9 : 12);
+            p.sweep_ptiles = p.sweep_gp == 12 ? (G.n_P + 12 * waves - 1) / (12 * waves) : 1;
+            if ((long)T.n_tables * G.n_m * p.sweep_ptiles > kMaxLaunch) return false;
         } else if (lanes_p) {
             // as many waves as the chip holds at four per SIMD, shared out over the tables and
-            // the groups of 64 process counts; each walks over every n_w-th message size
+            // the groups of 64 process counts; each walks over every n_w-th message size;
             // two process counts per lane when the grid has at least 512 of them
             const bool all = G.mask == 0x1FFFu;
-            const int ppl = G.n_P >= 512 && G.n_s <= 64 && all ? 2 : 1;
-            const int n_pg = (G.n_P + 64 * ppl - 1) / (64 * ppl);
-            // (a big job - config 5: 6 x 4096 groups of cells - runs best with one size per wave:
+            p.ppl = G.n_P >= 512 && G.n_s <= 64 && all ? 2 : 1;
+            p.n_pg = (G.n_P + 64 * p.ppl - 1) / (64 * p.ppl);
+            // (a big job - 6 x 4096 groups of cells - runs best with one size per wave:
             // 33.5 us against 37.8 with six)
-            const long wave_budget = (long)T.n_tables * n_pg * G.n_m >= 16384 ? 65536 * ppl : 8192;
-            long n_w = wave_budget / ppl / ((long)T.n_tables * n_pg);
+            const long wave_budget = (long)T.n_tables * p.n_pg * G.n_m >= 64 * n_cu ? 256 * n_cu * p.ppl : 32 * n_cu;
+            long n_w = wave_budget / p.ppl / ((long)T.n_tables * p.n_pg);
             if (n_w > G.n_m) n_w = G.n_m;
             if (n_w < 1) n_w = 1;
             n_w = (n_w + 3) / 4 * 4;
-            for (int t0 = 0; t0 < T.n_tables; t0 += 65535) {
-                const int nt = T.n_tables - t0 < 65535 ? T.n_tables - t0 : 65535;
-                const dim3 blocks((unsigned)(n_w / 4), (unsigned)n_pg, (unsigned)nt);
-                if (G.n_s <= 64 && all && ppl == 2)
-                    hipLaunchKernelGGL((k_sweep_p<1, true, 2>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
-                                       (int)n_w);
-                else if (G.n_s <= 64 && all)
-                    hipLaunchKernelGGL((k_sweep_p<1, true, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
-                                       (int)n_w);
-                else if (G.n_s <= 64)
-                    hipLaunchKernelGGL((k_sweep_p<1, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
-                                       (int)n_w);
-                else
-                    hipLaunchKernelGGL((k_sweep_p<4, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0,
-                                       (int)n_w);
-            }
+            p.n_w = (int)n_w;
         } else {
             constexpr int PC = 4;
-            const int n_mg = (G.n_m + 63) / 64;
-            const int n_pcg = (G.n_P + 4 * PC - 1) / (4 * PC);
-            hipLaunchKernelGGL(k_sweep_m<PC>, dim3((unsigned)T.n_tables * n_mg * n_pcg), dim3(256), 0, st,
-                               T, G, S, d_out, n_mg, n_pcg);
+            p.n_mg = (G.n_m + 63) / 64;
+            p.n_pcg = (G.n_P + 4 * PC - 1) / (4 * PC);
+            if ((long)T.n_tables * p.n_mg * p.n_pcg > kMaxLaunch) return false;
         }
     }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    PLOGP_MARK(4);
-#undef PLOGP_MARK
-    return hipSuccess;
+    // scratch: what the kernels of this path index (m-fastest arrays per distinct size where noted)
+    const bool binom = (G.mask & (1u << 12)) != 0;
+    p.lay.g1 = lb.take(nt * D);
+    p.lay.gs = lb.take(nt * n_s * D);
+    p.lay.gm = lb.take(nt * n_m * D);
+    p.lay.sum2 = lb.take(binom ? nt * n_m * (size_t)(G.cl_max + 1) * D : 0);
+    p.lay.blk = lb.take(chain ? nt * (size_t)G.n_blk * n_mu * D : 0);
+    p.lay.part = lb.take(chain ? nt * n_mu * n_P * D : 0);
+    p.lay.pre = lb.take(chain && G.blk_is_prefix ? nt * n_mu * n_P * D : 0);
+    p.lay.rcp = lb.take(n_s * D);
+    p.lay.segC = lb.take(nt * n_s * D);
+    p.lay.segA = lb.take(pairs ? nt * n_m * n_s * D : 0);
+    p.lay.segB = lb.take(pairs ? nt * n_m * n_s * D : 0);
+    p.lay.amin = lb.take(pairs ? nt * n_m * D : 0);
+    p.lay.nv = lb.take(n_m * sizeof(int));
+    if (terms_only)
+        p.lay.score_rows = lb.take((size_t)13 * n_m * 2 * D);
+    p.lay.total = lb.at;
+    return true;
 }
 
-hipError_t launch_score(const DeviceTables &T1, const DeviceGrid &G, const Scratch &S, double *rows,
-                        const double *d_meas, const uint32_t *d_seg, double *d_pred, void *d_verdict,
-                        void *d_scores, hipStream_t st, hipEvent_t *ev, int reps)
+hipError_t launch_tune_stage(const TunePlan &p, int stage, const DeviceTables &T, const DeviceGrid &G,
+                             const Scratch &S, plogp_cell_dev *d_out, hipStream_t st)
 {
-    hipError_t e;
-    if (reps < 1) reps = 1;
+    if (p.path == TUNE_TABLE_LANES) {
+        if (stage == TUNE_STAGE_TERMS) {
+            hipLaunchKernelGGL(k_batch_setup, dim3((unsigned)(p.n_stage + p.prep_wg)), dim3(256), p.setup_lds,
+                               st, T, G, S.batch, reinterpret_cast<f64x2 *>(S.batch_ys), p.n_stage);
+        } else if (stage == TUNE_STAGE_SWEEP) {
+            BatchDims D;
+            D.n = T.n; D.n_tables = T.n_tables; D.n_m = G.n_m; D.n_P = G.n_P; D.n_s = G.n_s;
+            D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = p.batch_mchunks; D.m_per_wave = p.m_per_wave;
+            D.mask = G.mask;
+            const auto kern = G.mask == 0x1FFFu ? k_batch_t<BATCH_T_PC, BATCH_T_PS, true>
+                                                : k_batch_t<BATCH_T_PC, BATCH_T_PS, false>;
+            hipLaunchKernelGGL(kern, dim3((unsigned)p.n_tg * p.batch_mchunks), dim3(64 * BATCH_T_WAVES),
+                               p.batch_lds, st, D, reinterpret_cast<const f64x2 *>(S.batch_ys), T.L,
+                               S.batch.rec, S.batch.tab, G.P, reinterpret_cast<const u64 *>(G.s), d_out);
+        }
+        return hipGetLastError();
+    }
+    if (p.path == TUNE_ROW) {
+        if (stage == TUNE_STAGE_SWEEP) {
+            const bool all = G.mask == 0x1FFFu, two = p.row_two != 0;
+            const auto kern = all ? (two ? k_row<true, 2> : k_row<true, 1>) : (two ? k_row<false, 2> : k_row<false, 1>);
+            hipLaunchKernelGGL(kern, dim3((unsigned)(T.n_tables * G.n_m)), dim3(ROW_THREADS), p.row_lds, st,
+                               T, G, d_out);
+        }
+        return hipGetLastError();
+    }
+    if (p.path == TUNE_FUSED) {
+        if (stage == TUNE_STAGE_SWEEP)
+            hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * p.fused_mchunks), dim3(256),
+                               (size_t)3 * T.n * sizeof(double) + 64, st, T, G, d_out, p.fused_mchunks);
+        return hipGetLastError();
+    }
+    switch (stage) {
+    case TUNE_STAGE_TERMS:
+        if (!p.together && !p.row_together && !p.terms_in_chain)
+            hipLaunchKernelGGL(k_terms, dim3((unsigned)p.terms_wg), dim3(256), p.terms_lds, st, T, G, S,
+                               p.n_chunks, p.n_mchunks, p.terms_mode);
+        break;
+    case TUNE_STAGE_CHAIN:
+        if (p.chain_row) {
+            if (p.row_together)
+                hipLaunchKernelGGL(k_terms_chain_row, dim3((unsigned)(p.terms_wg + T.n_tables * G.n_mu)),
+                                   dim3(CROW_THREADS), p.crow_lds > p.terms_lds ? p.crow_lds : p.terms_lds, st,
+                                   T, G, S, p.terms_wg, p.n_chunks, p.n_mchunks, p.terms_mode);
+            else
+                hipLaunchKernelGGL(k_chain_row, dim3((unsigned)(T.n_tables * G.n_mu)), dim3(CROW_THREADS),
+                                   p.crow_lds, st, T, G, S);
+        } else if (p.chain) {
+            if (p.together)
+                hipLaunchKernelGGL(k_terms_chain, dim3((unsigned)(p.n_chain_wg + p.terms_wg)), dim3(256),
+                                   p.both_lds, st, T, G, S, p.n_chain_wg, p.chain_wg, p.n_single, p.n_search,
+                                   p.n_chunks, p.n_mchunks, p.terms_mode);
+            else
+                hipLaunchKernelGGL(k_chain_blocks, dim3((unsigned)p.n_chain_wg), dim3(p.chain_threads),
+                                   p.chain_lds, st, T, G, S, p.chain_wg, p.n_single, p.n_search,
+                                   p.terms_in_chain ? p.terms_mode : -1);
+        }
+        break;
+    case TUNE_STAGE_PREFIX:
+        if (p.chain && !p.chain_row && G.blk_is_prefix)
+            hipLaunchKernelGGL(k_chain_prefix, dim3((unsigned)T.n_tables * p.n_mgroups), dim3(256), 0, st, G, S,
+                               p.n_mgroups);
+        break;
+    default:
+        if (p.terms_only)
+            break;
+        if (p.lanes_s) {
+            const unsigned rows = (unsigned)T.n_tables * G.n_m;
+            const dim3 threads(64 * SWEEP_S_MAX_WAVES);
+            if (p.sweep_gp == 6)
+                hipLaunchKernelGGL(k_sweep_s<6>, dim3(rows), threads, 0, st, T, G, S, d_out, 1);
+            else if (p.sweep_gp == 9)
+                hipLaunchKernelGGL(k_sweep_s<9>, dim3(rows), threads, 0, st, T, G, S, d_out, 1);
+            else
+                hipLaunchKernelGGL(k_sweep_s<12>, dim3(rows * p.sweep_ptiles), threads, 0, st, T, G, S, d_out,
+                                   p.sweep_ptiles);
+        } else if (p.lanes_p) {
+            const bool all = G.mask == 0x1FFFu;
+            for (int t0 = 0; t0 < T.n_tables; t0 += 65535) {
+                const int nt = T.n_tables - t0 < 65535 ? T.n_tables - t0 : 65535;
+                const dim3 blocks((unsigned)(p.n_w / 4), (unsigned)p.n_pg, (unsigned)nt);
+                if (G.n_s <= 64 && all && p.ppl == 2)
+                    hipLaunchKernelGGL((k_sweep_p<1, true, 2>), blocks, dim3(256), 0, st, T, G, S, d_out, t0, p.n_w);
+                else if (G.n_s <= 64 && all)
+                    hipLaunchKernelGGL((k_sweep_p<1, true, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0, p.n_w);
+                else if (G.n_s <= 64)
+                    hipLaunchKernelGGL((k_sweep_p<1, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0, p.n_w);
+                else
+                    hipLaunchKernelGGL((k_sweep_p<4, false, 1>), blocks, dim3(256), 0, st, T, G, S, d_out, t0, p.n_w);
+            }
+        } else {
+            hipLaunchKernelGGL(k_sweep_m<4>, dim3((unsigned)T.n_tables * p.n_mg * p.n_pcg), dim3(256), 0, st, T, G,
+                               S, d_out, p.n_mg, p.n_pcg);
+        }
+        break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_score_stage(int stage, const TunePlan &plan, const DeviceTables &T1, const DeviceGrid &G,
+                              const Scratch &S, double *rows, const double *d_meas, const uint32_t *d_seg,
+                              double *d_pred, void *d_verdict, void *d_scores, hipStream_t st)
+{
     int n_ids = 0;
     for (int id = 0; id < 13; ++id) n_ids += (G.mask >> id) & 1u;
-    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-    // g(m), g(1), the Scatter sums: the first stages of the tuning
-    if ((e = launch_tune(T1, G, S, nullptr, st, nullptr, reps)) != hipSuccess) return e;
-    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
-    const size_t lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
-    // a small table is staged by every workgroup of 256; a big one by at most one or
-    // two workgroups of 1024 per CU, which then walk the items with a stride
-    const bool big = lds > 16384;
-    const int threads = big ? 1024 : 256;
-    const int n_pchunks = (G.n_P + threads - 1) / threads;
-    const long n_items = (long)G.n_m * n_pchunks;
-    long n_wg = n_items;
-    if (big) {
-        const long fit = 256L * (long)((160 * 1024) / lds);
-        if (n_wg > fit) n_wg = fit;
-    }
-    if (n_items > 0x7FFFFFFFL) return hipErrorInvalidValue;
-    for (int r = 0; r < reps; ++r)
+    if (stage == 0)      // g(m), g(1), the Scatter sums: the first stages of the tuning
+        return launch_tune(plan, T1, G, S, nullptr, st);
+    if (stage == 1) {
+        const size_t lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
+        // a small table is staged by every workgroup of 256; a big one by at most one or
+        // two workgroups of 1024 per CU, which then walk the items with a stride
+        const bool big = lds > 16384;
+        const int threads = big ? 1024 : 256;
+        const int n_pchunks = (G.n_P + threads - 1) / threads;
+        const long n_items = (long)G.n_m * n_pchunks;
+        long n_wg = n_items;
+        if (big) {
+            const DeviceInfo &dev = device_info();
+            const long fit = (long)dev.n_cu * (long)(dev.lds_per_cu / lds);
+            if (n_wg > fit) n_wg = fit;
+        }
+        if (n_items > kMaxLaunch) return hipErrorInvalidValue;
         hipLaunchKernelGGL(k_score, dim3((unsigned)n_wg), dim3(threads), lds, st, T1, G, S, d_meas, d_seg,
-                           d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict), n_pchunks,
-                           (int)n_items);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
+                           d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict), n_pchunks, (int)n_items);
+        return hipGetLastError();
+    }
     const long n_rows = (long)n_ids * G.n_m;
     const long row_wg = (n_rows + SCORE_RT * SCORE_WAVES - 1) / (SCORE_RT * SCORE_WAVES);
-    for (int r = 0; r < reps; ++r) {
-        hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids,
-                           d_meas, d_pred, rows);
-        hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, rows,
-                           reinterpret_cast<plogp_score_dev *>(d_scores));
-    }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
-    return hipSuccess;
+    hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids, d_meas,
+                       d_pred, rows);
+    hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, rows,
+                       reinterpret_cast<plogp_score_dev *>(d_scores));
+    return hipGetLastError();
 }
 
 }  // namespace plogp

@@ -110,10 +110,8 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
 
 hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d_cells, int key_mode,
                              uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree,
-                             hipStream_t st, hipEvent_t *ev, int reps)
+                             hipStream_t st)
 {
-    hipError_t e;
-    if (reps < 1) reps = 1;
     RobustShape R;
     R.cells = cells;
     R.n_tables = n_tables;
@@ -130,8 +128,7 @@ hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d
     R.t_chunk = n_tables > 1 ? (int)((n_tables - 1 + slices - 1) / slices) : 1;
     slices = n_tables > 1 ? (n_tables - 1 + R.t_chunk - 1) / R.t_chunk : 0;
     u64 clear_items = cells > (u64)n_tables ? cells : (u64)n_tables;
-    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-    for (int r = 0; r < reps; ++r) {
+    {
         hipLaunchKernelGGL(k_robust_clear, dim3((unsigned)((clear_items + 255) / 256)), dim3(256), 0, st,
                            R, d_agree, reinterpret_cast<u64 *>(d_max_dev), d_table_agree);
         if (slices > 0) {
@@ -144,9 +141,7 @@ hipError_t launch_robustness(size_t cells, int n_tables, const plogp_cell_dev *d
                                    st, R, recs, d_agree, reinterpret_cast<u64 *>(d_max_dev), d_table_agree);
         }
     }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
-    return hipSuccess;
+    return hipGetLastError();
 }
 
 }  // namespace plogp

@@ -1,6 +1,7 @@
 """ctypes binding of libplogp.so -- argument marshalling only.
 
-Function names and argument order are those of include/plogp.h.  Device
+Function names and argument order are those of include/plogp.h (and, for the
+measurement twins, include/plogp_profile.h).  Device
 pointers are plain integers (e.g. torch.Tensor.data_ptr()); the stream is a
 hipStream_t as an integer (e.g. torch.cuda.current_stream().cuda_stream).
 The library has no CPU fallback: importing this module without the built
@@ -88,6 +89,7 @@ def _load_library():
         "plogp_robustness": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, vp, vp]),
         "plogp_robustness_profile": (ctypes.c_int, [vp, sz, vp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
                                                     ctypes.POINTER(ctypes.c_float)]),
+        "plogp_measure_ceilings": (ctypes.c_int, [vp, sz, vp, dp, dp]),
         "plogp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "plogp_last_hip_error": (ctypes.c_int, []),
     }
@@ -289,3 +291,11 @@ def plogp_robustness_profile(grid: Grid, n_tables: int, d_cells: int, key_mode: 
                                          d_max_dev or None, d_table_agree or None, stream, reps,
                                          ctypes.byref(ms)), "plogp_robustness_profile")
     return float(ms.value)
+
+
+def plogp_measure_ceilings(d_buf: int, buf_bytes: int, stream: int = 0):
+    """(fp64 multiply-add TFLOP/s, write-only fill GB/s) this device reaches now; d_buf is overwritten."""
+    fma, store = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.plogp_measure_ceilings(d_buf, buf_bytes, stream, ctypes.byref(fma), ctypes.byref(store)),
+           "plogp_measure_ceilings")
+    return float(fma.value), float(store.value)

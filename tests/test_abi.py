@@ -1,5 +1,5 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports
-every function include/plogp.h declares, and refuses bad arguments before it
+every function the headers under include/ declare, and refuses bad arguments before it
 ever touches the device.  (With no GPU, a valid call must fail loudly with
 PLOGP_EDEVICE: there is no CPU fallback.)"""
 import ctypes
@@ -21,14 +21,21 @@ def plogp():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "plogp.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(plogp_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(plogp_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(plogp):
     names = declared_functions()
-    assert {"plogp_load_table", "plogp_eval_strategy", "plogp_tune_grid"} <= set(names)
+    assert {"plogp_load_table", "plogp_eval_strategy", "plogp_tune_grid", "plogp_tune_grid_profile",
+            "plogp_measure_ceilings"} <= set(names)
     lib = ctypes.CDLL(str(plogp.LIB_PATH))
     for name in names:
         assert hasattr(lib, name), name

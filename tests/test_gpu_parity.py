@@ -130,14 +130,19 @@ def test_config3_full():
     assert assert_tables_equal(got, want, "cfg3"), "times not bit-identical"
 
 
-def test_config4_full_size_sampled_tables():
-    # the launch is the full 10 000-table job; the oracle recomputes every 97th table
+def test_config4_full():
+    # the launch is the full 10 000-table job; the oracle recomputes every table, a
+    # thousand at a time (the ragged last group of 16 tables included)
     wl = make_workload(4)
     got = gpu_tune(wl)
-    pick = np.arange(0, wl.n_tables, 97)
-    want, _ = oracle.tune_grid(wl.sizes[pick], wl.gaps[pick], wl.L[pick], wl.m, wl.P, wl.s,
-                               wl.s_cap, wl.strategy_mask)
-    assert assert_tables_equal(got[pick], want, "cfg4"), "times not bit-identical"
+    exact = True
+    for t0 in range(0, wl.n_tables, 1000):
+        pick = slice(t0, min(t0 + 1000, wl.n_tables))
+        want, _ = oracle.tune_grid(wl.sizes[pick], wl.gaps[pick], wl.L[pick], wl.m, wl.P, wl.s,
+                                   wl.s_cap, wl.strategy_mask)
+        exact = assert_tables_equal(got[pick], want, "cfg4 tables %d.." % t0) and exact
+        print("cfg4: tables %d..%d identical to the oracle" % (t0, pick.stop - 1), flush=True)
+    assert exact, "times not bit-identical"
     # every table: the properties that hold at any size
     assert (got["strategy"][:, 0] <= 9).all() and (got["strategy"][:, 1] >= 10).all()
     assert (got["strategy"][:, 1] <= 12).all()
@@ -238,6 +243,20 @@ def test_no_candidates_and_candidates_all_above_m():
         got = gpu_tune(wl)
         assert_tables_equal(got, want, "edge %s %x" % (s, mask))
     assert (got["strategy"][0, 0, 0] == 5).all() and (got["s"][0, 0, 0] == 8).all()
+
+
+def test_no_candidates_with_many_sizes_on_the_sweep_over_process_counts():
+    # an empty candidate list with at least 32 process counts and thousands of sizes: the staged
+    # path whose sweep runs its lanes over P; no per-(m, s) term may be written anywhere
+    base = make_workload(2)
+    rng = np.random.default_rng(77)
+    m = (rng.integers(1, 1 << 20, size=3000).astype(np.uint64)) * np.uint64(8)
+    P = np.unique(rng.integers(2, 3000, size=70)).astype(np.uint32)
+    for mask in (ALL_STRATEGIES_MASK, 0x3FF):
+        wl = Workload("no candidates", base.sizes, base.gaps, base.L, m, P, np.array([], dtype=np.uint64),
+                      NO_CAP, mask)
+        want, _ = oracle.tune_workload(wl)
+        assert assert_tables_equal(gpu_tune(wl), want, "no candidates, mask %x" % mask)
 
 
 def test_cap_below_m_and_scatter_only_and_bcast_only():

@@ -71,6 +71,39 @@ def test_scatter_chain_blocks_exact_beyond_many_blocks():
         assert F(got) == want
 
 
+def test_tuned_scatter_rows_match_the_closed_forms_far_beyond_one_block():
+    # the tuning forms the chain sums of all P in one pass over j (a prefix); with only the
+    # chain row (or only the binomial row) enabled the table's times are that row's values:
+    # they must equal the integer closed form and the one-point evaluation bit for bit,
+    # at the block boundaries (P - 1 = 64 b and 64 b +- 1) up to 1023 blocks
+    x, y = affine_table(top_exp=16)
+    P = np.array([2, 3, 64, 65, 66, 128, 129, 130, 200, 4096, 4097, 4098, 65535, 65536], dtype=np.uint32)
+    m = np.array([8, 1 << 10, 3 << 12], dtype=np.uint64)
+    for sid in (11, 12):
+        cells, _ = oracle.tune_grid(x, y, L, m, P, [], 0, 1 << sid)
+        assert cells.shape == (1, 1, len(m), len(P))
+        assert (cells["strategy"] == sid).all() and (cells["s"] == 0).all()
+        for mi, mv in enumerate(m):
+            for pi, Pv in enumerate(P):
+                got = float(cells["time"][0, 0, mi, pi])
+                assert F(got) == closed_forms(int(mv), int(Pv), 8, 32.125)[sid], (sid, mv, Pv)
+                one = oracle.eval_strategy(x, y, L, sid, int(mv), int(Pv))
+                assert np.float64(got).view(np.uint64) == np.float64(one).view(np.uint64)
+
+
+def test_tuned_chain_sums_equal_the_one_point_sums_on_a_noisy_table():
+    # the same on a table where the association order matters (sums are not exact): the
+    # one-pass prefix of the tuning and the per-point sum must agree in every bit
+    from plogp_workloads import make_workload
+    wl = make_workload(5, m_slice=slice(7, 4096, 1361), P_subset=[2, 65, 66, 129, 4097, 40000, 65536])
+    x, y, lat = wl.sizes[0], wl.gaps[0], float(wl.L[0])
+    cells, _ = oracle.tune_grid(x, y, lat, wl.m, wl.P, [], 0, 1 << 11)
+    for mi, mv in enumerate(wl.m):
+        for pi, Pv in enumerate(wl.P):
+            one = oracle.eval_strategy(x, y, lat, 11, int(mv), int(Pv))
+            assert cells["time"][0, 0, mi, pi].view(np.uint64) == np.float64(one).view(np.uint64), (mv, Pv)
+
+
 def test_g_hits_every_sample_and_matches_exact_rationals():
     # integer gaps y_i = i^2 on sizes 2^i: slopes (2i+1)/2^i are dyadic, so g is exact
     x = np.array([float(1 << i) for i in range(0, 21)])
