@@ -60,7 +60,9 @@ enum {
                         /* is too large for one launch                               */
     PLOGP_ENOSPC = 3,   /* output buffer too small                                   */
     PLOGP_ENOMEM = 4,   /* host or device allocation failed                          */
-    PLOGP_EDEVICE = 5   /* HIP error; plogp_last_hip_error() returns the HIP code    */
+    PLOGP_EDEVICE = 5,  /* HIP error; plogp_last_hip_error() returns the HIP code    */
+    PLOGP_ETOOBIG = 6   /* the job needs more scratch memory than the fixed buffer   */
+                        /* of plogp_tune_grid_static holds                           */
 };
 
 /* One or several pLogP parameter tables {g(.), L}, resident on the device. */
@@ -303,6 +305,30 @@ int plogp_score_grid(const plogp_table *t, size_t table_index, plogp_grid *g, co
  */
 int plogp_robustness(const plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, int key_mode,
                      uint32_t *d_agree, double *d_max_dev, uint32_t *d_table_agree, void *stream);
+
+/*
+ * plogp_tune_grid_static -- plogp_tune_grid for callers that cannot allocate:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result, same kernels; but the scratch memory
+ * of the kernels (the per-size and per-candidate terms, the Scatter-chain block
+ * sums, the tables turned round for a batch) is not taken from the grid handle:
+ * it is a fixed buffer of PLOGP_STATIC_SCRATCH_BYTES inside the library's code
+ * object, one per GPU, held until the process ends.  The call allocates and
+ * frees nothing and does not wait for the device.  A job whose scratch does not
+ * fit the buffer is refused with PLOGP_ETOOBIG before anything is launched (use
+ * plogp_tune_grid, or split the batch or the grid).  The grid handle is only
+ * read, so it may be shared with a plogp_tune_grid call in flight.
+ * Every call on one GPU uses that GPU's one buffer, whatever the handles and
+ * streams: calls that overlap on one GPU race; calls on one stream, or ordered
+ * by events, do not.  No kernel reads scratch it has not written in the same
+ * call, so nothing is cleared between calls.
+ * The buffer's address is looked up once per GPU (at the library's first call on
+ * that GPU, a table load or grid creation included), with that GPU current.
+ * Errors: as plogp_tune_grid, plus ETOOBIG; never ENOMEM.
+ */
+#define PLOGP_STATIC_SCRATCH_BYTES (64u << 20)
+int plogp_tune_grid_static(const plogp_table *t, const plogp_grid *g, plogp_cell *d_out,
+                           size_t d_out_bytes, void *stream);
 
 /* Message for a status code (static string). */
 const char *plogp_strerror(int status);

@@ -11,6 +11,11 @@
 
 using namespace plogp;
 
+// The scratch of plogp_tune_grid_static: device memory inside the code object, one copy per
+// GPU.  In host code this name stands for the symbol, not for an address: the address on
+// the current device comes from hipGetSymbolAddress, once per device (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[PLOGP_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int tl_hip_error = 0;
@@ -20,6 +25,10 @@ constexpr uint64_t kTwo53u = 1ull << 53;
 
 bool g_init_done = false;
 std::mutex g_init_mutex;
+
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices] = {};
+std::mutex g_static_mutex;
 
 int floor_log2_u32(uint32_t v) { int f = 0; while ((v >> (f + 1)) != 0) ++f; return f; }
 int ceil_log2_u32(uint32_t v) { int f = floor_log2_u32(v); return ((1u << f) == v) ? f : f + 1; }
@@ -43,17 +52,39 @@ int device_error(hipError_t e)
     return PLOGP_EDEVICE;
 }
 
+// Address of the static scratch buffer on the current device (looked up on first use there).
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return device_error(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_scratch[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return device_error(hipErrorInvalidSymbol);
+        g_static_scratch[dev] = p;
+    }
+    *out = g_static_scratch[dev];
+    return PLOGP_OK;
+}
+
 int ensure_init()
 {
-    std::lock_guard<std::mutex> lock(g_init_mutex);
-    if (!g_init_done) {
-        int count = 0;
-        HIP_TRY(hipGetDeviceCount(&count));
-        if (count < 1) return device_error(hipErrorNoDevice);
-        HIP_TRY(kernels_init());
-        g_init_done = true;
+    {
+        std::lock_guard<std::mutex> lock(g_init_mutex);
+        if (!g_init_done) {
+            int count = 0;
+            HIP_TRY(hipGetDeviceCount(&count));
+            if (count < 1) return device_error(hipErrorNoDevice);
+            HIP_TRY(kernels_init());
+            g_init_done = true;
+        }
     }
-    return PLOGP_OK;
+    // every table load and grid creation comes through here: the static scratch buffer of
+    // the device they are made on is known before the first tune call could need it
+    void *p = nullptr;
+    return static_scratch(&p);
 }
 
 }  // namespace plogp
@@ -208,6 +239,7 @@ const char *plogp_strerror(int status)
     case PLOGP_ENOSPC: return "output buffer too small";
     case PLOGP_ENOMEM: return "out of memory";
     case PLOGP_EDEVICE: return "HIP error (see plogp_last_hip_error)";
+    case PLOGP_ETOOBIG: return "job needs more scratch memory than the static buffer holds";
     default: return "unknown status";
     }
 }
@@ -424,6 +456,23 @@ int plogp_tune_grid(const plogp_table *t, plogp_grid *g, plogp_cell *d_out, size
     if (!plan_tune(T, G, false, plan)) return PLOGP_ERANGE;
     if ((rc = ensure_scratch_block(g, plan.lay.total)) != PLOGP_OK) return rc;
     HIP_TRY(launch_tune(plan, T, G, bind_scratch(g->scratch_block, plan.lay),
+                        reinterpret_cast<plogp_cell_dev *>(d_out), (hipStream_t)stream));
+    return PLOGP_OK;
+}
+
+int plogp_tune_grid_static(const plogp_table *t, const plogp_grid *g, plogp_cell *d_out,
+                           size_t d_out_bytes, void *stream)
+{
+    int rc = check_tune_args(t, g, d_out, d_out_bytes);
+    if (rc != PLOGP_OK) return rc;
+    const DeviceTables T = t->view();
+    const DeviceGrid G = g->view();
+    TunePlan plan;
+    if (!plan_tune(T, G, false, plan)) return PLOGP_ERANGE;
+    if (plan.lay.total > (size_t)PLOGP_STATIC_SCRATCH_BYTES) return PLOGP_ETOOBIG;
+    void *base = nullptr;
+    if ((rc = static_scratch(&base)) != PLOGP_OK) return rc;
+    HIP_TRY(launch_tune(plan, T, G, bind_scratch(base, plan.lay),
                         reinterpret_cast<plogp_cell_dev *>(d_out), (hipStream_t)stream));
     return PLOGP_OK;
 }

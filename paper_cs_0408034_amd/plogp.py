@@ -18,7 +18,8 @@ import numpy as np
 _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libplogp.so"
 
-OK, EINVAL, ERANGE, ENOSPC, ENOMEM, EDEVICE = range(6)
+OK, EINVAL, ERANGE, ENOSPC, ENOMEM, EDEVICE, ETOOBIG = range(7)
+STATIC_SCRATCH_BYTES = 64 << 20
 MASK_BCAST, MASK_SCATTER, MASK_ALL = 0x03FF, 0x1C00, 0x1FFF
 NO_STRATEGY = 0xFFFFFFFF
 NO_CAP = (1 << 64) - 1
@@ -76,6 +77,7 @@ def _load_library():
         "plogp_decision_table_cells": (sz, [sz, vp]),
         "plogp_decision_table_bytes": (sz, [sz, vp]),
         "plogp_tune_grid": (ctypes.c_int, [vp, vp, vp, sz, vp]),
+        "plogp_tune_grid_static": (ctypes.c_int, [vp, vp, vp, sz, vp]),
         "plogp_tune_grid_profile": (ctypes.c_int, [vp, vp, vp, sz, vp, ctypes.c_int,
                                                    ctypes.POINTER(ctypes.c_float)]),
         "plogp_cutover_rows": (sz, [sz, vp]),
@@ -222,6 +224,11 @@ def plogp_decision_table_bytes(n_tables: int, grid: Grid) -> int:
 
 def plogp_tune_grid(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0):
     _check(_lib.plogp_tune_grid(table._h, grid._h, d_out, d_out_bytes, stream), "plogp_tune_grid")
+
+
+def plogp_tune_grid_static(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0):
+    _check(_lib.plogp_tune_grid_static(table._h, grid._h, d_out, d_out_bytes, stream),
+           "plogp_tune_grid_static")
 
 
 def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0,
