@@ -4,14 +4,21 @@
 A step is one pass of the whole hot path (table terms, Scatter sums, sweep
 over s, arg-min over strategies, decision-table write: one plogp_tune_grid
 call) over one synthetic workload whose tables and grid are already resident
-in HBM.  The headline workload is config 2; configs 3-5 are timed too and
-reported under "workloads" in the same JSON line.  Beside the step, per
-workload: the same call replayed from a HIP graph, the cut-over extraction of
-the table just tuned, the scoring of predictions against synthetic
-measurements and (batches) the robustness summary, each with its own roofline
-and the oracle timed on the host.
+in HBM.  The headline workload is config 4 (10 000 tables: the largest job
+that one GPU holds); configs 3, 5 and 2 are timed the same way and reported,
+shortened, under "workloads"; the steps after the sweep (cut-over extraction,
+prediction scoring, robustness summary) under "next".
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--extra 3,4,5] [--no-cpu]
+Timing: whatever --steps says, a call is timed as the median of at least five
+batches of at least 100 back-to-back calls between two HIP events on the
+launch stream; per-kernel times are the median of five rounds in which every
+kernel of the call is launched 100 times between two events
+(plogp_*_profile).  The published peaks a fraction is taken of stand beside
+what a bare multiply-add kernel and a bare fill kernel reach on this device
+in the same run ("measured_ceiling").
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--extra 3,5,2] [--no-cpu]
+                    [--no-next] [--detail FILE]
 """
 import argparse
 import json
@@ -28,36 +35,58 @@ import numpy as np  # noqa: E402
 
 METRIC = "pLogP model evaluations/sec (strategy×m×P×s) + decision-table cells/sec"
 FP64_VECTOR_PEAK = 78.6e12        # flop/s: 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+VALU_ISSUE_PEAK = 39.3e12         # lane-instructions/s: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
 HBM_PEAK = 8.0e12                 # bytes/s
 STAGES = ("terms", "chain_blocks", "chain_prefix", "sweep")
+MIN_BATCHES, MIN_PER_BATCH = 5, 100
 
 # flops of one unsegmented row per (m, P), arg-min compare included
 # (convention: fma = 2, add/mul/compare = 1, select/convert/integer = 0)
 UNSEG_FLOPS = {0: 3, 1: 3, 3: 3, 4: 3, 6: 4, 7: 4, 8: 4, 10: 3, 11: 4, 12: 3}
 
+# Counter readings of the dominant kernel of each config, taken OFFLINE by rocprofv3 --pmc runs
+# of this file (summaries, with their commands, in profiles/tune_grid_cfg<N>_kernel_stats.txt)
+# - not measured in this run: HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what
+# the same counter reads for a copy of known size) and vector instructions issued per launch
+# (SQ_INSTS_VALU, in wave instructions).  A kernel change makes them stale until the profiles
+# are taken again; the line names its source.
+OFFLINE_COUNTERS = {
+    2: {"kernel": "k_row", "hbm_bytes": 0.336e6 + 33.560e6, "valu_insts": None},
+    3: {"kernel": "k_sweep_s", "hbm_bytes": 4.016e6 + 2.294e6, "valu_insts": 36.1e6},
+    4: {"kernel": "k_batch_t", "hbm_bytes": 88.979e6 + 1966.079e6, "valu_insts": 175.8e6},
+    5: {"kernel": "k_chain_blocks", "hbm_bytes": 1.839e6 + 73.536e6, "valu_insts": None},
+}
+
 
 def algorithmic_work(wl):
-    """Flops and bytes the method itself needs per stage (after hoisting the
-    terms of the segmented rows that do not depend on P), per tune call."""
+    """Per stage and per tune call: the flops and bytes the method delivers ("delivered": 3 flop
+    per segmented value for each of the three segmented rows, 6 flop per Scatter-chain term for
+    every grid m, repeats included) and the ones the kernels have to execute after the exact
+    shortcuts ("executed": rows 2 and 9 of Table 1 through min_s A, one min per (m, s); the
+    chain sums once per distinct m)."""
     c = wl.counts()
     mask, nt, n = wl.strategy_mask, wl.n_tables, wl.sizes.shape[1]
     n_m, n_P, n_s = len(wl.m), len(wl.P), len(wl.s)
+    n_mu = len(np.unique(wl.m))
     Pmax = int(wl.P.max())
     cl_max = (Pmax - 1).bit_length()
-    search = math.ceil(math.log2(n))
-    interp = search + 3                                   # compares + sub + fma
+    interp = math.ceil(math.log2(n)) + 3                  # compares + sub + fma
     n_seg = sum(1 for i in (2, 5, 9) if (mask >> i) & 1)
-    seg_evals = c["ms_pairs"] * n_P * n_seg
+    pairs = c["ms_pairs"]
     unseg = sum(f for i, f in UNSEG_FLOPS.items() if (mask >> i) & 1)
-    work = {
-        "terms": {"flops": nt * ((n - 1) * 3 + interp * (1 + n_s + n_m * (1 + (cl_max if (mask >> 12) & 1 else 0)))),
-                  "bytes": nt * n * 16},
-        "chain_blocks": {"flops": 6 * c["scatter_chain_interps"], "bytes": 0},
-        "chain_prefix": {"flops": nt * n_m * ((Pmax - 1) // 64) if (mask >> 11) & 1 else 0, "bytes": 0},
-        "sweep": {"flops": 3 * seg_evals + 5 * c["ms_pairs"] + unseg * nt * n_m * n_P,
-                  "bytes": c["output_bytes"]},
-    }
-    return work, c
+    terms = nt * ((n - 1) * 3 + interp * (1 + n_s + n_m * (1 + (cl_max if (mask >> 12) & 1 else 0))))
+    chain = 6 * c["scatter_chain_interps"]
+    chain_x = chain * n_mu // n_m
+    prefix = nt * n_m * ((Pmax - 1) // 64) if (mask >> 11) & 1 else 0
+    sweep = 3 * pairs * n_P * n_seg + 5 * pairs + unseg * nt * n_m * n_P
+    seg5 = 1 if (mask >> 5) & 1 else 0
+    sweep_x = 3 * pairs * n_P * seg5 + (pairs if mask & 0x204 else 0) + 5 * pairs + unseg * nt * n_m * n_P
+    return {
+        "terms": {"flops": terms, "flops_executed": terms, "bytes": nt * n * 16},
+        "chain_blocks": {"flops": chain, "flops_executed": chain_x, "bytes": 0},
+        "chain_prefix": {"flops": prefix, "flops_executed": prefix * n_mu // n_m, "bytes": 0},
+        "sweep": {"flops": sweep, "flops_executed": sweep_x, "bytes": c["output_bytes"]},
+    }, c
 
 
 def describe(wl):
@@ -65,58 +94,59 @@ def describe(wl):
         wl.name, wl.n_tables, wl.sizes.shape[1], len(wl.m), len(wl.P), len(wl.s), wl.strategy_mask)
 
 
-# HBM bytes per launch (fetched + written) of each stage's kernel, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters read for a copy
-# kernel of known size (profiles/tune_grid_cfg<N>_kernel_stats.txt, section 2).
-MEASURED_TRAFFIC = {
-    2: {"sweep": 0.336e6 + 33.560e6},
-    3: {"chain_blocks": 0.387e6 + 1.496e6, "sweep": 4.016e6 + 2.294e6},
-    4: {"terms": 5.283e6 + 10.736e6, "sweep": 88.979e6 + 1966.079e6},
-    5: {"chain_blocks": 1.839e6 + 73.536e6,
-        "chain_prefix": 50.976e6 + 18.581e6, "sweep": 44.802e6 + 93.321e6},
-}
-# the same for the kernels of the cut-over extraction (mark, scan1 [+ scan2 on config 4], emit)
-MEASURED_CUT_TRAFFIC = {
-    2: 34.270e6 + 2.095e6 + 0.563e6 + 0.526e6 + 9.296e6 + 0.486e6,
-    3: 2.387e6 + 0.141e6 + 0.060e6 + 0.035e6 + 1.734e6 + 0.982e6,
-    4: 1993.133e6 + 61.704e6 + 30.754e6 + 30.840e6 + 0.035e6 + 0.030e6 + 297.974e6 + 52.548e6,
-    5: 97.012e6 + 5.952e6 + 1.497e6 + 1.464e6 + 26.717e6 + 0.865e6,
-}
-# the scoring kernels (k_score, k_score_rows, k_score_final) and the robustness summary
-# (k_robust_clear, k_robust; its per-table counts are one atomic per wave and table, which the
-# write counter sees as 86 MB)
-MEASURED_SCORE_TRAFFIC = {
-    2: 139.182e6 + 144.107e6 + 221.466e6 + 0.213e6 + 0.256e6,
-    3: 11.925e6 + 9.961e6 + 14.767e6 + 0.213e6 + 0.256e6,
-    4: 1.516e6 + 0.836e6 + 1.350e6 + 0.053e6 + 0.096e6,
-    5: 401.050e6 + 400.357e6 + 623.124e6 + 0.852e6 + 0.895e6,
-}
-MEASURED_ROBUST_TRAFFIC = {4: 0.021e6 + 0.187e6 + 1967.171e6 + 86.391e6}
-
-
-def roofline_of(stage, work, ms, traffic=None):
-    r = _roofline_of(stage, work, ms)
-    r["traffic"] = traffic
+def roofline_of(stage, work, ms, ceilings=None, offline=None):
+    """The roofline object of one kernel: bound by whichever of its algorithmic flop time and
+    byte time is larger; achieved = delivered work per launch / average launch duration."""
+    w = work[stage]
+    sec = ms * 1e-3
+    r4 = lambda v: float("%.4g" % v)
+    if w["bytes"] / HBM_PEAK > w["flops"] / FP64_VECTOR_PEAK:
+        ach = w["bytes"] / sec / 1e9
+        r = {"kernel": stage, "bound": "hbm", "achieved": r4(ach), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+             "frac": r4(ach / (HBM_PEAK / 1e9)), "traffic": None, "algorithmic_bytes": w["bytes"], "avg_ms": r4(ms)}
+        if ceilings:
+            r["measured_ceiling"] = r4(ceilings["store_gbs"])
+            r["frac_of_measured_ceiling"] = r4(ach / ceilings["store_gbs"])
+    else:
+        ach = w["flops"] / sec / 1e12
+        r = {"kernel": stage, "bound": "alu", "achieved": r4(ach), "peak": FP64_VECTOR_PEAK / 1e12,
+             "unit": "TFLOP/s", "frac": r4(ach / (FP64_VECTOR_PEAK / 1e12)), "traffic": None,
+             "frac_executed": r4(w["flops_executed"] / sec / FP64_VECTOR_PEAK),
+             "algorithmic_flops": w["flops"], "executed_flops": w["flops_executed"], "avg_ms": r4(ms)}
+        if ceilings:
+            r["measured_ceiling"] = r4(ceilings["fma_tflops"])
+    r["frac_delivered"] = r["frac"]
+    if offline:
+        r["kernel"] = "%s (%s)" % (stage, offline["kernel"])
+        r["traffic"] = offline["hbm_bytes"]
+        r["counters_source"] = "offline rocprofv3 --pmc, profiles/tune_grid_cfg%d_kernel_stats.txt" % offline["cfg"]
+        if offline.get("valu_insts"):
+            r["valu_issue_util"] = r4(offline["valu_insts"] * 64 / (VALU_ISSUE_PEAK * sec))
     return r
 
 
-def _roofline_of(stage, work, ms):
-    w = work[stage]
-    t_alu = w["flops"] / FP64_VECTOR_PEAK
-    t_hbm = w["bytes"] / HBM_PEAK
-    sec = ms * 1e-3
-    if t_hbm > t_alu:
-        ach = w["bytes"] / sec / 1e9
-        return {"kernel": stage, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9,
-                "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9), "traffic": None,
-                "algorithmic_bytes": w["bytes"], "avg_ms": ms}
-    ach = w["flops"] / sec / 1e12
-    return {"kernel": stage, "bound": "alu", "achieved": ach, "peak": FP64_VECTOR_PEAK / 1e12,
-            "unit": "TFLOP/s", "frac": ach / (FP64_VECTOR_PEAK / 1e12), "traffic": None,
-            "algorithmic_flops": w["flops"], "avg_ms": ms}
+def timed_calls(torch, stream, call, steps, warmup):
+    """Median milliseconds per call over at least MIN_BATCHES batches of at least MIN_PER_BATCH
+    calls, each batch between two events on `stream` (and never less than the host saw)."""
+    per_batch = max(MIN_PER_BATCH, steps)
+    for _ in range(max(warmup, 3)):
+        call()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(MIN_BATCHES):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(per_batch):
+            call()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        times.append(max(wall_ms, e0.elapsed_time(e1)) / per_batch)
+    return float(np.median(times)), per_batch
 
 
-def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
+def run_gpu(wl, steps, warmup, with_next, ceilings_wanted):
     import torch
     from paper_cs_0408034_amd import plogp
 
@@ -127,70 +157,41 @@ def run_gpu(wl, steps, warmup, profile_reps, with_cut=True):
     out = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
-    for _ in range(warmup):
-        plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = e0.elapsed_time(e1)
-    ms_per_step = max(wall_ms, ev_ms) / steps
-    # the same call captured once in a HIP graph and replayed (what a caller with a launch-bound
-    # loop would do); reported beside the eager figure, never as `value`
-    graph_ms = None
-    if with_cut:
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, side.cuda_stream)
-        side.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        g0.record(stream)
-        for _ in range(steps):
-            graph.replay()
-        g1.record(stream)
-        torch.cuda.synchronize()
-        graph_ms = max((time.perf_counter() - t0) * 1e3, g0.elapsed_time(g1)) / steps
-        del graph
-    # per-kernel durations: every kernel launched profile_reps times back to back between two
-    # HIP events on the launch stream; the median of five such rounds
-    rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, profile_reps)
-              for _ in range(5)]
+    ms, per_batch = timed_calls(torch, stream,
+                                lambda: plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh), steps, warmup)
+    # per-kernel durations: every kernel launched MIN_PER_BATCH times back to back between two HIP
+    # events on the launch stream; the median of five such rounds
+    rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, MIN_PER_BATCH)
+              for _ in range(MIN_BATCHES)]
     stage_ms = dict(zip(STAGES, np.median(np.array(rounds), axis=0).tolist()))
-    cut = run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps) if with_cut else None
-    if cut is not None and wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16:
-        cut["roofline"]["traffic"] = MEASURED_CUT_TRAFFIC.get(int(wl.name[3:]))
-    score = run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps) if with_cut else None
-    full = wl.name in ("cfg2", "cfg3", "cfg4", "cfg5") and wl.counts()["cells"] == nbytes // 16
-    if score is not None and full and wl.strategy_mask == 0x1FFF:
-        score["roofline"]["traffic"] = MEASURED_SCORE_TRAFFIC.get(int(wl.name[3:]))
-    if score is not None and tab.count > 1:
-        score["robustness"] = run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps,
-                                             profile_reps)
-        if full:
-            score["robustness"]["roofline"]["traffic"] = MEASURED_ROBUST_TRAFFIC.get(int(wl.name[3:]))
+    res = {"ms": ms, "per_batch": per_batch, "stage_ms": stage_ms}
+    if ceilings_wanted:
+        side = torch.empty(max(nbytes, 1 << 30), dtype=torch.uint8, device="cuda")
+        fma, store = plogp.plogp_measure_ceilings(side.data_ptr(), side.numel(), sh)
+        res["ceilings"] = {"fma_tflops": fma, "store_gbs": store}
+        del side
+        plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh)
+    if with_next:
+        res["cutovers"] = run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps)
+        res["scoring"] = run_score(plogp, torch, wl, tab, grid, stream, steps)
+        if tab.count > 1:
+            res["robustness"] = run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps)
     del out
     grid.free()
     tab.free()
-    return ms_per_step, stage_ms, cut, score, graph_ms
+    return res
 
 
-CUT_STAGES = ("mark", "scan", "emit")
-SCORE_STAGES = ("terms", "score", "statistics")
+def hbm_leg(ms, k_ms, alg_bytes, extra):
+    ach = alg_bytes / (k_ms * 1e-3) / 1e9
+    r = {"ms_per_call": float("%.4g" % ms), "kernels_ms": float("%.4g" % k_ms),
+         "roofline": {"bound": "hbm", "achieved": float("%.4g" % ach), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                      "frac": float("%.3g" % (ach / (HBM_PEAK / 1e9))), "algorithmic_bytes": alg_bytes}}
+    r.update(extra)
+    return r
 
 
-def run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps):
+def run_score(plogp, torch, wl, tab, grid, stream, steps):
     """Prediction against measurement for table 0 of the workload on its (m, P) grid:
     synthetic measured times of every enabled strategy, already resident."""
     from plogp_workloads import make_measurements
@@ -205,35 +206,20 @@ def run_score(plogp, torch, wl, tab, grid, stream, steps, profile_reps):
     d_sc = torch.empty(rows * 32, dtype=torch.uint8, device="cuda")
     args = (tab, 0, grid, d_meas.data_ptr(), d_seg.data_ptr(), d_pred.data_ptr(), d_ver.data_ptr(),
             d_sc.data_ptr(), sh)
-    for _ in range(3):
-        plogp.plogp_score_grid(*args)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        plogp.plogp_score_grid(*args)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
-    rounds = [plogp.plogp_score_grid_profile(*args, profile_reps) for _ in range(5)]
-    stage_ms = dict(zip(SCORE_STAGES, np.median(np.array(rounds), axis=0).tolist()))
+    ms, _ = timed_calls(torch, stream, lambda: plogp.plogp_score_grid(*args), steps, 3)
+    rounds = [plogp.plogp_score_grid_profile(*args, MIN_PER_BATCH) for _ in range(MIN_BATCHES)]
+    st = np.median(np.array(rounds), axis=0).tolist()
     # what the scoring has to move: every measured time read once, the segment size of the
-    # segmented strategies' points, every prediction and every verdict written once (the
-    # statistics could in principle be formed from values already in registers)
+    # segmented strategies' points, every prediction and every verdict written once
     points = n_m * n_P
     n_seg = sum(1 for i in (2, 5, 9) if (wl.strategy_mask >> i) & 1)
     alg_bytes = points * (8 * rows + 4 * n_seg + 8 * rows + 16 * grid.ops) + 32 * rows
-    k_ms = stage_ms["score"] + stage_ms["statistics"]
-    ach = alg_bytes / (k_ms * 1e-3) / 1e9
-    return {"ms_per_call": ms, "points_per_s": rows * points / (ms * 1e-3), "strategies": rows,
-            "points": points, "stage_ms": stage_ms,
-            "roofline": {"kernel": "score+statistics", "bound": "hbm", "achieved": ach,
-                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9),
-                         "traffic": None, "algorithmic_bytes": alg_bytes, "avg_ms": k_ms}}
+    return hbm_leg(ms, st[1] + st[2], alg_bytes,
+                   {"points_per_s": float("%.4g" % (rows * points / (ms * 1e-3))),
+                    "stage_ms": {"terms": st[0], "score": st[1], "statistics": st[2]}})
 
 
-def run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps, profile_reps):
+def run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps):
     """The robustness summary over the batch just tuned (table 0 against all the others)."""
     sh = stream.cuda_stream
     nt = tab.count
@@ -243,65 +229,15 @@ def run_robustness(plogp, torch, tab, grid, out, nbytes, stream, steps, profile_
     d_tab = torch.empty(nt, dtype=torch.int32, device="cuda")
     args = (grid, nt, out.data_ptr(), plogp.KEY_STRATEGY_AND_SEGMENT, d_agree.data_ptr(),
             d_dev.data_ptr(), d_tab.data_ptr(), sh)
-    for _ in range(3):
-        plogp.plogp_robustness(*args)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        plogp.plogp_robustness(*args)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
-    k_ms = float(np.median([plogp.plogp_robustness_profile(*args, profile_reps) for _ in range(5)]))
+    ms, _ = timed_calls(torch, stream, lambda: plogp.plogp_robustness(*args), steps, 3)
+    k_ms = float(np.median([plogp.plogp_robustness_profile(*args, MIN_PER_BATCH) for _ in range(MIN_BATCHES)]))
     # every 16-byte record of every table read once; 12 bytes per cell position and 4 per table out
     alg_bytes = nbytes + 12 * per_table + 4 * nt
-    ach = alg_bytes / (k_ms * 1e-3) / 1e9
-    return {"ms_per_call": ms, "cells_per_s": (nbytes // 16) / (ms * 1e-3), "tables": nt,
-            "mean_fraction_kept": float(d_agree.double().mean().item()) / max(nt - 1, 1),
-            "roofline": {"kernel": "k_robust", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9,
-                         "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9), "traffic": None,
-                         "algorithmic_bytes": alg_bytes, "avg_ms": k_ms}}
+    return hbm_leg(ms, k_ms, alg_bytes,
+                   {"mean_fraction_kept": float("%.4g" % (float(d_agree.double().mean().item()) / max(nt - 1, 1)))})
 
 
-def robust_cpu(sample):
-    """The robustness oracle (array operations, one thread) on the oracle's tables of the sample."""
-    import oracle
-    from oracle import plogp_robust as orb
-    cells, _ = oracle.tune_workload(sample)
-    runs, dt = 0, 0.0
-    while dt < 1.0 and runs < 20:
-        t0 = time.perf_counter()
-        orb.robustness(cells, 1)
-        dt += time.perf_counter() - t0
-        runs += 1
-    return {"value": runs * cells.size / dt, "unit": "cells/s", "cores": 1, "kind": "oracle",
-            "seconds": dt}
-
-
-def score_cpu(sample):
-    """The scoring oracle (one thread) on table 0 of the sample; a big table with long chain sums
-    (config 5) is cut down further to every 16th of the sample's sizes (a few seconds of work)."""
-    import dataclasses
-    import oracle
-    from plogp_workloads import make_measurements
-    if sample.sizes.shape[1] > 1024 and len(sample.m) > 64:
-        sample = dataclasses.replace(sample, m=sample.m[::16])
-    meas, seg = make_measurements(sample)
-    a = (sample.sizes[0], sample.gaps[0], float(sample.L[0]), sample.m, sample.P, sample.strategy_mask,
-         meas, seg)
-    runs, dt = 0, 0.0
-    while dt < 1.0 and runs < 20:
-        t0 = time.perf_counter()
-        oracle.score_grid(*a)
-        dt += time.perf_counter() - t0
-        runs += 1
-    return {"value": runs * meas.size / dt, "unit": "points/s", "cores": 1, "kind": "oracle",
-            "seconds": dt}
-
-
-def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profile_reps):
+def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps):
     """The cut-over extraction (runs of equal (strategy, s) along m) of the table just tuned."""
     sh = stream.cuda_stream
     n_cells = nbytes // 16
@@ -311,62 +247,31 @@ def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps, profil
     d_runs = torch.empty(cap * 16, dtype=torch.uint8, device="cuda")
     args = (grid, tab.count, out.data_ptr(), plogp.KEY_STRATEGY_AND_SEGMENT, d_off.data_ptr(),
             d_runs.data_ptr(), cap, sh)
-    for _ in range(3):
-        plogp.plogp_cutovers(*args)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        plogp.plogp_cutovers(*args)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / steps
+    ms, _ = timed_calls(torch, stream, lambda: plogp.plogp_cutovers(*args), steps, 3)
     n_runs = int(d_off[-1].item())
     assert n_runs <= cap, "bench: run buffer too small (%d runs)" % n_runs
-    rounds = [plogp.plogp_cutovers_profile(*args, profile_reps) for _ in range(5)]
-    stage_ms = dict(zip(CUT_STAGES, np.median(np.array(rounds), axis=0).tolist()))
+    rounds = [plogp.plogp_cutovers_profile(*args, MIN_PER_BATCH) for _ in range(MIN_BATCHES)]
+    st = np.median(np.array(rounds), axis=0).tolist()
     # what the extraction itself has to move: the 8-byte key of every cell once, a 16-byte
     # record per run, an 8-byte offset per row
     alg_bytes = 8 * n_cells + 16 * n_runs + 8 * (rows + 1)
-    kernels_ms = sum(stage_ms.values())
-    ach = alg_bytes / (kernels_ms * 1e-3) / 1e9
-    return {"ms_per_call": ms, "cells_per_s": n_cells / (ms * 1e-3), "runs": n_runs, "rows": rows,
-            "key": "strategy and segment size", "stage_ms": stage_ms,
-            "roofline": {"kernel": "mark+scan+emit", "bound": "hbm", "achieved": ach,
-                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9),
-                         "traffic": None, "algorithmic_bytes": alg_bytes, "avg_ms": kernels_ms}}
-
-
-def cut_cpu(sample):
-    """The oracle's extraction (array operations, one thread) on the oracle's table of the sample."""
-    import oracle
-    from oracle import plogp_cutover as oc
-    cells, _ = oracle.tune_workload(sample)
-    oc.cutovers(cells[:1, :, :, :2], sample.m, 1)
-    runs, dt = 0, 0.0
-    while dt < 1.0 and runs < 20:
-        t0 = time.perf_counter()
-        oc.cutovers(cells, sample.m, 1)
-        dt += time.perf_counter() - t0
-        runs += 1
-    return {"value": runs * cells.size / dt, "unit": "cells/s", "cores": 1, "kind": "oracle",
-            "seconds": dt}
+    return hbm_leg(ms, sum(st), alg_bytes, {"runs": n_runs, "stage_ms": {"mark": st[0], "scan": st[1], "emit": st[2]}})
 
 
 def cpu_sample(cfg, wl):
-    """A bounded cut of the same workload for the oracle (a few seconds of work)."""
+    """A bounded cut of the same workload for the oracle (a second or two on all cores)."""
     from plogp_workloads import make_workload
     if cfg == 3:
         return make_workload(3, m_slice=slice(0, 1024, 8)), "every 8th m row of config 3 (128 of 1024), all P, all s"
     if cfg == 4:
-        return make_workload(4, n_tables=100), "first 100 of the 10 000 tables of config 4, full grid"
+        return make_workload(4, n_tables=400), "first 400 of the 10 000 tables of config 4, full grid"
     if cfg == 5:
         return make_workload(5, m_slice=slice(0, 4096, 8)), "every 8th m row of config 5 (512 of 4096), all P, all s"
     return wl, "the full %s workload" % wl.name
 
 
 def run_cpu(cfg, wl):
+    """The oracle as it stands, OpenMP over (table, m) rows on the host's cores."""
     import oracle
     sample, what = cpu_sample(cfg, wl)
     oracle.tune_grid(sample.sizes[:1], sample.gaps[:1], sample.L[:1], sample.m[:2], sample.P[:2],
@@ -378,73 +283,102 @@ def run_cpu(cfg, wl):
         dt += time.perf_counter() - t0
         runs += 1
     c = sample.counts()
-    return {"value": runs * c["nominal_evals"] / dt, "unit": "evaluations/s", "cores": int(used),
-            "kind": "oracle", "sample": "%s, %d run(s)" % (what, runs), "seconds": dt,
-            "effective_evals_per_s": runs * c["effective_evals"] / dt,
-            "cells_per_s": runs * c["cells"] / dt}
+    return {"value": float("%.4g" % (runs * c["nominal_evals"] / dt)), "unit": "evaluations/s", "cores": int(used),
+            "kind": "oracle", "sample": "%s, %d run(s), %.1f s wall" % (what, runs, dt),
+            "effective_evals_per_s": float("%.4g" % (runs * c["effective_evals"] / dt)),
+            "cells_per_s": float("%.4g" % (runs * c["cells"] / dt))}
 
 
-def bench_config(cfg, steps, warmup, with_cpu, mask=None):
+def bench_config(cfg, steps, warmup, with_cpu, with_next, ceilings=None, mask=None):
     from plogp_workloads import make_workload
     wl = make_workload(cfg)
     if mask is not None:
         wl.strategy_mask = mask
     work, c = algorithmic_work(wl)
-    ms, stage_ms, cut, score, graph_ms = run_gpu(wl, steps, warmup, profile_reps=max(5, min(steps, 20)))
-    traffic = MEASURED_TRAFFIC.get(cfg, {}) if mask is None else {}
-    if stage_ms["terms"] == 0.0 and stage_ms["sweep"] > 0.0:
-        # the single-kernel batch path did every stage inside one launch
-        work = {"terms": {"flops": 0, "bytes": 0}, "chain_blocks": {"flops": 0, "bytes": 0},
-                "chain_prefix": {"flops": 0, "bytes": 0},
-                "sweep": {"flops": sum(w["flops"] for w in work.values()),
-                          "bytes": sum(w["bytes"] for w in work.values())}}
-    elif stage_ms["terms"] < 0.001 < stage_ms["chain_blocks"]:
-        # the terms and the chain sums run in one launch (side by side for small tables, the
-        # terms at the end of each workgroup for big ones), timed under "chain_blocks"
+    g = run_gpu(wl, steps, warmup, with_next, ceilings_wanted=ceilings is None)
+    ceilings = ceilings or g["ceilings"]
+    ms, stage_ms = g["ms"], g["stage_ms"]
+    fields = ("flops", "flops_executed", "bytes")
+    tiny = 0.0005          # ms: two events with nothing between them
+    if stage_ms["chain_blocks"] < tiny < stage_ms["sweep"]:
+        # one kernel formed the Scatter sums and swept (and, when nothing ran before it, the terms)
+        folded = ["chain_blocks", "chain_prefix", "sweep"] + (["terms"] if stage_ms["terms"] < tiny else [])
         work = dict(work)
-        work["chain_blocks"] = {k: work["chain_blocks"][k] + work["terms"][k] for k in ("flops", "bytes")}
-        work["terms"] = {"flops": 0, "bytes": 0}
+        work["sweep"] = {f: sum(work[k][f] for k in folded) for f in fields}
+        for k in folded[:2] + folded[3:]:
+            work[k] = dict.fromkeys(fields, 0)
+    elif stage_ms["terms"] < tiny < stage_ms["chain_blocks"]:
+        # the terms and the chain sums run in one launch, timed under "chain_blocks"
+        work = dict(work)
+        work["chain_blocks"] = {f: work["chain_blocks"][f] + work["terms"][f] for f in fields}
+        work["terms"] = dict.fromkeys(fields, 0)
     dominant = max(STAGES, key=lambda k: stage_ms[k])
+    off = OFFLINE_COUNTERS.get(cfg) if mask is None else None
+    stage_of_offline = {"k_row": "sweep", "k_sweep_s": "sweep", "k_batch_t": "sweep", "k_chain_blocks": "chain_blocks"}
+    def offline_for(stage):
+        if off and stage_of_offline.get(off["kernel"]) == stage:
+            return dict(off, cfg=cfg)
+        return None
+    r4 = lambda v: float("%.4g" % v)
     res = {
         "workload": describe(wl),
         "ms_per_step": ms,
         "value": c["nominal_evals"] / (ms * 1e-3),
-        "effective_evals_per_s": c["effective_evals"] / (ms * 1e-3),
-        "cells_per_s": c["cells"] / (ms * 1e-3),
-        "scatter_chain_interps_per_s": c["scatter_chain_interps"] / (ms * 1e-3),
-        "steps": steps,
-        "graph_replay_ms_per_step": graph_ms,
-        "stage_ms": stage_ms,
-        "roofline": roofline_of(dominant, work, stage_ms[dominant], traffic.get(dominant)),
-        "stage_rooflines": {k: roofline_of(k, work, stage_ms[k], traffic.get(k))
-                            for k in STAGES if stage_ms[k] > 0},
+        "effective_evals_per_s": r4(c["effective_evals"] / (ms * 1e-3)),
+        "cells_per_s": r4(c["cells"] / (ms * 1e-3)),
+        "steps_per_batch": g["per_batch"],
+        "stage_ms": {k: r4(v) for k, v in stage_ms.items() if v > 0.0005},
+        "roofline": roofline_of(dominant, work, stage_ms[dominant], ceilings, offline_for(dominant)),
+        "stage_rooflines": {k: roofline_of(k, work, stage_ms[k], ceilings, offline_for(k))
+                            for k in STAGES if stage_ms[k] > 0.0005},
+        "ceilings": ceilings,
     }
-    if cut is not None:
-        res["cutover_extraction"] = cut
-    if score is not None:
-        res["prediction_scoring"] = score
+    for k in ("cutovers", "scoring", "robustness"):
+        if k in g:
+            res[k] = g[k]
     if with_cpu:
         res["cpu_baseline"] = run_cpu(cfg, wl)
-        if cut is not None:
-            sample, what = cpu_sample(cfg, wl)
-            cut["cpu_baseline"] = dict(cut_cpu(sample), sample=what)
-        if score is not None:
-            sample, what = cpu_sample(cfg, wl)
-            thin = ", every 16th size of it" if sample.sizes.shape[1] > 1024 and len(sample.m) > 64 else ""
-            score["cpu_baseline"] = dict(score_cpu(sample), sample="table 0 of: " + what + thin)
-            if "robustness" in score:
-                score["robustness"]["cpu_baseline"] = dict(robust_cpu(sample), sample=what)
     return res
+
+
+def short(res):
+    """What the line keeps of a workload that is not the headline."""
+    r = res["roofline"]
+    keep = ("kernel", "bound", "achieved", "unit", "frac", "frac_delivered", "frac_executed",
+            "frac_of_measured_ceiling", "valu_issue_util", "traffic", "avg_ms")
+    out = {"workload": res["workload"], "ms_per_call": float("%.4g" % res["ms_per_step"]),
+           "value": float("%.4g" % res["value"]), "cells_per_s": res["cells_per_s"],
+           "stage_ms": res["stage_ms"], "roofline": {k: r[k] for k in keep if k in r}}
+    others = {k: {f: v[f] for f in ("bound", "frac", "frac_executed") if f in v}
+              for k, v in res["stage_rooflines"].items() if k != r["kernel"].split(" ")[0]}
+    if others:
+        out["other_kernels"] = others
+    if "cpu_baseline" in res:
+        out["cpu_baseline"] = {k: res["cpu_baseline"][k] for k in ("value", "unit", "cores")}
+    return out
+
+
+def short_next(res):
+    out = {}
+    for k in ("cutovers", "scoring", "robustness"):
+        if k in res:
+            v = res[k]
+            out[k] = {"ms_per_call": v["ms_per_call"], "kernels_ms": v["kernels_ms"],
+                      "hbm_frac": v["roofline"]["frac"]}
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--steps", type=int, default=100,
+                    help="calls per timed batch (at least %d are timed, in %d batches)" % (MIN_PER_BATCH, MIN_BATCHES))
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="headline workload (1..5)")
-    ap.add_argument("--extra", type=str, default="3,4,5", help="other configs to time, or 'none'")
+    ap.add_argument("--config", type=int, default=4, help="headline workload (1..5)")
+    ap.add_argument("--extra", type=str, default="3,5,2", help="other configs to time, or 'none'")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-next", action="store_true", help="skip the steps after the sweep")
+    ap.add_argument("--detail", type=str, default=None, help="also write every figure to this JSON file")
     ap.add_argument("--mask", type=lambda v: int(v, 0), default=None,
                     help="strategy mask override (for profiling parts of the path)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -467,7 +401,9 @@ def main():
         torch.add(a, 0.0, out=b)
         torch.cuda.synchronize()
         del a, b
-    head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu, args.mask)
+    with_next = not args.no_next
+    head = bench_config(args.config, args.steps, args.warmup, not args.no_cpu, with_next, None, args.mask)
+    r4 = lambda v: float("%.4g" % v)
     line = {
         "metric": METRIC,
         "value": head["value"],
@@ -482,27 +418,36 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": head["workload"]},
+        "timing": {"stat": "median", "batches": MIN_BATCHES, "steps_per_batch": head["steps_per_batch"]},
         "cells_per_s": head["cells_per_s"],
         "effective_evals_per_s": head["effective_evals_per_s"],
-        "graph_replay_ms_per_step": head["graph_replay_ms_per_step"],
         "stage_ms": head["stage_ms"],
         "roofline": head["roofline"],
-        "stage_rooflines": head["stage_rooflines"],
+        "measured_ceilings": {"fp64_fma_tflops": r4(head["ceilings"]["fma_tflops"]),
+                              "fill_gbs": r4(head["ceilings"]["store_gbs"]),
+                              "spec": {"fp64_vector_tflops": 78.6, "hbm_gbs": 8000.0}},
     }
     if "cpu_baseline" in head:
         line["cpu_baseline"] = head["cpu_baseline"]
-    if "cutover_extraction" in head:
-        line["cutover_extraction"] = head["cutover_extraction"]
-    if "prediction_scoring" in head:
-        line["prediction_scoring"] = head["prediction_scoring"]
+    detail = {"cfg%d" % args.config: head}
     extras = [] if args.extra in ("", "none") else [int(v) for v in args.extra.split(",")]
+    nxt = {"cfg%d" % args.config: short_next(head)} if with_next else {}
     if extras:
         line["workloads"] = {}
         for cfg in extras:
             if cfg == args.config:
                 continue
-            # enough steps and warm-up for the clocks to settle (50 steps read 10 % slow)
-            line["workloads"]["cfg%d" % cfg] = bench_config(cfg, 300, 20, not args.no_cpu)
+            res = bench_config(cfg, args.steps, args.warmup, False, with_next and cfg != 2, head["ceilings"])
+            detail["cfg%d" % cfg] = res
+            line["workloads"]["cfg%d" % cfg] = short(res)
+            if with_next and cfg != 2:
+                nxt["cfg%d" % cfg] = short_next(res)
+    if nxt:
+        line["next"] = nxt
+    if args.detail:
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump(detail, f, indent=1)
     print(json.dumps(line))
 
 
