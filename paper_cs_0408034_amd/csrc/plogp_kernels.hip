@@ -2815,6 +2815,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     // per wave: the PC cells of 64 tables on their way out, rows padded by one cell
     char *stage_all = reinterpret_cast<char *>(GS + (size_t)(n_s ? n_s : 1) * 64);
     uint32_t *sS = reinterpret_cast<uint32_t *>(stage_all + (size_t)BATCH_T_WAVES * BATCH_T_STAGE);   // [n_s]
+    unsigned &next_m = *reinterpret_cast<unsigned *>(sS + (n_s ? n_s : 1));   // next size of this workgroup's chunk
     // the chunks of large sizes (more candidates, the longest) are handed out first, so that
     // the launch ends with short workgroups
     const int n_tg = (D.n_tables + 63) / 64;
@@ -2829,6 +2830,8 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         sS[si] = (uint32_t)p_s[si];
     for (int i = wave; i < n + 2; i += BATCH_T_WAVES)
         YS[i * 64 + lane] = ysT[(size_t)i * D.n_tables + tc];
+    if (threadIdx.x == 0)
+        next_m = 0u;
     __syncthreads();
     const f64x2 *ys = YS + lane;                               // this lane's table: ys[64 i]
     const double *tab_ds = tab + 2 + (n + 1), *tab_is = tab_ds + n_s, *Wd = tab + 2;
@@ -2935,10 +2938,20 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
     const bool has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
 
-    for (int mw = 0; mw < D.m_per_wave; ++mw) {
-        const int mi = (mc * BATCH_T_WAVES + wave) * D.m_per_wave + mw;      // wave-uniform
-        if (mi >= D.n_m)
+    // The waves take the sizes of the workgroup's chunk one at a time from a counter, the largest
+    // first (a size's cost grows with its number of candidates): the one workgroup that fits a
+    // compute unit then ends with all its waves busy, whatever the mix.
+    const int chunk = BATCH_T_WAVES * D.m_per_wave;
+    for (;;) {
+        unsigned k = 0u;
+        if (lane == 0)
+            k = atomicAdd(&next_m, 1u);
+        k = (unsigned)__builtin_amdgcn_readfirstlane((int)k);
+        if (k >= (unsigned)chunk)
             break;
+        const int mi = mc * chunk + chunk - 1 - (int)k;                      // wave-uniform
+        if (mi >= D.n_m)
+            continue;
         const double *rec = recs + (size_t)mi * R.slots;
         const double md = uniform_load(rec + R.MD);
         const int nvm = uniform_load(reinterpret_cast<const int *>(rec + R.IM_NV) + 1);
@@ -3516,7 +3529,7 @@ static bool use_row_path(const DeviceTables &T, const DeviceGrid &G)
 static size_t batch_t_lds(int n, int n_s)
 {
     return ((size_t)2 * (n + 2) + (n_s ? n_s : 1)) * 64 * sizeof(double) +
-           (size_t)BATCH_T_WAVES * BATCH_T_STAGE + (size_t)(n_s ? n_s : 1) * 4;
+           (size_t)BATCH_T_WAVES * BATCH_T_STAGE + (size_t)(n_s ? n_s : 1) * 4 + 16;
 }
 
 // Batches whose tables share their sample sizes, with enough tables to fill waves and
