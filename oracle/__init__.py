@@ -23,6 +23,10 @@ VERDICT_DTYPE = np.dtype([("regret", "<f8"), ("pred_best", "<u4"), ("meas_best",
 SCORE_DTYPE = np.dtype([("sum_abs_err", "<f8"), ("max_abs_err", "<f8"), ("count", "<u8"),
                         ("reserved", "<u8")])
 
+# strategy ids of each operation, in the order of the decision table's planes:
+# Broadcast (Table 1), Scatter (Table 2), Gather, Barrier
+OP_MASKS = (0x3FF, 0x1C00, 0xE000, 0x30000)
+
 _lib = None
 
 
@@ -109,7 +113,7 @@ def tune_grid(sizes, gaps, L, m, P, s, s_cap: int, strategy_mask: int, n_threads
     P = np.ascontiguousarray(P, dtype=np.uint32)
     s = np.ascontiguousarray(s, dtype=np.uint64)
     nt, n = sizes.shape
-    n_ops = (1 if strategy_mask & 0x3FF else 0) + (1 if strategy_mask & 0x1C00 else 0)
+    n_ops = sum(1 for op_mask in OP_MASKS if strategy_mask & op_mask)
     out = np.zeros((nt, n_ops, m.size, P.size), dtype=CELL_DTYPE)
     used = _load().plogp_oracle_tune(
         _dptr(sizes), _dptr(gaps), n, _dptr(L), nt,
@@ -130,7 +134,7 @@ def tune_workload(wl, n_threads: int = 0):
 
 def strategy_ids(strategy_mask: int):
     """The enabled strategy ids, ascending (the row order of measurements and predictions)."""
-    return [i for i in range(13) if (strategy_mask >> i) & 1]
+    return [i for i in range(13) if (strategy_mask >> i) & 1]     # the measured rows: Tables 1 and 2
 
 
 def score_grid(x, y, L, m, P, strategy_mask: int, meas, seg):
@@ -143,7 +147,7 @@ def score_grid(x, y, L, m, P, strategy_mask: int, meas, seg):
     meas = np.ascontiguousarray(meas, dtype=np.float64)
     seg = np.ascontiguousarray(seg, dtype=np.uint32)
     assert meas.shape == (n_ids, m.size, P.size) and seg.shape == meas.shape
-    n_ops = (1 if strategy_mask & 0x3FF else 0) + (1 if strategy_mask & 0x1C00 else 0)
+    n_ops = (1 if strategy_mask & 0x3FF else 0) + (1 if strategy_mask & 0x1C00 else 0)   # Tables 1 and 2 only
     pred = np.empty_like(meas)
     verdict = np.zeros((n_ops, m.size, P.size), dtype=VERDICT_DTYPE)
     score = np.zeros(n_ids, dtype=SCORE_DTYPE)

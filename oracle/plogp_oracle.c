@@ -13,7 +13,9 @@
  *
  *   for every (table, operation, m, P):
  *       best = +inf
- *       for strategy id ascending:                 (ids in table order, 0..12)
+ *       for strategy id ascending:                 (ids in table order, 0..12; then the
+ *                                                   Gather rows 13..15 and Barrier rows 16, 17
+ *                                                   that Section 3 says are built alike)
  *           unsegmented: T = model(id, m, P);      keep on strict T < best
  *           segmented:   for s ascending, s <= min(m, s_cap):
  *                            T = model(id, m, P, s); keep on strict T < best
@@ -67,7 +69,7 @@ typedef struct {
     double L;
 } oracle_table;
 
-#define N_STRATEGIES 13
+#define N_STRATEGIES 18       /* Table 1 (0..9), Table 2 (10..12), Gather (13..15), Barrier (16, 17) */
 #define SUM_BLOCK 64
 
 /* ---- g(): Section 2 defines g(m); the evaluation rule between samples is
@@ -210,6 +212,21 @@ static double model(const oracle_table *t, int id, uint64_t m, uint32_t P, uint6
         return fma(q, L, sum);                        /* sum_j g(j m) + (P-1) L               */
     }
     case 12: return fma(cl, L, scatter_binomial_sum(t, m, P)); /* sum_j g(2^j m) + ceil(log2 P) L */
+    /* Gather (Section 3 names it as built like these): a Scatter read backwards.  Every
+     * message of Table 2's schedules travels the other way, at the other end of the same
+     * time span, and the root's receptions are one gap apart as its sends were: the same
+     * three expressions, m again the share of one process. */
+    case 13: return fma(q, gm, L);                    /* flat: the root takes in P-1 shares   */
+    case 14: {
+        double sum = isnan(chain_sum) ? scatter_chain_sum(t, m, P) : chain_sum;
+        return fma(q, L, sum);                        /* chain: the shares pile up hop by hop */
+    }
+    case 15: return fma(cl, L, scatter_binomial_sum(t, m, P)); /* binomial: subtrees merge    */
+    /* Barrier (Section 3, likewise): no payload; a one-byte fan-in to the root followed by
+     * a one-byte fan-out.  Flat: each half is the flat-tree row of Table 1 with g(1);
+     * binomial: each half is its binomial-tree row with g(1).  m is not used. */
+    case 16: return 2.0 * fma(q, g1, L);              /* 2 ((P-1) g(1) + L)                   */
+    case 17: return 2.0 * fma(fl, g1, cl * L);        /* 2 (floor(log2 P) g(1) + ceil(log2 P) L) */
     default: return NAN;
     }
 }
@@ -264,7 +281,7 @@ static oracle_cell best_of(const oracle_table *t, int lo, int hi, uint32_t mask,
  * Decision tables for a batch of tables over one grid.
  * x, y: [n_tables][n]; L: [n_tables]; out: [n_tables][n_ops][n_m][n_P] with P
  * fastest, where the operations present are Broadcast (if any id 0..9 is in
- * mask) then Scatter (if any id 10..12 is).  Naive per cell, except that the
+ * mask), then Scatter (10..12), Gather (13..15), Barrier (16, 17).  Naive per cell, except that the
  * Scatter-chain sum is produced once per (table, m) for all P.
  * Returns the number of threads used, or -1 on a bad argument.
  */
@@ -275,8 +292,16 @@ int plogp_oracle_tune(const double *x, const double *y, size_t n, const double *
 {
     if (n < 2 || n_tables == 0 || n_m == 0 || n_P == 0)
         return -1;
-    const int has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
-    const size_t n_ops = (size_t)has_b + (size_t)has_s;
+    /* the operations present, in plane order: Broadcast, Scatter, Gather, Barrier */
+    static const int op_lo[4] = {0, 10, 13, 16}, op_hi[4] = {9, 12, 15, 17};
+    int has_op[4];
+    size_t n_ops = 0;
+    for (int op = 0; op < 4; ++op) {
+        has_op[op] = 0;
+        for (int id = op_lo[op]; id <= op_hi[op]; ++id)
+            if ((mask >> id) & 1u) has_op[op] = 1;
+        n_ops += (size_t)has_op[op];
+    }
     uint32_t Pmax = 0;
     for (size_t i = 0; i < n_P; ++i) {
         if (P[i] < 2) return -1;
@@ -303,20 +328,19 @@ int plogp_oracle_tune(const double *x, const double *y, size_t n, const double *
             oracle_table t;
             t.x = x + ti * n; t.y = y + ti * n; t.n = n; t.L = L[ti]; t.slope = slope;
             plogp_oracle_slopes(t.x, t.y, n, slope);
-            const int need_chain = (mask >> 11) & 1u;
+            const int need_chain = ((mask >> 11) & 1u) | ((mask >> 14) & 1u);
             if (need_chain)
                 scatter_chain_prefix(&t, m[mi], Pmax, chain);
             for (size_t pi = 0; pi < n_P; ++pi) {
                 const double cs = need_chain ? chain[P[pi]] : 0.0;
-                size_t op = 0;
-                if (has_b) {
-                    out[((ti * n_ops + op) * n_m + mi) * n_P + pi] =
-                        best_of(&t, 0, 9, mask, m[mi], P[pi], s, n_s, s_cap, cs);
-                    ++op;
+                size_t plane = 0;
+                for (int op = 0; op < 4; ++op) {
+                    if (!has_op[op])
+                        continue;
+                    out[((ti * n_ops + plane) * n_m + mi) * n_P + pi] =
+                        best_of(&t, op_lo[op], op_hi[op], mask, m[mi], P[pi], s, n_s, s_cap, cs);
+                    ++plane;
                 }
-                if (has_s)
-                    out[((ti * n_ops + op) * n_m + mi) * n_P + pi] =
-                        best_of(&t, 10, 12, mask, m[mi], P[pi], s, n_s, s_cap, cs);
             }
         }
         free(slope);
@@ -369,8 +393,9 @@ int plogp_oracle_score(const double *x, const double *y, size_t n, double L, con
 {
     if (n < 2 || n_m == 0 || n_P == 0 || (mask & 0x1FFFu) == 0)
         return -1;
+    mask &= 0x1FFFu;
     int ids[N_STRATEGIES], n_ids = 0;
-    for (int id = 0; id < N_STRATEGIES; ++id)
+    for (int id = 0; id < 13; ++id)                  /* the measured rows are those of Tables 1 and 2 */
         if ((mask >> id) & 1u)
             ids[n_ids++] = id;
     const int has_b = (mask & 0x3FFu) != 0;

@@ -13,6 +13,12 @@ Rules:
     t + g(z); the message is at the receiver at t + g(z) + L.
   * A receive completes when the message is there (waiting costs nothing
     else); the node's clock moves to that time.
+  * The gap holds at the receiving end as well (it is the least interval
+    between consecutive transmissions or receptions of a node): a reception
+    of z bytes completes no earlier than g(z) after the node's previous
+    reception did.  In the schedules of Tables 1 and 2 every node has one
+    parent, whose sends already lie a gap apart, so the rule only shows where
+    several nodes send to one (Gather, Barrier).
   * A node forwards only what it has fully received.
 The completion time of a collective is the largest clock over all nodes.
 """
@@ -28,7 +34,8 @@ def run(programs: Dict[int, List[Action]], g: Callable[[int], Fraction], L: Frac
     """Execute the per-node programs; return the time the last node finishes."""
     clock = {n: Fraction(0) for n in programs}
     pc = {n: 0 for n in programs}
-    arrival: Dict[Tuple[int, int, object], Fraction] = {}
+    last_reception = {n: None for n in programs}     # when the node's previous reception completed
+    arrival: Dict[Tuple[int, int, object], Tuple[Fraction, int]] = {}
     progressed = True
     while progressed:
         progressed = False
@@ -41,13 +48,17 @@ def run(programs: Dict[int, List[Action]], g: Callable[[int], Fraction], L: Frac
                     clock[n] = end
                     key = (n, dst, tag)
                     assert key not in arrival, "duplicate message"
-                    arrival[key] = end + L
+                    arrival[key] = (end + L, size)
                 else:
                     _, src, tag = act
                     key = (src, n, tag)
                     if key not in arrival:
                         break                    # not sent yet: come back later
-                    clock[n] = max(clock[n], arrival[key])
+                    there, size = arrival[key]
+                    if last_reception[n] is not None:
+                        there = max(there, last_reception[n] + g(size))
+                    last_reception[n] = there
+                    clock[n] = max(clock[n], there)
                 pc[n] += 1
                 progressed = True
     for n, prog in programs.items():
@@ -170,8 +181,68 @@ def scatter_binomial(P, m):
     return progs
 
 
+def gather_flat(P, m):
+    """Every node sends its share straight to the root, all at once; the root takes
+    them in one after the other."""
+    progs = {n: [] for n in range(P)}
+    for child in range(1, P):
+        _payload(progs, child, 0, m, "part", False)
+    return progs
+
+
+def gather_chain(P, m):
+    """The last node sends its share to its neighbour, which adds its own and passes
+    both on, and so on down to the root."""
+    progs = {n: [] for n in range(P)}
+    for n in range(P - 1, 0, -1):
+        _payload(progs, n, n - 1, (P - n) * m, "rest", False)
+    return progs
+
+
+def gather_binomial(P, m):
+    """The binomial tree of the Scatter, every message reversed: a node first takes
+    in the shares of its subtrees, the smallest first, then sends everything it
+    holds to its parent."""
+    progs = {n: [] for n in range(P)}
+    children = _binomial_children(P)
+    order = sorted(range(P), key=lambda n: -bin(n).count("1"))   # children before parents
+    parent = {c: n for n in range(P) for c, _ in children[n]}
+    slot_of = {c: slot for n in range(P) for c, slot in children[n]}
+    for n in order:
+        for child, slot in sorted(children[n], key=lambda cs: cs[1]):
+            progs[n].append(("recv", child, "part"))
+        if n != 0:
+            count = min(slot_of[n], P - n)
+            progs[n].append(("send", parent[n], count * m, "part"))
+    return progs
+
+
+def barrier_flat(P):
+    """Every node reports to the root with one byte; the root then releases each
+    of them with one byte."""
+    progs = {n: [] for n in range(P)}
+    for child in range(1, P):
+        _payload(progs, child, 0, 1, "in", False)
+    for child in range(1, P):
+        _payload(progs, 0, child, 1, "out", False)
+    return progs
+
+
+def barrier_binomial(P):
+    """Binomial fan-in of one-byte messages (subtrees report smallest first), then
+    the binomial broadcast of one byte."""
+    progs = gather_binomial(P, 0)
+    for n in progs:                                   # the reports carry one byte, whatever the subtree
+        progs[n] = [("send", a[1], 1, "in") if a[0] == "send" else ("recv", a[1], "in") for a in progs[n]]
+    out = bcast_binomial(P, 1)
+    for n in progs:
+        progs[n] += [("send", a[1], 1, "out") if a[0] == "send" else ("recv", a[1], "out") for a in out[n]]
+    return progs
+
+
 def completion_time(strategy: int, P: int, m: int, s: int, g, L) -> Fraction:
-    """Replay strategy id (0..12, the order of Tables 1 and 2)."""
+    """Replay strategy id (0..12 in the order of Tables 1 and 2, then Gather
+    13..15 and Barrier 16, 17)."""
     L = Fraction(L)
     table = {
         0: lambda: bcast_flat(P, m),
@@ -187,5 +258,10 @@ def completion_time(strategy: int, P: int, m: int, s: int, g, L) -> Fraction:
         10: lambda: scatter_flat(P, m),
         11: lambda: scatter_chain(P, m),
         12: lambda: scatter_binomial(P, m),
+        13: lambda: gather_flat(P, m),
+        14: lambda: gather_chain(P, m),
+        15: lambda: gather_binomial(P, m),
+        16: lambda: barrier_flat(P),
+        17: lambda: barrier_binomial(P),
     }
     return run(table[strategy](), g, L)

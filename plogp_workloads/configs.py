@@ -91,9 +91,9 @@ class Workload:
 
     @property
     def n_ops(self) -> int:
-        b = 1 if self.strategy_mask & 0x3FF else 0
-        sc = 1 if self.strategy_mask & 0x1C00 else 0
-        return b + sc
+        # planes of the decision table: Broadcast (ids 0..9), Scatter (10..12), Gather (13..15),
+        # Barrier (16, 17), each present if one of its ids is enabled
+        return sum(1 for op_mask in (0x3FF, 0x1C00, 0xE000, 0x30000) if self.strategy_mask & op_mask)
 
     @property
     def n_cells(self) -> int:
@@ -108,7 +108,7 @@ class Workload:
         interps = terms of the Scatter-chain sum when shared per m (P_max - 1 each).
         """
         mask = self.strategy_mask
-        n_unseg = sum(1 for i in range(13) if (mask >> i) & 1 and i not in SEGMENTED_IDS)
+        n_unseg = sum(1 for i in range(18) if (mask >> i) & 1 and i not in SEGMENTED_IDS)
         n_seg = sum(1 for i in SEGMENTED_IDS if (mask >> i) & 1)
         lim = np.minimum(self.m, np.uint64(self.s_cap))
         valid = np.searchsorted(self.s, lim, side="right")          # valid candidates per m
@@ -117,7 +117,7 @@ class Workload:
         eff = self.n_tables * (len(self.m) * nP * n_unseg + n_ms * nP * n_seg)
         nom = self.n_tables * bin(mask).count("1") * len(self.m) * nP * len(self.s)
         interps = 0
-        if (mask >> 11) & 1:
+        if (mask >> 11) & 1 or (mask >> 14) & 1:
             interps = self.n_tables * len(self.m) * (int(self.P.max()) - 1)
         return {
             "cells": self.n_cells,
