@@ -37,7 +37,7 @@ METRIC = "pLogP model evaluations/sec (strategy×m×P×s) + decision-table cells
 FP64_VECTOR_PEAK = 78.6e12        # flop/s: 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
 VALU_ISSUE_PEAK = 39.3e12         # lane-instructions/s: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
 HBM_PEAK = 8.0e12                 # bytes/s
-STAGES = ("terms", "chain_blocks", "chain_prefix", "sweep")
+STAGES = ("terms", "chain_blocks", "chain_prefix", "sweep", "more_planes")
 MIN_BATCHES, MIN_PER_BATCH = 5, 100
 
 # flops of one unsegmented row per (m, P), arg-min compare included
@@ -81,11 +81,17 @@ def algorithmic_work(wl):
     sweep = 3 * pairs * n_P * n_seg + 5 * pairs + unseg * nt * n_m * n_P
     seg5 = 1 if (mask >> 5) & 1 else 0
     sweep_x = 3 * pairs * n_P * seg5 + (pairs if mask & 0x204 else 0) + 5 * pairs + unseg * nt * n_m * n_P
+    # the planes of Gather and Barrier (rows beyond the tables; none in the five configs)
+    planes = [bool(mask & b) for b in (0x3FF, 0x1C00, 0xE000, 0x30000)]
+    more_bytes = c["output_bytes"] * sum(planes[2:]) // max(sum(planes), 1)
+    more_flops = nt * n_m * n_P * (sum(UNSEG_FLOPS[i - 3] for i in (13, 14, 15) if (mask >> i) & 1) +
+                                   sum(4 for i in (16, 17) if (mask >> i) & 1))
     return {
         "terms": {"flops": terms, "flops_executed": terms, "bytes": nt * n * 16},
         "chain_blocks": {"flops": chain, "flops_executed": chain_x, "bytes": 0},
         "chain_prefix": {"flops": prefix, "flops_executed": prefix * n_mu // n_m, "bytes": 0},
-        "sweep": {"flops": sweep, "flops_executed": sweep_x, "bytes": c["output_bytes"]},
+        "sweep": {"flops": sweep, "flops_executed": sweep_x, "bytes": c["output_bytes"] - more_bytes},
+        "more_planes": {"flops": more_flops, "flops_executed": more_flops, "bytes": more_bytes},
     }, c
 
 
@@ -256,6 +262,31 @@ def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps):
     # record per run, an 8-byte offset per row
     alg_bytes = 8 * n_cells + 16 * n_runs + 8 * (rows + 1)
     return hbm_leg(ms, sum(st), alg_bytes, {"runs": n_runs, "stage_ms": {"mark": st[0], "scan": st[1], "emit": st[2]}})
+
+
+def run_patterns(cfg, steps):
+    """The workload with the rows beyond Tables 1 and 2 switched on as well (Gather ids 13..15,
+    Barrier 16, 17: two more planes); their kernel is priced against the HBM write roofline."""
+    import torch
+    from paper_cs_0408034_amd import plogp
+    from plogp_workloads import make_workload
+    wl = make_workload(cfg)
+    wl.strategy_mask = 0x3FFFF
+    work, c = algorithmic_work(wl)
+    tab = plogp.plogp_load_tables(wl.sizes, wl.gaps, wl.L)
+    grid = plogp.plogp_grid_create(wl.m, wl.P, wl.s, wl.s_cap, wl.dtype_size, wl.strategy_mask)
+    nbytes = plogp.plogp_decision_table_bytes(tab.count, grid)
+    out = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    ms, _ = timed_calls(torch, stream, lambda: plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh), steps, 3)
+    rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, MIN_PER_BATCH)
+              for _ in range(MIN_BATCHES)]
+    k_ms = float(np.median(np.array(rounds), axis=0)[4])
+    del out
+    grid.free()
+    tab.free()
+    return hbm_leg(ms, k_ms, work["more_planes"]["bytes"], {"planes": 4, "kernel": "k_more_planes"})
 
 
 def cpu_sample(cfg, wl):
@@ -442,6 +473,10 @@ def main():
             line["workloads"]["cfg%d" % cfg] = short(res)
             if with_next and cfg != 2:
                 nxt["cfg%d" % cfg] = short_next(res)
+                pat = run_patterns(cfg, args.steps)
+                detail["cfg%d" % cfg]["more_patterns"] = pat
+                nxt["cfg%d" % cfg]["more_patterns"] = {"ms_per_call": pat["ms_per_call"], "kernels_ms": pat["kernels_ms"],
+                                                        "hbm_frac": pat["roofline"]["frac"]}
     if nxt:
         line["next"] = nxt
     if args.detail:

@@ -33,6 +33,16 @@
  *    5 Broadcast segmented chain          12 Scatter binomial tree
  *    6 Broadcast binary tree
  * Ids 2, 5 and 9 are the segmented rows (they take s); the others ignore s.
+ *
+ * Beyond the two tables (Section 3 names Gather and Barrier as patterns that are
+ * built like Broadcast and Scatter; the paper prints no rows for them, these
+ * follow from the same pLogP rules):
+ *   13 Gather flat tree      (P-1) g(m) + L                      the rows of Table 2:
+ *   14 Gather chain          sum_{j=1}^{P-1} g(j m) + (P-1) L    a Gather is its Scatter
+ *   15 Gather binomial tree  sum_j g(2^j m) + ceil(log2 P) L     with every message reversed
+ *   16 Barrier flat tree     2 ((P-1) g(1) + L)                  a one-byte fan-in to the root,
+ *   17 Barrier binomial tree 2 (floor(log2 P) g(1) + ceil(log2 P) L)   then a one-byte fan-out
+ * m of a Gather is the share of one process, as for Scatter; a Barrier ignores m.
  */
 #ifndef PLOGP_H
 #define PLOGP_H
@@ -44,10 +54,13 @@
 extern "C" {
 #endif
 
-#define PLOGP_N_STRATEGIES 13
+#define PLOGP_N_STRATEGIES 18
 #define PLOGP_MASK_BCAST 0x03FFu      /* ids 0..9  */
 #define PLOGP_MASK_SCATTER 0x1C00u    /* ids 10..12 */
-#define PLOGP_MASK_ALL 0x1FFFu
+#define PLOGP_MASK_ALL 0x1FFFu        /* every row of Tables 1 and 2 */
+#define PLOGP_MASK_GATHER 0xE000u     /* ids 13..15 */
+#define PLOGP_MASK_BARRIER 0x30000u   /* ids 16, 17 */
+#define PLOGP_MASK_EVERY 0x3FFFFu     /* ids 0..17 */
 #define PLOGP_NO_STRATEGY 0xFFFFFFFFu
 #define PLOGP_MAX_SAMPLES 4096        /* largest table that fits the LDS staging */
 #define PLOGP_NO_CAP UINT64_MAX
@@ -132,7 +145,8 @@ int plogp_interp_g(const plogp_table *t, size_t table_index, const uint64_t *d_z
  * strategy at n independent points (m, P, s) on table `table_index`.
  *   d_m [n] uint64 bytes, > 0; d_P [n] uint32, >= 2; d_s [n] uint64 segment
  *   sizes (only read for ids 2, 5, 9, where 0 < s <= m; may be NULL for
- *   the other ids); d_time_out [n] doubles.  All device pointers.
+ *   the other ids); d_time_out [n] doubles.  All device pointers.  Ids 13..17
+ *   (Gather, Barrier: see the list of ids above) are evaluated the same way.
  * A point outside the domain (m = 0, P < 2, bad s, or a product j*m that
  * would reach 2^53) yields NaN for that point.  Enqueued on `stream`.
  * Errors: EINVAL (null pointers, unknown strategy, bad index), EDEVICE.
@@ -147,15 +161,16 @@ int plogp_eval_strategy(const plogp_table *t, size_t table_index, int strategy,
  * Errors: EINVAL (null array with non-zero count; n_m = 0 or n_P = 0; m = 0;
  *         P < 2 or not strictly ascending; s = 0, s >= 2^32 or not strictly
  *         ascending; m or s not a multiple of dtype_size; mask selects no
- *         known strategy), ERANGE (m >= 2^53, or with Scatter chain / binomial
- *         enabled (Pmax-1)*m_max or 2^(ceil(log2 Pmax)-1)*m_max >= 2^53),
+ *         known strategy), ERANGE (m >= 2^53, or with a Scatter or Gather chain /
+ *         binomial row enabled (Pmax-1)*m_max or 2^(ceil(log2 Pmax)-1)*m_max >= 2^53),
  *         ENOMEM, EDEVICE.
  */
 int plogp_grid_create(const plogp_grid_desc *desc, plogp_grid **out);
 int plogp_grid_free(plogp_grid *g);
 
 /* Number of operation planes of the decision table: Broadcast if any of ids
- * 0..9 is in the mask, then Scatter if any of ids 10..12 is (1 or 2). */
+ * 0..9 is in the mask, then Scatter (10..12), Gather (13..15), Barrier (16, 17),
+ * each if any of its ids is: 1 to 4. */
 size_t plogp_grid_ops(const plogp_grid *g);
 /* Cells / bytes of the decision table for n_tables tables over this grid. */
 size_t plogp_decision_table_cells(size_t n_tables, const plogp_grid *g);
@@ -166,8 +181,8 @@ size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g);
  * every table of `t`, every operation plane and every (m, P) of the grid,
  * evaluates all enabled strategies (segmented ones for every candidate
  * s <= min(m, s_cap)) and writes the arg-min: smallest predicted time, ties
- * to the lowest strategy id, then to the smallest s.  Broadcast and Scatter
- * never compete with each other.
+ * to the lowest strategy id, then to the smallest s.  The operations (Broadcast,
+ * Scatter, Gather, Barrier) never compete with each other: each has a plane.
  *   d_out: DEVICE buffer, caller-owned, 16-byte aligned, laid out
  *          [table][operation plane][m index][P index] with P fastest;
  *          d_out_bytes must be >= plogp_decision_table_bytes().
@@ -236,7 +251,8 @@ int plogp_cutovers(plogp_grid *g, size_t n_tables, const plogp_cell *d_cells, in
  * Tables 1 and 2, and the question is whether the technique the models choose
  * is the fastest one in the measurement.  For ONE table and the (m, P) of grid
  * g (its candidate list and cap are not used), with r running over the
- * strategies enabled in the grid's mask in ascending id:
+ * strategies of Tables 1 and 2 (ids 0..12; the paper measures no other) that are
+ * enabled in the grid's mask, in ascending id:
  *   pred[r][m][P]     the model at the measured point;
  *   verdict[op][m][P] pred_best: the enabled strategy of the operation with the
  *                     smallest prediction; meas_best: the one with the smallest
@@ -260,7 +276,7 @@ typedef struct {
     uint64_t reserved;   /* 0                                                  */
 } plogp_strategy_score;  /* 32 bytes */
 
-/* Strategies enabled in the grid's mask: the rows of meas, seg, pred, scores. */
+/* Strategies with ids 0..12 enabled in the grid's mask: the rows of meas, seg, pred, scores. */
 size_t plogp_score_strategies(const plogp_grid *g);
 
 /*

@@ -23,10 +23,11 @@ extern "C" {
 
 /*
  * Twin of plogp_tune_grid (paper Section 3.1 / Section 1: the sweep).
- * stage_ms_out[0..3]:
+ * stage_ms_out[0..4]:
  *   [0] per-table and per-m terms (interval slopes, g(1), g(s), g(m), the
  *       Scatter-binomial prefix sums), [1] Scatter-chain block sums,
- *   [2] Scatter-chain block prefix, [3] sweep + arg-min + decision-table write.
+ *   [2] Scatter-chain block prefix, [3] sweep + arg-min + decision-table write,
+ *   [4] the planes of the rows beyond Tables 1 and 2 (Gather, Barrier), if enabled.
  * A stage that launched nothing reports 0.  For tables of up to about 1000
  * samples the terms and the Scatter-chain block sums are one launch, reported
  * under [1]; the paths that do everything in one kernel (batches of tables; one

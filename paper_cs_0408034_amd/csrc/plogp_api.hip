@@ -104,7 +104,8 @@ DeviceGrid plogp_grid::view() const
     g.mu = d_mu; g.m_map = d_m_map; g.n_mu = (int)n_mu;
     g.n_m = (int)n_m; g.n_P = (int)n_P; g.n_s = (int)n_s;
     g.n_blk = n_blk; g.last_terms = last_terms; g.cl_max = cl_max;
-    g.s_cap = s_cap; g.mask = mask; g.n_ops = n_ops;
+    g.s_cap = s_cap; g.mask = mask & PLOGP_MASK_ALL; g.extra = mask >> 13; g.n_ops = n_ops;
+    g.need = (((mask >> 11) | (mask >> 14)) & 1u) << 11 | (((mask >> 12) | (mask >> 15)) & 1u) << 12;
     g.blk_is_prefix = n_blk > 32 ? 1 : 0;
     return g;
 }
@@ -203,6 +204,7 @@ int check_score_args(const plogp_table *t, size_t table_index, const plogp_grid 
 {
     if (!t || !g || !d_meas || !d_pred || !d_verdict || !d_scores) return PLOGP_EINVAL;
     if (table_index >= t->n_tables) return PLOGP_EINVAL;
+    if ((g->mask & PLOGP_MASK_ALL) == 0) return PLOGP_EINVAL;       // no measured row is enabled
     if ((g->mask & 0x224u) != 0 && !d_seg) return PLOGP_EINVAL;
     if (((uintptr_t)d_verdict & 15u) != 0 || ((uintptr_t)d_scores & 15u) != 0 ||
         ((uintptr_t)d_meas & 7u) != 0 || ((uintptr_t)d_pred & 7u) != 0 || ((uintptr_t)d_seg & 3u) != 0)
@@ -345,7 +347,7 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     if (d->n_m == 0 || d->n_P == 0 || !d->m || !d->P) return PLOGP_EINVAL;
     if (d->n_s > 0 && !d->s) return PLOGP_EINVAL;
     if (d->n_m > (1u << 24) || d->n_P > (1u << 24) || d->n_s > (1u << 24)) return PLOGP_EINVAL;
-    const uint32_t mask = d->strategy_mask & PLOGP_MASK_ALL;
+    const uint32_t mask = d->strategy_mask & PLOGP_MASK_EVERY;
     if (mask == 0 || mask != d->strategy_mask) return PLOGP_EINVAL;
     const uint64_t unit = d->dtype_size > 1 ? d->dtype_size : 1;
     uint64_t m_max = 0;
@@ -366,8 +368,8 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     if (too_big) return PLOGP_ERANGE;
     const uint32_t Pmax = d->P[d->n_P - 1];
     const int cl_max = ceil_log2_u32(Pmax);
-    if ((mask & (1u << 11)) && (uint64_t)(Pmax - 1) > (kTwo53u - 1) / m_max) return PLOGP_ERANGE;
-    if ((mask & (1u << 12)) && m_max > ((kTwo53u - 1) >> (cl_max > 0 ? cl_max - 1 : 0)))
+    if ((mask & ((1u << 11) | (1u << 14))) && (uint64_t)(Pmax - 1) > (kTwo53u - 1) / m_max) return PLOGP_ERANGE;
+    if ((mask & ((1u << 12) | (1u << 15))) && m_max > ((kTwo53u - 1) >> (cl_max > 0 ? cl_max - 1 : 0)))
         return PLOGP_ERANGE;
 
     int rc = ensure_init();
@@ -378,7 +380,8 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     g->n_m = d->n_m; g->n_P = d->n_P; g->n_s = d->n_s;
     g->s_cap = d->s_cap;
     g->mask = mask;
-    g->n_ops = ((mask & PLOGP_MASK_BCAST) ? 1 : 0) + ((mask & PLOGP_MASK_SCATTER) ? 1 : 0);
+    g->n_ops = ((mask & PLOGP_MASK_BCAST) ? 1 : 0) + ((mask & PLOGP_MASK_SCATTER) ? 1 : 0) +
+               ((mask & PLOGP_MASK_GATHER) ? 1 : 0) + ((mask & PLOGP_MASK_BARRIER) ? 1 : 0);
     g->cl_max = cl_max;
     g->n_blk = (int)((Pmax - 1) / SUM_BLOCK) + 1;
     g->last_terms = (int)((Pmax - 1) - (uint32_t)SUM_BLOCK * (uint32_t)(g->n_blk - 1));
@@ -500,7 +503,7 @@ size_t plogp_score_strategies(const plogp_grid *g)
 {
     size_t n = 0;
     if (g)
-        for (int id = 0; id < PLOGP_N_STRATEGIES; ++id) n += (g->mask >> id) & 1u;
+        for (int id = 0; id < 13; ++id) n += (g->mask >> id) & 1u;      // the rows of Tables 1 and 2
     return n;
 }
 

@@ -46,8 +46,12 @@ struct DeviceGrid {
     int last_terms;       // number of terms of the last block: (Pmax-1) - SUM_BLOCK*(n_blk-1)
     int cl_max;           // ceil(log2 Pmax)
     uint64_t s_cap;
-    uint32_t mask;
-    int n_ops;
+    uint32_t mask;        // which rows of Tables 1 and 2 compete (bits 0..12)
+    uint32_t extra;       // rows beyond the tables: bits 0..2 Gather flat / chain / binomial (ids 13..15),
+                          // bits 3, 4 Barrier flat / binomial (ids 16, 17)
+    uint32_t need;        // bit 11: the sums over j of g(j m) are wanted, bit 12: those of g(2^j m)
+                          // (by a Scatter row or by its Gather twin)
+    int n_ops;            // planes of the decision table: Broadcast, Scatter, Gather, Barrier, those present
     int blk_is_prefix;    // 1: a kernel turns the block totals into their exclusive prefix;
                           // 0 (few blocks): the sweep adds the finished blocks itself
 };
@@ -154,7 +158,8 @@ struct TunePlan {
 
 // Stages of a tune call, in launch order; a stage may launch nothing.
 enum { TUNE_STAGE_TERMS = 0, TUNE_STAGE_CHAIN = 1, TUNE_STAGE_PREFIX = 2, TUNE_STAGE_SWEEP = 3,
-       TUNE_STAGES = 4 };
+       TUNE_STAGE_MORE = 4,       // the planes of the rows beyond Tables 1 and 2 (Gather, Barrier)
+       TUNE_STAGES = 5 };
 
 // Fills `plan`.  Returns false if a launch dimension or an index of the chosen path would not
 // fit 31 bits (the job is too large for one call).

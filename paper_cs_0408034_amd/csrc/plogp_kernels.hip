@@ -189,9 +189,9 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
     const u64 s = seg ? ds[i] : 0;
     const u64 lim = 1ull << 53;
     bool ok = m > 0 && m < lim && P >= 2 && (!seg || (s > 0 && s <= m));
-    if (ok && id == 11)
+    if (ok && (id == 11 || id == 14))
         ok = (u64)(P - 1) <= (lim - 1) / m;
-    if (ok && id == 12)
+    if (ok && (id == 12 || id == 15))
         ok = m <= ((lim - 1) >> (ceil_log2(P) > 0 ? ceil_log2(P) - 1 : 0));
     if (!ok) {
         out[i] = NAN;
@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
     }
     double r;
     switch (id) {
-    case 0: case 10: r = __builtin_fma(q, gm, L); break;
+    case 0: case 10: case 13: r = __builtin_fma(q, gm, L); break;
     case 1: r = __builtin_fma(q, gm, R); break;
     case 2: r = __builtin_fma(q, gs * k, L); break;
     case 3: r = q * (gm + L); break;
@@ -219,7 +219,9 @@ __global__ void __launch_bounds__(256) k_eval(DeviceTables T, int t, int id, con
     case 7: r = __builtin_fma(fl, gm, cl * L); break;
     case 8: r = __builtin_fma(fl, gm, cl * R); break;
     case 9: r = __builtin_fma(fl, gs * k, cl * L); break;
-    case 11: r = __builtin_fma(q, L, chain_sum(tab, m, P)); break;
+    case 11: case 14: r = __builtin_fma(q, L, chain_sum(tab, m, P)); break;
+    case 16: r = 2.0 * __builtin_fma(q, g1, L); break;
+    case 17: r = 2.0 * __builtin_fma(fl, g1, cl * L); break;
     default: {
         double sum = 0.0;
         const int c = ceil_log2(P);
@@ -328,7 +330,7 @@ __device__ __forceinline__ void terms_body(const DeviceTables &T, const DeviceGr
             if (t == 0)
                 S.nv[mi] = lo;
         }
-        if (G.mask & (1u << 12)) {
+        if (G.need & (1u << 12)) {
             double *o = S.sum2 + ((size_t)t * G.n_m + mi) * (G.cl_max + 1);   // [m][d]
             double acc = 0.0;
             o[0] = 0.0;
@@ -3422,6 +3424,53 @@ __global__ void __launch_bounds__(1024) k_score_final(DeviceGrid G, const double
     }
 }
 
+// ---- the planes beyond Tables 1 and 2 -------------------------------------------
+//
+// Section 3 of the paper names Gather and Barrier as patterns that are built like
+// Broadcast and Scatter.  In pLogP a Gather is its Scatter with every message
+// reversed (the same sends, the other way round, over the same span of time; the
+// root's receptions lie a gap apart as its sends did): rows 13..15 are the
+// expressions of Table 2, on the same two sums.  A Barrier carries no payload: a
+// one-byte fan-in to the root and a one-byte fan-out, flat (row 16: twice the flat
+// row of Table 1 at g(1)) or binomial (row 17: twice its binomial row at g(1)); it
+// does not depend on the message size.  One thread per (table, m, P), lanes along
+// P; g(m), g(1) and the sums come from the staged path's first steps.
+__global__ void __launch_bounds__(256) k_more_planes(DeviceTables T, DeviceGrid G, Scratch S,
+                                                     plogp_cell_dev *out, int n_pchunks)
+{
+    int bid = (int)blockIdx.x;
+    const int pi = (bid % n_pchunks) * 256 + (int)threadIdx.x;
+    bid /= n_pchunks;
+    const int mi = bid % G.n_m, t = bid / G.n_m;
+    if (pi >= G.n_P)
+        return;
+    const uint32_t P = G.P[pi];
+    const double L = T.L[t];
+    const double q = (double)(P - 1u), fl = (double)floor_log2(P), cl = (double)ceil_log2(P);
+    const size_t plane = (size_t)G.n_m * G.n_P;
+    const int first = ((G.mask & 0x3FFu) ? 1 : 0) + ((G.mask & 0x1C00u) ? 1 : 0);   // planes before these
+    plogp_cell_dev *o = out + ((size_t)t * G.n_ops + first) * plane + (size_t)mi * G.n_P + pi;
+    if (G.extra & 7u) {
+        // the rows of Table 2 under the ids of their Gather twins
+        const uint32_t as_scatter = (G.extra & 7u) << 10;
+        const double gm = S.gm[(size_t)t * G.n_m + mi];
+        const double s11 = (as_scatter & (1u << 11)) ? chain_sum_of(G, S, t, mi, pi, P) : 0.0;
+        const double s12 = (as_scatter & (1u << 12))
+                               ? S.sum2[((size_t)t * G.n_m + mi) * (size_t)(G.cl_max + 1) + ceil_log2(P)] : 0.0;
+        Best b = decide_scatter(as_scatter, q, cl, gm, L, s11, s12);
+        b.id += 3u;
+        store_cell(o, b);
+        o += plane;
+    }
+    if (G.extra & 0x18u) {
+        const double g1 = S.g1[t];
+        Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+        if (G.extra & 8u) consider(b, 2.0 * __builtin_fma(q, g1, L), 16, 0);
+        if (G.extra & 16u) consider(b, 2.0 * __builtin_fma(fl, g1, cl * L), 17, 0);
+        store_cell(o, b);
+    }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launch wrappers
@@ -3594,7 +3643,9 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
     const size_t nt = (size_t)T.n_tables, n_m = (size_t)G.n_m, n_mu = (size_t)G.n_mu;
     const size_t n_P = (size_t)G.n_P, n_s = (size_t)G.n_s;
     LayoutBuilder lb;
-    if (!terms_only && use_table_lane_path(T, G)) {
+    // the rows beyond Tables 1 and 2 are formed from the staged path's terms and sums
+    const bool fast_ok = !terms_only && G.extra == 0;
+    if (fast_ok && use_table_lane_path(T, G)) {
         p.path = TUNE_TABLE_LANES;
         // tables by interval and the per-m facts, then everything else in one kernel
         p.n_stage = (T.n_tables + BATCH_STAGE_TT - 1) / BATCH_STAGE_TT;
@@ -3621,7 +3672,7 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
         p.lay.total = lb.at;
         return true;
     }
-    if (!terms_only && !use_fused_path(T, G) && use_row_path(T, G)) {
+    if (fast_ok && !use_fused_path(T, G) && use_row_path(T, G)) {
         p.path = TUNE_ROW;
         // two process counts per lane when there are more groups of 64 than waves
         p.row_two = G.n_P > 64 * (ROW_THREADS / 64);
@@ -3629,7 +3680,7 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
         p.lay.total = lb.at;
         return true;
     }
-    if (!terms_only && use_fused_path(T, G)) {
+    if (fast_ok && use_fused_path(T, G)) {
         p.path = TUNE_FUSED;
         p.fused_mchunks = (G.n_m + 255) / 256;
         if ((long)T.n_tables * p.fused_mchunks > kMaxLaunch) return false;
@@ -3681,7 +3732,7 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
     const long terms_wg = (long)T.n_tables * (p.n_chunks + n_mchunks);
     if (terms_wg > kMaxLaunch) return false;
     p.terms_wg = (int)terms_wg;
-    const bool chain = (G.mask & (1u << 11)) != 0;
+    const bool chain = (G.need & (1u << 11)) != 0;
     p.chain = chain;
     // a big table fills most of the LDS of a CU: one large workgroup per CU then, which
     // stays for its whole share of the work (the table is staged once)
@@ -3771,8 +3822,9 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
             if ((long)T.n_tables * p.n_mg * p.n_pcg > kMaxLaunch) return false;
         }
     }
+    if (!terms_only && G.extra != 0 && (long)T.n_tables * G.n_m * ((G.n_P + 255) / 256) > kMaxLaunch) return false;
     // scratch: what the kernels of this path index (m-fastest arrays per distinct size where noted)
-    const bool binom = (G.mask & (1u << 12)) != 0;
+    const bool binom = (G.need & (1u << 12)) != 0;
     p.lay.g1 = lb.take(nt * D);
     p.lay.gs = lb.take(nt * n_s * D);
     p.lay.gm = lb.take(nt * n_m * D);
@@ -3825,6 +3877,14 @@ hipError_t launch_tune_stage(const TunePlan &p, int stage, const DeviceTables &T
         if (stage == TUNE_STAGE_SWEEP)
             hipLaunchKernelGGL(k_fused, dim3((unsigned)T.n_tables * p.fused_mchunks), dim3(256),
                                (size_t)3 * T.n * sizeof(double) + 64, st, T, G, d_out, p.fused_mchunks);
+        return hipGetLastError();
+    }
+    if (stage == TUNE_STAGE_MORE) {
+        if (!p.terms_only && G.extra != 0) {
+            const int n_pchunks = (G.n_P + 255) / 256;
+            hipLaunchKernelGGL(k_more_planes, dim3((unsigned)((long)T.n_tables * G.n_m * n_pchunks)), dim3(256), 0,
+                               st, T, G, S, d_out, n_pchunks);
+        }
         return hipGetLastError();
     }
     switch (stage) {

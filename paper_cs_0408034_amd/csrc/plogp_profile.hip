@@ -17,7 +17,7 @@ namespace {
 template <class Stage>
 int timed_stages(int n_stages, int reps, hipStream_t st, float *ms_out, Stage stage)
 {
-    constexpr int MAX_STAGES = 4;
+    constexpr int MAX_STAGES = 5;
     hipEvent_t ev[MAX_STAGES + 1] = {};
     hipError_t e = hipSuccess;
     for (int i = 0; i <= n_stages && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
@@ -27,7 +27,7 @@ int timed_stages(int n_stages, int reps, hipStream_t st, float *ms_out, Stage st
         if (e == hipSuccess) e = hipEventRecord(ev[i + 1], st);
     }
     if (e == hipSuccess) e = hipEventSynchronize(ev[n_stages]);
-    float ms[MAX_STAGES] = {0.f, 0.f, 0.f, 0.f};
+    float ms[MAX_STAGES] = {0.f, 0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < n_stages && e == hipSuccess; ++i) {
         e = hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]);
         ms[i] /= (float)reps;

@@ -21,6 +21,7 @@ LIB_PATH = _PKG / "libplogp.so"
 OK, EINVAL, ERANGE, ENOSPC, ENOMEM, EDEVICE, ETOOBIG = range(7)
 STATIC_SCRATCH_BYTES = 64 << 20
 MASK_BCAST, MASK_SCATTER, MASK_ALL = 0x03FF, 0x1C00, 0x1FFF
+MASK_GATHER, MASK_BARRIER, MASK_EVERY = 0xE000, 0x30000, 0x3FFFF
 NO_STRATEGY = 0xFFFFFFFF
 NO_CAP = (1 << 64) - 1
 MAX_SAMPLES = 4096
@@ -234,8 +235,8 @@ def plogp_tune_grid_static(table: Table, grid: Grid, d_out: int, d_out_bytes: in
 def plogp_tune_grid_profile(table: Table, grid: Grid, d_out: int, d_out_bytes: int, stream: int = 0,
                             reps: int = 1):
     """Runs the sweep with each kernel launched reps times between two events; returns the
-    mean time per launch of the four stages in ms."""
-    ms = (ctypes.c_float * 4)()
+    mean time per launch of the five stages in ms."""
+    ms = (ctypes.c_float * 5)()
     _check(_lib.plogp_tune_grid_profile(table._h, grid._h, d_out, d_out_bytes, stream, reps, ms),
            "plogp_tune_grid_profile")
     return [float(v) for v in ms]

@@ -47,8 +47,8 @@ def test_cell_is_sixteen_bytes(plogp):
 
 
 def test_strerror_covers_every_status(plogp):
-    msgs = {plogp._lib.plogp_strerror(i).decode() for i in range(6)}
-    assert len(msgs) == 6 and "unknown status" not in msgs
+    msgs = {plogp._lib.plogp_strerror(i).decode() for i in range(7)}
+    assert len(msgs) == 7 and "unknown status" not in msgs
     assert plogp._lib.plogp_strerror(99).decode() == "unknown status"
 
 
@@ -103,7 +103,7 @@ def test_load_table_rejects_too_many_samples_and_null(plogp):
     dict(m=[16], P=[2], s=[4]),                        # s not a multiple of the datatype
     dict(m=[8], P=[2], s=[1 << 32]),                   # s does not fit the record
     dict(m=[8], P=[2], s=[8], strategy_mask=0),        # nothing to evaluate
-    dict(m=[8], P=[2], s=[8], strategy_mask=1 << 13),  # unknown strategy
+    dict(m=[8], P=[2], s=[8], strategy_mask=1 << 18),  # unknown strategy
     dict(m=[], P=[2], s=[8]), dict(m=[8], P=[], s=[8]),
 ])
 def test_grid_create_rejects(plogp, kw):
@@ -121,6 +121,14 @@ def test_grid_create_range_errors(plogp):
     # binomial scatter alone: 2^(ceil(log2 Pmax) - 1) * m
     assert _status(plogp, plogp.plogp_grid_create, m=[1 << 40], P=[1 << 14], s=[8],
                    strategy_mask=1 << 12) == plogp.ERANGE
+    # the Gather twins of those rows add up the same sizes
+    for sid in (14, 15):
+        assert _status(plogp, plogp.plogp_grid_create, m=[1 << 40], P=[2, 1 << 14], s=[8],
+                       strategy_mask=1 << sid) == plogp.ERANGE
+    # a Barrier carries no payload: any size below 2^53 goes
+    st = _status(plogp, plogp.plogp_grid_create, m=[1 << 40], P=[2, 1 << 14], s=[8],
+                 strategy_mask=plogp.MASK_BARRIER)
+    assert st in (plogp.OK, plogp.EDEVICE)
 
 
 def test_null_handles_are_refused(plogp):
