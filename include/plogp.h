@@ -172,7 +172,8 @@ int plogp_grid_free(plogp_grid *g);
  * 0..9 is in the mask, then Scatter (10..12), Gather (13..15), Barrier (16, 17),
  * each if any of its ids is: 1 to 4. */
 size_t plogp_grid_ops(const plogp_grid *g);
-/* Cells / bytes of the decision table for n_tables tables over this grid. */
+/* Cells / bytes of the decision table for n_tables tables over this grid (0 for a null grid,
+ * and if the byte count would not fit a size_t). */
 size_t plogp_decision_table_cells(size_t n_tables, const plogp_grid *g);
 size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g);
 

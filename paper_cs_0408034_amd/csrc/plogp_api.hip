@@ -180,7 +180,9 @@ int check_tune_args(const plogp_table *t, const plogp_grid *g, const plogp_cell 
 {
     if (!t || !g || !d_out) return PLOGP_EINVAL;
     if (((uintptr_t)d_out & 15u) != 0) return PLOGP_EINVAL;
-    if (d_out_bytes < plogp_decision_table_bytes(t->n_tables, g)) return PLOGP_ENOSPC;
+    const size_t need = plogp_decision_table_bytes(t->n_tables, g);
+    if (need == 0) return PLOGP_ERANGE;                 // the table's size does not fit a size_t
+    if (d_out_bytes < need) return PLOGP_ENOSPC;
     return PLOGP_OK;
 }
 
@@ -372,9 +374,6 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
     if ((mask & ((1u << 12) | (1u << 15))) && m_max > ((kTwo53u - 1) >> (cl_max > 0 ? cl_max - 1 : 0)))
         return PLOGP_ERANGE;
 
-    int rc = ensure_init();
-    if (rc != PLOGP_OK) return rc;
-
     plogp_grid *g = new (std::nothrow) plogp_grid;
     if (!g) return PLOGP_ENOMEM;
     g->n_m = d->n_m; g->n_P = d->n_P; g->n_s = d->n_s;
@@ -404,6 +403,12 @@ int plogp_grid_create(const plogp_grid_desc *d, plogp_grid **out)
         m_map[i] = (int)(std::lower_bound(mu.begin(), mu.end(), d->m[i]) - mu.begin());
     g->n_mu = mu.size();
 
+    // everything above is host work; the device is first touched here
+    int rc = ensure_init();
+    if (rc != PLOGP_OK) {
+        delete g;
+        return rc;
+    }
     hipError_t e;
     if ((e = hipMalloc((void **)&g->d_m, d->n_m * sizeof(uint64_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->d_mu, mu.size() * sizeof(uint64_t))) != hipSuccess ||
@@ -440,7 +445,11 @@ size_t plogp_grid_ops(const plogp_grid *g) { return g ? (size_t)g->n_ops : 0; }
 
 size_t plogp_decision_table_cells(size_t n_tables, const plogp_grid *g)
 {
-    return g ? n_tables * (size_t)g->n_ops * g->n_m * g->n_P : 0;
+    if (!g) return 0;
+    // n_ops <= 4 and n_m, n_P <= 2^24 each: their product fits; the table count may not
+    const size_t per_table = (size_t)g->n_ops * g->n_m * g->n_P;
+    if (n_tables != 0 && per_table > (SIZE_MAX / sizeof(plogp_cell)) / n_tables) return 0;
+    return n_tables * per_table;
 }
 
 size_t plogp_decision_table_bytes(size_t n_tables, const plogp_grid *g)

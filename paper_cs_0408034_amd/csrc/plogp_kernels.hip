@@ -3597,11 +3597,20 @@ namespace {
 // 256 bytes stay free (arrays of size 0 point there).
 struct LayoutBuilder {
     size_t at = 256;
-    size_t take(size_t bytes)
+    bool too_big = false;          // a size did not fit: the plan is refused
+    // an array of a * b * c * d elements of `elem` bytes (a factor of 0 makes it empty)
+    size_t take(size_t elem, size_t a, size_t b = 1, size_t c = 1, size_t d = 1)
     {
-        if (bytes == 0) return 0;
+        constexpr size_t kMaxBytes = (size_t)1 << 46;       // no single array beyond 64 TiB: sizes stay far from wrapping
+        size_t count = a;
+        for (size_t f : {b, c, d}) {
+            if (f != 0 && count > kMaxBytes / f) too_big = true;
+            count *= f;
+        }
+        if (count > kMaxBytes / elem) too_big = true;
+        if (too_big || count == 0) return 0;
         const size_t here = at;
-        at += (bytes + 255) & ~(size_t)255;
+        at += (count * elem + 255) & ~(size_t)255;
         return here;
     }
 };
@@ -3666,11 +3675,11 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
         p.batch_lds = batch_t_lds(T.n, G.n_s);
         if ((long)p.n_tg * p.batch_mchunks > kMaxLaunch) return false;
         const BatchRec R(T.n, G.n_s, G.cl_max);
-        p.lay.rec = lb.take(n_m * (size_t)R.slots * D);
-        p.lay.tab = lb.take((2 + ((size_t)T.n + 1) + 2 * (n_s ? n_s : 1) + 3 * n_P) * D);
-        p.lay.batch_ys = lb.take(((size_t)T.n + 2) * nt * 2 * D);
+        p.lay.rec = lb.take(D, n_m, (size_t)R.slots);
+        p.lay.tab = lb.take(D, 2 + ((size_t)T.n + 1) + 2 * (n_s ? n_s : 1) + 3 * n_P);
+        p.lay.batch_ys = lb.take(D, (size_t)T.n + 2, nt, 2);
         p.lay.total = lb.at;
-        return true;
+        return !lb.too_big;
     }
     if (fast_ok && !use_fused_path(T, G) && use_row_path(T, G)) {
         p.path = TUNE_ROW;
@@ -3768,8 +3777,8 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
         if (wg > wg_need) wg = wg_need;
         if (wg < 1) wg = 1;
         // a small job (the walk would be bound by one lane's latency): every term by a search
-        const long n_terms = (long)T.n_tables * G.n_mu * G.n_blk * SUM_BLOCK;
-        const bool small = p.together && n_single == G.n_blk && n_terms <= (3L << 20);
+        const double n_terms = (double)T.n_tables * G.n_mu * G.n_blk * SUM_BLOCK;
+        const bool small = p.together && n_single == G.n_blk && n_terms <= (double)(3L << 20);
         p.both_lds = p.chain_lds > p.terms_lds ? p.chain_lds : p.terms_lds;
         if (small) {
             const size_t small_lds = ((size_t)3 * T.n + 10 + 64 * SMALL_LD) * D;
@@ -3825,23 +3834,23 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
     if (!terms_only && G.extra != 0 && (long)T.n_tables * G.n_m * ((G.n_P + 255) / 256) > kMaxLaunch) return false;
     // scratch: what the kernels of this path index (m-fastest arrays per distinct size where noted)
     const bool binom = (G.need & (1u << 12)) != 0;
-    p.lay.g1 = lb.take(nt * D);
-    p.lay.gs = lb.take(nt * n_s * D);
-    p.lay.gm = lb.take(nt * n_m * D);
-    p.lay.sum2 = lb.take(binom ? nt * n_m * (size_t)(G.cl_max + 1) * D : 0);
-    p.lay.blk = lb.take(chain ? nt * (size_t)G.n_blk * n_mu * D : 0);
-    p.lay.part = lb.take(chain ? nt * n_mu * n_P * D : 0);
-    p.lay.pre = lb.take(chain && G.blk_is_prefix ? nt * n_mu * n_P * D : 0);
-    p.lay.rcp = lb.take(n_s * D);
-    p.lay.segC = lb.take(nt * n_s * D);
-    p.lay.segA = lb.take(pairs ? nt * n_m * n_s * D : 0);
-    p.lay.segB = lb.take(pairs ? nt * n_m * n_s * D : 0);
-    p.lay.amin = lb.take(pairs ? nt * n_m * D : 0);
-    p.lay.nv = lb.take(n_m * sizeof(int));
+    p.lay.g1 = lb.take(D, nt);
+    p.lay.gs = lb.take(D, nt, n_s);
+    p.lay.gm = lb.take(D, nt, n_m);
+    p.lay.sum2 = lb.take(D, binom ? nt : 0, n_m, (size_t)(G.cl_max + 1));
+    p.lay.blk = lb.take(D, chain ? nt : 0, (size_t)G.n_blk, n_mu);
+    p.lay.part = lb.take(D, chain ? nt : 0, n_mu, n_P);
+    p.lay.pre = lb.take(D, chain && G.blk_is_prefix ? nt : 0, n_mu, n_P);
+    p.lay.rcp = lb.take(D, n_s);
+    p.lay.segC = lb.take(D, nt, n_s);
+    p.lay.segA = lb.take(D, pairs ? nt : 0, n_m, n_s);
+    p.lay.segB = lb.take(D, pairs ? nt : 0, n_m, n_s);
+    p.lay.amin = lb.take(D, pairs ? nt : 0, n_m);
+    p.lay.nv = lb.take(sizeof(int), n_m);
     if (terms_only)
-        p.lay.score_rows = lb.take((size_t)13 * n_m * 2 * D);
+        p.lay.score_rows = lb.take(D, 13, n_m, 2);
     p.lay.total = lb.at;
-    return true;
+    return !lb.too_big;
 }
 
 hipError_t launch_tune_stage(const TunePlan &p, int stage, const DeviceTables &T, const DeviceGrid &G,
