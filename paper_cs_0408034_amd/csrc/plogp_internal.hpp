@@ -61,11 +61,16 @@ struct DeviceGrid {
 // k_batch_setup).  Intervals: 0 = below the first sample, i + 1 = from sample i on.
 struct BatchPrep {
     double *rec;      // [n_m][BatchRec::slots]  everything about one message size (see BatchRec)
-    double *tab;      // [2 + (n+1) + 2 n_s + 3 n_P]  interval of size 1 and 1 minus its start; widths
-                      //                         of the intervals (the last: +inf); per candidate: s minus
-                      //                         the start of its interval, then that interval; per
-                      //                         process count: P - 1, floor(log2 P), ceil(log2 P)
+    double *tab;      // [2 + (n+1) + 2 n_s + 4 padded n_P]  interval of size 1 and 1 minus its start;
+                      //                         widths of the intervals (the last: +inf); per candidate: s
+                      //                         minus the start of its interval, then that interval; per
+                      //                         process count: P - 1, floor(log2 P), ceil(log2 P) as
+                      //                         doubles, then P - 1 and ceil(log2 P) as two uint32
 };
+
+// Entries of the per-process-count list of BatchPrep::tab: the grid's n_P, filled up to a
+// multiple of eight, plus one.
+__host__ __device__ inline long batch_padded_P(int n_P) { return ((long)n_P + 7) / 8 * 8 + 1; }
 
 // Layout of one record of BatchPrep::rec, in 8-byte slots.
 struct BatchRec {

@@ -2707,13 +2707,17 @@ __device__ __forceinline__ void batch_prep_body(const DeviceTables &T, const Dev
     }
     for (long e = tid; e <= n; e += stride)
         B.tab[2 + e] = e == 0 ? x[0] : (e < n ? x[e] - x[e - 1] : INFINITY);
-    // per process count: P - 1, floor(log2 P), ceil(log2 P) as doubles
-    for (long e = tid; e < G.n_P; e += stride) {
-        double *pt = B.tab + 2 + (n + 1) + 2 * (size_t)G.n_s + 3 * e;
-        const uint32_t P = G.P[e];
+    // per process count 32 bytes: P - 1, floor(log2 P), ceil(log2 P) as doubles, then P - 1 and
+    // ceil(log2 P) as integers; the list is filled up to a multiple of eight, plus one, with
+    // copies of its last entry (the kernel takes eight at a time and fetches one ahead)
+    for (long e = tid; e < batch_padded_P(G.n_P); e += stride) {
+        double *pt = B.tab + 2 + (n + 1) + 2 * (size_t)G.n_s + 4 * e;
+        const uint32_t P = G.P[e < G.n_P ? e : G.n_P - 1];
         pt[0] = (double)(P - 1u);
         pt[1] = (double)floor_log2(P);
         pt[2] = (double)ceil_log2(P);
+        reinterpret_cast<uint32_t *>(pt + 3)[0] = P - 1u;
+        reinterpret_cast<uint32_t *>(pt + 3)[1] = (uint32_t)ceil_log2(P);
     }
     if (tid == 0) {
         int i1;
@@ -2806,8 +2810,7 @@ template <int PC, int PS, bool ALL>
 __global__ void __launch_bounds__(64 * BATCH_T_WAVES)
 k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
           const double *__restrict__ recs, const double *__restrict__ tab,
-          const uint32_t *__restrict__ p_P, const u64 *__restrict__ p_s,
-          plogp_cell_dev *__restrict__ out)
+          const u64 *__restrict__ p_s, plogp_cell_dev *__restrict__ out)
 {
     extern __shared__ __align__(16) double batch_lds[];
     const int n = D.n, n_s = D.n_s, n_P = D.n_P;
@@ -2837,7 +2840,9 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     __syncthreads();
     const f64x2 *ys = YS + lane;                               // this lane's table: ys[64 i]
     const double *tab_ds = tab + 2 + (n + 1), *tab_is = tab_ds + n_s, *Wd = tab + 2;
-    const double *tab_P = tab_is + n_s;                        // {P - 1, floor log2 P, ceil log2 P}
+    // per process count {P - 1, floor log2 P, ceil log2 P, {P - 1, ceil log2 P} as integers}
+    typedef double f64x4 __attribute__((ext_vector_type(4)));
+    const f64x4 *tab_P = reinterpret_cast<const f64x4 *>(tab_is + n_s);
     for (int si = wave; si < n_s; si += BATCH_T_WAVES) {
         const f64x2 v = ys[64 * (int)uniform_load(tab_is + si)];
         GS[si * 64 + lane] = __builtin_fma(v.y, uniform_load(tab_ds + si), v.x);
@@ -2887,10 +2892,19 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         if (p0 + out_p < n_P) {
             char *ubase = o_grp + cell0 * sizeof(plogp_cell_dev);
             if (whole_group) {
+                // (four rows are read before their four stores go out: a store keeps the reads
+                // that follow it behind itself)
 #pragma unroll
-                for (int it = 0; it < 64 / PS; ++it) {
-                    store_run(ubase, scatter_cell((64 / PS) * it));
-                    ubase += run_step;
+                for (int it = 0; it < 64 / PS; it += 4) {
+                    u32x4 c[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        c[u] = scatter_cell((64 / PS) * (it + u));
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        store_run(ubase, c[u]);
+                        ubase += run_step;
+                    }
                 }
             } else {
                 // (the limit is made opaque here: its sixteen compares would otherwise be kept
@@ -2914,9 +2928,13 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
             char *ubase = o_grp + ((size_t)32 * half * table_cells + cell0) * sizeof(plogp_cell_dev);
             const u32x4 *rows = reinterpret_cast<const u32x4 *>(stage) + out_row * (PS + 1) + out_p;
             if (whole_group) {
+                u32x4 c[32 / PS];
+#pragma unroll
+                for (int it = 0; it < 32 / PS; ++it)
+                    c[it] = rows[(64 / PS) * it * (PS + 1)];
 #pragma unroll
                 for (int it = 0; it < 32 / PS; ++it) {
-                    store_run(ubase, rows[(64 / PS) * it * (PS + 1)]);
+                    store_run(ubase, c[it]);
                     ubase += run_step;
                 }
             } else {
@@ -2965,16 +2983,35 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         double d = uniform_load(rec + R.DM);                    // size - start of its interval
         const double gm = __builtin_fma(cur.y, d, cur.x);
         unsigned je = uniform_load(jend + ci);                  // last j inside interval ci
-        f64x2 nxt = ys[64 * (ci + 1)];                          // fetched one crossing ahead
+        // fetched one crossing ahead: the next interval's entries, its last j, this one's width
+        f64x2 nxt = ys[64 * (ci + 1)];
+        unsigned je_n = uniform_load(jend + (ci < n ? ci + 1 : n));
+        double w_n = uniform_load(Wd + ci);
         double run = 0.0, done = 0.0;
         unsigned j_done = 0;
         double s12 = 0.0;
         int cl_done = 0;
-        // minimum over s of A = g(s) k (rows 2 and 9 of Table 1 are monotone in A)
-        double amin = INFINITY;
-        if (mask & 0x204u)
-            for (int si = 0; si < nvm; ++si)
-                amin = min_f64(amin, gsl[64 * si] * uniform_load(Krow + si));
+        int i2_n = uniform_load(reinterpret_cast<const int *>(rec + R.I2));
+        double d2_n = uniform_load(rec + R.D2);
+        f64x4 P_n = uniform_load(tab_P);
+        // minimum over s of A = g(s) k (rows 2 and 9 of Table 1 are monotone in A), the first
+        // candidate that attains it, and the least A before that candidate (+inf if none)
+        double amin = INFINITY, abefore = INFINITY;
+        int imin = 0;
+        if (mask & 0x204u) {
+            // (the next candidate's g(s) and k are fetched while this one is worked on)
+            double gs_n = gsl[0], k_n = uniform_load(Krow);
+            for (int si = 0; si < nvm; ++si) {
+                const double A = gs_n * k_n;
+                const int nx = si + 1 < nvm ? si + 1 : si;
+                gs_n = gsl[64 * nx];
+                k_n = uniform_load(Krow + nx);
+                const bool lower = A < amin;
+                abefore = lower ? amin : abefore;
+                imin = lower ? si : imin;
+                amin = min_f64(amin, A);
+            }
+        }
 
         // PS process counts per pass over the candidates (the per-candidate terms are formed
         // once for all of them), then PC cells at a time are decided and written
@@ -2985,9 +3022,10 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                 // along j while P ascends, the binomial sum grows with ceil(log2 P)
 #pragma nounroll
                 for (int p = 0; p < PS; ++p) {
-                    const uint32_t P = uniform_load(p_P + (q0 + p < n_P ? q0 + p : n_P - 1));
+                    const f64x4 Pv = P_n;                       // (fetched one step ahead, like i2_n and d2_n)
+                    P_n = uniform_load(tab_P + q0 + p + 1);
                     if (want_chain) {
-                        const unsigned target = P - 1u;
+                        const unsigned target = (unsigned)__double2loint(Pv.w);
                         while (j_done < target) {
                             // up to the next process count, block end or interval end
                             const unsigned block_end = (j_done / SUM_BLOCK + 1u) * SUM_BLOCK;
@@ -3011,24 +3049,28 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                                 run = 0.0;
                             }
                             while (je <= j_done) {              // the next size lies further on
-                                d -= uniform_load(Wd + ci);
+                                d -= w_n;
                                 ++ci;
                                 cur = nxt;
-                                je = uniform_load(jend + ci);
+                                je = je_n;
                                 nxt = ys[64 * (ci + 1)];
+                                je_n = uniform_load(jend + (ci < n ? ci + 1 : n));
+                                w_n = uniform_load(Wd + ci);
                             }
                         }
                     }
                     if (want_binom) {
-                        const int cli = ceil_log2(P);
+                        const int cli = __double2hiint(Pv.w);
                         while (cl_done < cli) {
-                            const f64x2 v = ys[64 * uniform_load(reinterpret_cast<const int *>(rec + R.I2) + cl_done)];
-                            s12 = s12 + __builtin_fma(v.y, uniform_load(rec + R.D2 + cl_done), v.x);
+                            const f64x2 v = ys[64 * i2_n];
+                            s12 = s12 + __builtin_fma(v.y, d2_n, v.x);
                             ++cl_done;
+                            const int nx = cl_done < D.cl_max ? cl_done : cl_done - 1;
+                            i2_n = uniform_load(reinterpret_cast<const int *>(rec + R.I2) + nx);
+                            d2_n = uniform_load(rec + R.D2 + nx);
                         }
                     }
-                    const Best r = decide_scatter(mask, (double)(P - 1u), (double)ceil_log2(P), gm, L,
-                                                  done + run, s12);
+                    const Best r = decide_scatter(mask, Pv.x, Pv.z, gm, L, done + run, s12);
                     *reinterpret_cast<double *>(stage + lane * 72 + 8 * p) = r.t;
                     *reinterpret_cast<signed char *>(stage + lane * 72 + 64 + p) = (signed char)r.id;
                 }
@@ -3047,9 +3089,13 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                 double q[PS];                                   // wave-uniform
 #pragma unroll
                 for (int p = 0; p < PS; ++p)
-                    q[p] = uniform_load(tab_P + 3 * (q0 + p < n_P ? q0 + p : n_P - 1));
+                    q[p] = uniform_load(reinterpret_cast<const double *>(tab_P + q0 + p));
+                double gs_n = gsl[0], k_n = uniform_load(Krow);
                 for (int si = 0; si < nvm; ++si) {
-                    const double gs = gsl[64 * si], k = uniform_load(Krow + si);
+                    const double gs = gs_n, k = k_n;
+                    const int nx = si + 1 < nvm ? si + 1 : si;
+                    gs_n = gsl[64 * nx];
+                    k_n = uniform_load(Krow + nx);
                     const double Bv = gs * (k - 1.0), Cv = gs + L;
 #pragma unroll
                     for (int p = 0; p < PS; ++p) {
@@ -3066,7 +3112,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                 double q[PC], fl[PC], clL[PC], cl[PC];          // q, fl, cl: wave-uniform
 #pragma unroll
                 for (int p = 0; p < PC; ++p) {
-                    const double *pt = tab_P + 3 * (p0 + p < n_P ? p0 + p : n_P - 1);
+                    const double *pt = reinterpret_cast<const double *>(tab_P + p0 + p);
                     q[p] = uniform_load(pt);
                     fl[p] = uniform_load(pt + 1);
                     cl[p] = uniform_load(pt + 2);
@@ -3085,21 +3131,33 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                     any = any || bc[p].id == 2u || bc[p].id == 9u;
                 }
                 if (__ballot(any) != 0) {
-                    // a winning row 2 or 9: the first candidate whose value equals the minimum
+                    // A winning row 2 or 9: the first candidate whose value equals the minimum.
+                    // The rows grow with A, so that is the candidate of the least A, unless a
+                    // larger A before it rounds to the same time: only the least of those can.
                     bool open[PC];
+                    bool tie = false;
+                    const uint32_t smin = nvm > 0 ? sS[imin] : 0u;
 #pragma unroll
-                    for (int p = 0; p < PC; ++p)
+                    for (int p = 0; p < PC; ++p) {
                         open[p] = bc[p].id == 2u || bc[p].id == 9u;
-                    for (int si = 0; si < nvm; ++si) {
-                        const double A = gsl[64 * si] * uniform_load(Krow + si);
-                        const uint32_t sv = sS[si];
+                        const double Tb = bc[p].id == 2u ? __builtin_fma(q[p], abefore, L)
+                                                         : __builtin_fma(fl[p], abefore, clL[p]);
+                        tie = tie || (open[p] && Tb == bc[p].t);
+                        bc[p].s = open[p] ? smin : bc[p].s;
+                    }
+                    if (__ballot(tie) != 0) {
+                        // (rare) the search itself, for every lane
+                        for (int si = 0; si < nvm; ++si) {
+                            const double A = gsl[64 * si] * uniform_load(Krow + si);
+                            const uint32_t sv = sS[si];
 #pragma unroll
-                        for (int p = 0; p < PC; ++p) {
-                            const double Tv = bc[p].id == 2u ? __builtin_fma(q[p], A, L)
-                                                             : __builtin_fma(fl[p], A, clL[p]);
-                            if (open[p] && Tv == bc[p].t) {
-                                bc[p].s = sv;
-                                open[p] = false;
+                            for (int p = 0; p < PC; ++p) {
+                                const double Tv = bc[p].id == 2u ? __builtin_fma(q[p], A, L)
+                                                                 : __builtin_fma(fl[p], A, clL[p]);
+                                if (open[p] && Tv == bc[p].t) {
+                                    bc[p].s = sv;
+                                    open[p] = false;
+                                }
                             }
                         }
                     }
@@ -3676,7 +3734,7 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
         if ((long)p.n_tg * p.batch_mchunks > kMaxLaunch) return false;
         const BatchRec R(T.n, G.n_s, G.cl_max);
         p.lay.rec = lb.take(D, n_m, (size_t)R.slots);
-        p.lay.tab = lb.take(D, 2 + ((size_t)T.n + 1) + 2 * (n_s ? n_s : 1) + 3 * n_P);
+        p.lay.tab = lb.take(D, 2 + ((size_t)T.n + 1) + 2 * (n_s ? n_s : 1) + 4 * (size_t)batch_padded_P(G.n_P));
         p.lay.batch_ys = lb.take(D, (size_t)T.n + 2, nt, 2);
         p.lay.total = lb.at;
         return !lb.too_big;
@@ -3869,7 +3927,7 @@ hipError_t launch_tune_stage(const TunePlan &p, int stage, const DeviceTables &T
                                                 : k_batch_t<BATCH_T_PC, BATCH_T_PS, false>;
             hipLaunchKernelGGL(kern, dim3((unsigned)p.n_tg * p.batch_mchunks), dim3(64 * BATCH_T_WAVES),
                                p.batch_lds, st, D, reinterpret_cast<const f64x2 *>(S.batch_ys), T.L,
-                               S.batch.rec, S.batch.tab, G.P, reinterpret_cast<const u64 *>(G.s), d_out);
+                               S.batch.rec, S.batch.tab, reinterpret_cast<const u64 *>(G.s), d_out);
         }
         return hipGetLastError();
     }
