@@ -1787,6 +1787,8 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     __shared__ double2 AB[2][SWEEP_S_CHUNK];
     __shared__ double Cs[2][SWEEP_S_CHUNK];
     __shared__ double passMinA[SWEEP_S_PASSES];        // min of A over each of the first passes
+    __shared__ double fillMinA[2][64 * SWEEP_S_MAX_WAVES];   // per filling thread: min of A over its candidates
+    __shared__ double allMinA;                         // min of A over every candidate
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -1823,7 +1825,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
         best5[p] = INFINITY;
         blk5[p] = 0;
     }
-    double amin = INFINITY;
+    double amin = INFINITY;                            // (wave 0 only, the same in its lanes)
     // What lane p < GP needs at the end to decide its cells is asked for now, so that the end
     // of the wave does not wait for device memory: its process count, g(m), g(1), the two
     // Scatter sums.
@@ -1858,6 +1860,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     };
     auto fill_store = [&](int c) {
         const int buf = c & 1;
+        double mine_A = INFINITY;
 #pragma unroll
         for (int k = 0; k < FILL_SLOTS; ++k) {
             const int e = (int)threadIdx.x + k * (int)blockDim.x;
@@ -1867,8 +1870,12 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                     segment_terms(md, f_s[k], f_rcp[k], f_gs[k], L, A, B, C);
                 AB[buf][e] = make_double2(A, B);
                 Cs[buf][e] = C;
+                mine_A = min_f64(mine_A, A);
             }
         }
+        // A does not depend on the process count: its minimum over a pass is formed from these
+        // per-thread minima by one wave, not by every wave over every candidate
+        fillMinA[buf][threadIdx.x] = mine_A;
     };
     if (n_chunks > 0) {
         fill_load(0);
@@ -1886,26 +1893,29 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
 #pragma unroll
             for (int p = 0; p < GP; ++p)
                 cur5[p] = INFINITY;
-            double curA = INFINITY;
 #pragma unroll 2
             for (int i = 0; i < steps; ++i) {
-                const double2 ab = AB[buf][64 * i + lane];
+                const double B = AB[buf][64 * i + lane].y;
                 const double C = Cs[buf][64 * i + lane];
-                curA = min_f64(curA, ab.x);
 #pragma unroll
                 for (int p = 0; p < GP; ++p)
-                    cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], C, ab.y));
+                    cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], C, B));
             }
 #pragma unroll
             for (int p = 0; p < GP; ++p) {
                 blk5[p] = cur5[p] < best5[p] ? c : blk5[p];
                 best5[p] = min_f64(best5[p], cur5[p]);
             }
-            amin = min_f64(amin, curA);
-            if (wave == 0 && c < SWEEP_S_PASSES) {     // wave 0 always has work
+            if (wave == 0) {                           // wave 0 always has work
+                double curA = INFINITY;
+                for (int k = lane; k < (int)blockDim.x; k += 64)
+                    curA = min_f64(curA, fillMinA[buf][k]);
                 const double pm = wave_min(curA);
-                if (lane == 0)
+                amin = min_f64(amin, pm);
+                if (lane == 0 && c < SWEEP_S_PASSES)
                     passMinA[c] = pm;
+                if (lane == 0 && c + 1 == n_chunks)
+                    allMinA = amin;
             }
         }
         if (c + 1 < n_chunks)
@@ -1920,7 +1930,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
     // passed the last barrier), lane p reads the 64 minima of process count p0 + p (the
     // columns are 65 apart where they fit, so that the lanes hit different banks) and keeps
     // their minimum.
-    const double Aw = (mask & 0x204u) ? wave_min(amin) : INFINITY;
+    const double Aw = (mask & 0x204u) && n_chunks > 0 ? allMinA : INFINITY;
     const bool haveA = Aw < INFINITY;
     double V5 = INFINITY;
     if (mask & (1u << 5)) {
