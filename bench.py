@@ -51,10 +51,10 @@ UNSEG_FLOPS = {0: 3, 1: 3, 3: 3, 4: 3, 6: 4, 7: 4, 8: 4, 10: 3, 11: 4, 12: 3}
 # (SQ_INSTS_VALU, in wave instructions).  A kernel change makes them stale until the profiles
 # are taken again; the line names its source.
 OFFLINE_COUNTERS = {
-    2: {"kernel": "k_row", "hbm_bytes": 0.336e6 + 33.560e6, "valu_insts": None},
-    3: {"kernel": "k_sweep_s", "hbm_bytes": 4.016e6 + 2.294e6, "valu_insts": 36.1e6},
-    4: {"kernel": "k_batch_t", "hbm_bytes": 88.979e6 + 1966.079e6, "valu_insts": 175.8e6},
-    5: {"kernel": "k_chain_blocks", "hbm_bytes": 1.839e6 + 73.536e6, "valu_insts": None},
+    2: {"kernel": "k_row", "hbm_bytes": 0.336e6 + 33.560e6, "valu_insts": 4.872e6},
+    3: {"kernel": "k_sweep_s", "hbm_bytes": 4.030e6 + 2.294e6, "valu_insts": 35.22e6},
+    4: {"kernel": "k_batch_t", "hbm_bytes": 88.944e6 + 1966.049e6, "valu_insts": 175.7e6},
+    5: {"kernel": "k_chain_blocks", "hbm_bytes": 1.840e6 + 73.325e6, "valu_insts": 25.55e6},
 }
 
 
@@ -400,6 +400,7 @@ def short_next(res):
 
 
 def main():
+    global MIN_BATCHES, MIN_PER_BATCH
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100,
@@ -412,10 +413,17 @@ def main():
     ap.add_argument("--detail", type=str, default=None, help="also write every figure to this JSON file")
     ap.add_argument("--mask", type=lambda v: int(v, 0), default=None,
                     help="strategy mask override (for profiling parts of the path)")
+    ap.add_argument("--counters", action="store_true",
+                    help="for a rocprofv3 --pmc run, where every dispatch is serialised: one batch of "
+                         "three launches of everything, so the counters see each kernel a few times; "
+                         "the timings of such a run mean nothing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one elementwise kernel that copies 256 MiB (known traffic, "
                          "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
+    if args.counters:
+        MIN_BATCHES, MIN_PER_BATCH = 1, 3
+        args.steps, args.warmup = 3, 1
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no inter-GPU path exists); use --gpus 1")
 
