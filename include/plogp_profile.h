@@ -63,7 +63,8 @@ int plogp_robustness_profile(const plogp_grid *g, size_t n_tables, const plogp_c
  *   *store_gbs_out     write bandwidth of a kernel that does nothing but fill
  *                      d_buf (DEVICE, at least 16 bytes, 16-byte aligned; its
  *                      contents are overwritten) with 16-byte stores, a wave
- *                      writing 1 KB runs, in GB/s.
+ *                      writing 1 KB runs, in GB/s: the faster of a fill with
+ *                      plain stores and one with non-temporal stores.
  * Each is the best of three launches after a warm-up launch.  Synchronous.
  * Errors: EINVAL (null, misaligned, buf_bytes < 16), EDEVICE.
  */

@@ -1114,6 +1114,16 @@ __device__ __forceinline__ void consider(Best &b, double T, uint32_t id, uint32_
     }
 }
 
+// A 16-byte record of an output that no kernel of the call reads again: stored with the
+// non-temporal hint, so that the stream of cells does not push the tables and terms out of the
+// caches (measured on the 1.97 GB table of 10 000 clusters: 5 % off the whole kernel).
+__device__ __forceinline__ void stream_out(void *p, uint4 v)
+{
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    u32x4_t w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t *>(p));
+}
+
 __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
 {
     union {
@@ -1123,7 +1133,7 @@ __device__ __forceinline__ void store_cell(plogp_cell_dev *p, const Best &b)
     u.c.time = b.t;
     u.c.s = b.s;
     u.c.strategy = b.id;
-    *reinterpret_cast<uint4 *>(p) = u.v;
+    stream_out(p, u.v);
 }
 
 // Broadcast: the ten rows of Table 1 in id order, strict '<' (ties: lowest id).
@@ -2346,11 +2356,11 @@ __global__ void __launch_bounds__(256) k_fused(DeviceTables T, DeviceGrid G, plo
                 if (rmi < G.n_m && pi < G.n_P) {
                     plogp_cell_dev *o = o_tab + (size_t)rmi * G.n_P + pi;
                     if (has_b) {
-                        *reinterpret_cast<uint4 *>(o) = stage[wave][0][row * (FUSED_PC + 1) + pl];
+                        stream_out(o, stage[wave][0][row * (FUSED_PC + 1) + pl]);
                         o += plane;
                     }
                     if (has_s)
-                        *reinterpret_cast<uint4 *>(o) = stage[wave][1][row * (FUSED_PC + 1) + pl];
+                        stream_out(o, stage[wave][1][row * (FUSED_PC + 1) + pl]);
                 }
             }
         }
@@ -2880,7 +2890,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     // wave-uniform base in scalar registers + 32-bit lane offset
     auto store_run = [&](char *ubase, u32x4 cell) {
-        asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(lane_off), "v"(cell), "s"(ubase) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, %2 nt" : : "v"(lane_off), "v"(cell), "s"(ubase) : "memory");
     };
     const size_t run_step = (size_t)(64 / PS) * table_cells * sizeof(plogp_cell_dev);   // 8 tables on
     const bool whole_group = tg * 64 + 64 <= D.n_tables;       // wave-uniform: no row of tables is missing
@@ -3304,7 +3314,7 @@ __global__ void __launch_bounds__(1024) k_score(DeviceTables T, DeviceGrid G, Sc
             case 11: v = __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P)); break;
             default: v = __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]); break;
             }
-            pred[at] = v;
+            __builtin_nontemporal_store(v, pred + at);
             const double t_meas = tm[id];
             const int op = id < 10 ? 0 : 1;
             if (v < best_p[op]) {
@@ -3322,11 +3332,14 @@ __global__ void __launch_bounds__(1024) k_score(DeviceTables T, DeviceGrid G, Sc
         for (int op = 0; op < 2; ++op) {
             if (!(mask & (op == 0 ? 0x3FFu : 0x1C00u)))
                 continue;
-            plogp_verdict_dev vd;
-            vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
-            vd.pred_best = id_p[op];
-            vd.meas_best = id_m[op];
-            *o = vd;
+            union {
+                plogp_verdict_dev vd;
+                uint4 v;
+            } u;
+            u.vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
+            u.vd.pred_best = id_p[op];
+            u.vd.meas_best = id_m[op];
+            stream_out(o, u.v);
             o += plane;
         }
     }

@@ -68,13 +68,21 @@ __global__ void __launch_bounds__(256) k_fma_peak(double *out, int iters, double
         out[0] = s;
 }
 
+// STREAM: the stores carry the non-temporal hint, as the decision-table stores of the sweeps do.
+template <bool STREAM>
 __global__ void __launch_bounds__(256) k_store_fill(uint4 *buf, size_t n16, size_t per_wg)
 {
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
     const size_t first = (size_t)blockIdx.x * per_wg;
     const size_t last = first + per_wg < n16 ? first + per_wg : n16;
-    const uint4 v = make_uint4(blockIdx.x, threadIdx.x, 0u, 0u);
-    for (size_t i = first + threadIdx.x; i < last; i += 256)
-        buf[i] = v;
+    const u32x4_t v = {blockIdx.x, threadIdx.x, 0u, 0u};
+    u32x4_t *out = reinterpret_cast<u32x4_t *>(buf);
+    for (size_t i = first + threadIdx.x; i < last; i += 256) {
+        if (STREAM)
+            __builtin_nontemporal_store(v, out + i);
+        else
+            out[i] = v;
+    }
 }
 
 }  // namespace
@@ -170,8 +178,8 @@ int plogp_measure_ceilings(void *d_buf, size_t buf_bytes, void *stream, double *
     const size_t n16 = buf_bytes / 16;
     const size_t fill_blocks = (size_t)n_cu * 16;
     const size_t per_wg = (n16 + fill_blocks - 1) / fill_blocks;
-    float best[2] = {0.f, 0.f};
-    for (int which = 0; which < 2; ++which) {
+    float best[3] = {0.f, 0.f, 0.f};                    // multiply-adds, plain fill, streaming fill
+    for (int which = 0; which < 3; ++which) {
         for (int round = 0; round < 4; ++round) {       // round 0 warms up
             float ms = 0.f;
             rc = timed_stages(1, 1, st, &ms, [&](int) {
@@ -179,7 +187,8 @@ int plogp_measure_ceilings(void *d_buf, size_t buf_bytes, void *stream, double *
                     hipLaunchKernelGGL(k_fma_peak, dim3(fma_blocks), dim3(256), 0, st,
                                        static_cast<double *>(d_buf), fma_iters, 1.0, 1.0000001);
                 else
-                    hipLaunchKernelGGL(k_store_fill, dim3((unsigned)fill_blocks), dim3(256), 0, st,
+                    hipLaunchKernelGGL(which == 1 ? k_store_fill<false> : k_store_fill<true>,
+                                       dim3((unsigned)fill_blocks), dim3(256), 0, st,
                                        static_cast<uint4 *>(d_buf), n16, per_wg);
                 return hipGetLastError();
             });
@@ -188,7 +197,8 @@ int plogp_measure_ceilings(void *d_buf, size_t buf_bytes, void *stream, double *
         }
     }
     *fma_tflops_out = fma_flops / ((double)best[0] * 1e-3) / 1e12;
-    *store_gbs_out = (double)(n16 * 16) / ((double)best[1] * 1e-3) / 1e9;
+    const float fill_ms = best[2] < best[1] ? best[2] : best[1];
+    *store_gbs_out = (double)(n16 * 16) / ((double)fill_ms * 1e-3) / 1e9;
     return PLOGP_OK;
 }
 

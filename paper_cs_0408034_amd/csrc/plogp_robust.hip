@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
         f64x2_t r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            r[u] = p[(u64)u * R.cells];
+            r[u] = __builtin_nontemporal_load(p + (u64)u * R.cells);
         p += U * R.cells;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(256) k_robust(RobustShape R, const f64x2_t *__
         }
     }
     for (; t < t1; ++t) {
-        const f64x2_t r = *p;
+        const f64x2_t r = __builtin_nontemporal_load(p);
         p += R.cells;
         const bool same = live && key_of(r, R.strict) == base_key;
         cnt += same ? 1u : 0u;
