@@ -123,6 +123,7 @@ void plogp_grid::free_cut_scratch()
     if (cut.local) (void)hipFree(cut.local);
     if (cut.flags) (void)hipFree(cut.flags);
     if (cut.group_total) (void)hipFree(cut.group_total);
+    if (cut.ctl) (void)hipFree(cut.ctl);
     cut = CutScratch{};
     cut_tables = 0;
 }
@@ -168,7 +169,8 @@ int ensure_cut_scratch(plogp_grid *g, size_t n_tables)
     if ((e = hipMalloc((void **)&g->cut.counts, items * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->cut.local, items * sizeof(uint32_t))) != hipSuccess ||
         (e = hipMalloc((void **)&g->cut.flags, items * sizeof(uint32_t))) != hipSuccess ||
-        (e = hipMalloc((void **)&g->cut.group_total, (groups ? groups : 1) * sizeof(uint64_t))) != hipSuccess) {
+        (e = hipMalloc((void **)&g->cut.group_total, (groups ? groups : 1) * sizeof(uint64_t))) != hipSuccess ||
+        (e = hipMalloc((void **)&g->cut.ctl, cutover_ctl_words(g->view(), (int)n_tables) * sizeof(uint64_t))) != hipSuccess) {
         g->free_cut_scratch();
         return alloc_error(e);
     }

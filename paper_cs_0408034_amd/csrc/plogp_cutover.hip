@@ -20,6 +20,14 @@
 // The decision table is stored [table][operation][m][P] with P fastest, so the
 // lanes of a wave run over consecutive P (coalesced) and, when the grid has
 // fewer than 64 process counts, over consecutive tiles as well.
+//
+// Tables of many rows and at most CUT_ROWS_MAX_M sizes take one pass instead
+// (k_cut_rows): a thread owns a whole row, so a workgroup of 256 consecutive
+// rows owns a contiguous stretch of the output; it reads its rows once, keeps
+// the start flags in registers, learns where its stretch begins from the
+// workgroups before it (their totals, published through one 64-bit word each)
+// and writes its runs - the table is read once, nothing else goes through
+// device memory.
 #include "plogp_internal.hpp"
 
 namespace plogp {
@@ -267,7 +275,195 @@ __global__ void __launch_bounds__(256) k_cut_emit(CutShape sh, const plogp_cell_
     }
 }
 
+// ---- one pass, a thread per row ------------------------------------------------
+//
+// ctl[0]: the next workgroup number (workgroups number themselves in the order in
+// which they start, so that every lower number belongs to a workgroup that is
+// running or done); ctl[1]: set if a wait was given up; ctl[2 + w]: the status of
+// workgroup w, one word that carries its state in the two top bits (0 nothing
+// yet, 1 the number of runs of its rows, 2 the number of runs of all rows up to
+// and including its own) and the count in the others.  The words are written and
+// read with device-scope atomics: value and state travel together, so no other
+// ordering is needed.  A workgroup publishes state 1 before it waits for anyone,
+// and waits only for lower numbers: every wait ends.  The waits are bounded all
+// the same (spin_limit polls): a workgroup that gives up sets ctl[1] and goes on
+// with a wrong offset rather than hold the device.
+constexpr unsigned long long CUT_STATE_SHIFT = 62, CUT_COUNT_MASK = (1ull << 62) - 1ull;
+
+__global__ void __launch_bounds__(256) k_cut_rows_clear(u64 *ctl, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n)
+        ctl[i] = 0ull;
+}
+
+__device__ __forceinline__ u64 wave_sum_u64(u64 v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        v += (u64)__shfl_xor((long long)v, d, 64);
+    return v;
+}
+
+// NW: 32-bit words of start flags per row (the grid has at most 32 NW sizes).
+template <bool STREAM, int NW>
+__global__ void __launch_bounds__(256) k_cut_rows(CutShape sh, const plogp_cell_dev *cells, const u64 *m,
+                                                  int key_mode, u64 *ctl, u64 *row_offsets,
+                                                  plogp_run_dev *runs, u64 capacity, u64 n_rows,
+                                                  unsigned spin_limit)
+{
+    __shared__ unsigned wg_s;
+    __shared__ u64 wave_total[4];
+    __shared__ u64 before_s;
+    if (threadIdx.x == 0)
+        wg_s = (unsigned)atomicAdd(ctl, 1ull);
+    __syncthreads();
+    const unsigned wg = wg_s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u64 row = (u64)wg * 256 + threadIdx.x;
+    const bool live = row < n_rows;
+    const u64 rr = live ? row : n_rows - 1;            // padding threads read a valid row
+    const u64 plane = rr / (u64)sh.n_P;                // table * n_ops + operation
+    const int pi = (int)(rr % (u64)sh.n_P);
+    const size_t base = (size_t)plane * sh.n_m * sh.n_P + pi;
+
+    // first pass over the row: where a run starts
+    uint32_t bits[NW];
+    uint2 prev = make_uint2(0u, 0u);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        bits[w] = 0u;
+        if (32 * w >= sh.n_m)
+            continue;                                  // the same for every thread
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int m0 = 32 * w + 16 * half;
+            uint2 key[16];                             // sixteen keys are fetched before any is compared
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int mi = m0 + k < sh.n_m ? m0 + k : sh.n_m - 1;
+                key[k] = cell_key<STREAM>(cells, base + (size_t)mi * sh.n_P);
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                bool differs = key[k].y != prev.y;
+                if (key_mode == 1)
+                    differs = differs || key[k].x != prev.x;
+                if (m0 + k < sh.n_m && (differs || m0 + k == 0))
+                    bits[w] |= 1u << (16 * half + k);
+                prev = key[k];
+            }
+        }
+    }
+    u64 count = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+        count += (u64)__builtin_popcount(bits[w]);
+    if (!live)
+        count = 0;
+
+    // the runs before this row: inside the workgroup by a scan, before the workgroup from
+    // the status words of the lower-numbered workgroups
+    u64 inc = count;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const u64 up = (u64)__shfl_up((long long)inc, d, 64);
+        if (lane >= d)
+            inc += up;
+    }
+    if (lane == 63)
+        wave_total[wave] = inc;
+    __syncthreads();
+    u64 inside = inc - count, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        inside += w < wave ? wave_total[w] : 0ull;
+        total += wave_total[w];
+    }
+    if (wave == 0) {
+        u64 before = 0;
+        if (wg > 0) {
+            if (lane == 0)
+                __hip_atomic_store(ctl + 2 + wg, (1ull << CUT_STATE_SHIFT) | total, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            long long j = (long long)wg - 1;           // the nearest workgroup not yet counted
+            unsigned polls = 0;
+            for (;;) {
+                // 64 status words at a time, lane l looks at workgroup j - l
+                const long long idx = j - lane;
+                u64 sv = 2ull << CUT_STATE_SHIFT;      // before workgroup 0: nothing, and final
+                if (idx >= 0)
+                    sv = __hip_atomic_load(ctl + 2 + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const u64 state = sv >> CUT_STATE_SHIFT;
+                const u64 known = __ballot(state != 0ull), final_ = __ballot(state == 2ull);
+                const int stop = final_ ? __builtin_ctzll(final_) : 63;      // counted up to this lane
+                const u64 wanted = (2ull << stop) - 1ull;                    // lanes 0 .. stop
+                if ((known & wanted) == wanted) {
+                    before += wave_sum_u64(lane <= stop ? (sv & CUT_COUNT_MASK) : 0ull);
+                    if (final_)
+                        break;
+                    j -= 64;
+                    continue;
+                }
+                if (++polls > spin_limit) {
+                    if (lane == 0)
+                        atomicExch(ctl + 1, 1ull);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+        }
+        if (lane == 0) {
+            __hip_atomic_store(ctl + 2 + wg, (2ull << CUT_STATE_SHIFT) | (before + total), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            before_s = before;
+        }
+    }
+    __syncthreads();
+    u64 at = before_s + inside;
+    if (!live)
+        return;
+    row_offsets[row] = at;
+    if (row == n_rows - 1)
+        row_offsets[n_rows] = at + count;              // the grand total
+    // second pass: a record per start flag (its key is read once more: 2 % of the cells)
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        uint32_t b = bits[w];
+        while (b != 0u) {
+            const int k = 32 * w + __builtin_ctz(b);
+            b &= b - 1u;
+            if (at < capacity) {
+                const uint2 key = cell_key<false>(cells, base + (size_t)k * sh.n_P);
+                union {
+                    plogp_run_dev r;
+                    uint4 v;
+                } u;
+                u.r.m_from = m[k];
+                u.r.s = key.x;
+                u.r.strategy = key.y;
+                reinterpret_cast<uint4 *>(runs)[at] = u.v;
+            }
+            ++at;
+        }
+    }
+}
+
 }  // namespace
+
+bool cutover_by_rows(const DeviceGrid &G, int n_tables)
+{
+    // enough rows to fill the chip with one thread each, and few enough sizes for the start
+    // flags of a row to stay in registers
+    const size_t n_rows = (size_t)n_tables * G.n_ops * G.n_P;
+    return G.n_m <= CUT_ROWS_MAX_M && n_rows >= (size_t)128 * device_info().n_cu;
+}
+
+size_t cutover_ctl_words(const DeviceGrid &G, int n_tables)
+{
+    const size_t n_rows = (size_t)n_tables * G.n_ops * G.n_P;
+    return (n_rows + 255) / 256 + 2;
+}
 
 size_t cutover_items(const DeviceGrid &G, int n_tables)
 {
@@ -297,6 +493,24 @@ hipError_t launch_cutovers_stage(int stage, const DeviceGrid &G, int n_tables, c
     if ((sh.n_items + 255) / 256 > 0x7FFFFFFFL || n_groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)((sh.n_items + 255) / 256);
     const bool fuse = n_groups <= (size_t)CUT_FUSE_MAX;     // the prefix of the group totals inside the last step
+    if (cutover_by_rows(G, n_tables)) {
+        // one pass, a thread per row (stage 0; the other stages have nothing to do)
+        if (stage != 0) return hipSuccess;
+        const size_t n_wg = (n_rows + 255) / 256;
+        if (n_wg > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        u64 *ctl = reinterpret_cast<u64 *>(C.ctl);
+        hipLaunchKernelGGL(k_cut_rows_clear, dim3((unsigned)((n_wg + 2 + 255) / 256)), dim3(256), 0, st, ctl,
+                           n_wg + 2);
+        const bool stream = (size_t)n_rows * G.n_m * sizeof(plogp_cell_dev) > ((size_t)256 << 20);
+        const bool wide = G.n_m > 32 * 8;
+        const auto kern = stream ? (wide ? k_cut_rows<true, 16> : k_cut_rows<true, 8>)
+                                 : (wide ? k_cut_rows<false, 16> : k_cut_rows<false, 8>);
+        hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(256), 0, st, sh, d_cells,
+                           reinterpret_cast<const u64 *>(G.m), key_mode, ctl,
+                           reinterpret_cast<u64 *>(d_row_offsets), reinterpret_cast<plogp_run_dev *>(d_runs),
+                           (u64)capacity, (u64)n_rows, CUT_SPIN_LIMIT);
+        return hipGetLastError();
+    }
     if (stage == 0) {
         // a table beyond the 256 MB of the last-level cache is streamed
         const bool stream = n_counts * CUT_TM * sizeof(plogp_cell_dev) > ((size_t)256 << 20);

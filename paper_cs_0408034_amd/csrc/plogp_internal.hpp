@@ -203,7 +203,13 @@ struct CutScratch {
     uint32_t *local;         // their exclusive prefix inside a group of CUT_SCAN_WG entries
     uint32_t *flags;         // bit k: cell k of the tile starts a run
     uint64_t *group_total;   // [groups] totals, then their exclusive prefix
+    uint64_t *ctl;           // one-pass path: [2 + workgroups] numbering, give-up flag, status words
 };
+constexpr int CUT_ROWS_MAX_M = 512;        // sizes per row that the one-pass path keeps flags for
+constexpr unsigned CUT_SPIN_LIMIT = 1u << 22;   // polls before a wait is given up (never reached)
+// Whether the extraction takes the one-pass path, and the words of its control block.
+bool cutover_by_rows(const DeviceGrid &G, int n_tables);
+size_t cutover_ctl_words(const DeviceGrid &G, int n_tables);
 
 // Number of (row, tile) entries for n_tables tables over grid G.
 size_t cutover_items(const DeviceGrid &G, int n_tables);

@@ -99,6 +99,67 @@ def test_scan_over_many_groups():
     check(cells, m, P, 1)
 
 
+@pytest.mark.parametrize("key_mode", [0, 1])
+@pytest.mark.parametrize("shape,p_change", [
+    ((700, 2, 37, 24), 0.2),      # 33 600 rows: one thread per row; sizes end inside a flag word
+    ((1100, 2, 33, 15), 0.5),     # 33 000 rows: the last workgroup is ragged
+    ((300, 2, 257, 64), 0.03),    # more than 256 sizes: sixteen flag words, one size into the ninth
+    ((180, 1, 512, 200), 0.01),   # the most sizes this path takes
+    ((40000, 1, 1, 1), 0.5),      # one cell per row
+    ((600, 2, 64, 30), 1.0),      # every cell starts a run
+    ((600, 2, 64, 30), 0.0),      # one run per row
+])
+def test_tables_of_many_rows_take_one_pass_and_match_the_definition(shape, p_change, key_mode):
+    rng = np.random.default_rng(hash((shape, key_mode, "rows")) % (1 << 32))
+    nt, n_ops, n_m, n_P = shape
+    m = np.cumsum(rng.integers(1, 50, size=n_m)).astype(np.uint64)
+    P = (np.arange(n_P) + 2).astype(np.uint32)
+    check(random_table(rng, nt, n_ops, n_m, n_P, p_change), m, P, key_mode)
+
+
+def test_one_grid_handle_many_rows_then_fewer_then_many_again():
+    """The same handle serves a batch on the one-pass path, a smaller one on the tiled path and
+    the first again: whatever a call leaves in the handle's scratch, the next one starts clean."""
+    torch = torch_cuda()
+    plogp = _plogp()
+    rng = np.random.default_rng(23)
+    n_ops, n_m, n_P = 2, 40, 24
+    m = (np.arange(n_m) * 8 + 8).astype(np.uint64)
+    P = (np.arange(n_P) + 2).astype(np.uint32)
+    grid = plogp.plogp_grid_create(m, P, [], plogp.NO_CAP, 1, plogp.MASK_ALL)
+    big = random_table(rng, 800, n_ops, n_m, n_P, 0.1)
+    for nt in (800, 5, 800, 799):
+        cells = big[:nt]
+        want_off, want_runs = oc.cutovers(cells, m, 1)
+        rows = nt * n_ops * n_P
+        d_cells = torch.from_numpy(np.ascontiguousarray(cells).view(np.uint8).reshape(-1)).cuda()
+        d_off = torch.full((rows + 1,), -1, dtype=torch.int64, device="cuda")
+        d_runs = torch.full((cells.size * 16,), 0xEE, dtype=torch.uint8, device="cuda")
+        plogp.plogp_cutovers(grid, nt, d_cells.data_ptr(), 1, d_off.data_ptr(), d_runs.data_ptr(),
+                             cells.size, stream_handle())
+        torch.cuda.synchronize()
+        off = d_off.cpu().numpy().view(np.uint64)
+        assert (off == want_off).all(), nt
+        runs = d_runs.cpu().numpy().view(plogp.RUN_DTYPE)
+        assert (runs[:len(want_runs)] == want_runs).all(), nt
+        assert (runs[len(want_runs):].view(np.uint8) == 0xEE).all(), nt
+    grid.free()
+
+
+def test_capacity_smaller_than_the_number_of_runs_on_the_one_pass_path():
+    rng = np.random.default_rng(29)
+    cells = random_table(rng, 700, 2, 20, 24, 0.3)
+    m = (np.arange(20) * 8 + 8).astype(np.uint64)
+    P = (np.arange(24) + 2).astype(np.uint32)
+    want_off, want_runs = oc.cutovers(cells, m, 0)
+    cap = len(want_runs) // 3
+    off, runs = gpu_cutovers(cells, m, P, 0, capacity=cap)
+    assert (off == want_off).all() and int(off[-1]) > cap
+    assert (runs == want_runs[:cap]).all()
+    off, runs = gpu_cutovers(cells, m, P, 0, capacity=0)
+    assert (off == want_off).all()
+
+
 def test_capacity_smaller_than_the_number_of_runs_and_count_only():
     rng = np.random.default_rng(11)
     cells = random_table(rng, 2, 2, 50, 9, 0.5)
