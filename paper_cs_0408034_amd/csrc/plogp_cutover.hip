@@ -315,6 +315,7 @@ __global__ void __launch_bounds__(256) k_cut_rows(CutShape sh, const plogp_cell_
     __shared__ unsigned wg_s;
     __shared__ u64 wave_total[4];
     __shared__ u64 before_s;
+    __shared__ uint2 kept[CUT_ROWS_KEEP][256];         // the keys of a row's first run starts
     if (threadIdx.x == 0)
         wg_s = (unsigned)atomicAdd(ctl, 1ull);
     __syncthreads();
@@ -330,6 +331,7 @@ __global__ void __launch_bounds__(256) k_cut_rows(CutShape sh, const plogp_cell_
     // first pass over the row: where a run starts
     uint32_t bits[NW];
     uint2 prev = make_uint2(0u, 0u);
+    int starts = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         bits[w] = 0u;
@@ -349,18 +351,17 @@ __global__ void __launch_bounds__(256) k_cut_rows(CutShape sh, const plogp_cell_
                 bool differs = key[k].y != prev.y;
                 if (key_mode == 1)
                     differs = differs || key[k].x != prev.x;
-                if (m0 + k < sh.n_m && (differs || m0 + k == 0))
+                if (m0 + k < sh.n_m && (differs || m0 + k == 0)) {
                     bits[w] |= 1u << (16 * half + k);
+                    if (starts < CUT_ROWS_KEEP)
+                        kept[starts][threadIdx.x] = key[k];
+                    ++starts;
+                }
                 prev = key[k];
             }
         }
     }
-    u64 count = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w)
-        count += (u64)__builtin_popcount(bits[w]);
-    if (!live)
-        count = 0;
+    u64 count = live ? (u64)starts : 0ull;
 
     // the runs before this row: inside the workgroup by a scan, before the workgroup from
     // the status words of the lower-numbered workgroups
@@ -426,15 +427,19 @@ __global__ void __launch_bounds__(256) k_cut_rows(CutShape sh, const plogp_cell_
     row_offsets[row] = at;
     if (row == n_rows - 1)
         row_offsets[n_rows] = at + count;              // the grand total
-    // second pass: a record per start flag (its key is read once more: 2 % of the cells)
+    // second pass: a record per start flag; the keys of the first few were kept, those of the
+    // others are read once more
+    int nth = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         uint32_t b = bits[w];
         while (b != 0u) {
             const int k = 32 * w + __builtin_ctz(b);
             b &= b - 1u;
+            const int mine = nth++;
             if (at < capacity) {
-                const uint2 key = cell_key<false>(cells, base + (size_t)k * sh.n_P);
+                const uint2 key = mine < CUT_ROWS_KEEP ? kept[mine][threadIdx.x]
+                                                       : cell_key<false>(cells, base + (size_t)k * sh.n_P);
                 union {
                     plogp_run_dev r;
                     uint4 v;

@@ -205,6 +205,7 @@ struct CutScratch {
     uint64_t *group_total;   // [groups] totals, then their exclusive prefix
     uint64_t *ctl;           // one-pass path: [2 + workgroups] numbering, give-up flag, status words
 };
+constexpr int CUT_ROWS_KEEP = 8;           // run starts per row whose keys the one-pass path keeps in LDS
 constexpr int CUT_ROWS_MAX_M = 512;        // sizes per row that the one-pass path keeps flags for
 constexpr unsigned CUT_SPIN_LIMIT = 1u << 22;   // polls before a wait is given up (never reached)
 // Whether the extraction takes the one-pass path, and the words of its control block.
