@@ -261,7 +261,12 @@ def run_cutovers(plogp, torch, wl, tab, grid, out, nbytes, stream, steps):
     # what the extraction itself has to move: the 8-byte key of every cell once, a 16-byte
     # record per run, an 8-byte offset per row
     alg_bytes = 8 * n_cells + 16 * n_runs + 8 * (rows + 1)
-    return hbm_leg(ms, sum(st), alg_bytes, {"runs": n_runs, "stage_ms": {"mark": st[0], "scan": st[1], "emit": st[2]}})
+    # what it cannot avoid moving: the table keeps key and time in one 16-byte record and HBM
+    # moves 64-byte lines, so the whole table is read
+    moved = 16 * n_cells + 16 * n_runs + 8 * (rows + 1)
+    k_ms = sum(st)
+    return hbm_leg(ms, k_ms, alg_bytes, {"runs": n_runs, "stage_ms": {"mark": st[0], "scan": st[1], "emit": st[2]},
+                                         "frac_of_peak_whole_records": float("%.3g" % (moved / (k_ms * 1e-3) / HBM_PEAK))})
 
 
 def run_patterns(cfg, steps):
@@ -396,6 +401,8 @@ def short_next(res):
             v = res[k]
             out[k] = {"ms_per_call": v["ms_per_call"], "kernels_ms": v["kernels_ms"],
                       "hbm_frac": v["roofline"]["frac"]}
+            if "frac_of_peak_whole_records" in v:
+                out[k]["hbm_frac_whole_records"] = v["frac_of_peak_whole_records"]
     return out
 
 

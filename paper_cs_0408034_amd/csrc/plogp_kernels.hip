@@ -3229,10 +3229,34 @@ struct plogp_verdict_dev {
     uint32_t meas_best;
 };
 
+// The prediction of strategy `id` (rows of Tables 1 and 2 as the scoring evaluates them) at one
+// point: a segmented row at the segment size the point was measured with (gs, k; NaN if that
+// size is not usable), the Scatter rows from the tuning's sums.
+__device__ __forceinline__ double score_predict(int id, double q, double fl, double cl, double gm, double L,
+                                                double R, const double (&gs)[3], const double (&k)[3],
+                                                const bool (&ok)[3], const DeviceGrid &G, const Scratch &S,
+                                                int mi, int pi, uint32_t P)
+{
+    switch (id) {
+    case 0: case 10: return __builtin_fma(q, gm, L);
+    case 1: return __builtin_fma(q, gm, R);
+    case 2: return ok[0] ? __builtin_fma(q, gs[0] * k[0], L) : NAN;
+    case 3: return q * (gm + L);
+    case 4: return q * (gm + R);
+    case 5: return ok[1] ? __builtin_fma(q, gs[1] + L, gs[1] * (k[1] - 1.0)) : NAN;
+    case 6: return cl * __builtin_fma(2.0, gm, L);
+    case 7: return __builtin_fma(fl, gm, cl * L);
+    case 8: return __builtin_fma(fl, gm, cl * R);
+    case 9: return ok[2] ? __builtin_fma(fl, gs[2] * k[2], cl * L) : NAN;
+    case 11: return __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P));
+    default: return __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]);
+    }
+}
+
 // Workgroups walk the (m, chunk of P) items with a stride, so that a big table is
 // staged once per workgroup; the measured times and segment sizes of a point are
 // fetched before any arithmetic (13 + 3 independent loads per lane in flight).
-__global__ void __launch_bounds__(1024) k_score(DeviceTables T, DeviceGrid G, Scratch S,
+__global__ void __launch_bounds__(1024) k_score_points(DeviceTables T, DeviceGrid G, Scratch S,
                                                 const double *__restrict__ meas,
                                                 const uint32_t *__restrict__ seg,
                                                 double *__restrict__ pred,
@@ -3299,21 +3323,7 @@ __global__ void __launch_bounds__(1024) k_score(DeviceTables T, DeviceGrid G, Sc
                 continue;
             const size_t at = (size_t)r * plane + cell;
             ++r;
-            double v;
-            switch (id) {
-            case 0: case 10: v = __builtin_fma(q, gm, L); break;
-            case 1: v = __builtin_fma(q, gm, R); break;
-            case 2: v = ok[0] ? __builtin_fma(q, gs[0] * k[0], L) : NAN; break;
-            case 3: v = q * (gm + L); break;
-            case 4: v = q * (gm + R); break;
-            case 5: v = ok[1] ? __builtin_fma(q, gs[1] + L, gs[1] * (k[1] - 1.0)) : NAN; break;
-            case 6: v = cl * __builtin_fma(2.0, gm, L); break;
-            case 7: v = __builtin_fma(fl, gm, cl * L); break;
-            case 8: v = __builtin_fma(fl, gm, cl * R); break;
-            case 9: v = ok[2] ? __builtin_fma(fl, gs[2] * k[2], cl * L) : NAN; break;
-            case 11: v = __builtin_fma(q, L, chain_sum_of(G, S, 0, mi, pi, P)); break;
-            default: v = __builtin_fma(cl, L, S.sum2[(size_t)mi * (G.cl_max + 1) + ceil_log2(P)]); break;
-            }
+            const double v = score_predict(id, q, fl, cl, gm, L, R, gs, k, ok, G, S, mi, pi, P);
             __builtin_nontemporal_store(v, pred + at);
             const double t_meas = tm[id];
             const int op = id < 10 ? 0 : 1;
@@ -3431,6 +3441,227 @@ __global__ void __launch_bounds__(64 * SCORE_WAVES) k_score_rows(DeviceGrid G, i
         }
         rows[2 * (row0 + lane)] = sum;
         rows[2 * (row0 + lane) + 1] = worst;
+    }
+}
+
+// A wave takes one message size at a time and walks over its process counts, 64 (its lanes)
+// at a time: the measured times and segment sizes of a point are fetched before any
+// arithmetic (13 + 3 independent loads per lane in flight), the predictions and the verdicts
+// go out, and the relative errors e = |(pred - meas) / meas| stay in the wave for the
+// statistics, so that nothing is read a second time.  Per (strategy row r, m) the sum of e
+// over P is one serial chain in ascending P from +0.0: the lanes leave their e in an LDS tile
+// (SCORE_TILE_ROWS strategy rows at a time), then lane j adds the 64 values of row j in
+// order, sixteen LDS reads at a time, and keeps the running sum for the next 64 process
+// counts; the maximum does not depend on the order, every lane keeps its own per row and the
+// lanes are combined once per message size.  rows[(r * n_m + mi) * 2] = {sum, max}.
+// A big table is staged once per workgroup, and the waves take sizes with a stride.
+constexpr int SCORE_TILE_ROWS = 7;                     // 13 strategy rows go through the tile in two halves
+constexpr int SCORE_TILE_LD = 65;
+
+// BIG: workgroups of 1024 threads (128 registers a lane); otherwise 256, and the measured times
+// of the next 64 process counts are fetched while the current ones are worked on.
+template <bool BIG>
+__global__ void __launch_bounds__(BIG ? 1024 : 256) k_score_fused(DeviceTables T, DeviceGrid G, Scratch S,
+                                                const double *__restrict__ meas,
+                                                const uint32_t *__restrict__ seg,
+                                                double *__restrict__ pred,
+                                                plogp_verdict_dev *__restrict__ verdict,
+                                                double *__restrict__ rows)
+{
+    extern __shared__ double lds[];
+    const uint32_t mask = G.mask;
+    const bool any_seg = (mask & 0x224u) != 0;
+    LdsTable tab = {nullptr, nullptr, nullptr, T.n};
+    if (any_seg)
+        tab = stage_table(lds, T, 0);                 // for g(s) at the measured segment sizes
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_waves = blockDim.x >> 6;
+    double *tile = lds + (any_seg ? 3 * T.n : 0) + (size_t)wave * SCORE_TILE_ROWS * SCORE_TILE_LD;
+    const double L = T.L[0];
+    const double g1 = S.g1[0];
+    const double R = __builtin_fma(3.0, L, 2.0 * g1);
+    const int n_P = G.n_P;
+    const size_t plane = (size_t)G.n_m * n_P;
+    int n_ids = 0;
+#pragma unroll
+    for (int id = 0; id < 13; ++id)
+        n_ids += (mask >> id) & 1u;
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    for (int mi = blockIdx.x * n_waves + wave; mi < G.n_m; mi += gridDim.x * n_waves) {
+        const u64 m = G.m[mi];
+        const double gm = S.gm[mi];
+        double wmax[13];                               // this lane's largest e per strategy
+#pragma unroll
+        for (int id = 0; id < 13; ++id)
+            wmax[id] = 0.0;
+        double sum_lo = 0.0, sum_hi = 0.0;             // lane j: rows j and SCORE_TILE_ROWS + j
+        double tm_n[13];
+        uint32_t sv_n[3] = {0u, 0u, 0u};
+        auto fetch = [&](int p0, double (&tmv)[13], uint32_t (&svv)[3]) {
+            const int pi = p0 + lane < n_P ? p0 + lane : n_P - 1;
+            const size_t cell = (size_t)mi * n_P + pi;
+            int r = 0;
+#pragma unroll
+            for (int id = 0; id < 13; ++id) {
+                tmv[id] = 0.0;
+                if ((mask >> id) & 1u) {
+                    const size_t at = (size_t)r * plane + cell;
+                    tmv[id] = __builtin_nontemporal_load(meas + at);
+                    if (id == 2) svv[0] = seg[at];
+                    if (id == 5) svv[1] = seg[at];
+                    if (id == 9) svv[2] = seg[at];
+                    ++r;
+                }
+            }
+        };
+        if (!BIG)
+            fetch(0, tm_n, sv_n);
+        for (int p0 = 0; p0 < n_P; p0 += 64) {
+            const bool valid = p0 + lane < n_P;
+            const int pi = valid ? p0 + lane : n_P - 1;     // padding lanes work on a valid point, quietly
+            const size_t cell = (size_t)mi * n_P + pi;
+            double tm[13];
+            uint32_t sv[3] = {0u, 0u, 0u};
+            if (BIG) {
+                fetch(p0, tm, sv);
+            } else {
+#pragma unroll
+                for (int id = 0; id < 13; ++id)
+                    tm[id] = tm_n[id];
+#pragma unroll
+                for (int u = 0; u < 3; ++u)
+                    sv[u] = sv_n[u];
+                if (p0 + 64 < n_P)
+                    fetch(p0 + 64, tm_n, sv_n);
+            }
+            const uint32_t P = G.P[pi];
+            const double q = (double)(P - 1), fl = (double)floor_log2(P), cl = (double)ceil_log2(P);
+            double gs[3] = {0.0, 0.0, 0.0}, k[3] = {0.0, 0.0, 0.0};
+            bool ok[3] = {true, true, true};
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                if (!((mask >> (u == 0 ? 2 : u == 1 ? 5 : 9)) & 1u))
+                    continue;
+                const u64 sz = sv[u];
+                ok[u] = sz > 0 && sz <= m;
+                if (ok[u]) {
+                    gs[u] = gap_at(tab, (double)sz);
+                    k[u] = segments(m, sz);
+                }
+            }
+            double best_p[2] = {INFINITY, INFINITY}, best_m[2] = {INFINITY, INFINITY};
+            double meas_of_pred_best[2] = {NAN, NAN};
+            uint32_t id_p[2] = {0xFFFFFFFFu, 0xFFFFFFFFu}, id_m[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+            double ev[13];                             // e of this point per strategy (0 in padding lanes)
+            int r = 0;
+#pragma unroll
+            for (int id = 0; id < 13; ++id) {
+                ev[id] = 0.0;
+                if (!((mask >> id) & 1u))
+                    continue;
+                const size_t at = (size_t)r * plane + cell;
+                ++r;
+                const double v = score_predict(id, q, fl, cl, gm, L, R, gs, k, ok, G, S, mi, pi, P);
+                if (valid)
+                    __builtin_nontemporal_store(v, pred + at);
+                const double t_meas = tm[id];
+                const double e = fabs((v - t_meas) / t_meas);
+                ev[id] = valid ? e : 0.0;
+                wmax[id] = ev[id] > wmax[id] ? ev[id] : wmax[id];
+                const int op = id < 10 ? 0 : 1;
+                if (v < best_p[op]) {
+                    best_p[op] = v;
+                    id_p[op] = (uint32_t)id;
+                    meas_of_pred_best[op] = t_meas;
+                }
+                if (t_meas < best_m[op]) {
+                    best_m[op] = t_meas;
+                    id_m[op] = (uint32_t)id;
+                }
+            }
+            if (valid) {
+                plogp_verdict_dev *o = verdict + cell;
+#pragma unroll
+                for (int op = 0; op < 2; ++op) {
+                    if (!(mask & (op == 0 ? 0x3FFu : 0x1C00u)))
+                        continue;
+                    union {
+                        plogp_verdict_dev vd;
+                        uint4 v;
+                    } u;
+                    u.vd.regret = meas_of_pred_best[op] / best_m[op] - 1.0;
+                    u.vd.pred_best = id_p[op];
+                    u.vd.meas_best = id_m[op];
+                    stream_out(o, u.v);
+                    o += plane;
+                }
+            }
+            // the sums: the strategy rows go through the tile in two halves; a padding lane
+            // holds +0.0, which leaves a sum as it is
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                int rr = 0;
+#pragma unroll
+                for (int id = 0; id < 13; ++id) {
+                    if (!((mask >> id) & 1u))
+                        continue;
+                    if (rr / SCORE_TILE_ROWS == half)
+                        tile[(rr % SCORE_TILE_ROWS) * SCORE_TILE_LD + lane] = ev[id];
+                    ++rr;
+                }
+                wave_sync();
+                if (half * SCORE_TILE_ROWS + lane < n_ids && lane < SCORE_TILE_ROWS) {
+                    double acc = half == 0 ? sum_lo : sum_hi;
+                    const double *mine = tile + lane * SCORE_TILE_LD;
+#pragma unroll
+                    for (int j = 0; j < 64; j += 16) {     // 16 LDS reads in flight, added in order
+                        double err[16];
+#pragma unroll
+                        for (int u = 0; u < 16; ++u)
+                            err[u] = mine[j + u];
+#pragma unroll
+                        for (int u = 0; u < 16; ++u)
+                            acc = acc + err[u];
+                    }
+                    if (half == 0)
+                        sum_lo = acc;
+                    else
+                        sum_hi = acc;
+                }
+                wave_sync();
+            }
+        }
+        // the maxima over the lanes, the same way, and the two results of every row
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            int rr = 0;
+#pragma unroll
+            for (int id = 0; id < 13; ++id) {
+                if (!((mask >> id) & 1u))
+                    continue;
+                if (rr / SCORE_TILE_ROWS == half)
+                    tile[(rr % SCORE_TILE_ROWS) * SCORE_TILE_LD + lane] = wmax[id];
+                ++rr;
+            }
+            wave_sync();
+            const int row = half * SCORE_TILE_ROWS + lane;
+            if (row < n_ids && lane < SCORE_TILE_ROWS) {
+                const double *mine = tile + lane * SCORE_TILE_LD;
+                double worst = 0.0;
+#pragma unroll 16
+                for (int j = 0; j < 64; ++j) {
+                    const double v = mine[j];
+                    worst = v > worst ? v : worst;
+                }
+                rows[2 * ((size_t)row * G.n_m + mi)] = half == 0 ? sum_lo : sum_hi;
+                rows[2 * ((size_t)row * G.n_m + mi) + 1] = worst;
+            }
+            wave_sync();
+        }
     }
 }
 
@@ -3596,8 +3827,15 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fused),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score),
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score_points),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxTableLds);
+    if (e != hipSuccess) return e;
+    // (the table plus the waves' tiles; the launch checks the sum against the device's LDS)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score_fused<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)g_device.lds_per_cu);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score_fused<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)g_device.lds_per_cu);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
@@ -4052,29 +4290,52 @@ hipError_t launch_score_stage(int stage, const TunePlan &plan, const DeviceTable
     for (int id = 0; id < 13; ++id) n_ids += (G.mask >> id) & 1u;
     if (stage == 0)      // g(m), g(1), the Scatter sums: the first stages of the tuning
         return launch_tune(plan, T1, G, S, nullptr, st);
+    // With many message sizes a wave takes a whole size and forms the error sums on the way
+    // (one pass over the measurements); with fewer there would be too few waves to hide the
+    // memory latency of their serial walks, and the points go one to a thread with the sums
+    // formed by a second pass.
+    const bool fused = G.n_m >= 8 * device_info().n_cu;
+    const size_t tab_lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
+    // a small table is staged by every workgroup of 256; a big one by as few workgroups of 1024
+    // as fill the compute units, which then walk their items with a stride
+    const bool big = tab_lds > 16384;
+    const int threads = big ? 1024 : 256;
+    const DeviceInfo &dev = device_info();
+    if (stage == 1 && fused) {
+        const int waves = threads / 64;
+        const size_t lds = tab_lds + (size_t)waves * SCORE_TILE_ROWS * SCORE_TILE_LD * sizeof(double);
+        if (lds > dev.lds_per_cu) return hipErrorInvalidValue;
+        long n_wg = ((long)G.n_m + waves - 1) / waves;
+        if (big) {
+            const long fit = (long)dev.n_cu * (long)(dev.lds_per_cu / lds);
+            if (n_wg > fit) n_wg = fit;
+        }
+        hipLaunchKernelGGL(big ? k_score_fused<true> : k_score_fused<false>, dim3((unsigned)n_wg), dim3(threads),
+                           lds, st, T1, G, S, d_meas, d_seg, d_pred,
+                           reinterpret_cast<plogp_verdict_dev *>(d_verdict), rows);
+        return hipGetLastError();
+    }
     if (stage == 1) {
-        const size_t lds = (G.mask & 0x224u) ? (size_t)3 * T1.n * sizeof(double) : 0;
-        // a small table is staged by every workgroup of 256; a big one by at most one or
-        // two workgroups of 1024 per CU, which then walk the items with a stride
-        const bool big = lds > 16384;
-        const int threads = big ? 1024 : 256;
         const int n_pchunks = (G.n_P + threads - 1) / threads;
         const long n_items = (long)G.n_m * n_pchunks;
         long n_wg = n_items;
         if (big) {
-            const DeviceInfo &dev = device_info();
-            const long fit = (long)dev.n_cu * (long)(dev.lds_per_cu / lds);
+            const long fit = (long)dev.n_cu * (long)(dev.lds_per_cu / tab_lds);
             if (n_wg > fit) n_wg = fit;
         }
         if (n_items > kMaxLaunch) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(k_score, dim3((unsigned)n_wg), dim3(threads), lds, st, T1, G, S, d_meas, d_seg,
-                           d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict), n_pchunks, (int)n_items);
+        hipLaunchKernelGGL(k_score_points, dim3((unsigned)n_wg), dim3(threads), tab_lds, st, T1, G, S, d_meas,
+                           d_seg, d_pred, reinterpret_cast<plogp_verdict_dev *>(d_verdict), n_pchunks,
+                           (int)n_items);
         return hipGetLastError();
     }
-    const long n_rows = (long)n_ids * G.n_m;
-    const long row_wg = (n_rows + SCORE_RT * SCORE_WAVES - 1) / (SCORE_RT * SCORE_WAVES);
-    hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids, d_meas,
-                       d_pred, rows);
+    if (!fused) {
+        const long n_rows = (long)n_ids * G.n_m;
+        const long row_wg = (n_rows + SCORE_RT * SCORE_WAVES - 1) / (SCORE_RT * SCORE_WAVES);
+        hipLaunchKernelGGL(k_score_rows, dim3((unsigned)row_wg), dim3(64 * SCORE_WAVES), 0, st, G, n_ids, d_meas,
+                           d_pred, rows);
+    }
+    // the per-m sums of every strategy added in ascending m
     hipLaunchKernelGGL(k_score_final, dim3((unsigned)n_ids), dim3(1024), 0, st, G, rows,
                        reinterpret_cast<plogp_score_dev *>(d_scores));
     return hipGetLastError();

@@ -99,6 +99,43 @@ def test_model_free_measurements_and_many_process_counts():
     check(wl, meas, seg)
 
 
+@pytest.mark.parametrize("cfg,n_m,P_subset,mask", [
+    # at least 2048 sizes: a wave takes a whole size and forms the error sums in the same pass
+    (5, 4096, [2, 3, 65, 66, 130, 4097, 40000, 65536], 0x1FFF),                  # big table (4096 samples)
+    (5, 2100, list(range(2, 72)), 0x1FFF),                                       # 70 process counts: 64 + 6
+    (2, 2048, list(range(2, 131)), 0x1FFF),                                      # small table, 129 = 2 x 64 + 1
+    (2, 2500, [2, 5, 64, 65, 200], (1 << 0) | (1 << 5) | (1 << 9) | (1 << 11)),  # four strategy rows
+    (2, 2500, list(range(2, 67)), 0x1FFF & ~(1 << 6)),                           # twelve rows: 7 + 5
+    (2, 3000, [2, 1024], 0x1C00),                                                # the Scatter plane alone
+])
+def test_many_sizes_take_the_one_pass_path(cfg, n_m, P_subset, mask):
+    base = make_workload(cfg, n_m=n_m, P_subset=P_subset)
+    wl = Workload("score", base.sizes, base.gaps, base.L, base.m, base.P, base.s, base.s_cap, mask)
+    assert len(wl.m) >= 2048
+    meas, seg = make_measurements(wl, seed=cfg * 100 + len(P_subset))
+    check(wl, meas, seg)
+
+
+def test_unusable_segment_size_on_the_one_pass_path():
+    """NaN for that point's prediction and for its strategy's sum, nothing else disturbed."""
+    wl = make_workload(2, n_m=2048, P_subset=list(range(2, 70)))
+    meas, seg = make_measurements(wl, seed=77)
+    ids = oracle.strategy_ids(wl.strategy_mask)
+    r5 = ids.index(5)
+    good_p, good_v, good_s = gpu_score(wl, meas, seg)
+    bad = seg.copy()
+    bad[r5, 100, 67] = 0                      # the last process count: a lane of the ragged chunk
+    pred, ver, sc = gpu_score(wl, meas, bad)
+    assert np.isnan(pred[r5, 100, 67])
+    keep = np.ones(pred.shape, dtype=bool)
+    keep[r5, 100, 67] = False
+    assert same_bits(pred[keep], good_p[keep])
+    assert np.isnan(sc["sum_abs_err"][r5])
+    others = np.arange(len(ids)) != r5
+    assert same_bits(sc["sum_abs_err"][others], good_s["sum_abs_err"][others])
+    assert same_bits(sc["max_abs_err"][others], good_s["max_abs_err"][others])
+
+
 @pytest.mark.parametrize("mask", [0x3FF, 0x1C00, (1 << 0) | (1 << 3) | (1 << 7), (1 << 11), (1 << 5) | (1 << 12)])
 def test_masks_and_planes(mask):
     base = make_workload(2, m_slice=slice(5, 1024, 101), P_subset=[2, 5, 64, 65, 200])
