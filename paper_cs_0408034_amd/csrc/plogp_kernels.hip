@@ -1783,10 +1783,11 @@ constexpr int SWEEP_S_PASSES = 64;      // passes whose minimum of A is remember
 // of a pass of SWEEP_S_CHUNK candidates are computed once by the whole
 // workgroup into LDS (double-buffered) and read by every wave.  In the loop a
 // wave keeps, per process count, the running minimum of the segmented chain
-// (row 5: one fma and one min per value) and, once per candidate, the running
-// minimum of A (rows 2 and 9 are monotone in A); per lane it remembers in which
-// pass each row-5 minimum first appeared.  At the end the minima are reduced
-// across lanes with DPP, the winner is chosen in id order, and only for a
+// (row 5: one fma and one min per value); per lane it remembers in which pass
+// each row-5 minimum first appeared.  The minimum of A (rows 2 and 9 are monotone
+// in A, and A does not depend on P) is formed once per pass, by wave 0, from the
+// minima that the threads filling the pass leave in LDS.  At the end the row-5
+// minima are reduced across lanes, the winner is chosen in id order, and only for a
 // winning segmented row the smallest s that attains the minimum is looked for:
 // for row 5 among the candidates of the pass the holding lanes remember, for
 // rows 2 and 9 by one ascending walk over the candidates.
