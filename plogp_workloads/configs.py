@@ -283,8 +283,7 @@ def make_measurements(wl, seed: int = 1):
     m = np.asarray(wl.m, dtype=np.float64)
     P = np.asarray(wl.P, dtype=np.float64)
     rng = SplitMix64(408034000000 + 777 * seed)
-    noise = np.array([rng.uniform() for _ in range(len(ids) * m.size * P.size)]).reshape(
-        len(ids), m.size, P.size)
+    noise = rng.uniforms(len(ids) * m.size * P.size).reshape(len(ids), m.size, P.size)
     rank = (1.0 + np.arange(len(ids)) / 13.0)[:, None, None]
     base = (40.0 + m / 11.5)[None, :, None] * np.log2(P + 1.0)[None, None, :] * rank
     meas = base * (1.0 + 0.2 * noise) + 200.0

@@ -117,6 +117,19 @@ def test_tables_of_many_rows_take_one_pass_and_match_the_definition(shape, p_cha
     check(random_table(rng, nt, n_ops, n_m, n_P, p_change), m, P, key_mode)
 
 
+@pytest.mark.timeout(300)
+def test_full_size_of_config_4_random_decisions():
+    """The shape the benchmark times: 10 000 tables x 2 operations x 256 sizes x 24 process
+    counts (480 000 rows, one pass), with a run start in about 2 % of the cells as in the tuned
+    table; every offset and every run against the definition."""
+    rng = np.random.default_rng(41)
+    nt, n_ops, n_m, n_P = 10000, 2, 256, 24
+    cells = random_table(rng, nt, n_ops, n_m, n_P, 0.019)
+    m = (np.arange(n_m, dtype=np.uint64) + 1) * 8
+    P = (np.arange(n_P) + 2).astype(np.uint32)
+    check(cells, m, P, 1)
+
+
 def test_one_grid_handle_many_rows_then_fewer_then_many_again():
     """The same handle serves a batch on the one-pass path, a smaller one on the tiled path and
     the first again: whatever a call leaves in the handle's scratch, the next one starts clean."""

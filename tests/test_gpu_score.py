@@ -116,6 +116,35 @@ def test_many_sizes_take_the_one_pass_path(cfg, n_m, P_subset, mask):
     check(wl, meas, seg)
 
 
+@pytest.mark.timeout(300)
+def test_config5_full_size_sampled_rows_and_the_statistics_from_their_definition():
+    """Config 5 at full size, the launch the benchmark times (one pass, workgroups of 1024 around
+    the 4096-sample table).  The oracle needs minutes for all of it, so: the predictions and
+    verdicts of every 64th message size are compared with the oracle's, element by element;
+    the statistics are compared with their definition applied to the library's own predictions
+    (e per point, added per m in ascending P, then over ascending m, all from +0.0)."""
+    wl = make_workload(5)
+    meas, seg = make_measurements(wl, seed=5)
+    pred, ver, sc = gpu_score(wl, meas, seg)
+    rows = slice(0, len(wl.m), 64)
+    sub = Workload("score", wl.sizes, wl.gaps, wl.L, wl.m[rows], wl.P, wl.s, wl.s_cap, wl.strategy_mask)
+    x, y, L = wl.sizes[0], wl.gaps[0], float(wl.L[0])
+    want_p, want_v, _ = oracle.score_grid(x, y, L, sub.m, sub.P, sub.strategy_mask, meas[:, rows], seg[:, rows])
+    assert same_bits(pred[:, rows], want_p)
+    assert (ver["pred_best"][:, rows] == want_v["pred_best"]).all()
+    assert (ver["meas_best"][:, rows] == want_v["meas_best"]).all()
+    assert same_bits(ver["regret"][:, rows], want_v["regret"])
+    # every point has a finite, positive prediction here, and the verdicts name enabled ids
+    assert np.isfinite(pred).all() and (pred > 0).all()
+    assert (ver["pred_best"][0] <= 9).all() and (ver["pred_best"][1] >= 10).all()
+    e = np.abs((pred - meas) / meas)
+    per_m = np.cumsum(e, axis=2)[:, :, -1]                 # cumsum adds strictly left to right
+    total = np.cumsum(per_m, axis=1)[:, -1]
+    assert same_bits(sc["sum_abs_err"], total)
+    assert same_bits(sc["max_abs_err"], e.max(axis=(1, 2)))
+    assert (sc["count"] == len(wl.m) * len(wl.P)).all()
+
+
 def test_unusable_segment_size_on_the_one_pass_path():
     """NaN for that point's prediction and for its strategy's sum, nothing else disturbed."""
     wl = make_workload(2, n_m=2048, P_subset=list(range(2, 70)))
