@@ -1795,8 +1795,8 @@ template <int GP>
 __global__ void __launch_bounds__(64 * SWEEP_S_MAX_WAVES)
 k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_ptiles)
 {
-    __shared__ double2 AB[2][SWEEP_S_CHUNK];
-    __shared__ double Cs[2][SWEEP_S_CHUNK];
+    __shared__ double2 AB[2][SWEEP_S_CHUNK];           // {B, C} of the candidates of a pass
+    __shared__ double Cs[2][SWEEP_S_CHUNK];            // (only the reduction at the end uses it)
     __shared__ double passMinA[SWEEP_S_PASSES];        // min of A over each of the first passes
     __shared__ double fillMinA[2][64 * SWEEP_S_MAX_WAVES];   // per filling thread: min of A over its candidates
     __shared__ double allMinA;                         // min of A over every candidate
@@ -1879,8 +1879,7 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 double A = INFINITY, B = INFINITY, C = 0.0;
                 if (c * SWEEP_S_CHUNK + e < nv)
                     segment_terms(md, f_s[k], f_rcp[k], f_gs[k], L, A, B, C);
-                AB[buf][e] = make_double2(A, B);
-                Cs[buf][e] = C;
+                AB[buf][e] = make_double2(B, C);           // one 16-byte read per candidate in the loop
                 mine_A = min_f64(mine_A, A);
             }
         }
@@ -1906,11 +1905,10 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
                 cur5[p] = INFINITY;
 #pragma unroll 2
             for (int i = 0; i < steps; ++i) {
-                const double B = AB[buf][64 * i + lane].y;
-                const double C = Cs[buf][64 * i + lane];
+                const double2 bc = AB[buf][64 * i + lane];
 #pragma unroll
                 for (int p = 0; p < GP; ++p)
-                    cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], C, B));
+                    cur5[p] = min_f64(cur5[p], __builtin_fma(q[p], bc.y, bc.x));
             }
 #pragma unroll
             for (int p = 0; p < GP; ++p) {
