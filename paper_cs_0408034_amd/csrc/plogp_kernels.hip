@@ -1953,17 +1953,29 @@ k_sweep_s(DeviceTables T, DeviceGrid G, Scratch S, plogp_cell_dev *out, int n_pt
             (p < NLO ? lo + LD * p : hi + LD * (p - NLO))[lane] = best5[p];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        // in two steps, so that most lanes take part: lane l takes a stretch of the 64 minima of
+        // process count l % GP, then lane p the results of its stretches
+        constexpr int NPART = 64 / GP, PER = (64 + NPART - 1) / NPART;
+        double *mid = &fillMinA[0][0] + wave * 64;     // (free: every wave is past the last pass)
+        if (lane < GP * NPART) {
+            const int pp = lane % GP, part = lane / GP;
+            const double *col = pp < NLO ? lo + LD * pp : hi + LD * (pp - NLO);
+            double v[PER];
+#pragma unroll
+            for (int u = 0; u < PER; ++u)
+                v[u] = col[part * PER + u < 64 ? part * PER + u : 63];
+            double least = v[0];
+#pragma unroll
+            for (int u = 1; u < PER; ++u)
+                least = min_f64(least, v[u]);
+            mid[lane] = least;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         if (lane < GP) {
-            const double *col = lane < NLO ? lo + LD * lane : hi + LD * (lane - NLO);
-            for (int j0 = 0; j0 < 64; j0 += 16) {
-                double v[16];
 #pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    v[u] = col[j0 + u];
-#pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    V5 = min_f64(V5, v[u]);
-            }
+            for (int part = 0; part < NPART; ++part)
+                V5 = min_f64(V5, mid[part * GP + lane]);
         }
     }
 
