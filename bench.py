@@ -287,11 +287,15 @@ def run_patterns(cfg, steps):
     ms, _ = timed_calls(torch, stream, lambda: plogp.plogp_tune_grid(tab, grid, out.data_ptr(), nbytes, sh), steps, 3)
     rounds = [plogp.plogp_tune_grid_profile(tab, grid, out.data_ptr(), nbytes, sh, MIN_PER_BATCH)
               for _ in range(MIN_BATCHES)]
-    k_ms = float(np.median(np.array(rounds), axis=0)[4])
+    st = np.median(np.array(rounds), axis=0)
     del out
     grid.free()
     tab.free()
-    return hbm_leg(ms, k_ms, work["more_planes"]["bytes"], {"planes": 4, "kernel": "k_more_planes"})
+    if st[4] > 0.0005:
+        return hbm_leg(ms, float(st[4]), work["more_planes"]["bytes"], {"planes": 4, "kernel": "k_more_planes"})
+    # batches whose tables share their sizes: the sweep kernel writes all four planes
+    return hbm_leg(ms, float(st[3]), work["sweep"]["bytes"] + work["more_planes"]["bytes"],
+                   {"planes": 4, "kernel": "sweep (all four planes)"})
 
 
 def cpu_sample(cfg, wl):
@@ -348,6 +352,11 @@ def bench_config(cfg, steps, warmup, with_cpu, with_next, ceilings=None, mask=No
         work = dict(work)
         work["chain_blocks"] = {f: work["chain_blocks"][f] + work["terms"][f] for f in fields}
         work["terms"] = dict.fromkeys(fields, 0)
+    if stage_ms["more_planes"] < tiny < stage_ms["sweep"] and work["more_planes"]["bytes"]:
+        # the sweep kernel wrote the Gather and Barrier planes itself
+        work = dict(work)
+        work["sweep"] = {f: work["sweep"][f] + work["more_planes"][f] for f in fields}
+        work["more_planes"] = dict.fromkeys(fields, 0)
     dominant = max(STAGES, key=lambda k: stage_ms[k])
     off = OFFLINE_COUNTERS.get(cfg) if mask is None else None
     stage_of_offline = {"k_row": "sweep", "k_sweep_s": "sweep", "k_batch_t": "sweep", "k_chain_blocks": "chain_blocks"}
@@ -478,6 +487,11 @@ def main():
     detail = {"cfg%d" % args.config: head}
     extras = [] if args.extra in ("", "none") else [int(v) for v in args.extra.split(",")]
     nxt = {"cfg%d" % args.config: short_next(head)} if with_next else {}
+    if with_next and args.mask is None:
+        pat = run_patterns(args.config, args.steps)
+        detail["cfg%d" % args.config]["more_patterns"] = pat
+        nxt["cfg%d" % args.config]["more_patterns"] = {"ms_per_call": pat["ms_per_call"], "kernels_ms": pat["kernels_ms"],
+                                                        "hbm_frac": pat["roofline"]["frac"]}
     if extras:
         line["workloads"] = {}
         for cfg in extras:

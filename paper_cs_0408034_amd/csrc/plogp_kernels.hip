@@ -2824,6 +2824,7 @@ static_assert(BATCH_T_STAGE >= 32 * (BATCH_T_PS + 1) * 16 && BATCH_T_STAGE % 16 
 struct BatchDims {
     int n, n_tables, n_m, n_P, n_s, cl_max, n_ops, n_mchunks, m_per_wave;
     uint32_t mask;
+    uint32_t extra;   // rows beyond the tables: bits 0..2 Gather, bits 3, 4 Barrier (see DeviceGrid)
 };
 
 // A workgroup stages its 64 tables by interval in LDS (YS[i][lane] = {gap, slope}
@@ -2836,8 +2837,9 @@ struct BatchDims {
 // 4.5 KB of staging per wave, not for 64 rows of 8 cells: a Scatter cell is staged
 // as its time and a one-byte id (s is 0), the Broadcast cells go out in two halves
 // of 32 tables, the second half waiting in registers.
-// ALL: every strategy is enabled (the mask is a compile-time constant).
-template <int PC, int PS, bool ALL>
+// ALL: every strategy of Tables 1 and 2 is enabled (the mask is a compile-time constant).
+// EXTRA: rows beyond the tables are enabled as well (their planes cost nothing otherwise).
+template <int PC, int PS, bool ALL, bool EXTRA>
 __global__ void __launch_bounds__(64 * BATCH_T_WAVES)
 k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__ Lt,
           const double *__restrict__ recs, const double *__restrict__ tab,
@@ -2907,7 +2909,8 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
     const bool whole_group = tg * 64 + 64 <= D.n_tables;       // wave-uniform: no row of tables is missing
     // cell0: index of cell (plane, mi, p0) inside a table.  Scatter layout: row r of the stage
     // holds 8 times, then 8 ids as signed bytes (-1 = no strategy).
-    auto scatter_cell = [&](int r0) {
+    // id_add: 0, or 3 when the staged Scatter decisions go out as their Gather twins
+    auto scatter_cell = [&](int r0, int id_add) {
         const char *row = stage + (r0 + out_row) * 72;
         const double tv = *reinterpret_cast<const double *>(row + 8 * out_p);
         const int id = *reinterpret_cast<const signed char *>(row + 64 + out_p);
@@ -2915,10 +2918,10 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         cell.x = (unsigned)__double2loint(tv);
         cell.y = (unsigned)__double2hiint(tv);
         cell.z = 0u;
-        cell.w = (unsigned)id;
+        cell.w = (unsigned)(id < 0 ? id : id + id_add);
         return cell;
     };
-    auto flush_times = [&](size_t cell0, int p0) {
+    auto flush_times = [&](size_t cell0, int p0, int id_add) {
         __builtin_amdgcn_wave_barrier();
         if (p0 + out_p < n_P) {
             char *ubase = o_grp + cell0 * sizeof(plogp_cell_dev);
@@ -2930,7 +2933,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                     u32x4 c[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        c[u] = scatter_cell((64 / PS) * (it + u));
+                        c[u] = scatter_cell((64 / PS) * (it + u), id_add);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         store_run(ubase, c[u]);
@@ -2945,7 +2948,7 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
 #pragma unroll
                 for (int it = 0; it < 64 / PS; ++it) {
                     if ((64 / PS) * it < rl)
-                        store_run(ubase, scatter_cell((64 / PS) * it));
+                        store_run(ubase, scatter_cell((64 / PS) * it, id_add));
                     ubase += run_step;
                 }
             }
@@ -2986,8 +2989,19 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
         u.c.time = b.t; u.c.s = b.s; u.c.strategy = b.id;
         return u.v;
     };
-    const bool want_chain = (mask & (1u << 11)) != 0, want_binom = (mask & (1u << 12)) != 0;
-    const bool has_b = (mask & 0x3FFu) != 0, has_s = (mask & 0x1C00u) != 0;
+    // The Gather rows (ids 13..15) are the Scatter rows on the same sums: this kernel takes them
+    // when they are enabled exactly as the Scatter rows are, or without any Scatter row (the host
+    // sees to that), decides once and writes the decisions to both planes.  The Barrier rows
+    // (16, 17) need g(1), L and the process count only.
+    const uint32_t extra = EXTRA ? D.extra : 0u;
+    const uint32_t gather_rows = (extra & 7u) << 10;               // as the Scatter rows they mirror
+    const uint32_t sg_rows = (mask & 0x1C00u) | gather_rows;
+    const bool want_chain = (sg_rows & (1u << 11)) != 0, want_binom = (sg_rows & (1u << 12)) != 0;
+    const bool has_b = (mask & 0x3FFu) != 0, has_s = sg_rows != 0;
+    const bool has_scatter = (mask & 0x1C00u) != 0, has_gather = gather_rows != 0;
+    const bool has_barrier = (extra & 0x18u) != 0;
+    const size_t scatter_at = (has_b ? plane : 0), gather_at = scatter_at + (has_scatter ? plane : 0);
+    const size_t barrier_at = gather_at + (has_gather ? plane : 0);
 
     // The waves take the sizes of the workgroup's chunk one at a time from a counter, the largest
     // first (a size's cost grows with its number of candidates): the one workgroup that fits a
@@ -3101,11 +3115,29 @@ k_batch_t(BatchDims D, const f64x2 *__restrict__ ysT, const double *__restrict__
                             d2_n = uniform_load(rec + R.D2 + nx);
                         }
                     }
-                    const Best r = decide_scatter(mask, Pv.x, Pv.z, gm, L, done + run, s12);
+                    const Best r = decide_scatter(ALL ? mask : sg_rows, Pv.x, Pv.z, gm, L, done + run, s12);
                     *reinterpret_cast<double *>(stage + lane * 72 + 8 * p) = r.t;
                     *reinterpret_cast<signed char *>(stage + lane * 72 + 64 + p) = (signed char)r.id;
                 }
-                flush_times((has_b ? plane : 0) + cell0, q0);
+                if (has_scatter)
+                    flush_times(scatter_at + cell0, q0, 0);
+                if (has_gather)
+                    flush_times(gather_at + cell0, q0, 3);
+            }
+            if (has_barrier) {
+                // twice the flat-tree and the binomial row of Table 1 at one byte; the same for
+                // every message size, formed again for each (what it would take to keep them
+                // costs more than the few instructions)
+#pragma unroll
+                for (int p = 0; p < PS; ++p) {
+                    const f64x4 Pv = uniform_load(tab_P + q0 + p);
+                    Best b = {INFINITY, 0u, 0xFFFFFFFFu};
+                    if (extra & 8u) consider(b, 2.0 * __builtin_fma(Pv.x, g1, L), 16, 0);
+                    if (extra & 16u) consider(b, 2.0 * __builtin_fma(Pv.y, g1, Pv.z * L), 17, 0);
+                    *reinterpret_cast<double *>(stage + lane * 72 + 8 * p) = b.t;
+                    *reinterpret_cast<signed char *>(stage + lane * 72 + 64 + p) = (signed char)b.id;
+                }
+                flush_times(barrier_at + cell0, q0, 0);
             }
             if (!has_b)
                 continue;
@@ -3848,11 +3880,15 @@ hipError_t kernels_init()
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_score_fused<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)g_device.lds_per_cu);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
+    const void *batch_kernels[4] = {
+        reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, false, false>),
+        reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, false, true>),
+        reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, true, false>),
+        reinterpret_cast<const void *>(k_batch_t<BATCH_T_PC, BATCH_T_PS, true, true>)};
+    for (const void *k : batch_kernels) {
+        e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BATCH_T_LDS_MAX);
+        if (e != hipSuccess) return e;
+    }
     return e;
 }
 
@@ -3982,9 +4018,13 @@ bool plan_tune(const DeviceTables &T, const DeviceGrid &G, bool terms_only, Tune
     const size_t nt = (size_t)T.n_tables, n_m = (size_t)G.n_m, n_mu = (size_t)G.n_mu;
     const size_t n_P = (size_t)G.n_P, n_s = (size_t)G.n_s;
     LayoutBuilder lb;
-    // the rows beyond Tables 1 and 2 are formed from the staged path's terms and sums
+    // the rows beyond Tables 1 and 2 are formed from the staged path's terms and sums; only the
+    // table-lane kernel writes their planes itself, when the Gather rows are enabled exactly as
+    // the Scatter rows are (or one of the two patterns is absent): it decides once for both
     const bool fast_ok = !terms_only && G.extra == 0;
-    if (fast_ok && use_table_lane_path(T, G)) {
+    const uint32_t scatter_rows = G.mask & 0x1C00u, gather_rows = (G.extra & 7u) << 10;
+    const bool lanes_ok = !terms_only && (gather_rows == 0 || scatter_rows == 0 || gather_rows == scatter_rows);
+    if (lanes_ok && use_table_lane_path(T, G)) {
         p.path = TUNE_TABLE_LANES;
         // tables by interval and the per-m facts, then everything else in one kernel
         p.n_stage = (T.n_tables + BATCH_STAGE_TT - 1) / BATCH_STAGE_TT;
@@ -4195,8 +4235,12 @@ hipError_t launch_tune_stage(const TunePlan &p, int stage, const DeviceTables &T
             D.n = T.n; D.n_tables = T.n_tables; D.n_m = G.n_m; D.n_P = G.n_P; D.n_s = G.n_s;
             D.cl_max = G.cl_max; D.n_ops = G.n_ops; D.n_mchunks = p.batch_mchunks; D.m_per_wave = p.m_per_wave;
             D.mask = G.mask;
-            const auto kern = G.mask == 0x1FFFu ? k_batch_t<BATCH_T_PC, BATCH_T_PS, true>
-                                                : k_batch_t<BATCH_T_PC, BATCH_T_PS, false>;
+            D.extra = G.extra;
+            const bool all = G.mask == 0x1FFFu, more = G.extra != 0;
+            const auto kern = all ? (more ? k_batch_t<BATCH_T_PC, BATCH_T_PS, true, true>
+                                          : k_batch_t<BATCH_T_PC, BATCH_T_PS, true, false>)
+                                  : (more ? k_batch_t<BATCH_T_PC, BATCH_T_PS, false, true>
+                                          : k_batch_t<BATCH_T_PC, BATCH_T_PS, false, false>);
             hipLaunchKernelGGL(kern, dim3((unsigned)p.n_tg * p.batch_mchunks), dim3(64 * BATCH_T_WAVES),
                                p.batch_lds, st, D, reinterpret_cast<const f64x2 *>(S.batch_ys), T.L,
                                S.batch.rec, S.batch.tab, reinterpret_cast<const u64 *>(G.s), d_out);

@@ -104,8 +104,14 @@ int main()
             for (size_t o : offs)
                 CHECK(o < l.total && o % 256 == 0);
             CHECK(plan.path >= 0 && plan.path <= 3);
-            if (G.extra != 0 || terms_only)
+            // rows beyond the tables: the staged path, or the table-lane kernel when the Gather
+            // rows are enabled exactly as the Scatter rows are (or one of the two is absent)
+            const unsigned scatter_rows = G.mask & 0x1C00u, gather_rows = (G.extra & 7u) << 10;
+            const bool lanes_may = gather_rows == 0 || scatter_rows == 0 || gather_rows == scatter_rows;
+            if (terms_only)
                 CHECK(plan.path == plogp::TUNE_STAGED);
+            else if (G.extra != 0)
+                CHECK(plan.path == plogp::TUNE_STAGED || (plan.path == plogp::TUNE_TABLE_LANES && lanes_may));
             if (plan.path == plogp::TUNE_STAGED && plan.pairs)
                 CHECK(l.segA != 0 && l.segB != 0 && l.amin != 0 && G.n_s > 0);
         }

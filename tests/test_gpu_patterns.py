@@ -78,6 +78,33 @@ def test_subsets_of_the_new_rows(mask):
         assert assert_tables_equal(gpu_tune(wl), want, "mask %#x" % mask)
 
 
+@pytest.mark.parametrize("mask", [
+    EVERY,                                           # four planes, the Gather rows as the Scatter rows
+    0x3FF | 0xE000,                                  # Broadcast and Gather, no Scatter plane
+    (1 << 10) | (1 << 12) | (1 << 13) | (1 << 15),   # two Scatter rows and their two Gather twins
+    0x1C00 | 0x30000,                                # Scatter and Barrier
+    0x3FF | (1 << 16),                               # Broadcast and the flat Barrier alone
+    (1 << 14) | (1 << 17),                           # the Gather chain row and the binomial Barrier, nothing else
+    0x30000,                                         # a Barrier plane alone
+    0x1FFF | (1 << 14),                              # Gather rows unlike the Scatter rows: the staged path
+])
+def test_batches_of_tables_that_share_their_sizes(mask):
+    """100 tables of config 4 (a full group of 64 lanes and a ragged one of 36): the kernel whose
+    lanes run over tables writes the Gather and Barrier planes itself."""
+    wl = _with_mask(make_workload(4, n_tables=100, table_offset=500), mask)
+    want, _ = oracle.tune_workload(wl)
+    got = gpu_tune(wl)
+    assert assert_tables_equal(got, want, "100 tables, mask %#x" % mask), "times not bit-identical"
+
+
+def test_batch_with_process_counts_that_do_not_fill_a_group_of_eight():
+    # 21 process counts: the last store of a row covers five cells; 200 sizes: a ragged chunk
+    base = make_workload(4, n_tables=70, n_m=200)
+    wl = Workload(base.name, base.sizes, base.gaps, base.L, base.m, base.P[:21], base.s, base.s_cap, EVERY)
+    want, _ = oracle.tune_workload(wl)
+    assert assert_tables_equal(gpu_tune(wl), want, "70 tables, 21 process counts"), "times not bit-identical"
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_problems_with_random_masks(seed):
     rng = np.random.default_rng(9000 + seed)
