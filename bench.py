@@ -51,10 +51,10 @@ UNSEG_FLOPS = {0: 3, 1: 3, 3: 3, 4: 3, 6: 4, 7: 4, 8: 4, 10: 3, 11: 4, 12: 3}
 # (SQ_INSTS_VALU, in wave instructions).  A kernel change makes them stale until the profiles
 # are taken again; the line names its source.
 OFFLINE_COUNTERS = {
-    2: {"kernel": "k_row", "hbm_bytes": 0.336e6 + 34.326e6, "valu_insts": 4.864e6},
-    3: {"kernel": "k_sweep_s", "hbm_bytes": 4.040e6 + 2.881e6, "valu_insts": 35.22e6},
-    4: {"kernel": "k_batch_t", "hbm_bytes": 87.209e6 + 1966.436e6, "valu_insts": 175.7e6},
-    5: {"kernel": "k_chain_blocks", "hbm_bytes": 1.819e6 + 73.320e6, "valu_insts": 25.55e6},
+    2: {"kernel": "k_row", "hbm_bytes": 0.336e6 + 34.317e6, "valu_insts": 4.864e6},
+    3: {"kernel": "k_sweep_s", "hbm_bytes": 4.022e6 + 2.681e6, "valu_insts": 33.84e6},
+    4: {"kernel": "k_batch_t", "hbm_bytes": 87.199e6 + 1966.357e6, "valu_insts": 175.7e6},
+    5: {"kernel": "k_chain_blocks", "hbm_bytes": 1.840e6 + 73.784e6, "valu_insts": 25.60e6},
 }
 
 
