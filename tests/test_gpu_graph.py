@@ -11,7 +11,9 @@ from tests.gpu_util import assert_tables_equal, torch_cuda
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg,kw", [(1, {}), (2, dict(m_slice=slice(0, 1024, 9)))])
+# (700 tables of config 4: the kernel whose lanes run over tables, and 33 600 rows for the
+# one-pass extraction, whose workgroup counter and status words a small kernel clears)
+@pytest.mark.parametrize("cfg,kw", [(1, {}), (2, dict(m_slice=slice(0, 1024, 9))), (4, dict(n_tables=700))])
 def test_tune_and_cutovers_replayed_from_a_graph(cfg, kw):
     torch = torch_cuda()
     from paper_cs_0408034_amd import plogp
